@@ -1,0 +1,206 @@
+"""Pins for the oracle's network forward, loss and hand-derived backward.
+
+The architecture is the one in the paper's appendix "Implementation Details"; the loss is eq. (4) of Sec. 3 plus the
+squared value loss, and PPO's clipped surrogate.  The library cross-check uses torch's CPU conv2d/linear/autograd in
+float64 on random inputs: an independent formulation, not a copy of the oracle's loops.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import hts_synth as syn
+
+TINY = dict(C=2, H=20, W=20, A=3, convs=((3, 8, 4), (4, 3, 1), (4, 2, 1)), hidden=8)
+
+
+def _tiny(oracle):
+    net = oracle.make_net(TINY["C"], TINY["H"], TINY["W"], TINY["A"], TINY["convs"], TINY["hidden"])
+    return net
+
+
+def _torch_forward(p, obs, convs):
+    x = torch.from_numpy(obs.astype(np.float64)) / 255.0
+    for i, (co, k, s) in enumerate(convs):
+        x = F.relu(F.conv2d(x, p[f"conv{i + 1}.w"], p[f"conv{i + 1}.b"], stride=s))
+    h = F.relu(F.linear(x.flatten(1), p["fc.w"], p["fc.b"]))
+    return F.linear(h, p["pi.w"], p["pi.b"]), F.linear(h, p["v.w"], p["v.b"])[:, 0]
+
+
+def _torch_loss(p, obs, convs, actions, old_logp, adv, ret, algo, eps, cv, ce):
+    logits, v = _torch_forward(p, obs, convs)
+    lsm = F.log_softmax(logits, dim=1)
+    logp = lsm.gather(1, torch.from_numpy(actions.astype(np.int64))[:, None])[:, 0]
+    ent = -(lsm.exp() * lsm).sum(1)
+    adv_t, ret_t = torch.from_numpy(adv), torch.from_numpy(ret)
+    if algo == 0:
+        lpi = -(logp * adv_t).mean()
+    else:
+        rho = (logp - torch.from_numpy(old_logp)).exp()
+        lpi = -torch.minimum(rho * adv_t, rho.clamp(1 - eps, 1 + eps) * adv_t).mean()
+    lv = ((ret_t - v) ** 2).mean()
+    return lpi + cv * lv - ce * ent.mean(), lpi, lv, ent.mean()
+
+
+def _torch_params(flat, shape_kw, A):
+    parts = syn.split_params(flat.astype(np.float64), shape_kw["C"], shape_kw["H"], shape_kw["W"], A,
+                             convs=shape_kw["convs"], hidden=shape_kw["hidden"])
+    return {k: torch.from_numpy(np.ascontiguousarray(v)).requires_grad_(True) for k, v in parts.items()}
+
+
+def test_param_count_closed_forms(oracle):
+    atari = lambda A: 32 * 4 * 64 + 32 + 64 * 32 * 16 + 64 + 64 * 64 * 9 + 64 + 512 * 3136 + 512 + A * 512 + A + 512 + 1
+    assert oracle.param_count(oracle.make_net(4, 84, 84, 6)) == atari(6) == 1687719
+    assert oracle.param_count(oracle.make_net(4, 84, 84, 18)) == atari(18) == 1693875
+    assert oracle.param_count(oracle.make_net(16, 72, 96, 19)) == 1424052
+    for (C, H, W, A) in [(4, 84, 84, 6), (16, 72, 96, 19)]:
+        assert oracle.param_count(oracle.make_net(C, H, W, A)) == syn.param_count(C, H, W, A)
+
+
+def test_zero_weights_give_head_biases(oracle):
+    net = oracle.make_net(4, 84, 84, 6)
+    P = oracle.param_count(net)
+    p = np.zeros(P)
+    p[-1] = 0.7                                  # v.b
+    p[-1 - 512 - 6:-1 - 512] = np.arange(6) - 2  # pi.b
+    obs = syn.obs_uniform(3, 2)
+    logits, v = oracle.forward(net, p, obs)
+    assert np.array_equal(logits, np.tile(np.arange(6) - 2.0, (2, 1))) and np.array_equal(v, [0.7, 0.7])
+
+
+def test_kernel_equal_to_input_is_dot_product(oracle):
+    """A single conv layer whose kernel covers the whole input is one dot product per filter."""
+    net = oracle.make_net(3, 5, 5, 2, convs=((4, 5, 1),), hidden=4)
+    rng = np.random.default_rng(0)
+    P = oracle.param_count(net)
+    p = rng.normal(size=P)
+    obs = rng.integers(0, 256, size=(1, 3, 5, 5), dtype=np.uint8)
+    w1, b1 = p[:300].reshape(4, 75), p[300:304]
+    y1 = np.maximum(w1 @ (obs.reshape(75) / 255.0) + b1, 0)
+    off = 304
+    fw, fb = p[off:off + 16].reshape(4, 4), p[off + 16:off + 20]; off += 20
+    h = np.maximum(fw @ y1 + fb, 0)
+    pw, pb = p[off:off + 8].reshape(2, 4), p[off + 8:off + 10]; off += 10
+    vw, vb = p[off:off + 4], p[off + 4]
+    logits, v = oracle.forward(net, p, obs)
+    np.testing.assert_allclose(logits[0], pw @ h + pb, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(v[0], vw @ h + vb, rtol=1e-13, atol=1e-14)
+
+
+@pytest.mark.parametrize("shape", [(4, 84, 84, 6), (16, 72, 96, 19)])
+def test_forward_matches_torch_cpu(oracle, shape):
+    C, H, W, A = shape
+    net = oracle.make_net(C, H, W, A)
+    flat = syn.init_params(5, C, H, W, A, bias_scale=0.1)
+    obs = syn.obs_uniform(9, 3, C, H, W)
+    logits, v = oracle.forward(net, flat, obs)
+    kw = dict(C=C, H=H, W=W, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512)
+    with torch.no_grad():
+        tl, tv = _torch_forward(_torch_params(flat, kw, A), obs, kw["convs"])
+    np.testing.assert_allclose(logits, tl.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(v, tv.numpy(), rtol=1e-10, atol=1e-12)
+    # gather by index
+    l2, v2 = oracle.forward(net, flat, obs, index=np.array([2, 0], np.int32))
+    assert np.array_equal(l2, logits[[2, 0]]) and np.array_equal(v2, v[[2, 0]])
+
+
+def _problem(oracle, seed, B, algo, kw=TINY):
+    rng = np.random.default_rng(seed)
+    net = oracle.make_net(kw["C"], kw["H"], kw["W"], kw["A"], kw["convs"], kw["hidden"])
+    flat = syn.init_params(seed, kw["C"], kw["H"], kw["W"], kw["A"], bias_scale=0.2, convs=kw["convs"],
+                           hidden=kw["hidden"]).astype(np.float64)
+    obs = rng.integers(0, 256, size=(B, kw["C"], kw["H"], kw["W"]), dtype=np.uint8)
+    actions = rng.integers(0, kw["A"], size=B).astype(np.int32)
+    adv, ret = rng.normal(size=B), rng.normal(size=B)
+    logits, _ = oracle.forward(net, flat, obs)
+    lsm = logits - logits.max(1, keepdims=True); lsm -= np.log(np.exp(lsm).sum(1, keepdims=True))
+    old_logp = lsm[np.arange(B), actions] + rng.normal(0, 0.15, size=B) * (algo == 1)
+    return net, flat, obs, actions, old_logp, adv, ret
+
+
+@pytest.mark.parametrize("algo,eps", [(0, 0.1), (1, 0.1), (1, 0.3)])
+def test_loss_and_grads_match_torch_autograd(oracle, algo, eps):
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 21 + algo, 16, algo)
+    hp = oracle.make_hparams(algo=algo, clip_eps=eps, vf_coef=0.5, ent_coef=0.01)
+    g, st = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp)
+    p = _torch_params(flat, TINY, TINY["A"])
+    loss, lpi, lv, ent = _torch_loss(p, obs, TINY["convs"], actions, old_logp, adv, ret, algo, eps, 0.5, 0.01)
+    loss.backward()
+    tg = np.concatenate([p[name].grad.numpy().ravel() for name, _ in
+                         syn.param_shapes(TINY["C"], TINY["H"], TINY["W"], TINY["A"], convs=TINY["convs"],
+                                          hidden=TINY["hidden"])])
+    np.testing.assert_allclose(st["total_loss"], loss.item(), rtol=1e-12)
+    np.testing.assert_allclose(st["policy_loss"], lpi.item(), rtol=1e-12)
+    np.testing.assert_allclose(st["value_loss"], lv.item(), rtol=1e-12)
+    np.testing.assert_allclose(st["entropy"], ent.item(), rtol=1e-12)
+    np.testing.assert_allclose(g, tg, rtol=1e-9, atol=1e-13)
+    np.testing.assert_allclose(st["grad_norm"], np.linalg.norm(tg), rtol=1e-10)
+    if algo == 1:
+        assert 0.0 < st["clip_frac"] < 1.0      # the case exercises both clipped and unclipped rows
+
+
+def test_full_size_gradient_matches_torch_autograd(oracle):
+    """Full Atari-shaped net, 4 rows, PPO: every parameter tensor's gradient against autograd."""
+    kw = dict(C=4, H=84, W=84, A=6, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512)
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 4, 4, 1, kw)
+    hp = oracle.make_hparams(algo=1, clip_eps=0.1)
+    idx = np.array([3, 1, 0], np.int32)
+    g, st = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp, index=idx)
+    p = _torch_params(flat, kw, 6)
+    sel = idx.astype(np.int64)
+    loss, *_ = _torch_loss(p, obs[sel], kw["convs"], actions[sel], old_logp[sel], adv[sel], ret[sel], 1, 0.1, 0.5, 0.01)
+    loss.backward()
+    tg = np.concatenate([p[name].grad.numpy().ravel() for name, _ in syn.param_shapes(4, 84, 84, 6)])
+    np.testing.assert_allclose(g, tg, rtol=1e-8, atol=1e-13)
+
+
+def test_finite_differences(oracle):
+    """Central differences in float64 on the tiny net, at a point away from ReLU / clip kinks."""
+    for algo in (0, 1):
+        net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 31 + algo, 6, algo)
+        hp = oracle.make_hparams(algo=algo, clip_eps=0.2, vf_coef=0.5, ent_coef=0.01)
+        g, _ = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp)
+        rng = np.random.default_rng(0)
+        picks = rng.choice(flat.size, size=60, replace=False)
+        picks = np.concatenate([picks, np.arange(flat.size - 40, flat.size)])   # fc tail, heads, biases
+        h = 1e-6
+        for i in picks:
+            pp, pm = flat.copy(), flat.copy()
+            pp[i] += h; pm[i] -= h
+            lp_ = oracle.loss_grads(net, pp, obs, actions, old_logp, adv, ret, hp, want_grads=False)[1]["total_loss"]
+            lm_ = oracle.loss_grads(net, pm, obs, actions, old_logp, adv, ret, hp, want_grads=False)[1]["total_loss"]
+            fd = (lp_ - lm_) / (2 * h)
+            assert abs(fd - g[i]) <= 1e-6 * max(1.0, abs(g[i])) + 2e-8, (algo, i, fd, g[i])
+
+
+def test_ppo_ratio_one_is_a2c(oracle):
+    """rho == 1 (old_logp = current logp): PPO's gradient equals A2C's whatever eps is (Sec. 3 eq. (4))."""
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 41, 12, 0)     # algo 0 -> old_logp is exact
+    ga, sa = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, oracle.make_hparams(algo=0))
+    for eps in (0.0, 0.1, 1e9):
+        gp, sp = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, oracle.make_hparams(algo=1, clip_eps=eps))
+        np.testing.assert_allclose(gp, ga, rtol=1e-12, atol=1e-15)
+        assert sp["clip_frac"] == 0.0 and abs(sp["approx_kl"]) < 1e-15
+    # without clipping and arbitrary old_logp: PPO gradient = A2C gradient with adv scaled by rho
+    rng = np.random.default_rng(1)
+    olp = old_logp + rng.normal(0, 0.3, size=old_logp.size)
+    gp, _ = oracle.loss_grads(net, flat, obs, actions, olp, adv, ret, oracle.make_hparams(algo=1, clip_eps=1e9))
+    rho = np.exp(old_logp - olp)
+    ga2, _ = oracle.loss_grads(net, flat, obs, actions, old_logp, adv * rho, ret, oracle.make_hparams(algo=0))
+    np.testing.assert_allclose(gp, ga2, rtol=1e-12, atol=1e-15)
+
+
+def test_uniform_policy_entropy_and_zero_sum(oracle):
+    """Zero policy-head weights: p = 1/A, H = log A, and the policy-bias gradient sums to zero."""
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 51, 8, 0)
+    A, Hd = TINY["A"], TINY["hidden"]
+    P = flat.size
+    piw = P - 1 - Hd - A - A * Hd
+    flat[piw:piw + A * Hd + A] = 0.0
+    g, st = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, oracle.make_hparams(algo=0, ent_coef=0.5))
+    np.testing.assert_allclose(st["entropy"], np.log(A), rtol=1e-14)
+    gb = g[piw + A * Hd:piw + A * Hd + A]
+    assert abs(gb.sum()) < 1e-15
+    # at the uniform policy the entropy term has zero gradient: bias grad = -mean(adv * (onehot - 1/A))
+    want = -np.array([(adv * ((actions == j) - 1.0 / A)).mean() for j in range(A)])
+    np.testing.assert_allclose(gb, want, rtol=1e-12, atol=1e-15)

@@ -1,0 +1,61 @@
+"""Pins for the oracle's gradient-norm clip and Adam step."""
+import numpy as np
+
+
+def test_adam_first_step_closed_form(oracle):
+    rng = np.random.default_rng(0)
+    g = rng.normal(size=100); g[:5] = 0.0
+    th = rng.normal(size=100)
+    hp = oracle.make_hparams(lr=1e-3, adam_eps=1e-5)
+    t1, m, v = oracle.adam(th, g, np.zeros(100), np.zeros(100), 1, hp)
+    # bias corrections cancel at t=1: step = lr * g / (|g| + eps)
+    np.testing.assert_allclose(t1 - th, -1e-3 * g / (np.abs(g) + 1e-5), rtol=1e-12, atol=1e-18)
+    assert np.all(t1[:5] == th[:5])
+    np.testing.assert_allclose(m, 0.1 * g, rtol=1e-14)
+    np.testing.assert_allclose(v, 0.001 * g * g, rtol=1e-12)
+
+
+def test_adam_three_step_scalar_by_hand(oracle):
+    hp = oracle.make_hparams(lr=0.1, beta1=0.5, beta2=0.5, adam_eps=0.0)
+    th, m, v = np.array([1.0]), np.zeros(1), np.zeros(1)
+    gs = [2.0, -1.0, 4.0]
+    # by hand: m1=1, v1=2 -> mhat=2, vhat=4 -> th=1-.1*2/2=.9
+    #          m2=0, v2=1.5 -> mhat=0 -> th=.9
+    #          m3=2, v3=8.75 -> mhat=2/.875, vhat=10 -> th=.9-.1*(2/.875)/sqrt(10)
+    want = [0.9, 0.9, 0.9 - 0.1 * (2 / 0.875) / np.sqrt(10.0)]
+    for t, g in enumerate(gs, start=1):
+        th, m, v = oracle.adam(th, np.array([g]), m, v, t, hp)
+        np.testing.assert_allclose(th[0], want[t - 1], rtol=1e-14)
+
+
+def test_clip(oracle):
+    rng = np.random.default_rng(1)
+    g = rng.normal(size=1000)
+    n = np.linalg.norm(g)
+    s = oracle.clip_coef(g, 0.5)
+    np.testing.assert_allclose(np.linalg.norm(s * g), 0.5 * n / (n + 1e-6), rtol=1e-12)
+    assert oracle.clip_coef(g * 1e-3, 0.5) == 1.0
+    assert oracle.clip_coef(g, 0.0) == 1.0 and oracle.clip_coef(g, -1.0) == 1.0
+
+
+def test_learner_step_composes(oracle):
+    """learner_step == loss_grads -> clip -> adam, and gscale enters Adam as a plain factor on g."""
+    import hts_synth as syn
+    kw = dict(convs=((3, 8, 4), (4, 3, 1), (4, 2, 1)), hidden=8)
+    net = oracle.make_net(2, 20, 20, 3, **kw)
+    rng = np.random.default_rng(2)
+    p = syn.init_params(1, 2, 20, 20, 3, bias_scale=0.1, **kw).astype(np.float64)
+    B = 10
+    obs = rng.integers(0, 256, size=(B, 2, 20, 20), dtype=np.uint8)
+    act = rng.integers(0, 3, size=B).astype(np.int32)
+    adv, ret, olp = rng.normal(size=B) * 30, rng.normal(size=B), -np.ones(B)
+    hp = oracle.make_hparams(algo=0, max_grad_norm=0.5, lr=1e-2)
+    m0, v0 = np.zeros(p.size), np.zeros(p.size)
+    p1, m1, v1, g, st = oracle.learner_step(net, p, m0, v0, 1, obs, act, olp, adv, ret, hp)
+    g2, st2 = oracle.loss_grads(net, p, obs, act, olp, adv, ret, hp)
+    assert np.array_equal(g, g2)
+    s = oracle.clip_coef(g2, 0.5)
+    assert s < 1.0
+    p2, m2, v2 = oracle.adam(p, g2 * s, m0, v0, 1, hp)
+    np.testing.assert_allclose(p1, p2, rtol=1e-14, atol=1e-16)
+    np.testing.assert_allclose(m1, m2, rtol=1e-14, atol=1e-300)
