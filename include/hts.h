@@ -1,0 +1,156 @@
+/*
+ * hts.h -- C ABI of the GPU-resident hot path of HTS-RL's synchronous actor-learner loop
+ * (High-Throughput Synchronous Deep RL, Liu/Yeh/Schwing, NeurIPS 2020) for AMD MI355X (gfx950).
+ *
+ * Three calls follow the paper's decomposition of one training iteration (Sec. 4.1 "Overview"):
+ *   hts_act           what an actor does: one batched forward pass over the observations it grabbed and a
+ *                     seeded action sample per observation (Sec. 4.1 "Asynchronous actors and executors");
+ *   hts_returns_gae   the returns / advantages over one filled data storage (Sec. 3, n-step truncated return);
+ *   hts_learner_step  what a learner does with a storage: forward and backward pass on a minibatch and one
+ *                     optimiser step (Sec. 3 eq. (4); Sec. 4.1 "Concurrent rollout and learning").
+ *
+ * Conventions for every function
+ *   - All array arguments are DEVICE pointers owned by the caller (the library never frees or keeps them),
+ *     unless the comment says "host".  Structs (hts_net_desc, hts_buffer, hts_hparams, hts_opt_state) are host
+ *     structs passed by pointer; the device pointers they hold obey the same rule.
+ *   - Work is enqueued on the HIP stream given to hts_create and is NOT synchronised: outputs are valid once the
+ *     caller has synchronised that stream.
+ *   - Return value: 0 on success, a negative HTS_E* code on failure.  On HTS_EINVAL / HTS_ESHAPE nothing has been
+ *     launched.  No C++ types or exceptions cross this boundary.
+ *   - Same inputs give bit-identical outputs on every run: no atomics, every reduction has a fixed shape.
+ *   - The context owns a device workspace sized at creation (activations, split-K partials, permuted conv
+ *     weights); no call after hts_create allocates.  Calls on one context must not overlap in time.
+ *
+ * Network (appendix "Implementation Details"): conv 32@8x8 stride 4 -> conv 64@4x4 stride 2 -> conv 64@3x3
+ * stride 1 -> FC 512 -> {policy head with A logits, value head}; ReLU after each of the four hidden layers; no
+ * padding; observations are uint8 NCHW and are scaled by 1/255 inside the first layer.
+ *
+ * Parameter packing (one flat fp32 vector; gradients and optimiser moments use the same packing):
+ *   conv1.w[32,C,8,8] conv1.b[32] conv2.w[64,32,4,4] conv2.b[64] conv3.w[64,64,3,3] conv3.b[64]
+ *   fc.w[512,F] fc.b[512] pi.w[A,512] pi.b[A] v.w[512] v.b[1],  F = 64*H3*W3 flattened as (channel, y, x).
+ */
+#ifndef HTS_H
+#define HTS_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HTS_OK      0
+#define HTS_EINVAL  (-1)   /* null pointer, non-positive size, misaligned pointer, bad enum            */
+#define HTS_ESHAPE  (-2)   /* unsupported C/H/W/A/precision, or a batch larger than the context's max  */
+#define HTS_EHIP    (-3)   /* a HIP runtime call failed; hts_last_hip_error() returns its code         */
+#define HTS_ENOMEM  (-4)   /* host or device allocation failed in hts_create                           */
+
+#define HTS_PRECISION_FP32 0   /* fp32 operands, fp32 accumulate                                        */
+#define HTS_PRECISION_BF16 1   /* bf16 matrix operands, fp32 accumulate, fp32 heads/loss/optimiser      */
+
+#define HTS_ALGO_A2C 0
+#define HTS_ALGO_PPO 1
+
+#define HTS_MAX_ACTIONS 64
+
+typedef struct hts_ctx hts_ctx;
+
+/* Observation shape [C,H,W] (W must be a multiple of 4; all three conv outputs must be non-empty),
+ * number of actions A (1..HTS_MAX_ACTIONS) and arithmetic precision. */
+typedef struct { int32_t C, H, W, A; int32_t precision; } hts_net_desc;
+
+/* Number of fp32 parameters for a shape; negative error code if the shape is unsupported.  Host only. */
+int64_t hts_param_count(const hts_net_desc *desc);
+
+/* Create a context.  max_act_batch bounds N of hts_act, max_learn_batch bounds B of the learner calls (either may
+ * be 0 if that call is unused).  hip_stream is a hipStream_t (NULL = the default stream).  Allocates the device
+ * workspace.  *out receives the context, to be released with hts_destroy. */
+int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, int32_t max_learn_batch, void *hip_stream,
+                   hts_ctx **out);
+int32_t hts_destroy(hts_ctx *ctx);
+
+/* Actor step (Sec. 4.1 "Asynchronous actors and executors").
+ *   obs      u8 [N,C,H,W]    the N observations grabbed in this poll
+ *   params   f32 [P]         behaviour parameters
+ *   seed, step, env_offset   observation i belongs to environment env_offset+i; its action is drawn with the
+ *                            uniform u = top 24 bits of word 0 of Philox4x32-10(key = seed lo/hi,
+ *                            counter = (env, step, 0, 0)) * 2^-24, so the action does not depend on which call
+ *                            or which batch handles the observation.
+ *   actions  i32 [N]   logp f32 [N] (log pi(a|s))   values f32 [N]   logits_or_null f32 [N,A]
+ * Sampling rule (binary32, sequential): m = max logits; e_j = hts-exp(l_j - m); c_j = c_{j-1} + e_j;
+ * action = first j with c_j > u * c_{A-1}, else A-1. */
+int32_t hts_act(hts_ctx *ctx, const uint8_t *obs, const float *params, uint64_t seed, uint32_t step, int32_t N,
+                int32_t env_offset, int32_t *actions, float *logp, float *values, float *logits_or_null);
+
+/* The sampling stage of hts_act alone, on caller-supplied logits f32 [N,A] (test hook for bit-exact parity). */
+int32_t hts_sample_from_logits(hts_ctx *ctx, const float *logits, uint64_t seed, uint32_t step, int32_t N,
+                               int32_t env_offset, int32_t *actions, float *logp);
+
+/* Returns / advantages over one storage (Sec. 3 "Actor-Critic Algorithms"; lambda = 1 gives the n-step return).
+ *   rewards f32 [T,N]   values f32 [T+1,N] (row T = value of the state after the last step)
+ *   dones u8 [T,N] (1 = the action at step t ended the episode)
+ *   delta_t = r_t + gamma (1-d_t) V_{t+1} - V_t;  A_t = delta_t + gamma lambda (1-d_t) A_{t+1}, A_T = 0;
+ *   advantages f32 [T,N] = A;   returns f32 [T,N] = A + V.   ctx may be NULL only if stream 0 is intended. */
+int32_t hts_returns_gae(hts_ctx *ctx, const float *rewards, const float *values, const uint8_t *dones, float gamma,
+                        float lambda, int32_t T, int32_t N, float *advantages, float *returns);
+
+/* In-place (A - mean) / (std + 1e-5) over n entries, std with the n-1 divisor; fixed-shape reduction. */
+int32_t hts_normalize_advantages(hts_ctx *ctx, float *adv, int64_t n);
+
+/* One storage as the learner reads it: `count` rows (= T*N, time-major), of which the minibatch is the B rows
+ * index[0..B) (NULL = rows 0..B-1).  old_values is unused by the loss and may be NULL. */
+typedef struct {
+    const uint8_t *obs;        /* u8 [count,C,H,W] */
+    const int32_t *actions;    /* i32 [count]      */
+    const float   *old_logp;   /* f32 [count]  log-prob under the behaviour policy (PPO; may be NULL for A2C) */
+    const float   *old_values; /* f32 [count]  unused                                                        */
+    const float   *advantages; /* f32 [count]  treated as constants                                           */
+    const float   *returns;    /* f32 [count]                                                                 */
+    int32_t        count;
+    const int32_t *index;      /* i32 [B] or NULL */
+    int32_t        B;
+} hts_buffer;
+
+/* Loss (Sec. 3 eq. (4) as a loss to minimise, plus the squared value loss, no 1/2 factor):
+ *   L = L_pi + vf_coef * mean((R - v)^2) - ent_coef * mean(H(pi(.|s)))
+ *   A2C: L_pi = -mean(logp * adv);  PPO: L_pi = -mean(min(rho adv, clip(rho, 1-eps, 1+eps) adv)),
+ *   rho = exp(logp - old_logp).   max_grad_norm > 0: gradients are scaled by min(1, c / (||g||_2 + 1e-6)).
+ *   Adam: m <- b1 m + (1-b1) g; v <- b2 v + (1-b2) g^2; theta <- theta - lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps). */
+typedef struct {
+    int32_t algo;
+    float clip_eps, vf_coef, ent_coef, max_grad_norm;
+    float lr, beta1, beta2, adam_eps;
+} hts_hparams;
+
+/* Optimiser state: m, v device f32 [P]; step is a host counter of completed updates (the call uses t = step+1 and
+ * increments it). */
+typedef struct { float *m; float *v; int64_t step; } hts_opt_state;
+
+/* Device struct written by the learner calls when requested. */
+typedef struct {
+    float policy_loss, value_loss, entropy, grad_norm, clip_frac, approx_kl;
+    int32_t nonfinite;      /* 1 if the loss terms or the gradient norm are not finite */
+} hts_stats;
+
+/* One optimisation step on one minibatch: forward, loss, backward, optional clip, Adam on params (in/out). */
+int32_t hts_learner_step(hts_ctx *ctx, const hts_buffer *buf, float *params, hts_opt_state *opt,
+                         const hts_hparams *hp, hts_stats *stats_or_null);
+
+/* The same forward/loss/backward without the update: grads f32 [P] receives dL/dparams (unclipped). */
+int32_t hts_loss_and_grads(hts_ctx *ctx, const hts_buffer *buf, const float *params, const hts_hparams *hp,
+                           float *grads, hts_stats *stats_or_null);
+
+/* Clip (if hp->max_grad_norm > 0) and Adam alone, on caller-supplied gradients f32 [P]. */
+int32_t hts_adam_apply(hts_ctx *ctx, float *params, const float *grads, hts_opt_state *opt, const hts_hparams *hp,
+                       int64_t P);
+
+/* Test hook for the tiled matrix-multiply core every layer is built on: C[M,N] = A[M,K] * B[N,K]^T, all f32
+ * row-major device arrays; operands are rounded to bf16 first when precision = HTS_PRECISION_BF16.  K % 8 == 0. */
+int32_t hts_test_gemm(hts_ctx *ctx, int32_t precision, const float *A, const float *B, float *Cout, int32_t M,
+                      int32_t N, int32_t K);
+
+int32_t     hts_last_hip_error(void);
+const char *hts_strerror(int32_t code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HTS_H */

@@ -34,7 +34,7 @@ def build(force: bool = False) -> str:
 class Net(C.Structure):
     _fields_ = [("C", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("nconv", C.c_int32),
                 ("cout", C.c_int32 * MAX_CONV), ("ksz", C.c_int32 * MAX_CONV), ("stride", C.c_int32 * MAX_CONV),
-                ("hidden", C.c_int32), ("A", C.c_int32)]
+                ("hidden", C.c_int32), ("A", C.c_int32), ("operand_bf16", C.c_int32)]
 
 
 class HParams(C.Structure):
@@ -52,8 +52,9 @@ class Stats(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
-def make_net(C_in, H, W, A, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512) -> Net:
+def make_net(C_in, H, W, A, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512, operand_bf16=False) -> Net:
     n = Net()
+    n.operand_bf16 = 1 if operand_bf16 else 0
     n.C, n.H, n.W, n.A, n.hidden, n.nconv = C_in, H, W, A, hidden, len(convs)
     for i, (co, k, s) in enumerate(convs):
         n.cout[i], n.ksz[i], n.stride[i] = co, k, s
@@ -78,6 +79,8 @@ def lib():
         _lib.orc_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
         _lib.orc_expf.restype = C.c_float
         _lib.orc_expf.argtypes = [C.c_float]
+        _lib.orc_round_bf16.restype = C.c_double
+        _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_clip_coef.restype = C.c_double
         _lib.orc_clip_coef.argtypes = [C.c_void_p, C.c_int64, C.c_double]
     return _lib
@@ -109,6 +112,10 @@ def uniform(seed: int, env: int, step: int) -> float:
 
 def expf(x: float) -> np.float32:
     return np.float32(lib().orc_expf(C.c_float(float(x))))
+
+
+def round_bf16(x: float) -> float:
+    return float(lib().orc_round_bf16(C.c_double(float(x))))
 
 
 def forward(net: Net, params, obs, index=None, B=None):

@@ -46,6 +46,10 @@ typedef struct {
     int32_t stride[ORC_MAX_CONV]; /* stride                                           */
     int32_t hidden;               /* width of the fully connected layer               */
     int32_t A;                    /* number of actions                                */
+    int32_t operand_bf16;         /* 0: exact operands.  1: model of a reduced-precision matrix path -- conv and FC
+                                     weights and the stored outputs of the three conv layers are rounded to bfloat16
+                                     (round to nearest even) before use; sums, biases, FC output, heads and loss stay
+                                     exact.  Gradients treat the rounding as the identity.                          */
 } orc_net;
 
 typedef struct {
@@ -96,6 +100,34 @@ static void orc_shapes(const orc_net *n, orc_shape *s)
     s->total = off;
 }
 
+/* Round a double to the nearest bfloat16 value (8 significant bits, binary32 exponent range), ties to even.
+ * Done on the binary32 bit pattern: keep the top 16 bits, round on the dropped 16. */
+double orc_round_bf16(double x)
+{
+    union { float f; uint32_t u; } c;
+    c.f = (float)x;
+    if ((c.u & 0x7F800000u) == 0x7F800000u) return (double)c.f;       /* inf / nan unchanged */
+    const uint32_t low = c.u & 0xFFFFu, keep = c.u >> 16;
+    uint32_t r = keep;
+    if (low > 0x8000u || (low == 0x8000u && (keep & 1u))) r = keep + 1u;
+    c.u = r << 16;
+    return (double)c.f;
+}
+
+/* Copy of the parameters as the forward/backward passes use them (see orc_net.operand_bf16). */
+static double *operand_params(const orc_net *n, const orc_shape *s, const double *params)
+{
+    double *q = malloc(sizeof(double) * (size_t)s->total);
+    if (!q) return NULL;
+    memcpy(q, params, sizeof(double) * (size_t)s->total);
+    if (n->operand_bf16) {
+        for (int l = 0; l < n->nconv; ++l)
+            for (int64_t i = s->w_off[l]; i < s->b_off[l]; ++i) q[i] = orc_round_bf16(q[i]);
+        for (int64_t i = s->fcw; i < s->fcb; ++i) q[i] = orc_round_bf16(q[i]);
+    }
+    return q;
+}
+
 int64_t orc_param_count(const orc_net *n)
 {
     orc_shape s; orc_shapes(n, &s); return s.total;
@@ -129,7 +161,8 @@ static void forward_one(const orc_net *n, const orc_shape *s, const double *p, c
                             for (int v = 0; v < k; ++v)
                                 acc += wgt[((o * ci + c) * k + u) * k + v] *
                                        in[(c * hi + (i * st + u)) * wi + (j * st + v)];
-                    out[(o * ho + i) * wo + j] = acc > 0.0 ? acc : 0.0;
+                    const double y = acc > 0.0 ? acc : 0.0;
+                    out[(o * ho + i) * wo + j] = n->operand_bf16 ? orc_round_bf16(y) : y;
                 }
         in = out;
     }
@@ -158,13 +191,13 @@ int32_t orc_forward(const orc_net *n, const double *params, const uint8_t *obs, 
     orc_shape s; orc_shapes(n, &s);
     const int in_sz = n->C * n->H * n->W;
     double *x = malloc(sizeof(double) * in_sz), *act = malloc(sizeof(double) * s.act_total),
-           *h = malloc(sizeof(double) * n->hidden);
-    if (!x || !act || !h) return -1;
+           *h = malloc(sizeof(double) * n->hidden), *pq = operand_params(n, &s, params);
+    if (!x || !act || !h || !pq) return -1;
     for (int b = 0; b < B; ++b) {
         const int64_t row = index ? index[b] : b;
-        forward_one(n, &s, params, obs + row * in_sz, x, act, h, logits + (int64_t)b * n->A, values + b);
+        forward_one(n, &s, pq, obs + row * in_sz, x, act, h, logits + (int64_t)b * n->A, values + b);
     }
-    free(x); free(act); free(h);
+    free(x); free(act); free(h); free(pq);
     return 0;
 }
 
@@ -310,11 +343,13 @@ void orc_normalize_adv(double *adv, int64_t n)
  *   A2C: L_pi = -mean(logp * adv)                                     [eq. (4), sign flipped: a loss]
  *   PPO: L_pi = -mean(min(rho adv, clip(rho, 1-eps, 1+eps) adv)), rho = exp(logp - old_logp)
  * adv and ret are constants.  grads (may be NULL) receives dL/dparams in the packing of params. */
-int32_t orc_loss_grads(const orc_net *n, const double *params, const uint8_t *obs, const int32_t *index, int32_t B,
+int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t *obs, const int32_t *index, int32_t B,
                        const int32_t *actions, const double *old_logp, const double *adv, const double *ret,
                        const orc_hparams *hp, double *grads, orc_stats *stats)
 {
     orc_shape s; orc_shapes(n, &s);
+    double *params = operand_params(n, &s, params_in);   /* the weights as the passes use them */
+    if (!params) return -1;
     const int in_sz = n->C * n->H * n->W;
     const int A = n->A, Hd = n->hidden;
     double *x = malloc(sizeof(double) * in_sz), *act = malloc(sizeof(double) * s.act_total),
@@ -435,7 +470,7 @@ int32_t orc_loss_grads(const orc_net *n, const double *params, const uint8_t *ob
         if (grads) for (int64_t i = 0; i < s.total; ++i) ss += grads[i] * grads[i];
         stats->grad_norm = sqrt(ss);
     }
-    free(x); free(act); free(dact); free(h); free(dh); free(logits); free(lp); free(dl);
+    free(x); free(act); free(dact); free(h); free(dh); free(logits); free(lp); free(dl); free(params);
     return 0;
 }
 

@@ -1,0 +1,273 @@
+// C ABI of libhts: argument checks, context/workspace, and the launch sequence of each call (see include/hts.h).
+#include <math.h>
+#include <new>
+
+#include "internal.hpp"
+
+using namespace hts;
+
+struct hts_ctx { Ctx c; };
+
+static thread_local int32_t g_last_hip = 0;
+
+static int32_t hip_fail(hipError_t e)
+{
+    g_last_hip = (int32_t)e;
+    return HTS_EHIP;
+}
+#define HIP_TRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
+
+static int32_t make_geom(const hts_net_desc *d, Geom *g)
+{
+    if (!d) return HTS_EINVAL;
+    if (d->C < 1 || d->H < 8 || d->W < 8 || d->A < 1 || d->A > HTS_MAX_ACTIONS) return HTS_ESHAPE;
+    if (d->W % 4 != 0) return HTS_ESHAPE;
+    if (d->precision != HTS_PRECISION_FP32 && d->precision != HTS_PRECISION_BF16) return HTS_ESHAPE;
+    if ((long long)d->C * d->H * d->W > (1ll << 24) || d->C > 1024) return HTS_ESHAPE;
+    g->C = d->C; g->H = d->H; g->W = d->W; g->A = d->A;
+    g->H1 = (d->H - 8) / 4 + 1; g->W1 = (d->W - 8) / 4 + 1;
+    if (g->H1 < 4 || g->W1 < 4) return HTS_ESHAPE;
+    g->H2 = (g->H1 - 4) / 2 + 1; g->W2 = (g->W1 - 4) / 2 + 1;
+    if (g->H2 < 3 || g->W2 < 3) return HTS_ESHAPE;
+    g->H3 = g->H2 - 2; g->W3 = g->W2 - 2;
+    g->P1 = g->H1 * g->W1; g->P2 = g->H2 * g->W2; g->P3 = g->H3 * g->W3;
+    g->F = 64 * g->P3; g->K1 = d->C * 64;
+    long long o = 0;
+    g->w1 = o; o += 32ll * g->K1; g->b1 = o; o += 32;
+    g->w2 = o; o += 64ll * 512;   g->b2 = o; o += 64;
+    g->w3 = o; o += 64ll * 576;   g->b3 = o; o += 64;
+    g->fcw = o; o += 512ll * g->F; g->fcb = o; o += 512;
+    g->piw = o; o += 512ll * d->A; g->pib = o; o += d->A;
+    g->vw = o; o += 512; g->vb = o; o += 1;
+    g->P = o;
+    return HTS_OK;
+}
+
+extern "C" int64_t hts_param_count(const hts_net_desc *desc)
+{
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    return rc == HTS_OK ? (int64_t)g.P : (int64_t)rc;
+}
+
+extern "C" int32_t hts_last_hip_error(void) { return g_last_hip; }
+
+extern "C" const char *hts_strerror(int32_t code)
+{
+    switch (code) {
+    case HTS_OK: return "ok";
+    case HTS_EINVAL: return "invalid argument (null pointer, non-positive size, misaligned pointer or bad enum)";
+    case HTS_ESHAPE: return "unsupported shape, precision or batch larger than the context allows";
+    case HTS_EHIP: return "HIP runtime error (see hts_last_hip_error)";
+    case HTS_ENOMEM: return "allocation failed";
+    default: return "unknown error code";
+    }
+}
+
+namespace {
+struct Carver {
+    size_t off = 0;
+    char *base = nullptr;
+    template <typename P> void take(P *&ptr, size_t bytes)
+    {
+        off = (off + 255) & ~(size_t)255;
+        if (base) ptr = reinterpret_cast<P *>(base + off);
+        off += bytes;
+    }
+};
+
+void carve(Ctx &c, Carver &cv)
+{
+    const Geom &g = c.g;
+    Workspace &w = c.ws;
+    const size_t ts = c.desc.precision == HTS_PRECISION_BF16 ? 2 : 4;
+    const size_t mb = (size_t)c.max_b, ml = (size_t)c.max_learn;
+    cv.take(w.wf2, 64 * 512 * ts); cv.take(w.wf3, 64 * 576 * ts);
+    cv.take(w.wd2, 32 * 1024 * ts); cv.take(w.wd3, 64 * 576 * ts);
+    cv.take(w.act1, mb * g.P1 * 32 * ts); cv.take(w.act2, mb * g.P2 * 64 * ts); cv.take(w.a3, mb * g.F * ts);
+    cv.take(w.h, mb * 512 * 4); cv.take(w.logits, mb * g.A * 4); cv.take(w.val, mb * 4);
+    cv.take(w.clip, 2 * 4);
+    cv.take(w.norm_part, (size_t)((g.P + NORM_CHUNK - 1) / NORM_CHUNK) * 4);
+    if (ml > 0) {
+        cv.take(w.dz, ml * (g.A + 1) * 4); cv.take(w.dh, ml * 512 * 4); cv.take(w.terms, ml * N_TERMS * 4);
+        cv.take(w.dy3, ml * g.P3 * 64 * ts); cv.take(w.dy2, ml * g.P2 * 64 * ts); cv.take(w.dy1, ml * g.P1 * 32 * ts);
+        cv.take(w.grads, (size_t)g.P * 4);
+        // upper bounds of the split counts over every minibatch size B <= max_learn (see split_for)
+        auto bound = [](long long kp, int maxz) { const long long n = (kp + 255) / 256; return (size_t)(n < maxz ? n : maxz); };
+        w.part_elems = bound((long long)ml * g.P3, 64) * 64 * 577 + bound((long long)ml * g.P2, 64) * 64 * 513 +
+                       bound((long long)ml * g.P1, 128) * 32 * (size_t)(g.K1 + 1);
+        cv.take(w.part, w.part_elems * 4);
+    }
+}
+}  // namespace
+
+extern "C" int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, int32_t max_learn_batch, void *hip_stream,
+                              hts_ctx **out)
+{
+    if (!desc || !out) return HTS_EINVAL;
+    if (max_act_batch < 0 || max_learn_batch < 0 || (max_act_batch == 0 && max_learn_batch == 0)) return HTS_EINVAL;
+    if (max_act_batch > (1 << 16) || max_learn_batch > (1 << 16)) return HTS_ESHAPE;
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    if (rc != HTS_OK) return rc;
+    hts_ctx *h = new (std::nothrow) hts_ctx();
+    if (!h) return HTS_ENOMEM;
+    Ctx &c = h->c;
+    c.desc = *desc; c.g = g; c.stream = (hipStream_t)hip_stream;
+    c.max_act = max_act_batch; c.max_learn = max_learn_batch;
+    c.max_b = max_act_batch > max_learn_batch ? max_act_batch : max_learn_batch;
+    c.ws = Workspace();
+    Carver size_pass;
+    carve(c, size_pass);
+    c.ws.bytes = size_pass.off + 256;
+    const hipError_t e = hipMalloc(&c.ws.slab, c.ws.bytes);
+    if (e != hipSuccess) { delete h; g_last_hip = (int32_t)e; return HTS_ENOMEM; }
+    Carver place;
+    place.base = (char *)c.ws.slab;
+    carve(c, place);
+    const hipError_t e2 = hipMemsetAsync(c.ws.slab, 0, c.ws.bytes, c.stream);
+    if (e2 != hipSuccess) { (void)hipFree(c.ws.slab); delete h; return hip_fail(e2); }
+    *out = h;
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_destroy(hts_ctx *ctx)
+{
+    if (!ctx) return HTS_EINVAL;
+    hipError_t e = hipSuccess;
+    if (ctx->c.ws.slab) e = hipFree(ctx->c.ws.slab);
+    delete ctx;
+    return e == hipSuccess ? HTS_OK : hip_fail(e);
+}
+
+extern "C" int32_t hts_act(hts_ctx *ctx, const uint8_t *obs, const float *params, uint64_t seed, uint32_t step, int32_t N,
+                           int32_t env_offset, int32_t *actions, float *logp, float *values, float *logits_or_null)
+{
+    if (!ctx || !obs || !params || !actions || !logp || !values) return HTS_EINVAL;
+    if (N <= 0 || env_offset < 0) return HTS_EINVAL;
+    if (N > ctx->c.max_act) return HTS_ESHAPE;
+    if (((uintptr_t)obs & 3u) || ((uintptr_t)params & 15u)) return HTS_EINVAL;
+    Ctx &c = ctx->c;
+    HIP_TRY(launch_prep(c, params));
+    HIP_TRY(run_forward(c, obs, nullptr, params, N));
+    HIP_TRY(launch_heads_act(c, params, nullptr, seed, step, N, env_offset, actions, logp, values, logits_or_null));
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_sample_from_logits(hts_ctx *ctx, const float *logits, uint64_t seed, uint32_t step, int32_t N,
+                                          int32_t env_offset, int32_t *actions, float *logp)
+{
+    if (!ctx || !logits || !actions || !logp) return HTS_EINVAL;
+    if (N <= 0 || env_offset < 0) return HTS_EINVAL;
+    HIP_TRY(launch_heads_act(ctx->c, nullptr, logits, seed, step, N, env_offset, actions, logp, nullptr, nullptr));
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_returns_gae(hts_ctx *ctx, const float *rewards, const float *values, const uint8_t *dones,
+                                   float gamma, float lambda, int32_t T, int32_t N, float *advantages, float *returns)
+{
+    if (!rewards || !values || !dones || !advantages || !returns) return HTS_EINVAL;
+    if (T <= 0 || N <= 0) return HTS_EINVAL;
+    if ((long long)(T + 1) * N >= (1ll << 40)) return HTS_ESHAPE;
+    HIP_TRY(launch_gae(ctx ? ctx->c.stream : (hipStream_t)0, rewards, values, dones, gamma, lambda, T, N, advantages,
+                       returns));
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_normalize_advantages(hts_ctx *ctx, float *adv, int64_t n)
+{
+    if (!adv || n <= 0) return HTS_EINVAL;
+    HIP_TRY(launch_normalize(ctx ? ctx->c.stream : (hipStream_t)0, adv, n));
+    return HTS_OK;
+}
+
+static int32_t check_learn(hts_ctx *ctx, const hts_buffer *buf, const float *params, const hts_hparams *hp)
+{
+    if (!ctx || !buf || !params || !hp) return HTS_EINVAL;
+    if (!buf->obs || !buf->actions || !buf->advantages || !buf->returns) return HTS_EINVAL;
+    if (hp->algo != HTS_ALGO_A2C && hp->algo != HTS_ALGO_PPO) return HTS_EINVAL;
+    if (hp->algo == HTS_ALGO_PPO && !buf->old_logp) return HTS_EINVAL;
+    if (buf->B <= 0 || buf->count <= 0) return HTS_EINVAL;
+    if (!buf->index && buf->B > buf->count) return HTS_EINVAL;
+    if (buf->B > ctx->c.max_learn) return HTS_ESHAPE;
+    if (((uintptr_t)buf->obs & 3u) || ((uintptr_t)params & 15u)) return HTS_EINVAL;
+    return HTS_OK;
+}
+
+static int32_t loss_and_grads(Ctx &c, const hts_buffer *buf, const float *params, const hts_hparams *hp, float *grads)
+{
+    LossArgs la;
+    la.actions = buf->actions; la.index = buf->index; la.old_logp = buf->old_logp;
+    la.adv = buf->advantages; la.ret = buf->returns;
+    la.algo = hp->algo; la.clip_eps = hp->clip_eps; la.vf_coef = hp->vf_coef; la.ent_coef = hp->ent_coef;
+    HIP_TRY(launch_prep(c, params));
+    HIP_TRY(run_forward(c, buf->obs, buf->index, params, buf->B));
+    HIP_TRY(launch_heads_learn(c, params, la, buf->B));
+    HIP_TRY(run_backward(c, buf->obs, buf->index, params, buf->B, grads));
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_loss_and_grads(hts_ctx *ctx, const hts_buffer *buf, const float *params, const hts_hparams *hp,
+                                      float *grads, hts_stats *stats_or_null)
+{
+    const int32_t rc = check_learn(ctx, buf, params, hp);
+    if (rc != HTS_OK) return rc;
+    if (!grads) return HTS_EINVAL;
+    Ctx &c = ctx->c;
+    const int32_t rc2 = loss_and_grads(c, buf, params, hp, grads);
+    if (rc2 != HTS_OK) return rc2;
+    if (stats_or_null) {
+        HIP_TRY(launch_grad_norm(c, grads, c.g.P, 0.0f, nullptr));
+        HIP_TRY(launch_stats(c, buf->B, stats_or_null));
+    }
+    return HTS_OK;
+}
+
+static int32_t adam_apply(Ctx &c, float *params, const float *grads, hts_opt_state *opt, const hts_hparams *hp,
+                          long long P, bool have_norm)
+{
+    const int64_t t = opt->step + 1;
+    const float bc1 = (float)(1.0 - pow((double)hp->beta1, (double)t));
+    const float bc2 = (float)(1.0 - pow((double)hp->beta2, (double)t));
+    const bool clip = hp->max_grad_norm > 0.0f;
+    if (clip && !have_norm) HIP_TRY(launch_grad_norm(c, grads, P, hp->max_grad_norm, nullptr));
+    HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, clip ? c.ws.clip : nullptr, hp->lr, hp->beta1, hp->beta2,
+                        hp->adam_eps, bc1, bc2));
+    opt->step = t;
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_learner_step(hts_ctx *ctx, const hts_buffer *buf, float *params, hts_opt_state *opt,
+                                    const hts_hparams *hp, hts_stats *stats_or_null)
+{
+    const int32_t rc = check_learn(ctx, buf, params, hp);
+    if (rc != HTS_OK) return rc;
+    if (!opt || !opt->m || !opt->v || opt->step < 0) return HTS_EINVAL;
+    Ctx &c = ctx->c;
+    const int32_t rc2 = loss_and_grads(c, buf, params, hp, c.ws.grads);
+    if (rc2 != HTS_OK) return rc2;
+    const bool need_norm = hp->max_grad_norm > 0.0f || stats_or_null;
+    if (need_norm) HIP_TRY(launch_grad_norm(c, c.ws.grads, c.g.P, hp->max_grad_norm, nullptr));
+    if (stats_or_null) HIP_TRY(launch_stats(c, buf->B, stats_or_null));
+    return adam_apply(c, params, c.ws.grads, opt, hp, c.g.P, need_norm);
+}
+
+extern "C" int32_t hts_adam_apply(hts_ctx *ctx, float *params, const float *grads, hts_opt_state *opt,
+                                  const hts_hparams *hp, int64_t P)
+{
+    if (!ctx || !params || !grads || !opt || !opt->m || !opt->v || !hp) return HTS_EINVAL;
+    if (P <= 0 || opt->step < 0) return HTS_EINVAL;
+    if (P > ctx->c.g.P) return HTS_ESHAPE;       // the norm workspace is sized for the network's parameter count
+    return adam_apply(ctx->c, params, grads, opt, hp, P, false);
+}
+
+extern "C" int32_t hts_test_gemm(hts_ctx *ctx, int32_t precision, const float *A, const float *B, float *Cout, int32_t M,
+                                 int32_t N, int32_t K)
+{
+    if (!ctx || !A || !B || !Cout) return HTS_EINVAL;
+    if (M <= 0 || N <= 0 || K <= 0 || (K % 8) != 0) return HTS_EINVAL;
+    if (precision != HTS_PRECISION_FP32 && precision != HTS_PRECISION_BF16) return HTS_EINVAL;
+    if (((uintptr_t)A | (uintptr_t)B) & 15u) return HTS_EINVAL;
+    HIP_TRY(run_plain_gemm(ctx->c, precision, A, B, Cout, M, N, K));
+    return HTS_OK;
+}

@@ -1,0 +1,87 @@
+// Backward pass: every weight gradient and input gradient of the network as tiled contractions.  Weight gradients
+// of the conv layers reduce over B*Ho*Wo positions; they are split into fixed chunks along that axis (split_for),
+// each chunk writes its own partial, and wgrad_reduce adds the partials in chunk order -- no atomics, so the
+// gradient is bit-identical from run to run.
+#include "internal.hpp"
+
+namespace hts {
+
+template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params,
+                                                   int B, float *grads)
+{
+    const Geom &g = c.g;
+    hipError_t e;
+    {   // heads: pi.w, pi.b, v.w, v.b
+        HeadsWgrad p;
+        p.M = g.A + 1; p.N = 513; p.K = B; p.klen = B;
+        p.dz = c.ws.dz; p.h = c.ws.h; p.g = grads; p.A = g.A;
+        p.piw = g.piw; p.pib = g.pib; p.vw = g.vw; p.vb = g.vb;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {   // fc.w, fc.b
+        FcWgrad<T> p;
+        p.M = 512; p.N = g.F + 1; p.K = B; p.klen = B;
+        p.dh = c.ws.dh; p.a3 = (const T *)c.ws.a3; p.g = grads; p.F = g.F; p.fcw = g.fcw; p.fcb = g.fcb;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {   // d(conv3 pre-activation)
+        FcDgrad<T> p;
+        p.M = B; p.N = g.F; p.K = 512; p.klen = 512;
+        p.dh = c.ws.dh; p.w = params + g.fcw; p.a3 = (const T *)c.ws.a3; p.dy3 = (T *)c.ws.dy3; p.P3 = g.P3;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    // partial buffers of the three conv weight gradients live side by side in ws.part
+    const SplitK s3 = split_for((long long)B * g.P3, 64), s2 = split_for((long long)B * g.P2, 64),
+                 s1 = split_for((long long)B * g.P1, 128);
+    float *part3 = c.ws.part;
+    float *part2 = part3 + (size_t)s3.nz * 64 * 577;
+    float *part1 = part2 + (size_t)s2.nz * 64 * 513;
+    {   // conv3.w, conv3.b
+        ConvWgrad<T> p;
+        p.M = 64; p.N = 577; p.K = B * g.P3; p.klen = s3.klen;
+        p.dy = (const T *)c.ws.dy3; p.in = (const T *)c.ws.act2; p.part = part3;
+        p.Kc = 576; p.Cin = 64; p.Hin = g.H2; p.Win = g.W2; p.ksz = 3; p.stride = 1; p.Wo = g.W3; p.Po = g.P3;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {   // d(conv2 pre-activation)
+        ConvDgrad<T, 64> p;
+        p.M = B * g.P2; p.N = 64; p.K = 576; p.klen = 576;
+        p.dy = (const T *)c.ws.dy3; p.wd = (const T *)c.ws.wd3; p.act_in = (const T *)c.ws.act2; p.dy_in = (T *)c.ws.dy2;
+        p.Hin = g.H2; p.Win = g.W2; p.Pin = g.P2; p.Ho = g.H3; p.Wo = g.W3; p.Cout = 64; p.ksz = 3; p.stride = 1;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {   // conv2.w, conv2.b
+        ConvWgrad<T> p;
+        p.M = 64; p.N = 513; p.K = B * g.P2; p.klen = s2.klen;
+        p.dy = (const T *)c.ws.dy2; p.in = (const T *)c.ws.act1; p.part = part2;
+        p.Kc = 512; p.Cin = 32; p.Hin = g.H1; p.Win = g.W1; p.ksz = 4; p.stride = 2; p.Wo = g.W2; p.Po = g.P2;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {   // d(conv1 pre-activation)
+        ConvDgrad<T, 32> p;
+        p.M = B * g.P1; p.N = 32; p.K = 1024; p.klen = 1024;
+        p.dy = (const T *)c.ws.dy2; p.wd = (const T *)c.ws.wd2; p.act_in = (const T *)c.ws.act1; p.dy_in = (T *)c.ws.dy1;
+        p.Hin = g.H1; p.Win = g.W1; p.Pin = g.P1; p.Ho = g.H2; p.Wo = g.W2; p.Cout = 64; p.ksz = 4; p.stride = 2;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {   // conv1.w, conv1.b
+        Conv1Wgrad<T> p;
+        p.M = 32; p.N = g.K1 + 1; p.K = B * g.P1; p.klen = s1.klen;
+        p.dy = (const T *)c.ws.dy1; p.obs = obs; p.index = index; p.part = part1;
+        p.Kc = g.K1; p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    if ((e = launch_wgrad_reduce(c, part3, s3.nz, 64, 577, 64, 3, true, 1.0f, grads, g.w3, g.b3)) != hipSuccess) return e;
+    if ((e = launch_wgrad_reduce(c, part2, s2.nz, 64, 513, 32, 4, true, 1.0f, grads, g.w2, g.b2)) != hipSuccess) return e;
+    if ((e = launch_wgrad_reduce(c, part1, s1.nz, 32, g.K1 + 1, g.C, 8, false, 1.0f / 255.0f, grads, g.w1, g.b1)) !=
+        hipSuccess) return e;
+    return hipSuccess;
+}
+
+hipError_t run_backward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B, float *grads)
+{
+    return c.desc.precision == HTS_PRECISION_BF16 ? backward_t<bf16_t>(c, obs, index, params, B, grads)
+                                                  : backward_t<float>(c, obs, index, params, B, grads);
+}
+
+}  // namespace hts

@@ -1,0 +1,59 @@
+// Forward pass of the policy/value network (appendix "Implementation Details") as four tiled contractions:
+// conv1 (uint8 gather, 1/255 folded in), conv2, conv3, FC.  The heads run in misc.hip.
+#include "internal.hpp"
+
+namespace hts {
+
+template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B)
+{
+    const Geom &g = c.g;
+    hipError_t e;
+    {
+        Conv1Fwd<T> p;
+        p.M = B * g.P1; p.N = 32; p.K = g.K1; p.klen = g.K1;
+        p.obs = obs; p.index = index; p.w = params + g.w1; p.bias = params + g.b1; p.out = (T *)c.ws.act1;
+        p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {
+        ConvFwd<T, false> p;
+        p.M = B * g.P2; p.N = 64; p.K = 512; p.klen = 512;
+        p.in = (const T *)c.ws.act1; p.wf = (const T *)c.ws.wf2; p.bias = params + g.b2; p.out = (T *)c.ws.act2;
+        p.Cin = 32; p.Hin = g.H1; p.Win = g.W1; p.ksz = 4; p.stride = 2; p.Wo = g.W2; p.Po = g.P2; p.Cout = 64;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {
+        ConvFwd<T, true> p;
+        p.M = B * g.P3; p.N = 64; p.K = 576; p.klen = 576;
+        p.in = (const T *)c.ws.act2; p.wf = (const T *)c.ws.wf3; p.bias = params + g.b3; p.out = (T *)c.ws.a3;
+        p.Cin = 64; p.Hin = g.H2; p.Win = g.W2; p.ksz = 3; p.stride = 1; p.Wo = g.W3; p.Po = g.P3; p.Cout = 64;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    {
+        FcFwd<T> p;
+        p.M = B; p.N = 512; p.K = g.F; p.klen = g.F;
+        p.a3 = (const T *)c.ws.a3; p.w = params + g.fcw; p.bias = params + g.fcb; p.h = c.ws.h;
+        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t run_forward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B)
+{
+    return c.desc.precision == HTS_PRECISION_BF16 ? forward_t<bf16_t>(c, obs, index, params, B)
+                                                  : forward_t<float>(c, obs, index, params, B);
+}
+
+template <typename T> static hipError_t plain_t(Ctx &c, const float *A, const float *Bm, float *C, int M, int N, int K)
+{
+    PlainGemm<T> p;
+    p.M = M; p.N = N; p.K = K; p.klen = K; p.A = A; p.B = Bm; p.C = C;
+    return launch_gemm(p, c.stream);
+}
+
+hipError_t run_plain_gemm(Ctx &c, int precision, const float *A, const float *B, float *C, int M, int N, int K)
+{
+    return precision == HTS_PRECISION_BF16 ? plain_t<bf16_t>(c, A, B, C, M, N, K) : plain_t<float>(c, A, B, C, M, N, K);
+}
+
+}  // namespace hts

@@ -1,0 +1,77 @@
+// Library-internal declarations shared by the translation units of libhts (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/hts.h"
+#include "problems.hpp"
+
+namespace hts {
+
+constexpr int NORM_CHUNK = 8192;   // elements per workgroup in the gradient-norm pass (fixes the reduction shape)
+constexpr int N_TERMS = 5;         // per-sample loss terms: policy, value, entropy, clipped flag, kl
+
+struct Workspace {
+    void *slab = nullptr;
+    size_t bytes = 0;
+    // permuted conv weights (T)
+    void *wf2, *wf3, *wd2, *wd3;
+    // forward activations
+    void *act1, *act2, *a3;   // T
+    float *h, *logits, *val;
+    // backward
+    float *dz, *dh, *terms, *grads, *part, *norm_part, *clip;   // clip[0] = scale, clip[1] = ||g||
+    void *dy3, *dy2, *dy1;    // T
+    size_t part_elems;
+};
+
+struct Ctx {
+    hts_net_desc desc;
+    Geom g;
+    hipStream_t stream;
+    int max_act, max_learn, max_b;
+    Workspace ws;
+};
+
+struct SplitK { int klen, nz; };
+// Split of a weight-gradient reduction of length kp; depends on kp only, so results are reproducible.
+inline SplitK split_for(long long kp, int maxz)
+{
+    long long klen = (kp + maxz - 1) / maxz;
+    klen = ((klen + 31) / 32) * 32;
+    if (klen < 256) klen = 256;
+    SplitK s;
+    s.klen = (int)klen;
+    s.nz = (int)((kp + klen - 1) / klen);
+    if (s.nz < 1) s.nz = 1;
+    return s;
+}
+
+struct LossArgs {
+    const int32_t *actions, *index;
+    const float *old_logp, *adv, *ret;
+    int algo;
+    float clip_eps, vf_coef, ent_coef;
+};
+
+// fwd.hip
+hipError_t run_forward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B);
+hipError_t run_plain_gemm(Ctx &c, int precision, const float *A, const float *B, float *C, int M, int N, int K);
+// bwd.hip
+hipError_t run_backward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B, float *grads);
+// misc.hip
+hipError_t launch_prep(Ctx &c, const float *params);
+hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in, uint64_t seed, uint32_t step, int N,
+                            int env_offset, int32_t *actions, float *logp, float *values, float *logits_out);
+hipError_t launch_heads_learn(Ctx &c, const float *params, const LossArgs &la, int B);
+hipError_t launch_stats(Ctx &c, int B, hts_stats *stats);
+hipError_t launch_wgrad_reduce(Ctx &c, const float *part, int nz, int rows, int ncol, int cin, int ksz, bool taps_outer,
+                               float scale, float *g, long long w_off, long long b_off);
+hipError_t launch_gae(hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
+                      int N, float *adv, float *ret);
+hipError_t launch_normalize(hipStream_t s, float *adv, long long n);
+hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, hts_stats *stats);
+hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale_or_null,
+                       float lr, float b1, float b2, float eps, float bc1, float bc2);
+
+}  // namespace hts

@@ -1,0 +1,529 @@
+// Streaming and per-sample kernels: conv-weight permutation, policy/value heads with seeded sampling (actor) or
+// loss gradient (learner), split-K combine, returns/GAE, advantage normalisation, gradient norm, Adam.
+//
+// This file is compiled with floating-point contraction off: the sampler's decision rule is a fixed sequence of
+// binary32 operations (see hts_act in hts.h) and must not be re-associated or fused.
+#include "internal.hpp"
+
+#pragma clang fp contract(off)
+
+namespace hts {
+
+// ------------------------------------------------------------------------------------------------------------
+// conv weight permutation (run at the start of every call that needs the network: no cached state)
+// ------------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void prep_kernel(const float *__restrict__ params, long long w2, long long w3, T *__restrict__ wf2,
+                            T *__restrict__ wf3, T *__restrict__ wd2, T *__restrict__ wd3)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 64 * 32 * 16) {               // conv2.w[n][c][u][v], 64 x 32 x 4 x 4
+        const int n = i / 512, r = i % 512, c = r / 16, tap = r % 16;
+        const T w = from_f32<T>(params[w2 + i]);
+        wf2[n * 512 + tap * 32 + c] = w;
+        wd2[c * 1024 + tap * 64 + n] = w;
+    }
+    if (i < 64 * 64 * 9) {                // conv3.w[n][c][u][v], 64 x 64 x 3 x 3
+        const int n = i / 576, r = i % 576, c = r / 9, tap = r % 9;
+        const T w = from_f32<T>(params[w3 + i]);
+        wf3[n * 576 + tap * 64 + c] = w;
+        wd3[c * 576 + tap * 64 + n] = w;
+    }
+}
+
+hipError_t launch_prep(Ctx &c, const float *params)
+{
+    const int n = 64 * 64 * 9;
+    if (c.desc.precision == HTS_PRECISION_BF16)
+        hipLaunchKernelGGL(prep_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, c.stream, params, c.g.w2, c.g.w3,
+                           (bf16_t *)c.ws.wf2, (bf16_t *)c.ws.wf3, (bf16_t *)c.ws.wd2, (bf16_t *)c.ws.wd3);
+    else
+        hipLaunchKernelGGL(prep_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, c.stream, params, c.g.w2, c.g.w3,
+                           (float *)c.ws.wf2, (float *)c.ws.wf3, (float *)c.ws.wd2, (float *)c.ws.wd3);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// counter-based uniform and the sampler's binary32 exponential
+// ------------------------------------------------------------------------------------------------------------
+
+// Philox4x32-10 (Salmon et al., SC'11), word 0 only is used by the caller.
+__device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                 uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+        c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+
+__device__ __forceinline__ float seeded_uniform(uint64_t seed, uint32_t env, uint32_t step)
+{
+    const uint32_t w = philox_word0(env, step, 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+    return (float)(w >> 8) * 5.9604644775390625e-08f;     // 24 random bits * 2^-24, exact
+}
+
+// exp(x), x <= 0:  0 below -87; n = rint(x*log2e); r = x - n*ln2 (two-constant reduction, fma);
+// degree-6 Taylor polynomial by Horner with fma; exact scaling by 2^n.
+__device__ __forceinline__ float sampler_exp(float x)
+{
+    if (x < -87.0f) return 0.0f;
+    const float n = rintf(x * 1.44269504088896340736f);
+    float r = __builtin_fmaf(n, -0.693145751953125f, x);
+    r = __builtin_fmaf(n, -1.42860682030941723212e-6f, r);
+    float q = 1.0f / 720.0f;
+    q = __builtin_fmaf(q, r, 1.0f / 120.0f);
+    q = __builtin_fmaf(q, r, 1.0f / 24.0f);
+    q = __builtin_fmaf(q, r, 1.0f / 6.0f);
+    q = __builtin_fmaf(q, r, 0.5f);
+    q = __builtin_fmaf(q, r, 1.0f);
+    q = __builtin_fmaf(q, r, 1.0f);
+    const float scale = __uint_as_float((uint32_t)((int)n + 127) << 23);
+    return q * scale;
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// heads: one wavefront per sample.  Lane j (< A) ends up holding logit j; every lane holds the value.
+// ------------------------------------------------------------------------------------------------------------
+struct HeadsArgs {
+    const float *h;            // [B][512]
+    const float *wpi, *bpi, *wv, *bv;
+    const float *logits_in;    // optional: skip the head product and sample from these
+    int B, A;
+    // actor outputs
+    uint64_t seed; uint32_t step; int env_offset;
+    int32_t *actions; float *logp, *values, *logits_out;
+    // learner inputs / outputs
+    LossArgs la;
+    float *dz, *dh, *terms;
+};
+
+template <bool LEARN>
+__global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (b >= a.B) return;                        // whole wavefront leaves together; no block-level barrier below
+    const int A = a.A;
+
+    float hv[8];
+    float mylogit = 0.0f, value = 0.0f;
+    if (a.logits_in) {
+        if (lane < A) mylogit = a.logits_in[(long long)b * A + lane];
+    } else {
+        load_vec(a.h + (long long)b * 512 + lane * 8, hv);
+        for (int j = 0; j <= A; ++j) {
+            const float *w = (j < A ? a.wpi + (long long)j * 512 : a.wv) + lane * 8;
+            float wv8[8];
+            load_vec(w, wv8);
+            float s = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s = __builtin_fmaf(hv[i], wv8[i], s);
+            s = wave_sum(s);
+            if (j < A) { if (lane == j) mylogit = s + a.bpi[j]; }
+            else value = s + a.bv[0];
+        }
+    }
+
+    float m = -INFINITY;
+    for (int j = 0; j < A; ++j) m = fmaxf(m, __shfl(mylogit, j, 64));
+
+    if constexpr (!LEARN) {
+        // sequential binary32 inverse-CDF, evaluated identically by every lane
+        float total = 0.0f;
+        for (int j = 0; j < A; ++j) total = total + sampler_exp(__shfl(mylogit, j, 64) - m);
+        const float u = seeded_uniform(a.seed, (uint32_t)(a.env_offset + b), a.step);
+        const float thr = u * total;
+        int act = A - 1;
+        float run = 0.0f;
+        for (int j = 0; j < A; ++j) {
+            run = run + sampler_exp(__shfl(mylogit, j, 64) - m);
+            if (run > thr) { act = j; break; }
+        }
+        const float la = __shfl(mylogit, act, 64);
+        if (lane == 0) {
+            a.actions[b] = act;
+            a.logp[b] = (la - m) - logf(total);
+            if (a.values) a.values[b] = value;
+        }
+        if (a.logits_out && lane < A) a.logits_out[(long long)b * A + lane] = mylogit;
+    } else {
+        const long long row = a.la.index ? a.la.index[b] : b;
+        const float e = lane < A ? expf(mylogit - m) : 0.0f;
+        const float lse = m + logf(wave_sum(e));
+        const float lsm = lane < A ? mylogit - lse : 0.0f;
+        const float p = lane < A ? expf(lsm) : 0.0f;
+        const float ent = -wave_sum(p * lsm);
+        const int act = a.la.actions[row];
+        const float logp = __shfl(lsm, act, 64);
+        const float adv = a.la.adv[row], R = a.la.ret[row];
+        const float invB = 1.0f / (float)a.B;
+        float dlogp, pi_term, clipped = 0.0f, kl = 0.0f;
+        if (a.la.algo == HTS_ALGO_A2C) {
+            pi_term = -logp * adv;
+            dlogp = -adv * invB;
+        } else {
+            const float old = a.la.old_logp[row];
+            const float rho = expf(logp - old);
+            const float lo = 1.0f - a.la.clip_eps, hi = 1.0f + a.la.clip_eps;
+            const float rc = fminf(fmaxf(rho, lo), hi);
+            pi_term = -fminf(rho * adv, rc * adv);
+            const bool cut = (adv > 0.0f && rho > hi) || (adv < 0.0f && rho < lo);
+            dlogp = cut ? 0.0f : -adv * rho * invB;
+            clipped = (rho > hi || rho < lo) ? 1.0f : 0.0f;
+            kl = old - logp;
+        }
+        const float dl = lane < A ? dlogp * ((lane == act ? 1.0f : 0.0f) - p) + a.la.ent_coef * invB * p * (lsm + ent)
+                                  : 0.0f;
+        const float dv = 2.0f * a.la.vf_coef * (value - R) * invB;
+        if (lane < A) a.dz[(long long)b * (A + 1) + lane] = dl;
+        if (lane == 0) {
+            a.dz[(long long)b * (A + 1) + A] = dv;
+            float *t = a.terms + (long long)b * N_TERMS;
+            t[0] = pi_term; t[1] = (R - value) * (R - value); t[2] = ent; t[3] = clipped; t[4] = kl;
+        }
+        // dL/d(FC pre-activation) for this lane's 8 hidden units
+        float acc[8];
+        {
+            float wv8[8];
+            load_vec(a.wv + lane * 8, wv8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = dv * wv8[i];
+        }
+        for (int j = 0; j < A; ++j) {
+            const float dj = __shfl(dl, j, 64);
+            float w8[8];
+            load_vec(a.wpi + (long long)j * 512 + lane * 8, w8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(dj, w8[i], acc[i]);
+        }
+        f32x4 o0, o1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o0[i] = hv[i] > 0.0f ? acc[i] : 0.0f;
+            o1[i] = hv[4 + i] > 0.0f ? acc[4 + i] : 0.0f;
+        }
+        f32x4 *dst = reinterpret_cast<f32x4 *>(a.dh + (long long)b * 512 + lane * 8);
+        dst[0] = o0; dst[1] = o1;
+    }
+}
+
+hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in, uint64_t seed, uint32_t step, int N,
+                            int env_offset, int32_t *actions, float *logp, float *values, float *logits_out)
+{
+    HeadsArgs a = {};
+    a.h = c.ws.h;
+    if (params) { a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb; }
+    a.logits_in = logits_in;
+    a.B = N; a.A = c.g.A;
+    a.seed = seed; a.step = step; a.env_offset = env_offset;
+    a.actions = actions; a.logp = logp; a.values = values; a.logits_out = logits_out;
+    hipLaunchKernelGGL(heads_kernel<false>, dim3((N + 3) / 4), dim3(256), 0, c.stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_heads_learn(Ctx &c, const float *params, const LossArgs &la, int B)
+{
+    HeadsArgs a = {};
+    a.h = c.ws.h;
+    a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb;
+    a.B = B; a.A = c.g.A;
+    a.la = la;
+    a.dz = c.ws.dz; a.dh = c.ws.dh; a.terms = c.ws.terms;
+    hipLaunchKernelGGL(heads_kernel<true>, dim3((B + 3) / 4), dim3(256), 0, c.stream, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// loss statistics: one workgroup, fixed strided sums then a fixed LDS tree
+// ------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void stats_kernel(const float *__restrict__ terms, int B, const float *clip,
+                                                    hts_stats *stats)
+{
+    __shared__ float red[N_TERMS][256];
+    const int t = threadIdx.x;
+    float s[N_TERMS];
+#pragma unroll
+    for (int i = 0; i < N_TERMS; ++i) s[i] = 0.0f;
+    for (int b = t; b < B; b += 256)
+#pragma unroll
+        for (int i = 0; i < N_TERMS; ++i) s[i] += terms[(long long)b * N_TERMS + i];
+#pragma unroll
+    for (int i = 0; i < N_TERMS; ++i) red[i][t] = s[i];
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if (t < w)
+#pragma unroll
+            for (int i = 0; i < N_TERMS; ++i) red[i][t] += red[i][t + w];
+        __syncthreads();
+    }
+    if (t == 0) {
+        const float invB = 1.0f / (float)B;
+        stats->policy_loss = red[0][0] * invB;
+        stats->value_loss = red[1][0] * invB;
+        stats->entropy = red[2][0] * invB;
+        stats->clip_frac = red[3][0] * invB;
+        stats->approx_kl = red[4][0] * invB;
+        const float gn = clip ? clip[1] : 0.0f;
+        stats->grad_norm = gn;
+        const float chk = red[0][0] + red[1][0] + red[2][0] + gn;
+        stats->nonfinite = (chk - chk == 0.0f) ? 0 : 1;
+    }
+}
+
+hipError_t launch_stats(Ctx &c, int B, hts_stats *stats)
+{
+    hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(256), 0, c.stream, c.ws.terms, B, c.ws.clip, stats);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// split-K combine: g[dest(n,kcol)] = scale * sum_z part[z][n][kcol], z ascending
+// ------------------------------------------------------------------------------------------------------------
+__global__ void wgrad_reduce_kernel(const float *__restrict__ part, int nz, int rows, int ncol, int cin, int ksz,
+                                    int taps_outer, float scale, float *__restrict__ g, long long w_off,
+                                    long long b_off)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * ncol) return;
+    const int n = i / ncol, kcol = i - n * ncol;
+    float s = 0.0f;
+    for (int z = 0; z < nz; ++z) s += part[(long long)z * rows * ncol + i];
+    s *= scale;
+    const int kc = ncol - 1;
+    if (kcol == kc) { g[b_off + n] = s; return; }
+    long long dst;
+    if (taps_outer) {                 // kcol = (tap, c)  ->  w[n][c][tap]
+        const int tap = kcol / cin, c = kcol - tap * cin;
+        dst = ((long long)n * cin + c) * (ksz * ksz) + tap;
+    } else dst = (long long)n * kc + kcol;
+    g[w_off + dst] = s;
+}
+
+hipError_t launch_wgrad_reduce(Ctx &c, const float *part, int nz, int rows, int ncol, int cin, int ksz, bool taps_outer,
+                               float scale, float *g, long long w_off, long long b_off)
+{
+    const int n = rows * ncol;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, part, nz, rows, ncol, cin,
+                       ksz, taps_outer ? 1 : 0, scale, g, w_off, b_off);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// returns / GAE: one lane per environment column, reverse time; neighbouring lanes read neighbouring columns
+// ------------------------------------------------------------------------------------------------------------
+constexpr int GAE_U = 8;
+// The recurrence runs in double precision inside the lane (inputs and outputs are fp32), so a long unroll does not
+// accumulate binary32 rounding: each output is the correctly rounded result of an almost exact recurrence.
+__global__ __launch_bounds__(64) void gae_kernel(const float *__restrict__ r, const float *__restrict__ v,
+                                                 const uint8_t *__restrict__ d, float gamma, float lambda, int T, int N,
+                                                 float *__restrict__ adv, float *__restrict__ ret)
+{
+    const int n = blockIdx.x * 64 + threadIdx.x;
+    if (n >= N) return;
+    const double g = (double)gamma, gl = (double)gamma * (double)lambda;
+    double a = 0.0;
+    double vnext = (double)v[(long long)T * N + n];
+    int t = T - 1;
+    for (; t >= GAE_U - 1; t -= GAE_U) {
+        float rr[GAE_U], vv[GAE_U];
+        uint8_t dd[GAE_U];
+#pragma unroll
+        for (int i = 0; i < GAE_U; ++i) {
+            const long long o = (long long)(t - i) * N + n;
+            rr[i] = r[o]; vv[i] = v[o]; dd[i] = d[o];
+        }
+#pragma unroll
+        for (int i = 0; i < GAE_U; ++i) {
+            const long long o = (long long)(t - i) * N + n;
+            const double nd = dd[i] ? 0.0 : 1.0;
+            const double delta = (double)rr[i] + g * nd * vnext - (double)vv[i];
+            a = delta + gl * nd * a;
+            adv[o] = (float)a;
+            ret[o] = (float)(a + (double)vv[i]);
+            vnext = (double)vv[i];
+        }
+    }
+    for (; t >= 0; --t) {
+        const long long o = (long long)t * N + n;
+        const double vt = (double)v[o];
+        const double nd = d[o] ? 0.0 : 1.0;
+        const double delta = (double)r[o] + g * nd * vnext - vt;
+        a = delta + gl * nd * a;
+        adv[o] = (float)a;
+        ret[o] = (float)(a + vt);
+        vnext = vt;
+    }
+}
+
+hipError_t launch_gae(hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
+                      int N, float *adv, float *ret)
+{
+    hipLaunchKernelGGL(gae_kernel, dim3((N + 63) / 64), dim3(64), 0, s, r, v, d, gamma, lambda, T, N, adv, ret);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// advantage normalisation: one workgroup, double-precision fixed-shape sums
+// ------------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ double block_sum_1024(double x, double *red)
+{
+    const int t = threadIdx.x;
+    red[t] = x;
+    __syncthreads();
+    for (int w = 512; w >= 1; w >>= 1) {
+        if (t < w) red[t] += red[t + w];
+        __syncthreads();
+    }
+    const double s = red[0];
+    __syncthreads();
+    return s;
+}
+
+__global__ __launch_bounds__(1024) void normalize_kernel(float *__restrict__ adv, long long n)
+{
+    __shared__ double red[1024];
+    const int t = threadIdx.x;
+    double s = 0.0;
+    for (long long i = t; i < n; i += 1024) s += (double)adv[i];
+    const double mean = block_sum_1024(s, red) / (double)n;
+    double q = 0.0;
+    for (long long i = t; i < n; i += 1024) { const double dlt = (double)adv[i] - mean; q += dlt * dlt; }
+    const double var = block_sum_1024(q, red) / (double)(n > 1 ? n - 1 : 1);
+    const double inv = 1.0 / (sqrt(var) + 1e-5);
+    for (long long i = t; i < n; i += 1024) adv[i] = (float)(((double)adv[i] - mean) * inv);
+}
+
+hipError_t launch_normalize(hipStream_t s, float *adv, long long n)
+{
+    hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, s, adv, n);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// gradient norm: per-chunk sums of squares (fixed chunking), then one workgroup combines them in index order
+// ------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sumsq_kernel(const float *__restrict__ g, long long P, float *__restrict__ part)
+{
+    __shared__ float red[256];
+    const int t = threadIdx.x;
+    const long long base = (long long)blockIdx.x * NORM_CHUNK;
+    float s = 0.0f;
+#pragma unroll 4
+    for (int i = t; i < NORM_CHUNK; i += 256) {
+        const long long o = base + i;
+        const float x = o < P ? g[o] : 0.0f;
+        s = __builtin_fmaf(x, x, s);
+    }
+    red[t] = s;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if (t < w) red[t] += red[t + w];
+        __syncthreads();
+    }
+    if (t == 0) part[blockIdx.x] = red[0];
+}
+
+__global__ __launch_bounds__(256) void clip_finalize_kernel(const float *__restrict__ part, int nparts, float max_norm,
+                                                            float *__restrict__ clip)
+{
+    __shared__ float red[256];
+    const int t = threadIdx.x;
+    float s = 0.0f;
+    for (int i = t; i < nparts; i += 256) s += part[i];
+    red[t] = s;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if (t < w) red[t] += red[t + w];
+        __syncthreads();
+    }
+    if (t == 0) {
+        const float nrm = sqrtf(red[0]);
+        float sc = 1.0f;
+        if (max_norm > 0.0f) sc = fminf(1.0f, max_norm / (nrm + 1e-6f));
+        clip[0] = sc;
+        clip[1] = nrm;
+    }
+}
+
+hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, hts_stats *)
+{
+    const int nparts = (int)((P + NORM_CHUNK - 1) / NORM_CHUNK);
+    hipLaunchKernelGGL(sumsq_kernel, dim3(nparts), dim3(256), 0, c.stream, g, P, c.ws.norm_part);
+    hipLaunchKernelGGL(clip_finalize_kernel, dim3(1), dim3(256), 0, c.stream, c.ws.norm_part, nparts, max_norm,
+                       c.ws.clip);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Adam
+// ------------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void adam_one(float &th, float g, float &m, float &v, float gs, float lr, float b1, float b2,
+                                         float eps, float ibc1, float ibc2)
+{
+    g *= gs;
+    m = b1 * m + (1.0f - b1) * g;
+    v = b2 * v + (1.0f - b2) * g * g;
+    th = th - lr * (m * ibc1) / (sqrtf(v * ibc2) + eps);
+}
+
+template <bool VEC4>
+__global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ theta, const float *__restrict__ g,
+                                                   float *__restrict__ m, float *__restrict__ v, long long P,
+                                                   const float *__restrict__ scale, float lr, float b1, float b2,
+                                                   float eps, float ibc1, float ibc2)
+{
+    const float gs = scale ? scale[0] : 1.0f;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if constexpr (VEC4) {
+        const long long o = i * 4;
+        if (o + 3 < P) {
+            f32x4 th = *reinterpret_cast<f32x4 *>(theta + o);
+            const f32x4 gg = *reinterpret_cast<const f32x4 *>(g + o);
+            f32x4 mm = *reinterpret_cast<f32x4 *>(m + o), vv = *reinterpret_cast<f32x4 *>(v + o);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float a = th[k], b = mm[k], c2 = vv[k];
+                adam_one(a, gg[k], b, c2, gs, lr, b1, b2, eps, ibc1, ibc2);
+                th[k] = a; mm[k] = b; vv[k] = c2;
+            }
+            *reinterpret_cast<f32x4 *>(theta + o) = th;
+            *reinterpret_cast<f32x4 *>(m + o) = mm;
+            *reinterpret_cast<f32x4 *>(v + o) = vv;
+        } else {
+            for (long long k = o; k < P; ++k) adam_one(theta[k], g[k], m[k], v[k], gs, lr, b1, b2, eps, ibc1, ibc2);
+        }
+    } else {
+        if (i < P) adam_one(theta[i], g[i], m[i], v[i], gs, lr, b1, b2, eps, ibc1, ibc2);
+    }
+}
+
+hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale,
+                       float lr, float b1, float b2, float eps, float bc1, float bc2)
+{
+    const bool aligned = (((uintptr_t)theta | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15u) == 0;
+    const float ibc1 = 1.0f / bc1, ibc2 = 1.0f / bc2;
+    if (aligned) {
+        const long long nthreads = (P + 3) / 4;
+        hipLaunchKernelGGL(adam_kernel<true>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, c.stream, theta, g,
+                           m, v, P, scale, lr, b1, b2, eps, ibc1, ibc2);
+    } else {
+        hipLaunchKernelGGL(adam_kernel<false>, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, c.stream, theta, g, m, v,
+                           P, scale, lr, b1, b2, eps, ibc1, ibc2);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace hts

@@ -204,3 +204,51 @@ def test_uniform_policy_entropy_and_zero_sum(oracle):
     # at the uniform policy the entropy term has zero gradient: bias grad = -mean(adv * (onehot - 1/A))
     want = -np.array([(adv * ((actions == j) - 1.0 / A)).mean() for j in range(A)])
     np.testing.assert_allclose(gb, want, rtol=1e-12, atol=1e-15)
+
+
+# ---- the reduced-precision operand model (operand_bf16 = 1) -------------------------------------------------------
+def test_round_bf16_against_torch_and_ties(oracle):
+    rng = np.random.default_rng(0)
+    xs = np.concatenate([rng.normal(size=2000) * 10.0 ** rng.integers(-6, 6, size=2000), [0.0, -0.0, 1.0, 255.0]])
+    xs = xs.astype(np.float32)
+    want = torch.from_numpy(xs).to(torch.bfloat16).to(torch.float32).numpy()
+    got = np.array([oracle.round_bf16(float(x)) for x in xs], np.float32)
+    assert np.array_equal(got, want)
+    # ties go to the even 8-bit significand
+    assert oracle.round_bf16(1.0 + 2.0 ** -8) == 1.0
+    assert oracle.round_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert oracle.round_bf16(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7
+    assert oracle.round_bf16(255.0) == 255.0 and oracle.round_bf16(257.0) == 256.0
+
+
+def test_operand_model_matches_torch_with_rounded_operands(oracle):
+    """Forward and gradients in the operand-rounding model vs autograd through the same roundings (straight-through)."""
+    def rb(t):
+        q = t.detach().to(torch.float32).to(torch.bfloat16).to(torch.float64)
+        return t + (q - t).detach()
+    kw = dict(C=3, H=44, W=52, A=5, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512)
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 61, 4, 1, kw)
+    flat = flat.astype(np.float32).astype(np.float64)
+    qnet = oracle.make_net(3, 44, 52, 5, operand_bf16=True)
+    p = _torch_params(flat, kw, 5)
+    x = torch.from_numpy(obs.astype(np.float64)) / 255.0
+    for i, (co, k, s) in enumerate(kw["convs"]):
+        x = rb(F.relu(F.conv2d(x, rb(p[f"conv{i + 1}.w"]), p[f"conv{i + 1}.b"], stride=s)))
+    h = F.relu(F.linear(x.flatten(1), rb(p["fc.w"]), p["fc.b"]))
+    logits, v = F.linear(h, p["pi.w"], p["pi.b"]), F.linear(h, p["v.w"], p["v.b"])[:, 0]
+    ql, qv = oracle.forward(qnet, flat, obs)
+    np.testing.assert_allclose(ql, logits.detach().numpy(), rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(qv, v.detach().numpy(), rtol=1e-9, atol=1e-12)
+    el, _ = oracle.forward(net, flat, obs)
+    assert 1e-5 < np.abs(ql - el).max() < 0.1 * np.abs(el).max()       # the rounding is really applied
+    lsm = F.log_softmax(logits, dim=1)
+    logp = lsm.gather(1, torch.from_numpy(actions.astype(np.int64))[:, None])[:, 0]
+    rho = (logp - torch.from_numpy(old_logp)).exp()
+    ad = torch.from_numpy(adv)
+    loss = (-torch.minimum(rho * ad, rho.clamp(0.9, 1.1) * ad).mean() + 0.5 * ((torch.from_numpy(ret) - v) ** 2).mean()
+            - 0.01 * (-(lsm.exp() * lsm).sum(1)).mean())
+    loss.backward()
+    tg = np.concatenate([p[name].grad.numpy().ravel() for name, _ in syn.param_shapes(3, 44, 52, 5)])
+    g, st = oracle.loss_grads(qnet, flat, obs, actions, old_logp, adv, ret, oracle.make_hparams(algo=1, clip_eps=0.1))
+    np.testing.assert_allclose(st["total_loss"], loss.item(), rtol=1e-11)
+    np.testing.assert_allclose(g, tg, rtol=1e-8, atol=1e-13)
