@@ -1,0 +1,271 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+One step = one training iteration of the Atari-shaped A2C configuration (N=16 environments, unroll T=5, fp32,
+18 actions): T batched hts_act calls with seeded sampling + one bootstrap hts_act, hts_returns_gae (gamma=0.99,
+lambda=1) and one hts_learner_step (A2C loss, Adam) on the 80 collected rows -- all enqueued back to back on one
+stream, no host synchronisation inside the timed region, inputs resident in HBM.
+
+Prints ONE JSON line: env-frames/s (N*T per step over wall time), plus learner samples/s, a roofline entry for the
+dominant kernel (timed live with HIP events inside the library) and the CPU oracle timed on the host beside it.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+CONFIGS = {
+    # name: (C, H, W, A, N, T, precision, algo, gamma, lambda, lr, epochs, minibatches, clip, max_grad_norm, ent)
+    "atari_a2c_n16_t5_fp32": dict(C=4, H=84, W=84, A=18, N=16, T=5, precision=0, algo=0, gamma=0.99, lam=1.0,
+                                  lr=7e-4, epochs=1, minibatches=1, clip=0.1, max_norm=0.0, ent=0.01, obs="atari"),
+    "atari_ppo_n32_t128_bf16": dict(C=4, H=84, W=84, A=18, N=32, T=128, precision=1, algo=1, gamma=0.99, lam=0.95,
+                                    lr=2.5e-4, epochs=4, minibatches=4, clip=0.1, max_norm=0.5, ent=0.01, obs="atari"),
+    "football_ppo_n16_t512_bf16": dict(C=16, H=72, W=96, A=19, N=16, T=512, precision=1, algo=1, gamma=0.993,
+                                       lam=0.95, lr=3.4e-4, epochs=2, minibatches=4, clip=0.08, max_norm=0.0,
+                                       ent=0.003, obs="football"),
+}
+FWD_FLOP = {"atari": 18.71e6, "football": 35.80e6}
+FWDBWD_FLOP = {"atari": 49.56e6, "football": 81.78e6}
+
+
+def make_inputs(cfg, torch, syn):
+    N, T = cfg["N"], cfg["T"]
+    if cfg["obs"] == "atari":
+        obs = syn.obs_atari(syn.MASTER_SEED, T + 1, N)
+        rew = syn.rewards_ternary(syn.MASTER_SEED, T, N) if cfg["algo"] == 0 else syn.rewards_score_clipped(syn.MASTER_SEED, T, N)
+        dones = syn.dones_bernoulli(syn.MASTER_SEED, T, N, 0.05 if cfg["algo"] == 0 else 0.01)
+    else:
+        obs = syn.obs_football(syn.MASTER_SEED, T + 1, N)
+        rew = syn.rewards_ternary(syn.MASTER_SEED, T, N, p_nonzero=0.002)
+        dones = ((rew != 0) | (syn.dones_bernoulli(syn.MASTER_SEED, T, N, 0.001) != 0)).astype("uint8")
+    params = syn.init_params(syn.MASTER_SEED, cfg["C"], cfg["H"], cfg["W"], cfg["A"])
+    return obs, rew, dones, params
+
+
+class Loop:
+    """Device buffers of one storage plus the calls of one iteration."""
+
+    def __init__(self, cfg, hts, torch, syn):
+        self.cfg, self.hts, self.torch = cfg, hts, torch
+        N, T, A = cfg["N"], cfg["T"], cfg["A"]
+        obs, rew, dones, params = make_inputs(cfg, torch, syn)
+        self.host = dict(obs=obs, rew=rew, dones=dones, params=params)
+        dev = "cuda"
+        self.obs = torch.from_numpy(obs).to(dev)                      # [T+1, N, C, H, W]
+        self.rew = torch.from_numpy(rew).to(dev)
+        self.dones = torch.from_numpy(dones).to(dev)
+        self.params = torch.from_numpy(params).to(dev)
+        B = N * T // cfg["minibatches"]
+        self.B = B
+        self.ctx = hts.Context(cfg["C"], cfg["H"], cfg["W"], A, precision=cfg["precision"], max_act_batch=N,
+                               max_learn_batch=B)
+        P = self.ctx.P
+        self.opt = hts.OptState(torch.zeros(P, device=dev), torch.zeros(P, device=dev), 0)
+        self.actions = torch.zeros(T + 1, N, dtype=torch.int32, device=dev)
+        self.logp = torch.zeros(T + 1, N, device=dev)
+        self.values = torch.zeros(T + 1, N, device=dev)
+        self.adv = torch.zeros(T, N, device=dev)
+        self.ret = torch.zeros(T, N, device=dev)
+        self.hp = hts.HParams(algo=cfg["algo"], clip_eps=cfg["clip"], vf_coef=0.5, ent_coef=cfg["ent"],
+                              max_grad_norm=cfg["max_norm"], lr=cfg["lr"])
+        self.perms = [torch.from_numpy(syn.permutation(syn.MASTER_SEED, N * T, e)).to(dev) for e in range(cfg["epochs"])]
+        self.iteration = 0
+
+    def rollout(self):
+        c, cfg = self.ctx, self.cfg
+        base = self.iteration * (cfg["T"] + 1)
+        for t in range(cfg["T"] + 1):
+            c.hts_act(self.obs[t], self.params, 20201209, base + t, 0, self.actions[t], self.logp[t], self.values[t])
+
+    def returns(self):
+        cfg = self.cfg
+        self.ctx.hts_returns_gae(self.rew, self.values, self.dones, cfg["gamma"], cfg["lam"], self.adv, self.ret)
+        if cfg["algo"] == 1:
+            self.ctx.hts_normalize_advantages(self.adv)
+
+    def learn(self):
+        cfg, T, N = self.cfg, self.cfg["T"], self.cfg["N"]
+        obs = self.obs[:T].reshape(T * N, cfg["C"], cfg["H"], cfg["W"])
+        actions, logp = self.actions[:T].reshape(-1), self.logp[:T].reshape(-1)
+        adv, ret = self.adv.reshape(-1), self.ret.reshape(-1)
+        for e in range(cfg["epochs"]):
+            for k in range(cfg["minibatches"]):
+                idx = None if cfg["minibatches"] == 1 and cfg["epochs"] == 1 else self.perms[e][k * self.B:(k + 1) * self.B]
+                self.ctx.hts_learner_step(obs, actions, logp, adv, ret, self.params, self.opt, self.hp, index=idx,
+                                          B=self.B)
+
+    def step(self):
+        self.rollout()
+        self.returns()
+        self.learn()
+        self.iteration += 1
+
+
+PEAK = {"mfma_f32": 157.3e12, "mfma_bf16": 2.5e15, "hbm": 8.0e12}
+
+
+def site_work(cfg, loop):
+    """Algorithmic work of one step per launch site: name -> (kind, amount per step); kind is 'flop' or 'byte'.
+
+    FLOPs are 2*MACs of the unpadded contraction; bytes are the arrays each streaming kernel must read and write once.
+    """
+    C, H, W, A, N, T = (cfg[k] for k in ("C", "H", "W", "A", "N", "T"))
+    H1, W1 = (H - 8) // 4 + 1, (W - 8) // 4 + 1
+    H2, W2 = (H1 - 4) // 2 + 1, (W1 - 4) // 2 + 1
+    P1, P2, P3 = H1 * W1, H2 * W2, (H2 - 2) * (W2 - 2)
+    F, K1 = 64 * P3, C * 64
+    act_rows = N * (T + 1)
+    learn_rows = N * T * cfg["epochs"]
+    steps = cfg["epochs"] * cfg["minibatches"]
+    c1, c2, c3, fc = 2.0 * P1 * 32 * K1, 2.0 * P2 * 64 * 512, 2.0 * P3 * 64 * 576, 2.0 * 512 * F
+    P = loop.ctx.P
+    return {
+        "conv1_fwd": ("flop", (act_rows + learn_rows) * c1), "conv2_fwd": ("flop", (act_rows + learn_rows) * c2),
+        "conv3_fwd": ("flop", (act_rows + learn_rows) * c3), "fc_fwd": ("flop", (act_rows + learn_rows) * fc),
+        "fc_wgrad": ("flop", learn_rows * fc), "fc_dgrad": ("flop", learn_rows * fc),
+        "conv3_wgrad": ("flop", learn_rows * c3), "conv3_dgrad": ("flop", learn_rows * c3),
+        "conv2_wgrad": ("flop", learn_rows * c2), "conv2_dgrad": ("flop", learn_rows * c2),
+        "conv1_wgrad": ("flop", learn_rows * c1),
+        "adam": ("byte", steps * 28.0 * P), "grad_norm": ("byte", steps * 4.0 * P),
+        "gae": ("byte", 17.0 * T * N + 4.0 * N),
+    }
+
+
+def find_dominant(loop, work):
+    """Time every launch site with the library's event timer over a few steps; return per-site ms per step."""
+    names = loop.ctx.profile_sites()
+    per_step = {}
+    for i, nm in enumerate(names):
+        loop.ctx.hts_profile_begin(i)
+        for _ in range(3):
+            loop.step()
+        n, ms = loop.ctx.hts_profile_end()
+        if n:
+            per_step[nm] = (ms / 3.0, n // 3)
+    ranked = sorted(((v[0], k) for k, v in per_step.items() if k in work), reverse=True)
+    return ranked[0][1], per_step
+
+
+def cpu_baseline(cfg, loop, budget_s=20.0):
+    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    h = loop.host
+    N, T = cfg["N"], cfg["T"]
+    net = oracle.make_net(cfg["C"], cfg["H"], cfg["W"], cfg["A"])
+    p = h["params"].astype(np.float64)
+    t0 = time.perf_counter()
+    # act on one step's N frames
+    logits, vals = oracle.forward(net, p, h["obs"][0])
+    oracle.sample(logits.astype(np.float32), 1, 0, 0)
+    t_act = time.perf_counter() - t0
+    rows = min(N * T, 16 if N * T > 80 else N * T)
+    obs = h["obs"][:T].reshape(N * T, cfg["C"], cfg["H"], cfg["W"])[:rows]
+    rng_act = np.zeros(rows, np.int32)
+    t0 = time.perf_counter()
+    oracle.gae(h["rew"], np.zeros((T + 1, N)), h["dones"], cfg["gamma"], cfg["lam"])
+    t_gae = time.perf_counter() - t0
+    hp = oracle.make_hparams(algo=cfg["algo"], clip_eps=cfg["clip"], lr=cfg["lr"], max_grad_norm=cfg["max_norm"])
+    t0 = time.perf_counter()
+    oracle.learner_step(net, p, np.zeros(p.size), np.zeros(p.size), 1, obs, rng_act, np.zeros(rows), np.ones(rows),
+                        np.ones(rows), hp)
+    t_learn = time.perf_counter() - t0
+    learn_rows = N * T * cfg["epochs"]
+    total = t_act * (T + 1) + t_gae + t_learn * (learn_rows / rows)
+    return {"value": N * T / total, "unit": "env-frames/s", "cores": 1, "kind": "oracle",
+            "sample": f"hts_act on one step's {N} frames (x{T + 1}), GAE in full, learner on {rows} rows scaled "
+                      f"linearly to {learn_rows}; measured {t_act + t_gae + t_learn:.1f} s of CPU work",
+            "learner_samples_per_s": rows / t_learn}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="atari_a2c_n16_t5_fp32", choices=sorted(CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); multi-GPU sharding is a design note, not code",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import hts_synth as syn
+    import paper_2012_09849_amd as hts
+
+    cfg = CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    loop = Loop(cfg, hts, torch, syn)
+    for _ in range(args.warmup):
+        loop.step()
+    torch.cuda.synchronize()
+    work = site_work(cfg, loop)
+    dominant, per_step = find_dominant(loop, work)
+    site_id = loop.ctx.profile_sites().index(dominant)
+    torch.cuda.synchronize()
+
+    # timed region: the dominant kernel's launches are bracketed by HIP events on the library's stream
+    loop.ctx.hts_profile_begin(site_id)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loop.step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    n_timed, ms_timed = loop.ctx.hts_profile_end()
+
+    # learner part alone
+    torch.cuda.synchronize()
+    nl = max(1, args.steps // 4)
+    t1 = time.perf_counter()
+    for _ in range(nl):
+        loop.learn()
+    torch.cuda.synchronize()
+    learn_wall = time.perf_counter() - t1
+
+    N, T = cfg["N"], cfg["T"]
+    frames = N * T
+    ms = wall / args.steps * 1e3
+    learn_rows = frames * cfg["epochs"]
+    out = {
+        "metric": "env-frames/sec (act+GAE+learner update), 1xMI355X",
+        "value": frames * args.steps / wall,
+        "unit": "env-frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg["precision"] == 0 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "envs": N, "unroll": T, "actions": cfg["A"],
+                   "obs": [cfg["C"], cfg["H"], cfg["W"]], "learner_rows_per_step": learn_rows},
+        "learner_samples_per_s": learn_rows * nl / learn_wall,
+        "learner_ms_per_step": learn_wall / nl * 1e3,
+    }
+    kind, amount = work[dominant]
+    launches_per_step = per_step[dominant][1]
+    avg_s = ms_timed / max(n_timed, 1) * 1e-3
+    per_launch = amount / launches_per_step
+    if kind == "flop":
+        peak = PEAK["mfma_f32"] if cfg["precision"] == 0 else PEAK["mfma_bf16"]
+        out["roofline"] = {"kernel": dominant, "bound": "mfma", "achieved": per_launch / avg_s / 1e12, "peak": peak / 1e12,
+                           "unit": "TFLOP/s", "frac": per_launch / avg_s / peak, "traffic": None,
+                           "avg_launch_us": avg_s * 1e6, "launches_timed": n_timed,
+                           "launches_per_step": launches_per_step}
+    else:
+        out["roofline"] = {"kernel": dominant, "bound": "hbm", "achieved": per_launch / avg_s / 1e9, "peak": 8000.0,
+                           "unit": "GB/s", "frac": per_launch / avg_s / PEAK["hbm"], "traffic": None,
+                           "avg_launch_us": avg_s * 1e6, "launches_timed": n_timed,
+                           "launches_per_step": launches_per_step}
+    out["kernel_ms_per_step"] = {k: round(v[0], 5) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1][0])}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, loop)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -147,6 +147,17 @@ int32_t hts_adam_apply(hts_ctx *ctx, float *params, const float *grads, hts_opt_
 int32_t hts_test_gemm(hts_ctx *ctx, int32_t precision, const float *A, const float *B, float *Cout, int32_t M,
                       int32_t N, int32_t K);
 
+/* Built-in event timer (measurement aid, for callers that need per-kernel times without an external profiler).
+ * Launch sites are numbered 0..hts_profile_site_count()-1 and named by hts_profile_site_name (host strings owned by
+ * the library).  Between hts_profile_begin(ctx, site) and hts_profile_end every launch of that site is bracketed by
+ * a pair of HIP events recorded on the context's stream (at most 4096 launches; later ones are not timed).
+ * hts_profile_end waits for the recorded events and returns the number of timed launches and the sum of their
+ * durations in milliseconds (host pointers).  Timing does not change any result. */
+int32_t     hts_profile_site_count(void);
+const char *hts_profile_site_name(int32_t site);
+int32_t     hts_profile_begin(hts_ctx *ctx, int32_t site);
+int32_t     hts_profile_end(hts_ctx *ctx, int32_t *launches, double *total_ms);
+
 int32_t     hts_last_hip_error(void);
 const char *hts_strerror(int32_t code);
 

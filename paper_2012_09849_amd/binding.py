@@ -14,7 +14,8 @@ ALGO_A2C, ALGO_PPO = 0, 1
 
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
-           "hts_last_hip_error", "hts_strerror"]
+           "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
+           "hts_profile_end"]
 
 
 class HtsError(RuntimeError):
@@ -85,6 +86,10 @@ def load_library():
                                        C.c_int64]
         lib.hts_test_gemm.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_int32]
+        lib.hts_profile_site_name.restype = C.c_char_p
+        lib.hts_profile_site_name.argtypes = [C.c_int32]
+        lib.hts_profile_begin.argtypes = [C.c_void_p, C.c_int32]
+        lib.hts_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         _lib = lib
     return _lib
 
@@ -204,6 +209,18 @@ class Context:
         N = B.shape[0]
         _check(self.lib.hts_test_gemm(self._h, precision, _ptr(A, torch.float32, "A"), _ptr(B, torch.float32, "B"),
                                       _ptr(out, torch.float32, "out"), M, N, K), "hts_test_gemm")
+
+    def profile_sites(self):
+        return [self.lib.hts_profile_site_name(i).decode() for i in range(self.lib.hts_profile_site_count())]
+
+    def hts_profile_begin(self, site: int):
+        _check(self.lib.hts_profile_begin(self._h, site), "hts_profile_begin")
+
+    def hts_profile_end(self):
+        """-> (timed launches, total milliseconds)."""
+        n, ms = C.c_int32(), C.c_double()
+        _check(self.lib.hts_profile_end(self._h, C.byref(n), C.byref(ms)), "hts_profile_end")
+        return n.value, ms.value
 
     @staticmethod
     def new_stats(device="cuda"):

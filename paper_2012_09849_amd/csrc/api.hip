@@ -135,6 +135,10 @@ extern "C" int32_t hts_destroy(hts_ctx *ctx)
 {
     if (!ctx) return HTS_EINVAL;
     hipError_t e = hipSuccess;
+    if (ctx->c.prof.ev) {
+        for (int i = 0; i < 2 * PROF_CAP; ++i) (void)hipEventDestroy(ctx->c.prof.ev[i]);
+        delete[] ctx->c.prof.ev;
+    }
     if (ctx->c.ws.slab) e = hipFree(ctx->c.ws.slab);
     delete ctx;
     return e == hipSuccess ? HTS_OK : hip_fail(e);
@@ -169,7 +173,7 @@ extern "C" int32_t hts_returns_gae(hts_ctx *ctx, const float *rewards, const flo
     if (!rewards || !values || !dones || !advantages || !returns) return HTS_EINVAL;
     if (T <= 0 || N <= 0) return HTS_EINVAL;
     if ((long long)(T + 1) * N >= (1ll << 40)) return HTS_ESHAPE;
-    HIP_TRY(launch_gae(ctx ? ctx->c.stream : (hipStream_t)0, rewards, values, dones, gamma, lambda, T, N, advantages,
+    HIP_TRY(launch_gae(ctx ? &ctx->c : nullptr, ctx ? ctx->c.stream : (hipStream_t)0, rewards, values, dones, gamma, lambda, T, N, advantages,
                        returns));
     return HTS_OK;
 }
@@ -177,7 +181,7 @@ extern "C" int32_t hts_returns_gae(hts_ctx *ctx, const float *rewards, const flo
 extern "C" int32_t hts_normalize_advantages(hts_ctx *ctx, float *adv, int64_t n)
 {
     if (!adv || n <= 0) return HTS_EINVAL;
-    HIP_TRY(launch_normalize(ctx ? ctx->c.stream : (hipStream_t)0, adv, n));
+    HIP_TRY(launch_normalize(ctx ? &ctx->c : nullptr, ctx ? ctx->c.stream : (hipStream_t)0, adv, n));
     return HTS_OK;
 }
 
@@ -269,5 +273,55 @@ extern "C" int32_t hts_test_gemm(hts_ctx *ctx, int32_t precision, const float *A
     if (precision != HTS_PRECISION_FP32 && precision != HTS_PRECISION_BF16) return HTS_EINVAL;
     if (((uintptr_t)A | (uintptr_t)B) & 15u) return HTS_EINVAL;
     HIP_TRY(run_plain_gemm(ctx->c, precision, A, B, Cout, M, N, K));
+    return HTS_OK;
+}
+
+// ---- built-in event timer -------------------------------------------------------------------------------------
+static const char *const k_site_names[SITE_COUNT] = {
+    "prep", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc_fwd", "heads_act", "heads_learn", "heads_wgrad", "fc_wgrad",
+    "fc_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "wgrad_reduce", "grad_norm",
+    "adam", "gae", "normalize", "stats"};
+
+extern "C" int32_t hts_profile_site_count(void) { return SITE_COUNT; }
+
+extern "C" const char *hts_profile_site_name(int32_t site)
+{
+    return (site >= 0 && site < SITE_COUNT) ? k_site_names[site] : "";
+}
+
+extern "C" int32_t hts_profile_begin(hts_ctx *ctx, int32_t site)
+{
+    if (!ctx || site < 0 || site >= SITE_COUNT) return HTS_EINVAL;
+    Profiler &p = ctx->c.prof;
+    if (!p.ev) {
+        p.ev = new (std::nothrow) hipEvent_t[2 * PROF_CAP];
+        if (!p.ev) return HTS_ENOMEM;
+        for (int i = 0; i < 2 * PROF_CAP; ++i) {
+            const hipError_t e = hipEventCreate(&p.ev[i]);
+            if (e != hipSuccess) {
+                for (int k = 0; k < i; ++k) (void)hipEventDestroy(p.ev[k]);
+                delete[] p.ev; p.ev = nullptr;
+                return hip_fail(e);
+            }
+        }
+    }
+    p.site = site; p.n = 0;
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_profile_end(hts_ctx *ctx, int32_t *launches, double *total_ms)
+{
+    if (!ctx || !launches || !total_ms) return HTS_EINVAL;
+    Profiler &p = ctx->c.prof;
+    if (p.site < 0 || !p.ev) return HTS_EINVAL;
+    double tot = 0.0;
+    for (int i = 0; i < p.n; ++i) {
+        HIP_TRY(hipEventSynchronize(p.ev[2 * i + 1]));
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]));
+        tot += (double)ms;
+    }
+    *launches = p.n; *total_ms = tot;
+    p.site = -1; p.n = 0;
     return HTS_OK;
 }

@@ -16,19 +16,22 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.M = g.A + 1; p.N = 513; p.K = B; p.klen = B;
         p.dz = c.ws.dz; p.h = c.ws.h; p.g = grads; p.A = g.A;
         p.piw = g.piw; p.pib = g.pib; p.vw = g.vw; p.vb = g.vb;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_HEADS_WGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     {   // fc.w, fc.b
         FcWgrad<T> p;
         p.M = 512; p.N = g.F + 1; p.K = B; p.klen = B;
         p.dh = c.ws.dh; p.a3 = (const T *)c.ws.a3; p.g = grads; p.F = g.F; p.fcw = g.fcw; p.fcb = g.fcb;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_FC_WGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     {   // d(conv3 pre-activation)
         FcDgrad<T> p;
         p.M = B; p.N = g.F; p.K = 512; p.klen = 512;
         p.dh = c.ws.dh; p.w = params + g.fcw; p.a3 = (const T *)c.ws.a3; p.dy3 = (T *)c.ws.dy3; p.P3 = g.P3;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_FC_DGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     // partial buffers of the three conv weight gradients live side by side in ws.part
     const SplitK s3 = split_for((long long)B * g.P3, 64), s2 = split_for((long long)B * g.P2, 64),
@@ -41,35 +44,40 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.M = 64; p.N = 577; p.K = B * g.P3; p.klen = s3.klen;
         p.dy = (const T *)c.ws.dy3; p.in = (const T *)c.ws.act2; p.part = part3;
         p.Kc = 576; p.Cin = 64; p.Hin = g.H2; p.Win = g.W2; p.ksz = 3; p.stride = 1; p.Wo = g.W3; p.Po = g.P3;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_CONV3_WGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     {   // d(conv2 pre-activation)
         ConvDgrad<T, 64> p;
         p.M = B * g.P2; p.N = 64; p.K = 576; p.klen = 576;
         p.dy = (const T *)c.ws.dy3; p.wd = (const T *)c.ws.wd3; p.act_in = (const T *)c.ws.act2; p.dy_in = (T *)c.ws.dy2;
         p.Hin = g.H2; p.Win = g.W2; p.Pin = g.P2; p.Ho = g.H3; p.Wo = g.W3; p.Cout = 64; p.ksz = 3; p.stride = 1;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_CONV3_DGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     {   // conv2.w, conv2.b
         ConvWgrad<T> p;
         p.M = 64; p.N = 513; p.K = B * g.P2; p.klen = s2.klen;
         p.dy = (const T *)c.ws.dy2; p.in = (const T *)c.ws.act1; p.part = part2;
         p.Kc = 512; p.Cin = 32; p.Hin = g.H1; p.Win = g.W1; p.ksz = 4; p.stride = 2; p.Wo = g.W2; p.Po = g.P2;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_CONV2_WGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     {   // d(conv1 pre-activation)
         ConvDgrad<T, 32> p;
         p.M = B * g.P1; p.N = 32; p.K = 1024; p.klen = 1024;
         p.dy = (const T *)c.ws.dy2; p.wd = (const T *)c.ws.wd2; p.act_in = (const T *)c.ws.act1; p.dy_in = (T *)c.ws.dy1;
         p.Hin = g.H1; p.Win = g.W1; p.Pin = g.P1; p.Ho = g.H2; p.Wo = g.W2; p.Cout = 64; p.ksz = 4; p.stride = 2;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_CONV2_DGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     {   // conv1.w, conv1.b
         Conv1Wgrad<T> p;
         p.M = 32; p.N = g.K1 + 1; p.K = B * g.P1; p.klen = s1.klen;
         p.dy = (const T *)c.ws.dy1; p.obs = obs; p.index = index; p.part = part1;
         p.Kc = g.K1; p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
-        if ((e = launch_gemm(p, c.stream)) != hipSuccess) return e;
+        { SiteTimer tm(c, SITE_CONV1_WGRAD); e = launch_gemm(p, c.stream); }
+        if (e != hipSuccess) return e;
     }
     if ((e = launch_wgrad_reduce(c, part3, s3.nz, 64, 577, 64, 3, true, 1.0f, grads, g.w3, g.b3)) != hipSuccess) return e;
     if ((e = launch_wgrad_reduce(c, part2, s2.nz, 64, 513, 32, 4, true, 1.0f, grads, g.w2, g.b2)) != hipSuccess) return e;

@@ -25,12 +25,41 @@ struct Workspace {
     size_t part_elems;
 };
 
+// Launch sites that the built-in event timer can bracket (hts_profile_begin / hts_profile_end).
+enum Site {
+    SITE_PREP = 0, SITE_CONV1_FWD, SITE_CONV2_FWD, SITE_CONV3_FWD, SITE_FC_FWD, SITE_HEADS_ACT, SITE_HEADS_LEARN,
+    SITE_HEADS_WGRAD, SITE_FC_WGRAD, SITE_FC_DGRAD, SITE_CONV3_WGRAD, SITE_CONV3_DGRAD, SITE_CONV2_WGRAD,
+    SITE_CONV2_DGRAD, SITE_CONV1_WGRAD, SITE_WGRAD_REDUCE, SITE_GRAD_NORM, SITE_ADAM, SITE_GAE, SITE_NORMALIZE,
+    SITE_STATS, SITE_COUNT
+};
+constexpr int PROF_CAP = 4096;     // event pairs kept per profiling window
+
+struct Profiler {
+    int site = -1, n = 0;
+    hipEvent_t *ev = nullptr;      // 2*PROF_CAP events, created on first use
+};
+
 struct Ctx {
+    Profiler prof;
     hts_net_desc desc;
     Geom g;
     hipStream_t stream;
     int max_act, max_learn, max_b;
     Workspace ws;
+};
+
+// Brackets the launches of one site with a pair of events on the context's stream while that site is selected.
+struct SiteTimer {
+    Ctx &c;
+    bool on;
+    SiteTimer(Ctx &ctx, int site) : c(ctx), on(ctx.prof.site == site && ctx.prof.ev && ctx.prof.n < PROF_CAP)
+    {
+        if (on) (void)hipEventRecord(c.prof.ev[2 * c.prof.n], c.stream);
+    }
+    ~SiteTimer()
+    {
+        if (on) { (void)hipEventRecord(c.prof.ev[2 * c.prof.n + 1], c.stream); ++c.prof.n; }
+    }
 };
 
 struct SplitK { int klen, nz; };
@@ -67,9 +96,9 @@ hipError_t launch_heads_learn(Ctx &c, const float *params, const LossArgs &la, i
 hipError_t launch_stats(Ctx &c, int B, hts_stats *stats);
 hipError_t launch_wgrad_reduce(Ctx &c, const float *part, int nz, int rows, int ncol, int cin, int ksz, bool taps_outer,
                                float scale, float *g, long long w_off, long long b_off);
-hipError_t launch_gae(hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
+hipError_t launch_gae(Ctx *c, hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
                       int N, float *adv, float *ret);
-hipError_t launch_normalize(hipStream_t s, float *adv, long long n);
+hipError_t launch_normalize(Ctx *c, hipStream_t s, float *adv, long long n);
 hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, hts_stats *stats);
 hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale_or_null,
                        float lr, float b1, float b2, float eps, float bc1, float bc2);

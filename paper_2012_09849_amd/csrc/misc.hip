@@ -33,6 +33,7 @@ __global__ void prep_kernel(const float *__restrict__ params, long long w2, long
 
 hipError_t launch_prep(Ctx &c, const float *params)
 {
+    SiteTimer tm(c, SITE_PREP);
     const int n = 64 * 64 * 9;
     if (c.desc.precision == HTS_PRECISION_BF16)
         hipLaunchKernelGGL(prep_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, c.stream, params, c.g.w2, c.g.w3,
@@ -223,6 +224,7 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
 hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in, uint64_t seed, uint32_t step, int N,
                             int env_offset, int32_t *actions, float *logp, float *values, float *logits_out)
 {
+    SiteTimer tm(c, SITE_HEADS_ACT);
     HeadsArgs a = {};
     a.h = c.ws.h;
     if (params) { a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb; }
@@ -236,6 +238,7 @@ hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in,
 
 hipError_t launch_heads_learn(Ctx &c, const float *params, const LossArgs &la, int B)
 {
+    SiteTimer tm(c, SITE_HEADS_LEARN);
     HeadsArgs a = {};
     a.h = c.ws.h;
     a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb;
@@ -285,6 +288,7 @@ __global__ __launch_bounds__(256) void stats_kernel(const float *__restrict__ te
 
 hipError_t launch_stats(Ctx &c, int B, hts_stats *stats)
 {
+    SiteTimer tm(c, SITE_STATS);
     hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(256), 0, c.stream, c.ws.terms, B, c.ws.clip, stats);
     return hipGetLastError();
 }
@@ -315,6 +319,7 @@ __global__ void wgrad_reduce_kernel(const float *__restrict__ part, int nz, int 
 hipError_t launch_wgrad_reduce(Ctx &c, const float *part, int nz, int rows, int ncol, int cin, int ksz, bool taps_outer,
                                float scale, float *g, long long w_off, long long b_off)
 {
+    SiteTimer tm(c, SITE_WGRAD_REDUCE);
     const int n = rows * ncol;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, part, nz, rows, ncol, cin,
                        ksz, taps_outer ? 1 : 0, scale, g, w_off, b_off);
@@ -368,9 +373,11 @@ __global__ __launch_bounds__(64) void gae_kernel(const float *__restrict__ r, co
     }
 }
 
-hipError_t launch_gae(hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
-                      int N, float *adv, float *ret)
+hipError_t launch_gae(Ctx *c, hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda,
+                      int T, int N, float *adv, float *ret)
 {
+    Ctx dummy;
+    SiteTimer tm(c ? *c : dummy, SITE_GAE);
     hipLaunchKernelGGL(gae_kernel, dim3((N + 63) / 64), dim3(64), 0, s, r, v, d, gamma, lambda, T, N, adv, ret);
     return hipGetLastError();
 }
@@ -406,8 +413,10 @@ __global__ __launch_bounds__(1024) void normalize_kernel(float *__restrict__ adv
     for (long long i = t; i < n; i += 1024) adv[i] = (float)(((double)adv[i] - mean) * inv);
 }
 
-hipError_t launch_normalize(hipStream_t s, float *adv, long long n)
+hipError_t launch_normalize(Ctx *c, hipStream_t s, float *adv, long long n)
 {
+    Ctx dummy;
+    SiteTimer tm(c ? *c : dummy, SITE_NORMALIZE);
     hipLaunchKernelGGL(normalize_kernel, dim3(1), dim3(1024), 0, s, adv, n);
     return hipGetLastError();
 }
@@ -460,6 +469,7 @@ __global__ __launch_bounds__(256) void clip_finalize_kernel(const float *__restr
 
 hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, hts_stats *)
 {
+    SiteTimer tm(c, SITE_GRAD_NORM);
     const int nparts = (int)((P + NORM_CHUNK - 1) / NORM_CHUNK);
     hipLaunchKernelGGL(sumsq_kernel, dim3(nparts), dim3(256), 0, c.stream, g, P, c.ws.norm_part);
     hipLaunchKernelGGL(clip_finalize_kernel, dim3(1), dim3(256), 0, c.stream, c.ws.norm_part, nparts, max_norm,
@@ -513,6 +523,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ theta, co
 hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale,
                        float lr, float b1, float b2, float eps, float bc1, float bc2)
 {
+    SiteTimer tm(c, SITE_ADAM);
     const bool aligned = (((uintptr_t)theta | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15u) == 0;
     const float ibc1 = 1.0f / bc1, ibc2 = 1.0f / bc2;
     if (aligned) {
