@@ -1,5 +1,6 @@
 // C ABI of libhts: argument checks, context/workspace, and the launch sequence of each call (see include/hts.h).
 #include <math.h>
+#include <stdlib.h>
 #include <new>
 
 #include "internal.hpp"
@@ -86,6 +87,10 @@ void carve(Ctx &c, Carver &cv)
     cv.take(w.wd2, 32 * 1024 * ts); cv.take(w.wd3, 64 * 576 * ts);
     cv.take(w.act1, mb * g.P1 * 32 * ts); cv.take(w.act2, mb * g.P2 * 64 * ts); cv.take(w.a3, mb * g.F * ts);
     cv.take(w.h, mb * 512 * 4); cv.take(w.logits, mb * g.A * 4); cv.take(w.val, mb * 4);
+    {
+        const size_t sb = (size_t)(c.small_b < c.max_b ? c.small_b : c.max_b);
+        cv.take(w.fc_part, (size_t)((g.F + 127) / 128) * sb * 512 * 4);
+    }
     cv.take(w.clip, 2 * 4);
     cv.take(w.norm_part, (size_t)((g.P + NORM_CHUNK - 1) / NORM_CHUNK) * 4);
     if (ml > 0) {
@@ -116,6 +121,8 @@ extern "C" int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, i
     c.desc = *desc; c.g = g; c.stream = (hipStream_t)hip_stream;
     c.max_act = max_act_batch; c.max_learn = max_learn_batch;
     c.max_b = max_act_batch > max_learn_batch ? max_act_batch : max_learn_batch;
+    c.small_b = 128; c.fc_nseg = 0;
+    if (const char *sb = getenv("HTS_SMALL_BATCH")) c.small_b = atoi(sb);   // tuning knob: 0 disables the small path
     c.ws = Workspace();
     Carver size_pass;
     carve(c, size_pass);

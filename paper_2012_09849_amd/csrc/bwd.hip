@@ -11,6 +11,17 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
 {
     const Geom &g = c.g;
     hipError_t e;
+    // Small minibatches take the wave-per-segment kernels: many more, much shorter dependency chains.
+    const bool small = B <= c.small_b;
+    // groups of 64-row segments for the split weight gradients on that path: at most 32 partial buffers per layer
+    auto groups_for = [](long long kp, int *spg) {
+        const int nseg = (int)((kp + 63) / 64);
+        int s = (nseg + 31) / 32;
+        s = ((s + 3) / 4) * 4;
+        if (s < 8) s = 8;
+        *spg = s;
+        return (nseg + s - 1) / s;
+    };
     {   // heads: pi.w, pi.b, v.w, v.b
         HeadsWgrad p;
         p.M = g.A + 1; p.N = 513; p.K = B; p.klen = B;
@@ -30,29 +41,43 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         FcDgrad<T> p;
         p.M = B; p.N = g.F; p.K = 512; p.klen = 512;
         p.dh = c.ws.dh; p.w = params + g.fcw; p.a3 = (const T *)c.ws.a3; p.dy3 = (T *)c.ws.dy3; p.P3 = g.P3;
-        { SiteTimer tm(c, SITE_FC_DGRAD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_FC_DGRAD);
+            e = small ? launch_wsgemm<FcDgrad<T>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     // partial buffers of the three conv weight gradients live side by side in ws.part
     const SplitK s3 = split_for((long long)B * g.P3, 64), s2 = split_for((long long)B * g.P2, 64),
                  s1 = split_for((long long)B * g.P1, 128);
+    int spg3 = 0, spg2 = 0, spg1 = 0;
+    const int nz3 = small ? groups_for((long long)B * g.P3, &spg3) : s3.nz;
+    const int nz2 = small ? groups_for((long long)B * g.P2, &spg2) : s2.nz;
+    const int nz1 = small ? groups_for((long long)B * g.P1, &spg1) : s1.nz;
     float *part3 = c.ws.part;
-    float *part2 = part3 + (size_t)s3.nz * 64 * 577;
-    float *part1 = part2 + (size_t)s2.nz * 64 * 513;
+    float *part2 = part3 + (size_t)nz3 * 64 * 577;
+    float *part1 = part2 + (size_t)nz2 * 64 * 513;
     {   // conv3.w, conv3.b
         ConvWgrad<T> p;
         p.M = 64; p.N = 577; p.K = B * g.P3; p.klen = s3.klen;
         p.dy = (const T *)c.ws.dy3; p.in = (const T *)c.ws.act2; p.part = part3;
         p.Kc = 576; p.Cin = 64; p.Hin = g.H2; p.Win = g.W2; p.ksz = 3; p.stride = 1; p.Wo = g.W3; p.Po = g.P3;
-        { SiteTimer tm(c, SITE_CONV3_WGRAD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_CONV3_WGRAD);
+            e = small ? launch_wsgemm<ConvWgrad<T>, 4, 64, false>(p, c.stream, spg3) : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {   // d(conv2 pre-activation)
         ConvDgrad<T, 64> p;
-        p.M = B * g.P2; p.N = 64; p.K = 576; p.klen = 576;
+        p.N = 64; p.K = 576; p.klen = 576;
         p.dy = (const T *)c.ws.dy3; p.wd = (const T *)c.ws.wd3; p.act_in = (const T *)c.ws.act2; p.dy_in = (T *)c.ws.dy2;
-        p.Hin = g.H2; p.Win = g.W2; p.Pin = g.P2; p.Ho = g.H3; p.Wo = g.W3; p.Cout = 64; p.ksz = 3; p.stride = 1;
-        { SiteTimer tm(c, SITE_CONV3_DGRAD); e = launch_gemm(p, c.stream); }
+        p.Bn = B; p.Hin = g.H2; p.Win = g.W2; p.Ho = g.H3; p.Wo = g.W3; p.Cout = 64; p.ksz = 3; p.stride = 1;
+        p.set_batch(0);
+        {
+            SiteTimer tm(c, SITE_CONV3_DGRAD);
+            e = small ? launch_wsgemm<ConvDgrad<T, 64>, 4, 96, false>(p, c.stream) : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {   // conv2.w, conv2.b
@@ -60,15 +85,22 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.M = 64; p.N = 513; p.K = B * g.P2; p.klen = s2.klen;
         p.dy = (const T *)c.ws.dy2; p.in = (const T *)c.ws.act1; p.part = part2;
         p.Kc = 512; p.Cin = 32; p.Hin = g.H1; p.Win = g.W1; p.ksz = 4; p.stride = 2; p.Wo = g.W2; p.Po = g.P2;
-        { SiteTimer tm(c, SITE_CONV2_WGRAD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_CONV2_WGRAD);
+            e = small ? launch_wsgemm<ConvWgrad<T>, 4, 64, false>(p, c.stream, spg2) : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {   // d(conv1 pre-activation)
         ConvDgrad<T, 32> p;
-        p.M = B * g.P1; p.N = 32; p.K = 1024; p.klen = 1024;
+        p.N = 32; p.K = 256; p.klen = 256;      // four parity classes, 2x2 taps each
         p.dy = (const T *)c.ws.dy2; p.wd = (const T *)c.ws.wd2; p.act_in = (const T *)c.ws.act1; p.dy_in = (T *)c.ws.dy1;
-        p.Hin = g.H1; p.Win = g.W1; p.Pin = g.P1; p.Ho = g.H2; p.Wo = g.W2; p.Cout = 64; p.ksz = 4; p.stride = 2;
-        { SiteTimer tm(c, SITE_CONV2_DGRAD); e = launch_gemm(p, c.stream); }
+        p.Bn = B; p.Hin = g.H1; p.Win = g.W1; p.Ho = g.H2; p.Wo = g.W2; p.Cout = 64; p.ksz = 4; p.stride = 2;
+        p.set_batch(0);
+        {
+            SiteTimer tm(c, SITE_CONV2_DGRAD);
+            e = small ? launch_wsgemm<ConvDgrad<T, 32>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {   // conv1.w, conv1.b
@@ -76,12 +108,15 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.M = 32; p.N = g.K1 + 1; p.K = B * g.P1; p.klen = s1.klen;
         p.dy = (const T *)c.ws.dy1; p.obs = obs; p.index = index; p.part = part1;
         p.Kc = g.K1; p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
-        { SiteTimer tm(c, SITE_CONV1_WGRAD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_CONV1_WGRAD);
+            e = small ? launch_wsgemm<Conv1Wgrad<T>, 4, 64, false>(p, c.stream, spg1) : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
-    if ((e = launch_wgrad_reduce(c, part3, s3.nz, 64, 577, 64, 3, true, 1.0f, grads, g.w3, g.b3)) != hipSuccess) return e;
-    if ((e = launch_wgrad_reduce(c, part2, s2.nz, 64, 513, 32, 4, true, 1.0f, grads, g.w2, g.b2)) != hipSuccess) return e;
-    if ((e = launch_wgrad_reduce(c, part1, s1.nz, 32, g.K1 + 1, g.C, 8, false, 1.0f / 255.0f, grads, g.w1, g.b1)) !=
+    if ((e = launch_wgrad_reduce(c, part3, nz3, 64, 577, 64, 3, true, 1.0f, grads, g.w3, g.b3)) != hipSuccess) return e;
+    if ((e = launch_wgrad_reduce(c, part2, nz2, 64, 513, 32, 4, true, 1.0f, grads, g.w2, g.b2)) != hipSuccess) return e;
+    if ((e = launch_wgrad_reduce(c, part1, nz1, 32, g.K1 + 1, g.C, 8, false, 1.0f / 255.0f, grads, g.w1, g.b1)) !=
         hipSuccess) return e;
     return hipSuccess;
 }

@@ -8,12 +8,17 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
 {
     const Geom &g = c.g;
     hipError_t e;
+    const bool small = B <= c.small_b;
+    c.fc_nseg = 0;
     {
         Conv1Fwd<T> p;
         p.M = B * g.P1; p.N = 32; p.K = g.K1; p.klen = g.K1;
         p.obs = obs; p.index = index; p.w = params + g.w1; p.bias = params + g.b1; p.out = (T *)c.ws.act1;
         p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
-        { SiteTimer tm(c, SITE_CONV1_FWD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_CONV1_FWD);
+            e = small ? launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream) : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {
@@ -21,7 +26,11 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.M = B * g.P2; p.N = 64; p.K = 512; p.klen = 512;
         p.in = (const T *)c.ws.act1; p.wf = (const T *)c.ws.wf2; p.bias = params + g.b2; p.out = (T *)c.ws.act2;
         p.Cin = 32; p.Hin = g.H1; p.Win = g.W1; p.ksz = 4; p.stride = 2; p.Wo = g.W2; p.Po = g.P2; p.Cout = 64;
-        { SiteTimer tm(c, SITE_CONV2_FWD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_CONV2_FWD);
+            e = small ? launch_wsgemm<ConvFwd<T, false>, 4, ConvFwd<T, false>::SEG, false>(p, c.stream)
+                      : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {
@@ -29,14 +38,23 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.M = B * g.P3; p.N = 64; p.K = 576; p.klen = 576;
         p.in = (const T *)c.ws.act2; p.wf = (const T *)c.ws.wf3; p.bias = params + g.b3; p.out = (T *)c.ws.a3;
         p.Cin = 64; p.Hin = g.H2; p.Win = g.W2; p.ksz = 3; p.stride = 1; p.Wo = g.W3; p.Po = g.P3; p.Cout = 64;
-        { SiteTimer tm(c, SITE_CONV3_FWD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_CONV3_FWD);
+            e = small ? launch_wsgemm<ConvFwd<T, true>, 4, ConvFwd<T, true>::SEG, false>(p, c.stream)
+                      : launch_gemm(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {
         FcFwd<T> p;
         p.M = B; p.N = 512; p.K = g.F; p.klen = g.F;
         p.a3 = (const T *)c.ws.a3; p.w = params + g.fcw; p.bias = params + g.fcb; p.h = c.ws.h;
-        { SiteTimer tm(c, SITE_FC_FWD); e = launch_gemm(p, c.stream); }
+        p.part = small ? c.ws.fc_part : nullptr;
+        {
+            SiteTimer tm(c, SITE_FC_FWD);
+            e = small ? launch_wsgemm<FcFwd<T>, 4, FcFwd<T>::SEG, true>(p, c.stream) : launch_gemm(p, c.stream);
+        }
+        if (small) c.fc_nseg = (g.F + FcFwd<T>::SEG - 1) / FcFwd<T>::SEG;
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -18,6 +18,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #define HTS_HD __host__ __device__ __forceinline__
 
 namespace hts {
@@ -78,6 +81,26 @@ template <int V> HTS_HD void zero_vec(float (&v)[V])
     for (int i = 0; i < V; ++i) v[i] = 0.0f;
 }
 
+// Optional segmented accumulation: a problem that defines `static constexpr int SEG` (a multiple of BK) gets
+//   D = (((s_0 + s_1) + s_2) + ...),  s_i = MFMA-accumulated sum over k in [i*SEG, (i+1)*SEG)
+// instead of one long accumulation chain.  The wave-per-segment kernel of wsgemm.hpp computes the s_i in parallel
+// and adds them in the same order, so both kernels return identical bits for the same problem.
+template <class P, class = void> struct SegOf { static constexpr int value = 0; };
+template <class P> struct SegOf<P, std::void_t<decltype(P::SEG)>> { static constexpr int value = P::SEG; };
+
+// Optional batching: a problem with `int batches() const`, `int max_m() const` and `void set_batch(int)` is launched
+// with gridDim.z = batches(); each z works on its own sub-problem (own M, own gathers) selected by set_batch.
+template <class P, class = void> struct HasBatch : std::false_type {};
+template <class P> struct HasBatch<P, std::void_t<decltype(std::declval<const P &>().batches())>> : std::true_type {};
+template <class P> inline int grid_rows(const P &p)
+{
+    if constexpr (HasBatch<P>::value) return p.max_m(); else return p.M;
+}
+template <class P> inline int grid_batches(const P &p)
+{
+    if constexpr (HasBatch<P>::value) return p.batches(); else return 1;
+}
+
 // A problem type P provides:
 //   using T                          operand type in LDS / MFMA (float or bf16_t)
 //   static constexpr int BM, BN, BK  workgroup tile; WAVES_M in {1,2,4} wavefronts along M (4/WAVES_M along N)
@@ -90,8 +113,10 @@ template <int V> HTS_HD void zero_vec(float (&v)[V])
 //   void load_b(int col, int k, int kend, float (&v)[VB]) const
 //   void store(int m, int n, float acc, int z) const              called only for m < M, n < N
 template <class P>
-__global__ __launch_bounds__(256) void gemm_kernel(const P p)
+__global__ __launch_bounds__(256) void gemm_kernel(const P p_in)
 {
+    P p = p_in;
+    if constexpr (HasBatch<P>::value) p.set_batch(blockIdx.z);
     using T = typename P::T;
     using Tr = OperandTraits<T>;
     constexpr int BM = P::BM, BN = P::BN, BK = P::BK;
@@ -105,6 +130,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const P p)
     static_assert(CA * VA == BM * BK && CB * VB == BN * BK && BK % VA == 0 && BK % VB == 0 && BM % VA == 0 &&
                       BN % VB == 0, "loader shape");
     static_assert(BK % Tr::KINST == 0, "BK");
+    constexpr int SEG = SegOf<P>::value;
+    static_assert(SEG % BK == 0, "SEG must be a multiple of BK");
 
     __shared__ __attribute__((aligned(16))) T As[BM * LS];
     __shared__ __attribute__((aligned(16))) T Bs[BN * LS];
@@ -113,6 +140,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const P p)
     const int wm = wave % WM, wn = wave / WM;
     const int tiles_n = (p.N + BN - 1) / BN;
     const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
+    if (m0 >= p.M) return;                 // a batch smaller than the largest one: the whole workgroup leaves
     const int z = blockIdx.y;
     const int kbeg = z * p.klen;
     const int kend = min(p.K, kbeg + p.klen);
@@ -173,6 +201,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const P p)
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    f32x16 tot[SEG > 0 ? TM : 1][SEG > 0 ? TN : 1];
+    if constexpr (SEG > 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tot[i][j][r] = 0.0f;
+    }
 
     const int lrow = lane & 31, lk = lane >> 5;
     const T *a_base = As + (wm * TM * 32 + lrow) * LS;
@@ -211,7 +248,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(const P p)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
         }
+        if constexpr (SEG > 0) {
+            if ((k0 + BK) % SEG == 0 || k0 + BK >= kend) {      // end of a segment: fold it into the running total
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { tot[i][j][r] += acc[i][j][r]; acc[i][j][r] = 0.0f; }
+            }
+        }
         __syncthreads();
+    }
+    if constexpr (SEG > 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = tot[i][j];
     }
 
 #pragma unroll
@@ -229,10 +282,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const P p)
 
 template <class P> inline hipError_t launch_gemm(const P &p, hipStream_t stream)
 {
-    const int tiles = ((p.M + P::BM - 1) / P::BM) * ((p.N + P::BN - 1) / P::BN);
+    const int tiles = ((grid_rows(p) + P::BM - 1) / P::BM) * ((p.N + P::BN - 1) / P::BN);
     const int nz = (p.K + p.klen - 1) / p.klen;
     if (tiles <= 0 || nz <= 0) return hipSuccess;
-    hipLaunchKernelGGL(gemm_kernel<P>, dim3(tiles, nz, 1), dim3(256, 1, 1), 0, stream, p);
+    hipLaunchKernelGGL(gemm_kernel<P>, dim3(tiles, nz, grid_batches(p)), dim3(256, 1, 1), 0, stream, p);
     return hipGetLastError();
 }
 

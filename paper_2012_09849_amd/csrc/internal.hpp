@@ -5,6 +5,7 @@
 
 #include "../../include/hts.h"
 #include "problems.hpp"
+#include "wsgemm.hpp"
 
 namespace hts {
 
@@ -19,6 +20,7 @@ struct Workspace {
     // forward activations
     void *act1, *act2, *a3;   // T
     float *h, *logits, *val;
+    float *fc_part;           // [FC_NSEG_MAX][small_b][512] segment sums of the FC layer on the small-batch path
     // backward
     float *dz, *dh, *terms, *grads, *part, *norm_part, *clip;   // clip[0] = scale, clip[1] = ||g||
     void *dy3, *dy2, *dy1;    // T
@@ -45,6 +47,8 @@ struct Ctx {
     Geom g;
     hipStream_t stream;
     int max_act, max_learn, max_b;
+    int small_b;              // batches up to this size take the wave-per-segment forward kernels
+    int fc_nseg;              // FC segments on the small-batch path of the last forward (0: h already holds the output)
     Workspace ws;
 };
 

@@ -95,11 +95,21 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
+// value of x in lane `src`; src must be the same in every lane (it is read into a scalar register)
+__device__ __forceinline__ float lane_value(float x, int src)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), __builtin_amdgcn_readfirstlane(src)));
+}
+
 // ------------------------------------------------------------------------------------------------------------
 // heads: one wavefront per sample.  Lane j (< A) ends up holding logit j; every lane holds the value.
 // ------------------------------------------------------------------------------------------------------------
 struct HeadsArgs {
     const float *h;            // [B][512]
+    const float *fc_part;      // when nseg > 0: h = relu(fc_bias + sum_seg fc_part[seg][B][512]) is formed here ...
+    const float *fc_bias;
+    float *h_out;              // ... and written back for the backward pass when not null
+    int nseg;
     const float *wpi, *bpi, *wv, *bv;
     const float *logits_in;    // optional: skip the head product and sample from these
     int B, A;
@@ -114,6 +124,7 @@ struct HeadsArgs {
 template <bool LEARN>
 __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
 {
+    extern __shared__ float heads_lds[];          // [4 wavefronts][A][65]
     const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (b >= a.B) return;                        // whole wavefront leaves together; no block-level barrier below
@@ -124,36 +135,88 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
     if (a.logits_in) {
         if (lane < A) mylogit = a.logits_in[(long long)b * A + lane];
     } else {
-        load_vec(a.h + (long long)b * 512 + lane * 8, hv);
-        for (int j = 0; j <= A; ++j) {
-            const float *w = (j < A ? a.wpi + (long long)j * 512 : a.wv) + lane * 8;
-            float wv8[8];
-            load_vec(w, wv8);
-            float s = 0.0f;
+        if (a.nseg > 0) {
+            // fold the FC layer's segment sums in segment order (the order the tile kernel uses), then bias + ReLU;
+            // five segments' loads are issued together so that their latencies overlap
 #pragma unroll
-            for (int i = 0; i < 8; ++i) s = __builtin_fmaf(hv[i], wv8[i], s);
-            s = wave_sum(s);
-            if (j < A) { if (lane == j) mylogit = s + a.bpi[j]; }
-            else value = s + a.bv[0];
+            for (int i = 0; i < 8; ++i) hv[i] = 0.0f;
+            const float *src = a.fc_part + (long long)b * 512 + lane * 8;
+            const long long sstride = (long long)a.B * 512;
+            int s = 0;
+            for (; s + 5 <= a.nseg; s += 5) {
+                float pv[5][8];
+#pragma unroll
+                for (int q = 0; q < 5; ++q) load_vec(src + (s + q) * sstride, pv[q]);
+#pragma unroll
+                for (int q = 0; q < 5; ++q)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) hv[i] += pv[q][i];
+            }
+            for (; s < a.nseg; ++s) {
+                float pv[8];
+                load_vec(src + s * sstride, pv);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) hv[i] += pv[i];
+            }
+            float bv8[8];
+            load_vec(a.fc_bias + lane * 8, bv8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { const float y = hv[i] + bv8[i]; hv[i] = y > 0.0f ? y : 0.0f; }
+            if (a.h_out) {
+                f32x4 o0, o1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { o0[i] = hv[i]; o1[i] = hv[4 + i]; }
+                f32x4 *dst = reinterpret_cast<f32x4 *>(a.h_out + (long long)b * 512 + lane * 8);
+                dst[0] = o0; dst[1] = o1;
+            }
+        } else load_vec(a.h + (long long)b * 512 + lane * 8, hv);
+        // A dot products of length 512 for the logits: every lane forms its 8-element partial of each, the partials
+        // go through this wavefront's LDS panel [A][65], and lane j adds row j in lane order (a fixed order; no
+        // barrier is needed because a wavefront's LDS operations execute in order).  The value head is one more dot
+        // product, reduced by a butterfly.
+        float *panel = heads_lds + (threadIdx.x >> 6) * A * 65;
+        for (int j = 0; j < A; ++j) {
+            float wv8[8];
+            load_vec(a.wpi + (long long)j * 512 + lane * 8, wv8);
+            float sj = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sj = __builtin_fmaf(hv[i], wv8[i], sj);
+            panel[j * 65 + lane] = sj;
+        }
+        {
+            float wv8[8];
+            load_vec(a.wv + lane * 8, wv8);
+            float sv = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sv = __builtin_fmaf(hv[i], wv8[i], sv);
+            value = wave_sum(sv) + a.bv[0];
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane < A) {
+            const float *row = panel + lane * 65;
+            float rowsum = 0.0f;
+#pragma unroll 16
+            for (int t = 0; t < 64; ++t) rowsum += row[t];
+            mylogit = rowsum + a.bpi[lane];
         }
     }
 
     float m = -INFINITY;
-    for (int j = 0; j < A; ++j) m = fmaxf(m, __shfl(mylogit, j, 64));
+    for (int j = 0; j < A; ++j) m = fmaxf(m, lane_value(mylogit, j));
 
     if constexpr (!LEARN) {
         // sequential binary32 inverse-CDF, evaluated identically by every lane
         float total = 0.0f;
-        for (int j = 0; j < A; ++j) total = total + sampler_exp(__shfl(mylogit, j, 64) - m);
+        for (int j = 0; j < A; ++j) total = total + sampler_exp(lane_value(mylogit, j) - m);
         const float u = seeded_uniform(a.seed, (uint32_t)(a.env_offset + b), a.step);
         const float thr = u * total;
         int act = A - 1;
         float run = 0.0f;
         for (int j = 0; j < A; ++j) {
-            run = run + sampler_exp(__shfl(mylogit, j, 64) - m);
+            run = run + sampler_exp(lane_value(mylogit, j) - m);
             if (run > thr) { act = j; break; }
         }
-        const float la = __shfl(mylogit, act, 64);
+        const float la = lane_value(mylogit, act);
         if (lane == 0) {
             a.actions[b] = act;
             a.logp[b] = (la - m) - logf(total);
@@ -168,7 +231,7 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         const float p = lane < A ? expf(lsm) : 0.0f;
         const float ent = -wave_sum(p * lsm);
         const int act = a.la.actions[row];
-        const float logp = __shfl(lsm, act, 64);
+        const float logp = lane_value(lsm, act);
         const float adv = a.la.adv[row], R = a.la.ret[row];
         const float invB = 1.0f / (float)a.B;
         float dlogp, pi_term, clipped = 0.0f, kl = 0.0f;
@@ -204,7 +267,7 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
             for (int i = 0; i < 8; ++i) acc[i] = dv * wv8[i];
         }
         for (int j = 0; j < A; ++j) {
-            const float dj = __shfl(dl, j, 64);
+            const float dj = lane_value(dl, j);
             float w8[8];
             load_vec(a.wpi + (long long)j * 512 + lane * 8, w8);
 #pragma unroll
@@ -221,6 +284,12 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
     }
 }
 
+static size_t heads_lds_bytes(int A) { return (size_t)4 * A * 65 * sizeof(float); }
+static hipError_t raise_lds_limit(const void *fn, size_t bytes)
+{
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
 hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in, uint64_t seed, uint32_t step, int N,
                             int env_offset, int32_t *actions, float *logp, float *values, float *logits_out)
 {
@@ -229,10 +298,13 @@ hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in,
     a.h = c.ws.h;
     if (params) { a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb; }
     a.logits_in = logits_in;
+    if (params && c.fc_nseg > 0) { a.fc_part = c.ws.fc_part; a.fc_bias = params + c.g.fcb; a.nseg = c.fc_nseg; }
     a.B = N; a.A = c.g.A;
     a.seed = seed; a.step = step; a.env_offset = env_offset;
     a.actions = actions; a.logp = logp; a.values = values; a.logits_out = logits_out;
-    hipLaunchKernelGGL(heads_kernel<false>, dim3((N + 3) / 4), dim3(256), 0, c.stream, a);
+    const size_t lds = heads_lds_bytes(c.g.A);
+    if (lds > 65536) { const hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(heads_kernel<false>), lds); if (e != hipSuccess) return e; }
+    hipLaunchKernelGGL(heads_kernel<false>, dim3((N + 3) / 4), dim3(256), lds, c.stream, a);
     return hipGetLastError();
 }
 
@@ -242,10 +314,13 @@ hipError_t launch_heads_learn(Ctx &c, const float *params, const LossArgs &la, i
     HeadsArgs a = {};
     a.h = c.ws.h;
     a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb;
+    if (c.fc_nseg > 0) { a.fc_part = c.ws.fc_part; a.fc_bias = params + c.g.fcb; a.nseg = c.fc_nseg; a.h_out = c.ws.h; }
     a.B = B; a.A = c.g.A;
     a.la = la;
     a.dz = c.ws.dz; a.dh = c.ws.dh; a.terms = c.ws.terms;
-    hipLaunchKernelGGL(heads_kernel<true>, dim3((B + 3) / 4), dim3(256), 0, c.stream, a);
+    const size_t lds = heads_lds_bytes(c.g.A);
+    if (lds > 65536) { const hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(heads_kernel<true>), lds); if (e != hipSuccess) return e; }
+    hipLaunchKernelGGL(heads_kernel<true>, dim3((B + 3) / 4), dim3(256), lds, c.stream, a);
     return hipGetLastError();
 }
 

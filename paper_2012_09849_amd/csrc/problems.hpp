@@ -53,6 +53,7 @@ template <typename T_> struct Conv1Fwd {
     static constexpr int BM = 128, BN = 32, BK = 32, WAVES_M = 4;
     static constexpr int VA = 8, VB = 4;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
+    static constexpr int SEG = 64;       // forward sums are segmented so every kernel variant returns the same bits
     int M, N, K, klen;
     const uint8_t *obs;
     const int32_t *index;
@@ -94,6 +95,7 @@ template <typename T_, bool FLAT_OUT> struct ConvFwd {
     static constexpr int BM = 64, BN = 64, BK = 32, WAVES_M = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
+    static constexpr int SEG = FLAT_OUT ? 96 : 64;
     int M, N, K, klen;
     const T *in;      // [B][Hin][Win][Cin]
     const T *wf;      // [Cout][K]
@@ -131,10 +133,12 @@ template <typename T_> struct FcFwd {
     static constexpr int BM = 64, BN = 64, BK = 32, WAVES_M = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = 4;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
+    static constexpr int SEG = 128;
     int M, N, K, klen;
     const T *a3;
     const float *w, *bias;
     float *h;
+    float *part;      // when set: segment sums go to part[seg][M][N]; bias and ReLU are applied by the consumer
     HTS_HD void load_a(int m, int k, int kend, float (&v)[VA]) const
     {
         if (m < M && k < kend) load_vec(a3 + (long long)m * K + k, v); else zero_vec(v);
@@ -143,8 +147,9 @@ template <typename T_> struct FcFwd {
     {
         if (n < N && k < kend) load_vec(w + (long long)n * K + k, v); else zero_vec(v);
     }
-    HTS_HD void store(int m, int n, float acc, int) const
+    HTS_HD void store(int m, int n, float acc, int seg) const
     {
+        if (part) { part[((long long)seg * M + m) * N + n] = acc; return; }
         const float y = acc + bias[n];
         h[(long long)m * N + n] = y > 0.0f ? y : 0.0f;
     }
@@ -240,45 +245,60 @@ template <typename T_> struct FcDgrad {
 };
 
 // ------------------------------------------------------------------------------------------------------------
-// conv input gradient (layers 3 and 2): D[(b,y,x)][c] = sum_{u,v,n} dy[b][(y-u)/s][(x-v)/s][n] W[n][c][u][v]
-// over the taps where (y-u), (x-v) are non-negative multiples of s inside the output; masked by the ReLU of the
-// layer below.  k = (u,v,n); wd = [Cin][(u,v,n)].
+// conv input gradient (layers 3 and 2): dX[b][y][x][c] = sum_{u,v,n} dy[b][(y-u)/s][(x-v)/s][n] W[n][c][u][v] over the
+// taps where (y-u), (x-v) are non-negative multiples of the stride s inside the output; masked by the ReLU of the
+// layer below.  Input positions are split into s*s parity classes (y%s, x%s): within a class only the (ksz/s)^2
+// taps u = y%s + s*a, v = x%s + s*bb can contribute, so each class is its own dense contraction
+//   M = B*Hc*Wc (positions of the class),  N = Cin,  K = (ksz/s)^2 * Cout,  k = (a, bb, n),
+// launched as one batch entry per class (no multiplications by structural zeros).  wd = [Cin][(u,v,n)].
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_, int BN_> struct ConvDgrad {
     using T = T_;
     static constexpr int BM = (BN_ == 32 ? 128 : 64), BN = BN_, BK = 32, WAVES_M = (BN_ == 32 ? 4 : 2);
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    int M, N, K, klen;     // M = B*Hin*Win, N = Cin, K = ksz*ksz*Cout
+    int M, N, K, klen;     // M is per class (set_batch); N = Cin; K = (ksz/s)^2 * Cout
     const T *dy;           // [B][Ho][Wo][Cout]
-    const T *wd;           // [Cin][K]
+    const T *wd;           // [Cin][ksz*ksz*Cout]
     const T *act_in;       // [B][Hin][Win][Cin] post-ReLU output of the layer below
     T *dy_in;              // [B][Hin][Win][Cin]
-    int Hin, Win, Pin, Ho, Wo, Cout, ksz, stride;
+    int Bn, Hin, Win, Ho, Wo, Cout, ksz, stride;
+    int py, px, Hc, Wc;    // current class and its extent
+    HTS_HD int batches() const { return stride * stride; }
+    HTS_HD int max_m() const { return Bn * ((Hin + stride - 1) / stride) * ((Win + stride - 1) / stride); }
+    HTS_HD void set_batch(int z)
+    {
+        py = z / stride; px = z - py * stride;
+        Hc = (Hin - py + stride - 1) / stride; Wc = (Win - px + stride - 1) / stride;
+        M = Bn * Hc * Wc;
+    }
     HTS_HD void load_a(int m, int k, int kend, float (&v)[VA]) const
     {
         if (m < M && k < kend) {
-            const int b = m / Pin, p = m - b * Pin, y = p / Win, x = p - y * Win;
-            const int tap = k / Cout, n = k - tap * Cout, u = tap / ksz, vv = tap - u * ksz;
-            const int ty = y - u, tx = x - vv;
-            if (ty >= 0 && tx >= 0) {
-                const int oy = ty / stride, ox = tx / stride;
-                if (oy * stride == ty && ox * stride == tx && oy < Ho && ox < Wo) {
-                    load_vec(dy + (((long long)b * Ho + oy) * Wo + ox) * Cout + n, v);
-                    return;
-                }
+            const int b = m / (Hc * Wc), p = m - b * (Hc * Wc), yy = p / Wc, xx = p - yy * Wc;
+            const int tap = k / Cout, n = k - tap * Cout, tk = ksz / stride, a = tap / tk, bb = tap - a * tk;
+            const int oy = yy - a, ox = xx - bb;         // (y - u)/s with y = yy*s + py, u = py + s*a
+            if (oy >= 0 && ox >= 0 && oy < Ho && ox < Wo) {
+                load_vec(dy + (((long long)b * Ho + oy) * Wo + ox) * Cout + n, v);
+                return;
             }
         }
         zero_vec(v);
     }
     HTS_HD void load_b(int c, int k, int kend, float (&v)[VB]) const
     {
-        if (c < N && k < kend) load_vec(wd + (long long)c * K + k, v); else zero_vec(v);
+        if (c < N && k < kend) {
+            const int tap = k / Cout, n = k - tap * Cout, tk = ksz / stride, a = tap / tk, bb = tap - a * tk;
+            const int u = py + stride * a, vv = px + stride * bb;
+            load_vec(wd + ((long long)c * ksz * ksz + u * ksz + vv) * Cout + n, v);
+        } else zero_vec(v);
     }
     HTS_HD void store(int m, int c, float acc, int) const
     {
-        const float a = to_f32(act_in[(long long)m * N + c]);
-        dy_in[(long long)m * N + c] = from_f32<T>(a > 0.0f ? acc : 0.0f);
+        const int b = m / (Hc * Wc), p = m - b * (Hc * Wc), yy = p / Wc, xx = p - yy * Wc;
+        const long long o = ((((long long)b * Hin + yy * stride + py) * Win) + xx * stride + px) * N + c;
+        const float a = to_f32(act_in[o]);
+        dy_in[o] = from_f32<T>(a > 0.0f ? acc : 0.0f);
     }
 };
 

@@ -1,0 +1,173 @@
+// Wave-per-segment contraction for small problems (few rows, as in an actor's batch of 16-32 observations).
+//
+// The tile kernel of gemm.hpp walks K in one dependent chain per workgroup; with a handful of workgroups that chain
+// (global-load latency + 64-cycle fp32 MFMAs) is the whole run time.  Here every wavefront owns one 32x32 output
+// tile and ONE K segment of SEG elements: it fetches its two 32xSEG operand panels in a single burst, multiplies
+// them, and the segment sums of a tile are added in segment order,
+//     D = (((s_0 + s_1) + s_2) + ...),
+// exactly the order the tile kernel uses for a problem with the same SEG -- results are bit-identical.
+//
+// Two forms:
+//   PARTIAL = false  workgroup (tile, y) owns the segments [y*spg, (y+1)*spg) of its tile (spg = segments per group,
+//                    a launch argument; spg >= number of segments means one group).  Its WAVES wavefronts take them
+//                    in rounds of WAVES; after each round the partial tiles go through LDS and are folded into the
+//                    running total in wave order; the epilogue p.store(m, n, total, y) runs once.
+//   PARTIAL = true   every wavefront stores its segment sum with p.store(m, n, s_seg, seg); the consumer adds the
+//                    partials in segment order (used when K is too long for one workgroup, i.e. the FC layer).
+#pragma once
+#include "gemm.hpp"
+
+namespace hts {
+
+template <class P, int WAVES, int SEG, bool PARTIAL>
+__global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p_in, const int spg)
+{
+    P p = p_in;
+    if constexpr (HasBatch<P>::value) p.set_batch(blockIdx.z);
+    using T = typename P::T;
+    using Tr = OperandTraits<T>;
+    constexpr int LS = SEG + Tr::PAD;
+    constexpr int VA = P::VA, VB = P::VB;
+    constexpr int CA = 32 * SEG / VA, CB = 32 * SEG / VB;      // vectors per operand panel
+    constexpr int NA = (CA + 63) / 64, NB = (CB + 63) / 64;
+    static_assert(SEG % Tr::KINST == 0 && SEG % VA == 0 && SEG % VB == 0 && 32 % VA == 0 && 32 % VB == 0, "segment shape");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    T *panels = reinterpret_cast<T *>(smem);                                   // [WAVES][2][32*LS]
+    float *red = reinterpret_cast<float *>(smem + (size_t)WAVES * 2 * 32 * LS * sizeof(T));   // [WAVES][1024]
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tiles_n = (p.N + 31) / 32;
+    const int m0 = (blockIdx.x / tiles_n) * 32, n0 = (blockIdx.x % tiles_n) * 32;
+    if (m0 >= p.M) return;
+    const int nseg = (p.K + SEG - 1) / SEG;
+    T *As = panels + (size_t)w * 2 * 32 * LS, *Bs = As + 32 * LS;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    auto segment_sum = [&](int seg) -> f32x16 {
+        const int kbeg = seg * SEG, kend = min(p.K, kbeg + SEG);
+        float ra[NA][VA], rb[NB][VB];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int id = lane + i * 64;
+            if (CA % 64 != 0 && id >= CA) continue;
+            if constexpr (P::A_ALONG_K) p.load_a(m0 + id / (SEG / VA), kbeg + (id % (SEG / VA)) * VA, kend, ra[i]);
+            else                        p.load_a(m0 + (id % (32 / VA)) * VA, kbeg + id / (32 / VA), kend, ra[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int id = lane + i * 64;
+            if (CB % 64 != 0 && id >= CB) continue;
+            if constexpr (P::B_ALONG_K) p.load_b(n0 + id / (SEG / VB), kbeg + (id % (SEG / VB)) * VB, kend, rb[i]);
+            else                        p.load_b(n0 + (id % (32 / VB)) * VB, kbeg + id / (32 / VB), kend, rb[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int id = lane + i * 64;
+            if (CA % 64 != 0 && id >= CA) continue;
+            if constexpr (P::A_ALONG_K) {
+                T *d = As + (id / (SEG / VA)) * LS + (id % (SEG / VA)) * VA;
+#pragma unroll
+                for (int j = 0; j < VA; ++j) d[j] = from_f32<T>(ra[i][j]);
+            } else {
+                T *d = As + ((id % (32 / VA)) * VA) * LS + id / (32 / VA);
+#pragma unroll
+                for (int j = 0; j < VA; ++j) d[j * LS] = from_f32<T>(ra[i][j]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int id = lane + i * 64;
+            if (CB % 64 != 0 && id >= CB) continue;
+            if constexpr (P::B_ALONG_K) {
+                T *d = Bs + (id / (SEG / VB)) * LS + (id % (SEG / VB)) * VB;
+#pragma unroll
+                for (int j = 0; j < VB; ++j) d[j] = from_f32<T>(rb[i][j]);
+            } else {
+                T *d = Bs + ((id % (32 / VB)) * VB) * LS + id / (32 / VB);
+#pragma unroll
+                for (int j = 0; j < VB; ++j) d[j * LS] = from_f32<T>(rb[i][j]);
+            }
+        }
+        // the panels are private to this wavefront and a wavefront's LDS operations execute in order
+        __builtin_amdgcn_wave_barrier();
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        const T *a = As + lrow * LS, *b = Bs + lrow * LS;
+#pragma unroll 8
+        for (int kk = 0; kk < SEG; kk += Tr::KINST) {
+            if constexpr (sizeof(T) == 4)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk + lk], b[kk + lk], acc, 0, 0, 0);
+            else
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(a + kk + lk * 8),
+                                                              *reinterpret_cast<const bf16x8 *>(b + kk + lk * 8), acc, 0, 0, 0);
+        }
+        return acc;
+    };
+
+    if constexpr (PARTIAL) {
+        const int seg = blockIdx.y * WAVES + w;
+        if (seg >= nseg) return;
+        const f32x16 acc = segment_sum(seg);
+        const int n = n0 + lrow;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + 8 * (r / 4) + 4 * lk + (r % 4);
+            if (m < p.M && n < p.N) p.store(m, n, acc[r], seg);
+        }
+    } else {
+        constexpr int PER = 1024 / (WAVES * 64);        // tile elements owned by each thread in the fold
+        static_assert(PER * WAVES * 64 == 1024, "WAVES must divide 16");
+        float total[PER];
+#pragma unroll
+        for (int e = 0; e < PER; ++e) total[e] = 0.0f;
+        const int gbeg = blockIdx.y * spg, gend = min(nseg, gbeg + spg);
+        const int rounds = (gend - gbeg + WAVES - 1) / WAVES;
+        for (int rd = 0; rd < rounds; ++rd) {
+            const int seg = gbeg + rd * WAVES + w;
+            if (seg < gend) {
+                const f32x16 acc = segment_sum(seg);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) red[w * 1024 + r * 64 + lane] = acc[r];
+            }
+            __syncthreads();
+            const int live = min(WAVES, gend - gbeg - rd * WAVES);
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+                for (int ww = 0; ww < live; ++ww) total[e] += red[ww * 1024 + e * (WAVES * 64) + tid];
+            __syncthreads();
+        }
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int idx = e * (WAVES * 64) + tid;          // = r*64 + lane of the accumulator layout
+            const int r = idx >> 6, l = idx & 63;
+            const int m = m0 + 8 * (r / 4) + 4 * (l >> 5) + (r % 4), n = n0 + (l & 31);
+            if (m < p.M && n < p.N) p.store(m, n, total[e], (int)blockIdx.y);
+        }
+    }
+}
+
+template <class P, int WAVES, int SEG, bool PARTIAL>
+inline hipError_t launch_wsgemm(const P &p, hipStream_t stream, int segs_per_group = 1 << 30)
+{
+    using T = typename P::T;
+    const int tiles = ((grid_rows(p) + 31) / 32) * ((p.N + 31) / 32);
+    const int nseg = (p.K + SEG - 1) / SEG;
+    if (tiles <= 0 || nseg <= 0) return hipSuccess;
+    const size_t lds = (size_t)WAVES * 2 * 32 * (SEG + OperandTraits<T>::PAD) * sizeof(T) + (PARTIAL ? 0 : (size_t)WAVES * 4096);
+    auto kern = wsgemm_kernel<P, WAVES, SEG, PARTIAL>;
+    static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int spg = segs_per_group < nseg ? segs_per_group : nseg;
+    const int gy = PARTIAL ? (nseg + WAVES - 1) / WAVES : (nseg + spg - 1) / spg;
+    hipLaunchKernelGGL(kern, dim3(tiles, gy, grid_batches(p)), dim3(WAVES * 64, 1, 1), lds, stream, p, spg);
+    return hipGetLastError();
+}
+
+}  // namespace hts

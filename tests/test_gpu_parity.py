@@ -180,6 +180,28 @@ def test_act_parity(hts, oracle, shape, A, N, prec, tol):
     ctx.close()
 
 
+@pytest.mark.parametrize("shape,A,prec", [(ATARI, 18, 0), (FOOT, 19, 0), ((3, 44, 52), 7, 0), (ATARI, 18, 1), (FOOT, 19, 1)])
+def test_act_small_and_large_batch_kernels_agree_bitwise(hts, shape, A, prec, monkeypatch):
+    """Small batches run wave-per-segment kernels, large ones the tile kernels; both add the same K segments in the
+    same order, so an observation's outputs do not depend on which kernels served it."""
+    Cc, H, W = shape
+    N = 40
+    params = dev(syn.init_params(9, Cc, H, W, A, bias_scale=0.05))
+    obs = dev(syn.obs_uniform(13, N, Cc, H, W))
+    outs = []
+    for knob in ("128", "0", "16"):          # all small / all tile kernels / mixed (the 40-batch is "large", splits small)
+        monkeypatch.setenv("HTS_SMALL_BATCH", knob)
+        ctx = hts.Context(Cc, H, W, A, precision=prec, max_act_batch=N)
+        full = _act(ctx, obs, params, 5, 1, 0, A)
+        a = _act(ctx, obs[:16], params, 5, 1, 0, A)
+        b = _act(ctx, obs[16:], params, 5, 1, 16, A)
+        assert all(np.array_equal(np.concatenate([x, y]), z) for x, y, z in zip(a, b, full))
+        outs.append(full)
+        ctx.close()
+    for o in outs[1:]:
+        assert all(np.array_equal(x, y) for x, y in zip(o, outs[0]))
+
+
 # ------------------------------------------------------------------------------------------------------------
 # learner
 # ------------------------------------------------------------------------------------------------------------
@@ -219,8 +241,10 @@ LEARN_CASES = [
 ]
 
 
+@pytest.mark.parametrize("small_batch", ["128", "0"])      # wave-per-segment kernels / tile kernels
 @pytest.mark.parametrize("shape,A,count,B,algo,eps,max_norm,prec", LEARN_CASES)
-def test_loss_and_grads_parity(hts, oracle, shape, A, count, B, algo, eps, max_norm, prec):
+def test_loss_and_grads_parity(hts, oracle, shape, A, count, B, algo, eps, max_norm, prec, small_batch, monkeypatch):
+    monkeypatch.setenv("HTS_SMALL_BATCH", small_batch)
     Cc, H, W = shape
     net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 100 + count, algo == 1)
     index = None if B is None else syn.permutation(5, count)[:B]
@@ -352,8 +376,10 @@ def test_learner_errors_launch_nothing(hts):
 # ------------------------------------------------------------------------------------------------------------
 # bf16 operands (fp32 accumulate, fp32 heads/loss/optimiser); the oracle is the unrounded computation
 # ------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("small_batch", ["128", "0"])
 @pytest.mark.parametrize("shape,A,count,B,algo", [(ATARI, 18, 48, 40, 1), (FOOT, 19, 10, 8, 1), ((3, 44, 52), 7, 70, 67, 0)])
-def test_bf16_loss_and_grads(hts, oracle, shape, A, count, B, algo):
+def test_bf16_loss_and_grads(hts, oracle, shape, A, count, B, algo, small_batch, monkeypatch):
+    monkeypatch.setenv("HTS_SMALL_BATCH", small_batch)
     Cc, H, W = shape
     net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 300 + count, algo == 1)
     index = syn.permutation(8, count)[:B]
