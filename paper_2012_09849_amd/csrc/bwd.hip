@@ -27,7 +27,10 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.M = g.A + 1; p.N = 513; p.K = B; p.klen = B;
         p.dz = c.ws.dz; p.h = c.ws.h; p.g = grads; p.A = g.A;
         p.piw = g.piw; p.pib = g.pib; p.vw = g.vw; p.vb = g.vb;
-        { SiteTimer tm(c, SITE_HEADS_WGRAD); e = launch_gemm(p, c.stream); }
+        {
+            SiteTimer tm(c, SITE_HEADS_WGRAD);        // tiny output, long reduction: 16 wavefronts share each tile
+            e = launch_wsgemm<HeadsWgrad, 16, 32, false>(p, c.stream);
+        }
         if (e != hipSuccess) return e;
     }
     {   // fc.w, fc.b
@@ -41,6 +44,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         FcDgrad<T> p;
         p.M = B; p.N = g.F; p.K = 512; p.klen = 512;
         p.dh = c.ws.dh; p.w = params + g.fcw; p.a3 = (const T *)c.ws.a3; p.dy3 = (T *)c.ws.dy3; p.P3 = g.P3;
+        p.dP3 = FastDiv::make(g.P3);
         {
             SiteTimer tm(c, SITE_FC_DGRAD);
             e = small ? launch_wsgemm<FcDgrad<T>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
@@ -58,48 +62,50 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     float *part2 = part3 + (size_t)nz3 * 64 * 577;
     float *part1 = part2 + (size_t)nz2 * 64 * 513;
     {   // conv3.w, conv3.b
-        ConvWgrad<T> p;
+        ConvWgrad<T, Layer3> p;
         p.M = 64; p.N = 577; p.K = B * g.P3; p.klen = s3.klen;
         p.dy = (const T *)c.ws.dy3; p.in = (const T *)c.ws.act2; p.part = part3;
-        p.Kc = 576; p.Cin = 64; p.Hin = g.H2; p.Win = g.W2; p.ksz = 3; p.stride = 1; p.Wo = g.W3; p.Po = g.P3;
+        p.Hin = g.H2; p.Win = g.W2; p.Wo = g.W3; p.Po = g.P3;
+        p.dPo = FastDiv::make(g.P3); p.dWo = FastDiv::make(g.W3);
         {
             SiteTimer tm(c, SITE_CONV3_WGRAD);
-            e = small ? launch_wsgemm<ConvWgrad<T>, 4, 64, false>(p, c.stream, spg3) : launch_gemm(p, c.stream);
+            e = small ? launch_wsgemm<ConvWgrad<T, Layer3>, 4, 64, false>(p, c.stream, spg3) : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }
     {   // d(conv2 pre-activation)
-        ConvDgrad<T, 64> p;
+        ConvDgrad<T, Layer3> p;
         p.N = 64; p.K = 576; p.klen = 576;
         p.dy = (const T *)c.ws.dy3; p.wd = (const T *)c.ws.wd3; p.act_in = (const T *)c.ws.act2; p.dy_in = (T *)c.ws.dy2;
-        p.Bn = B; p.Hin = g.H2; p.Win = g.W2; p.Ho = g.H3; p.Wo = g.W3; p.Cout = 64; p.ksz = 3; p.stride = 1;
-        p.set_batch(0);
+        p.Bn = B; p.Hin = g.H2; p.Win = g.W2; p.Ho = g.H3; p.Wo = g.W3;
+        p.prepare();
         {
             SiteTimer tm(c, SITE_CONV3_DGRAD);
-            e = small ? launch_wsgemm<ConvDgrad<T, 64>, 4, 96, false>(p, c.stream) : launch_gemm(p, c.stream);
+            e = small ? launch_wsgemm<ConvDgrad<T, Layer3>, 4, (sizeof(T) == 2 ? 192 : 96), false>(p, c.stream) : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }
     {   // conv2.w, conv2.b
-        ConvWgrad<T> p;
+        ConvWgrad<T, Layer2> p;
         p.M = 64; p.N = 513; p.K = B * g.P2; p.klen = s2.klen;
         p.dy = (const T *)c.ws.dy2; p.in = (const T *)c.ws.act1; p.part = part2;
-        p.Kc = 512; p.Cin = 32; p.Hin = g.H1; p.Win = g.W1; p.ksz = 4; p.stride = 2; p.Wo = g.W2; p.Po = g.P2;
+        p.Hin = g.H1; p.Win = g.W1; p.Wo = g.W2; p.Po = g.P2;
+        p.dPo = FastDiv::make(g.P2); p.dWo = FastDiv::make(g.W2);
         {
             SiteTimer tm(c, SITE_CONV2_WGRAD);
-            e = small ? launch_wsgemm<ConvWgrad<T>, 4, 64, false>(p, c.stream, spg2) : launch_gemm(p, c.stream);
+            e = small ? launch_wsgemm<ConvWgrad<T, Layer2>, 4, 64, false>(p, c.stream, spg2) : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }
     {   // d(conv1 pre-activation)
-        ConvDgrad<T, 32> p;
+        ConvDgrad<T, Layer2> p;
         p.N = 32; p.K = 256; p.klen = 256;      // four parity classes, 2x2 taps each
         p.dy = (const T *)c.ws.dy2; p.wd = (const T *)c.ws.wd2; p.act_in = (const T *)c.ws.act1; p.dy_in = (T *)c.ws.dy1;
-        p.Bn = B; p.Hin = g.H1; p.Win = g.W1; p.Ho = g.H2; p.Wo = g.W2; p.Cout = 64; p.ksz = 4; p.stride = 2;
-        p.set_batch(0);
+        p.Bn = B; p.Hin = g.H1; p.Win = g.W1; p.Ho = g.H2; p.Wo = g.W2;
+        p.prepare();
         {
             SiteTimer tm(c, SITE_CONV2_DGRAD);
-            e = small ? launch_wsgemm<ConvDgrad<T, 32>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
+            e = small ? launch_wsgemm<ConvDgrad<T, Layer2>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }
@@ -108,6 +114,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.M = 32; p.N = g.K1 + 1; p.K = B * g.P1; p.klen = s1.klen;
         p.dy = (const T *)c.ws.dy1; p.obs = obs; p.index = index; p.part = part1;
         p.Kc = g.K1; p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
+        p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
         {
             SiteTimer tm(c, SITE_CONV1_WGRAD);
             e = small ? launch_wsgemm<Conv1Wgrad<T>, 4, 64, false>(p, c.stream, spg1) : launch_gemm(p, c.stream);

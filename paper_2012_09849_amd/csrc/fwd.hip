@@ -15,6 +15,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.M = B * g.P1; p.N = 32; p.K = g.K1; p.klen = g.K1;
         p.obs = obs; p.index = index; p.w = params + g.w1; p.bias = params + g.b1; p.out = (T *)c.ws.act1;
         p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
+        p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
         {
             SiteTimer tm(c, SITE_CONV1_FWD);
             e = small ? launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream) : launch_gemm(p, c.stream);
@@ -22,25 +23,27 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         if (e != hipSuccess) return e;
     }
     {
-        ConvFwd<T, false> p;
+        ConvFwd<T, Layer2, false> p;
         p.M = B * g.P2; p.N = 64; p.K = 512; p.klen = 512;
         p.in = (const T *)c.ws.act1; p.wf = (const T *)c.ws.wf2; p.bias = params + g.b2; p.out = (T *)c.ws.act2;
-        p.Cin = 32; p.Hin = g.H1; p.Win = g.W1; p.ksz = 4; p.stride = 2; p.Wo = g.W2; p.Po = g.P2; p.Cout = 64;
+        p.Hin = g.H1; p.Win = g.W1; p.Wo = g.W2; p.Po = g.P2;
+        p.dPo = FastDiv::make(g.P2); p.dWo = FastDiv::make(g.W2);
         {
             SiteTimer tm(c, SITE_CONV2_FWD);
-            e = small ? launch_wsgemm<ConvFwd<T, false>, 4, ConvFwd<T, false>::SEG, false>(p, c.stream)
+            e = small ? launch_wsgemm<ConvFwd<T, Layer2, false>, 4, ConvFwd<T, Layer2, false>::SEG, false>(p, c.stream)
                       : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }
     {
-        ConvFwd<T, true> p;
+        ConvFwd<T, Layer3, true> p;
         p.M = B * g.P3; p.N = 64; p.K = 576; p.klen = 576;
         p.in = (const T *)c.ws.act2; p.wf = (const T *)c.ws.wf3; p.bias = params + g.b3; p.out = (T *)c.ws.a3;
-        p.Cin = 64; p.Hin = g.H2; p.Win = g.W2; p.ksz = 3; p.stride = 1; p.Wo = g.W3; p.Po = g.P3; p.Cout = 64;
+        p.Hin = g.H2; p.Win = g.W2; p.Wo = g.W3; p.Po = g.P3;
+        p.dPo = FastDiv::make(g.P3); p.dWo = FastDiv::make(g.W3);
         {
             SiteTimer tm(c, SITE_CONV3_FWD);
-            e = small ? launch_wsgemm<ConvFwd<T, true>, 4, ConvFwd<T, true>::SEG, false>(p, c.stream)
+            e = small ? launch_wsgemm<ConvFwd<T, Layer3, true>, 4, ConvFwd<T, Layer3, true>::SEG, false>(p, c.stream)
                       : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;

@@ -11,9 +11,11 @@
 // Accumulator register r of lane l is D[8*(r/4) + 4*(l/32) + r%4][l%32].
 //
 // Operand tiles go global -> registers -> LDS ([row][k], padded) -> MFMA; the global loads of tile i+1 are in
-// flight while tile i is multiplied.  blockIdx.y selects a contiguous K range of length p.klen (split-K); the
-// problem's store() receives that index so partial sums go to distinct slots and are later combined in a fixed
-// order (no atomics anywhere).
+// flight while tile i is multiplied.  Gathers are separable: the part of an address that depends on the tile row
+// (batch / y / x decomposition, done with multiply-shift division) is computed once per thread before the K loop
+// (ctx_a / ctx_b); the part that depends on k is cheap.  blockIdx.y selects a contiguous K range of length p.klen
+// (split-K); the problem's store() receives that index so partial sums go to distinct slots and are later combined
+// in a fixed order (no atomics anywhere).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -26,21 +28,32 @@
 namespace hts {
 
 typedef __bf16 bf16_t;
-typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
-typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T, int V> struct VecOf { typedef T type __attribute__((ext_vector_type(V))); };
+template <typename T> struct VecOf<T, 1> {
+    struct type {
+        T x;
+        HTS_HD T &operator[](int) { return x; }
+        HTS_HD const T &operator[](int) const { return x; }
+    };
+};
+template <typename T, int V> using Vec = typename VecOf<T, V>::type;
+typedef Vec<bf16_t, 8> bf16x8;
 
 template <typename T> struct OperandTraits;
 template <> struct OperandTraits<float> {
     static constexpr int KINST = 2;   // k consumed per MFMA
-    static constexpr int PAD = 1;     // LDS row padding (elements)
+    static constexpr int PAD = 1;     // LDS row padding (elements); rows are written element by element
     static constexpr int VEC = 4;     // elements per 16-byte global access
+    static constexpr int BK = 32;     // k per staged tile
 };
 template <> struct OperandTraits<bf16_t> {
     static constexpr int KINST = 16;
-    static constexpr int PAD = 8;
+    static constexpr int PAD = 8;     // keeps rows 16-byte aligned and spreads them over the banks
     static constexpr int VEC = 8;
+    static constexpr int BK = 64;
 };
 
 HTS_HD float to_f32(float x) { return x; }
@@ -49,36 +62,62 @@ template <typename T> HTS_HD T from_f32(float x);
 template <> HTS_HD float from_f32<float>(float x) { return x; }
 template <> HTS_HD bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }   // round to nearest even
 
-// 16-byte (or shorter) contiguous loads returning floats
-HTS_HD void load_vec(const float *p, float (&v)[4])
+// Exact floor(x / d) for 0 <= x < 2^31 by multiply-shift: mul = ceil(2^p / d), p = 31 + ceil(log2 d).
+struct FastDiv {
+    uint32_t mul;
+    int shr, d;
+    static inline FastDiv make(int d)
+    {
+        FastDiv f;
+        f.d = d < 1 ? 1 : d;
+        int lg = 0;
+        while ((1ll << lg) < f.d) ++lg;
+        const int p = 31 + lg;
+        f.mul = (uint32_t)(((1ull << p) + (unsigned long long)f.d - 1) / (unsigned long long)f.d);
+        f.shr = p - 32;
+        return f;
+    }
+    HTS_HD int div(int x) const
+    {
+        if (d == 1) return x;
+#if defined(__HIP_DEVICE_COMPILE__)
+        return (int)(__umulhi((uint32_t)x, mul) >> shr);
+#else
+        return (int)((((unsigned long long)(uint32_t)x * mul) >> 32) >> shr);
+#endif
+    }
+};
+
+// contiguous loads of V operands of type T from memory of type S (conversion to T happens here)
+template <typename T, int V> HTS_HD Vec<T, V> zero_vec()
 {
-    const f32x4 t = *reinterpret_cast<const f32x4 *>(p);
-    v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
-}
-HTS_HD void load_vec(const bf16_t *p, float (&v)[8])
-{
-    const bf16x8 t = *reinterpret_cast<const bf16x8 *>(p);
+    Vec<T, V> v;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = (float)t[i];
+    for (int i = 0; i < V; ++i) v[i] = from_f32<T>(0.0f);
+    return v;
 }
-HTS_HD void load_vec(const float *p, float (&v)[8])
+template <typename T, int V, typename S> HTS_HD Vec<T, V> load_vec(const S *p)
 {
-    const f32x4 t0 = *reinterpret_cast<const f32x4 *>(p);
-    const f32x4 t1 = *reinterpret_cast<const f32x4 *>(p + 4);
+    if constexpr (std::is_same<S, T>::value) return *reinterpret_cast<const Vec<T, V> *>(p);
+    else {
+        const Vec<S, V> s = *reinterpret_cast<const Vec<S, V> *>(p);
+        Vec<T, V> v;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { v[i] = t0[i]; v[4 + i] = t1[i]; }
+        for (int i = 0; i < V; ++i) v[i] = from_f32<T>(to_f32(s[i]));
+        return v;
+    }
 }
-HTS_HD void load_vec(const bf16_t *p, float (&v)[4])
+// 8 bytes (4-byte aligned) as 8 operands
+template <typename T> HTS_HD Vec<T, 8> load_u8x8(const uint8_t *p)
 {
-    const bf16x4 t = *reinterpret_cast<const bf16x4 *>(p);
+    const uint32_t lo = *reinterpret_cast<const uint32_t *>(p), hi = *reinterpret_cast<const uint32_t *>(p + 4);
+    Vec<T, 8> v;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = (float)t[i];
-}
-HTS_HD void load_vec(const float *p, float (&v)[1]) { v[0] = *p; }
-template <int V> HTS_HD void zero_vec(float (&v)[V])
-{
-#pragma unroll
-    for (int i = 0; i < V; ++i) v[i] = 0.0f;
+    for (int i = 0; i < 4; ++i) {
+        v[i] = from_f32<T>((float)((lo >> (8 * i)) & 0xFFu));
+        v[4 + i] = from_f32<T>((float)((hi >> (8 * i)) & 0xFFu));
+    }
+    return v;
 }
 
 // Optional segmented accumulation: a problem that defines `static constexpr int SEG` (a multiple of BK) gets
@@ -88,8 +127,9 @@ template <int V> HTS_HD void zero_vec(float (&v)[V])
 template <class P, class = void> struct SegOf { static constexpr int value = 0; };
 template <class P> struct SegOf<P, std::void_t<decltype(P::SEG)>> { static constexpr int value = P::SEG; };
 
-// Optional batching: a problem with `int batches() const`, `int max_m() const` and `void set_batch(int)` is launched
-// with gridDim.z = batches(); each z works on its own sub-problem (own M, own gathers) selected by set_batch.
+// Optional batching: a problem with `int batches() const`, `int max_m() const`, `int batch_m(int z) const` is
+// launched with gridDim.z = batches(); batch z has batch_m(z) rows and its own gathers: ctx_a(row, z),
+// ctx_b(col, z) and store(m, n, acc, split, z) receive the batch index (the problem object stays read-only).
 template <class P, class = void> struct HasBatch : std::false_type {};
 template <class P> struct HasBatch<P, std::void_t<decltype(std::declval<const P &>().batches())>> : std::true_type {};
 template <class P> inline int grid_rows(const P &p)
@@ -100,38 +140,59 @@ template <class P> inline int grid_batches(const P &p)
 {
     if constexpr (HasBatch<P>::value) return p.batches(); else return 1;
 }
+template <class P> HTS_HD int rows_of(const P &p, int zb)
+{
+    if constexpr (HasBatch<P>::value) return p.batch_m(zb); else return p.M;
+}
+template <class P> HTS_HD typename P::CtxA make_ctx_a(const P &p, int row, int zb)
+{
+    if constexpr (HasBatch<P>::value) return p.ctx_a(row, zb); else return p.ctx_a(row);
+}
+template <class P> HTS_HD typename P::CtxB make_ctx_b(const P &p, int col, int zb)
+{
+    if constexpr (HasBatch<P>::value) return p.ctx_b(col, zb); else return p.ctx_b(col);
+}
+template <class P> HTS_HD void do_store(const P &p, int m, int n, float acc, int z, int zb)
+{
+    if constexpr (HasBatch<P>::value) p.store(m, n, acc, z, zb); else p.store(m, n, acc, z);
+}
 
 // A problem type P provides:
 //   using T                          operand type in LDS / MFMA (float or bf16_t)
-//   static constexpr int BM, BN, BK  workgroup tile; WAVES_M in {1,2,4} wavefronts along M (4/WAVES_M along N)
-//   static constexpr int VA, VB      elements fetched per load_a / load_b call
+//   static constexpr int BM, BN, BK  workgroup tile; WAVES_M x WAVES_N wavefronts (64 lanes each) share it
+//   static constexpr int VA, VB      operands fetched per load_a / load_b call
 //   static constexpr bool A_ALONG_K, B_ALONG_K
-//                                    true : the VA elements are k, k+1, ... of one row
-//                                    false: the VA elements are rows row, row+1, ... at one k
+//                                    true : the VA operands are k, k+1, ... of one row
+//                                    false: the VA operands are rows row, row+1, ... at one k; a thread then fetches
+//                                           VA consecutive k and transposes the VA x VA block in registers, so
+//                                           that LDS rows are still written as whole k-contiguous vectors
 //   int M, N, K, klen                logical sizes; blockIdx.y covers k in [y*klen, min(K,(y+1)*klen))
-//   void load_a(int row, int k, int kend, float (&v)[VA]) const   zero-filled outside [0,M) x [.,kend)
-//   void load_b(int col, int k, int kend, float (&v)[VB]) const
-//   void store(int m, int n, float acc, int z) const              called only for m < M, n < N
+//   CtxA ctx_a(int row) const        row-dependent part of the gather (row = first row of the vector)
+//   Vec<T,VA> load_a(const CtxA &, int k, int kend) const     zero outside [0,M) x [.,kend)
+//   CtxB ctx_b(int col) const,  Vec<T,VB> load_b(const CtxB &, int k, int kend) const
+//   void store(int m, int n, float acc, int z) const          called only for m < M, n < N
 template <class P>
-__global__ __launch_bounds__(256) void gemm_kernel(const P p_in)
+__global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(const P p)
 {
-    P p = p_in;
-    if constexpr (HasBatch<P>::value) p.set_batch(blockIdx.z);
+    const int zb = blockIdx.z, M = rows_of(p, zb);
     using T = typename P::T;
     using Tr = OperandTraits<T>;
     constexpr int BM = P::BM, BN = P::BN, BK = P::BK;
-    constexpr int WM = P::WAVES_M, WN = 4 / WM;
+    constexpr int WM = P::WAVES_M, WN = P::WAVES_N, NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int LS = BK + Tr::PAD;
     constexpr int VA = P::VA, VB = P::VB;
-    constexpr int CA = BM * BK / VA, CB = BN * BK / VB;             // vectors per operand tile
-    constexpr int NA = (CA + 255) / 256, NB = (CB + 255) / 256;     // vectors per thread (last one may be idle)
+    // work items per operand tile: a k-contiguous vector (ALONG_K) or a V x V block to transpose (otherwise)
+    constexpr int CA = P::A_ALONG_K ? BM * BK / VA : (BM / VA) * (BK / VA);
+    constexpr int CB = P::B_ALONG_K ? BN * BK / VB : (BN / VB) * (BK / VB);
+    constexpr int NA = (CA + NT - 1) / NT, NB = (CB + NT - 1) / NT;     // items per thread (last one may be idle)
+    constexpr int RA = P::A_ALONG_K ? 1 : VA, RB = P::B_ALONG_K ? 1 : VB; // vectors held per item
     static_assert(TM >= 1 && TN >= 1 && TM * 32 * WM == BM && TN * 32 * WN == BN, "tile shape");
-    static_assert(CA * VA == BM * BK && CB * VB == BN * BK && BK % VA == 0 && BK % VB == 0 && BM % VA == 0 &&
-                      BN % VB == 0, "loader shape");
+    static_assert(BK % VA == 0 && BK % VB == 0 && BM % VA == 0 && BN % VB == 0, "loader shape");
     static_assert(BK % Tr::KINST == 0, "BK");
     constexpr int SEG = SegOf<P>::value;
     static_assert(SEG % BK == 0, "SEG must be a multiple of BK");
+    constexpr bool VEC_LDS = sizeof(T) == 2;      // bf16 rows are 16-byte aligned: whole vectors are stored at once
 
     __shared__ __attribute__((aligned(16))) T As[BM * LS];
     __shared__ __attribute__((aligned(16))) T Bs[BN * LS];
@@ -140,56 +201,95 @@ __global__ __launch_bounds__(256) void gemm_kernel(const P p_in)
     const int wm = wave % WM, wn = wave / WM;
     const int tiles_n = (p.N + BN - 1) / BN;
     const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
-    if (m0 >= p.M) return;                 // a batch smaller than the largest one: the whole workgroup leaves
+    if (m0 >= M) return;                   // a batch smaller than the largest one: the whole workgroup leaves
     const int z = blockIdx.y;
     const int kbeg = z * p.klen;
     const int kend = min(p.K, kbeg + p.klen);
 
-    float ra[NA][VA], rb[NB][VB];
+    // fixed assignment of operand items to threads; the row part of every gather is resolved once
+    typename P::CtxA ca[NA];
+    typename P::CtxB cb[NB];
+    int ka[NA], kb[NB], la[NA], lb[NB];          // k offset inside the tile, LDS offset
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int id = tid + i * NT;
+        int r;
+        if constexpr (P::A_ALONG_K) { r = id / (BK / VA); ka[i] = (id % (BK / VA)) * VA; }
+        else { r = (id % (BM / VA)) * VA; ka[i] = (id / (BM / VA)) * VA; }
+        la[i] = r * LS + ka[i];
+        ca[i] = make_ctx_a(p, m0 + r, zb);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int id = tid + i * NT;
+        int r;
+        if constexpr (P::B_ALONG_K) { r = id / (BK / VB); kb[i] = (id % (BK / VB)) * VB; }
+        else { r = (id % (BN / VB)) * VB; kb[i] = (id / (BN / VB)) * VB; }
+        lb[i] = r * LS + kb[i];
+        cb[i] = make_ctx_b(p, n0 + r, zb);
+    }
 
+    Vec<T, VA> ra[NA][RA];
+    Vec<T, VB> rb[NB][RB];
     auto gload = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int id = tid + i * 256;
-            if (CA % 256 != 0 && id >= CA) continue;
-            if constexpr (P::A_ALONG_K) p.load_a(m0 + id / (BK / VA), k0 + (id % (BK / VA)) * VA, kend, ra[i]);
-            else                        p.load_a(m0 + (id % (BM / VA)) * VA, k0 + id / (BM / VA), kend, ra[i]);
-        }
+        for (int i = 0; i < NA; ++i)
+            if (CA % NT == 0 || tid + i * NT < CA)
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int id = tid + i * 256;
-            if (CB % 256 != 0 && id >= CB) continue;
-            if constexpr (P::B_ALONG_K) p.load_b(n0 + id / (BK / VB), k0 + (id % (BK / VB)) * VB, kend, rb[i]);
-            else                        p.load_b(n0 + (id % (BN / VB)) * VB, k0 + id / (BN / VB), kend, rb[i]);
-        }
+                for (int q = 0; q < RA; ++q) ra[i][q] = p.load_a(ca[i], k0 + ka[i] + q, kend);
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+            if (CB % NT == 0 || tid + i * NT < CB)
+#pragma unroll
+                for (int q = 0; q < RB; ++q) rb[i][q] = p.load_b(cb[i], k0 + kb[i] + q, kend);
     };
     auto sstore = [&]() {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            const int id = tid + i * 256;
-            if (CA % 256 != 0 && id >= CA) continue;
+            if (CA % NT != 0 && tid + i * NT >= CA) continue;
+            T *d = As + la[i];
             if constexpr (P::A_ALONG_K) {
-                T *d = As + (id / (BK / VA)) * LS + (id % (BK / VA)) * VA;
+                if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VA> *>(d) = ra[i][0];
+                else {
 #pragma unroll
-                for (int j = 0; j < VA; ++j) d[j] = from_f32<T>(ra[i][j]);
+                    for (int j = 0; j < VA; ++j) d[j] = ra[i][0][j];
+                }
             } else {
-                T *d = As + ((id % (BM / VA)) * VA) * LS + id / (BM / VA);
 #pragma unroll
-                for (int j = 0; j < VA; ++j) d[j * LS] = from_f32<T>(ra[i][j]);
+                for (int j = 0; j < VA; ++j) {          // row r+j gets the k-contiguous vector (block column j)
+                    Vec<T, VA> t;
+#pragma unroll
+                    for (int q = 0; q < VA; ++q) t[q] = ra[i][q][j];
+                    if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VA> *>(d + j * LS) = t;
+                    else {
+#pragma unroll
+                        for (int q = 0; q < VA; ++q) d[j * LS + q] = t[q];
+                    }
+                }
             }
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int id = tid + i * 256;
-            if (CB % 256 != 0 && id >= CB) continue;
+            if (CB % NT != 0 && tid + i * NT >= CB) continue;
+            T *d = Bs + lb[i];
             if constexpr (P::B_ALONG_K) {
-                T *d = Bs + (id / (BK / VB)) * LS + (id % (BK / VB)) * VB;
+                if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VB> *>(d) = rb[i][0];
+                else {
 #pragma unroll
-                for (int j = 0; j < VB; ++j) d[j] = from_f32<T>(rb[i][j]);
+                    for (int j = 0; j < VB; ++j) d[j] = rb[i][0][j];
+                }
             } else {
-                T *d = Bs + ((id % (BN / VB)) * VB) * LS + id / (BN / VB);
 #pragma unroll
-                for (int j = 0; j < VB; ++j) d[j * LS] = from_f32<T>(rb[i][j]);
+                for (int j = 0; j < VB; ++j) {
+                    Vec<T, VB> t;
+#pragma unroll
+                    for (int q = 0; q < VB; ++q) t[q] = rb[i][q][j];
+                    if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VB> *>(d + j * LS) = t;
+                    else {
+#pragma unroll
+                        for (int q = 0; q < VB; ++q) d[j * LS + q] = t[q];
+                    }
+                }
             }
         }
     };
@@ -275,7 +375,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const P p_in)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (m < p.M && n < p.N) p.store(m, n, acc[i][j][r], z);
+                if (m < M && n < p.N) do_store(p, m, n, acc[i][j][r], z, zb);
             }
         }
 }
@@ -285,7 +385,8 @@ template <class P> inline hipError_t launch_gemm(const P &p, hipStream_t stream)
     const int tiles = ((grid_rows(p) + P::BM - 1) / P::BM) * ((p.N + P::BN - 1) / P::BN);
     const int nz = (p.K + p.klen - 1) / p.klen;
     if (tiles <= 0 || nz <= 0) return hipSuccess;
-    hipLaunchKernelGGL(gemm_kernel<P>, dim3(tiles, nz, grid_batches(p)), dim3(256, 1, 1), 0, stream, p);
+    hipLaunchKernelGGL(gemm_kernel<P>, dim3(tiles, nz, grid_batches(p)), dim3(P::WAVES_M * P::WAVES_N * 64, 1, 1), 0,
+                       stream, p);
     return hipGetLastError();
 }
 

@@ -9,6 +9,14 @@
 
 namespace hts {
 
+// 8 consecutive floats (16-byte aligned) into registers
+__device__ __forceinline__ void load_vec(const float *p, float (&v)[8])
+{
+    const f32x4 t0 = *reinterpret_cast<const f32x4 *>(p), t1 = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = t0[i]; v[4 + i] = t1[i]; }
+}
+
 // ------------------------------------------------------------------------------------------------------------
 // conv weight permutation (run at the start of every call that needs the network: no cached state)
 // ------------------------------------------------------------------------------------------------------------
@@ -379,7 +387,16 @@ __global__ void wgrad_reduce_kernel(const float *__restrict__ part, int nz, int 
     if (i >= rows * ncol) return;
     const int n = i / ncol, kcol = i - n * ncol;
     float s = 0.0f;
-    for (int z = 0; z < nz; ++z) s += part[(long long)z * rows * ncol + i];
+    const long long zs = (long long)rows * ncol;
+    int z = 0;
+    for (; z + 8 <= nz; z += 8) {            // eight loads in flight, added in z order
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = part[(z + q) * zs + i];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += v[q];
+    }
+    for (; z < nz; ++z) s += part[z * zs + i];
     s *= scale;
     const int kc = ncol - 1;
     if (kcol == kc) { g[b_off + n] = s; return; }

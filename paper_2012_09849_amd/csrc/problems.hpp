@@ -1,6 +1,6 @@
 // Operand gathers and epilogues that turn each layer of the policy/value network (appendix "Implementation
 // Details": conv 32@8x8 s4, conv 64@4x4 s2, conv 64@3x3 s1, FC 512, heads) and each piece of its backward pass
-// into the D[m][n] = sum_k A(m,k) B(n,k) form of gemm.hpp.
+// into the D[m][n] = sum_k A(m,k) B(n,k) form of gemm.hpp / wsgemm.hpp.
 //
 // Layouts inside the library's workspace (T = float or bf16):
 //   act1 [B][H1][W1][32], act2 [B][H2][W2][64]   channel-innermost, post-ReLU
@@ -11,6 +11,9 @@
 //   dy3 [B][H3][W3][64], dy2 [B][H2][W2][64], dy1 [B][H1][W1][32]   dL/d(conv pre-activation), T
 //   wf2 [64][(u,v,c)], wf3 [64][(u,v,c)]   conv weights with taps outermost, for the forward gathers
 //   wd2 [32][(u,v,n)], wd3 [64][(u,v,n)]   conv weights transposed for the input-gradient gathers
+//
+// Every gather is split into a row part (ctx_a / ctx_b: the batch / y / x decomposition, evaluated once per thread)
+// and a k part (load_a / load_b: taps and channels, with compile-time layer constants).
 #pragma once
 #include "gemm.hpp"
 
@@ -22,24 +25,37 @@ struct Geom {
     long long w1, b1, w2, b2, w3, b3, fcw, fcb, piw, pib, vw, vb, P;
 };
 
+// conv2: 32 -> 64 channels, 4x4 stride 2;  conv3: 64 -> 64 channels, 3x3 stride 1
+template <int CIN_, int KSZ_, int STRIDE_> struct ConvLayer {
+    static constexpr int CIN = CIN_, KSZ = KSZ_, STRIDE = STRIDE_, COUT = 64, K = KSZ_ * KSZ_ * CIN_;
+};
+typedef ConvLayer<32, 4, 2> Layer2;
+typedef ConvLayer<64, 3, 1> Layer3;
+
+struct OffCtx { long long off; };          // element offset of the row's first operand, or -1 for a row outside M
+
 // ------------------------------------------------------------------------------------------------------------
 // plain C = A * B^T on f32 arrays (test hook for the tile core)
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct PlainGemm {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = 32, WAVES_M = 2;
+    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = 4, VB = 4;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
+    typedef OffCtx CtxA;
+    typedef OffCtx CtxB;
     int M, N, K, klen;
     const float *A, *B;
     float *C;
-    HTS_HD void load_a(int m, int k, int kend, float (&v)[VA]) const
+    HTS_HD CtxA ctx_a(int m) const { return {m < M ? (long long)m * K : -1}; }
+    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (m < M && k < kend) load_vec(A + (long long)m * K + k, v); else zero_vec(v);
+        return (c.off >= 0 && k < kend) ? load_vec<T, VA>(A + c.off + k) : zero_vec<T, VA>();
     }
-    HTS_HD void load_b(int n, int k, int kend, float (&v)[VB]) const
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        if (n < N && k < kend) load_vec(B + (long long)n * K + k, v); else zero_vec(v);
+        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(B + c.off + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int m, int n, float acc, int) const { C[(long long)m * N + n] = acc; }
 };
@@ -50,35 +66,36 @@ template <typename T_> struct PlainGemm {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct Conv1Fwd {
     using T = T_;
-    static constexpr int BM = 128, BN = 32, BK = 32, WAVES_M = 4;
+    static constexpr int BM = 128, BN = 32, BK = OperandTraits<T>::BK, WAVES_M = 4, WAVES_N = 1;
     static constexpr int VA = 8, VB = 4;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 64;       // forward sums are segmented so every kernel variant returns the same bits
+    typedef OffCtx CtxA;
+    typedef OffCtx CtxB;
     int M, N, K, klen;
     const uint8_t *obs;
     const int32_t *index;
     const float *w, *bias;
     T *out;
     int C, H, W, W1, P1;
-    HTS_HD void load_a(int m, int k, int kend, float (&v)[VA]) const
+    FastDiv dP1, dW1;
+    HTS_HD CtxA ctx_a(int m) const
     {
-        if (m < M && k < kend) {
-            const int b = m / P1, p = m - b * P1, oy = p / W1, ox = p - oy * W1;
-            const int c = k >> 6, u = (k >> 3) & 7;
-            const long long row = index ? index[b] : b;
-            const uint8_t *src = obs + ((row * C + c) * H + (oy * 4 + u)) * (long long)W + ox * 4;
-            const uint32_t lo = *reinterpret_cast<const uint32_t *>(src);
-            const uint32_t hi = *reinterpret_cast<const uint32_t *>(src + 4);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[i] = (float)((lo >> (8 * i)) & 0xFFu);
-                v[4 + i] = (float)((hi >> (8 * i)) & 0xFFu);
-            }
-        } else zero_vec(v);
+        if (m >= M) return {-1};
+        const int b = dP1.div(m), p = m - b * P1, oy = dW1.div(p), ox = p - oy * W1;
+        const long long row = index ? index[b] : b;
+        return {row * C * H * W + (long long)(oy * 4) * W + ox * 4};
     }
-    HTS_HD void load_b(int n, int k, int kend, float (&v)[VB]) const
+    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (n < N && k < kend) load_vec(w + (long long)n * K + k, v); else zero_vec(v);
+        if (c.off < 0 || k >= kend) return zero_vec<T, VA>();
+        const int ch = k >> 6, u = (k >> 3) & 7;
+        return load_u8x8<T>(obs + c.off + (ch * H + u) * W);
+    }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
+    {
+        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(w + c.off + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int m, int n, float acc, int) const
     {
@@ -90,38 +107,47 @@ template <typename T_> struct Conv1Fwd {
 // ------------------------------------------------------------------------------------------------------------
 // conv2 / conv3 forward from channel-innermost activations; k = (u,v,c)
 // ------------------------------------------------------------------------------------------------------------
-template <typename T_, bool FLAT_OUT> struct ConvFwd {
+template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = 32, WAVES_M = 2;
+    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    static constexpr int SEG = FLAT_OUT ? 96 : 64;
+    // conv2: one tap row (4*32 = 128); conv3: one tap row (3*64 = 192) for bf16, half of one for fp32
+    static constexpr int SEG = L::KSZ == 4 ? 128 : (sizeof(T) == 2 ? 192 : 96);
+    typedef OffCtx CtxA;
+    typedef OffCtx CtxB;
     int M, N, K, klen;
     const T *in;      // [B][Hin][Win][Cin]
     const T *wf;      // [Cout][K]
     const float *bias;
     T *out;
-    int Cin, Hin, Win, ksz, stride, Wo, Po, Cout;
-    HTS_HD void load_a(int m, int k, int kend, float (&v)[VA]) const
+    int Hin, Win, Wo, Po;
+    FastDiv dPo, dWo;
+    HTS_HD CtxA ctx_a(int m) const
     {
-        if (m < M && k < kend) {
-            const int b = m / Po, p = m - b * Po, oy = p / Wo, ox = p - oy * Wo;
-            const int tap = k / Cin, c = k - tap * Cin, u = tap / ksz, vv = tap - u * ksz;
-            load_vec(in + (((long long)b * Hin + oy * stride + u) * Win + ox * stride + vv) * Cin + c, v);
-        } else zero_vec(v);
+        if (m >= M) return {-1};
+        const int b = dPo.div(m), p = m - b * Po, oy = dWo.div(p), ox = p - oy * Wo;
+        return {(((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN};
     }
-    HTS_HD void load_b(int n, int k, int kend, float (&v)[VB]) const
+    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (n < N && k < kend) load_vec(wf + (long long)n * K + k, v); else zero_vec(v);
+        if (c.off < 0 || k >= kend) return zero_vec<T, VA>();
+        const int u = k / (L::KSZ * L::CIN), r = k - u * (L::KSZ * L::CIN);     // a tap row is contiguous in memory
+        return load_vec<T, VA>(in + c.off + (long long)u * Win * L::CIN + r);
+    }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
+    {
+        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(wf + c.off + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int m, int n, float acc, int) const
     {
         const float y = acc + bias[n];
         const T r = from_f32<T>(y > 0.0f ? y : 0.0f);
         if constexpr (FLAT_OUT) {
-            const int b = m / Po, p = m - b * Po;
-            out[((long long)b * Cout + n) * Po + p] = r;
-        } else out[(long long)m * Cout + n] = r;
+            const int b = dPo.div(m), p = m - b * Po;
+            out[((long long)b * L::COUT + n) * Po + p] = r;
+        } else out[(long long)m * L::COUT + n] = r;
     }
 };
 
@@ -130,22 +156,26 @@ template <typename T_, bool FLAT_OUT> struct ConvFwd {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcFwd {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = 32, WAVES_M = 2;
+    static constexpr int BM = 64, BN = 32, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 1;   // 16 x B/64 workgroups
     static constexpr int VA = OperandTraits<T>::VEC, VB = 4;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 128;
+    typedef OffCtx CtxA;
+    typedef OffCtx CtxB;
     int M, N, K, klen;
     const T *a3;
     const float *w, *bias;
     float *h;
     float *part;      // when set: segment sums go to part[seg][M][N]; bias and ReLU are applied by the consumer
-    HTS_HD void load_a(int m, int k, int kend, float (&v)[VA]) const
+    HTS_HD CtxA ctx_a(int m) const { return {m < M ? (long long)m * K : -1}; }
+    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (m < M && k < kend) load_vec(a3 + (long long)m * K + k, v); else zero_vec(v);
+        return (c.off >= 0 && k < kend) ? load_vec<T, VA>(a3 + c.off + k) : zero_vec<T, VA>();
     }
-    HTS_HD void load_b(int n, int k, int kend, float (&v)[VB]) const
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        if (n < N && k < kend) load_vec(w + (long long)n * K + k, v); else zero_vec(v);
+        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(w + c.off + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int m, int n, float acc, int seg) const
     {
@@ -161,22 +191,30 @@ template <typename T_> struct FcFwd {
 // ------------------------------------------------------------------------------------------------------------
 struct HeadsWgrad {
     using T = float;
-    static constexpr int BM = 32, BN = 128, BK = 32, WAVES_M = 1;
+    static constexpr int BM = 32, BN = 128, BK = 32, WAVES_M = 1, WAVES_N = 4;
     static constexpr int VA = 1, VB = 4;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
+    struct CtxA { int j; };
+    struct CtxB { int kk; };
     int M, N, K, klen;     // M = A+1, N = 513, K = B
     const float *dz, *h;
     float *g;
     int A;
     long long piw, pib, vw, vb;
-    HTS_HD void load_a(int j, int b, int kend, float (&v)[VA]) const
+    HTS_HD CtxA ctx_a(int j) const { return {j}; }
+    HTS_HD CtxB ctx_b(int kk) const { return {kk}; }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int b, int kend) const
     {
-        v[0] = (j < M && b < kend) ? dz[(long long)b * M + j] : 0.0f;
+        Vec<T, VA> v;
+        v[0] = (c.j < M && b < kend) ? dz[(long long)b * M + c.j] : 0.0f;
+        return v;
     }
-    HTS_HD void load_b(int kk, int b, int kend, float (&v)[VB]) const
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int b, int kend) const
     {
-        if (b < kend && kk < 512) load_vec(h + (long long)b * 512 + kk, v);
-        else { zero_vec(v); if (b < kend && kk == 512) v[0] = 1.0f; }
+        if (b < kend && c.kk < 512) return load_vec<T, VB>(h + (long long)b * 512 + c.kk);
+        Vec<T, VB> v = zero_vec<T, VB>();
+        if (b < kend && c.kk == 512) v[0] = 1.0f;
+        return v;
     }
     HTS_HD void store(int j, int kk, float acc, int) const
     {
@@ -190,23 +228,29 @@ struct HeadsWgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcWgrad {
     using T = T_;
-    static constexpr int BM = 128, BN = 64, BK = 32, WAVES_M = 4;
+    static constexpr int BM = 128, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 4, WAVES_N = 1;
     static constexpr int VA = 4, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
+    struct CtxA { int j; };
+    struct CtxB { int f; };
     int M, N, K, klen;     // M = 512, N = F+1, K = B
     const float *dh;
     const T *a3;
     float *g;
     int F;
     long long fcw, fcb;
-    HTS_HD void load_a(int j, int b, int kend, float (&v)[VA]) const
+    HTS_HD CtxA ctx_a(int j) const { return {j}; }
+    HTS_HD CtxB ctx_b(int f) const { return {f}; }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int b, int kend) const
     {
-        if (b < kend) load_vec(dh + (long long)b * 512 + j, v); else zero_vec(v);   // M = 512 is a multiple of BM
+        return b < kend ? load_vec<T, VA>(dh + (long long)b * 512 + c.j) : zero_vec<T, VA>();   // M = 512: no row tail
     }
-    HTS_HD void load_b(int f, int b, int kend, float (&v)[VB]) const
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int b, int kend) const
     {
-        if (b < kend && f < F) load_vec(a3 + (long long)b * F + f, v);
-        else { zero_vec(v); if (b < kend && f == F) v[0] = 1.0f; }
+        if (b < kend && c.f < F) return load_vec<T, VB>(a3 + (long long)b * F + c.f);
+        Vec<T, VB> v = zero_vec<T, VB>();
+        if (b < kend && c.f == F) v[0] = from_f32<T>(1.0f);
+        return v;
     }
     HTS_HD void store(int j, int f, float acc, int) const
     {
@@ -220,25 +264,30 @@ template <typename T_> struct FcWgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcDgrad {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = 32, WAVES_M = 2;
+    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = 4, VB = 4;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = false;
+    typedef OffCtx CtxA;
+    struct CtxB { int f; };
     int M, N, K, klen;     // M = B, N = F, K = 512
     const float *dh, *w;
     const T *a3;
     T *dy3;
     int P3;
-    HTS_HD void load_a(int b, int k, int kend, float (&v)[VA]) const
+    FastDiv dP3;
+    HTS_HD CtxA ctx_a(int b) const { return {b < M ? (long long)b * 512 : -1}; }
+    HTS_HD CtxB ctx_b(int f) const { return {f}; }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (b < M && k < kend) load_vec(dh + (long long)b * 512 + k, v); else zero_vec(v);
+        return (c.off >= 0 && k < kend) ? load_vec<T, VA>(dh + c.off + k) : zero_vec<T, VA>();
     }
-    HTS_HD void load_b(int f, int j, int kend, float (&v)[VB]) const
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int j, int kend) const
     {
-        if (j < kend && f < N) load_vec(w + (long long)j * N + f, v); else zero_vec(v);      // N = F is a multiple of 4
+        return (j < kend && c.f < N) ? load_vec<T, VB>(w + (long long)j * N + c.f) : zero_vec<T, VB>();   // F % 4 == 0
     }
     HTS_HD void store(int b, int f, float acc, int) const
     {
-        const int c = f / P3, p = f - c * P3;
+        const int c = dP3.div(f), p = f - c * P3;
         const float a = to_f32(a3[(long long)b * N + f]);
         dy3[((long long)b * P3 + p) * 64 + c] = from_f32<T>(a > 0.0f ? acc : 0.0f);
     }
@@ -252,81 +301,126 @@ template <typename T_> struct FcDgrad {
 //   M = B*Hc*Wc (positions of the class),  N = Cin,  K = (ksz/s)^2 * Cout,  k = (a, bb, n),
 // launched as one batch entry per class (no multiplications by structural zeros).  wd = [Cin][(u,v,n)].
 // ------------------------------------------------------------------------------------------------------------
-template <typename T_, int BN_> struct ConvDgrad {
+template <typename T_, class L> struct ConvDgrad {
     using T = T_;
-    static constexpr int BM = (BN_ == 32 ? 128 : 64), BN = BN_, BK = 32, WAVES_M = (BN_ == 32 ? 4 : 2);
+    static constexpr int BN = L::CIN, BM = (BN == 32 ? 128 : 64), BK = OperandTraits<T>::BK, WAVES_M = (BN == 32 ? 4 : 2),
+                         WAVES_N = 4 / WAVES_M;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    int M, N, K, klen;     // M is per class (set_batch); N = Cin; K = (ksz/s)^2 * Cout
+    static constexpr int TK = L::KSZ / L::STRIDE;                  // taps per axis within a class
+    static constexpr int KC = TK * TK * L::COUT;                   // contraction length per class
+    static constexpr int NCLS = L::STRIDE * L::STRIDE;
+    static_assert(NCLS <= 4, "at most four parity classes");
+    struct CtxA { long long off; int yy, xx; };
+    struct CtxB { long long off; int py, px; };
+    struct Cls { int py, px, Hc, Wc, M; FastDiv dHW, dW; };       // one parity class
+    int M, N, K, klen;     // M = rows of the largest class (grid size); N = Cin; K = KC
     const T *dy;           // [B][Ho][Wo][Cout]
     const T *wd;           // [Cin][ksz*ksz*Cout]
     const T *act_in;       // [B][Hin][Win][Cin] post-ReLU output of the layer below
     T *dy_in;              // [B][Hin][Win][Cin]
-    int Bn, Hin, Win, Ho, Wo, Cout, ksz, stride;
-    int py, px, Hc, Wc;    // current class and its extent
-    HTS_HD int batches() const { return stride * stride; }
-    HTS_HD int max_m() const { return Bn * ((Hin + stride - 1) / stride) * ((Win + stride - 1) / stride); }
-    HTS_HD void set_batch(int z)
+    int Bn, Hin, Win, Ho, Wo;
+    FastDiv dHW0, dHW1, dHW2, dHW3, dW0, dW1, dW2, dW3;   // per class: division by Hc*Wc and by Wc
+    HTS_HD int batches() const { return NCLS; }
+    HTS_HD int max_m() const { return Bn * ((Hin + L::STRIDE - 1) / L::STRIDE) * ((Win + L::STRIDE - 1) / L::STRIDE); }
+    HTS_HD Cls cls(int z) const       // the problem object itself is never modified, so it stays in registers
     {
-        py = z / stride; px = z - py * stride;
-        Hc = (Hin - py + stride - 1) / stride; Wc = (Win - px + stride - 1) / stride;
-        M = Bn * Hc * Wc;
+        Cls c;
+        c.py = z / L::STRIDE; c.px = z - c.py * L::STRIDE;
+        c.Hc = (Hin - c.py + L::STRIDE - 1) / L::STRIDE; c.Wc = (Win - c.px + L::STRIDE - 1) / L::STRIDE;
+        c.M = Bn * c.Hc * c.Wc;
+        c.dHW = z == 0 ? dHW0 : z == 1 ? dHW1 : z == 2 ? dHW2 : dHW3;
+        c.dW = z == 0 ? dW0 : z == 1 ? dW1 : z == 2 ? dW2 : dW3;
+        return c;
     }
-    HTS_HD void load_a(int m, int k, int kend, float (&v)[VA]) const
+    HTS_HD int batch_m(int z) const { return cls(z).M; }
+    void prepare()      // host: division constants of every class
     {
-        if (m < M && k < kend) {
-            const int b = m / (Hc * Wc), p = m - b * (Hc * Wc), yy = p / Wc, xx = p - yy * Wc;
-            const int tap = k / Cout, n = k - tap * Cout, tk = ksz / stride, a = tap / tk, bb = tap - a * tk;
-            const int oy = yy - a, ox = xx - bb;         // (y - u)/s with y = yy*s + py, u = py + s*a
-            if (oy >= 0 && ox >= 0 && oy < Ho && ox < Wo) {
-                load_vec(dy + (((long long)b * Ho + oy) * Wo + ox) * Cout + n, v);
-                return;
-            }
+        FastDiv hw[4], ww[4];
+        for (int z = 0; z < 4; ++z) {
+            const Cls c = cls(z < NCLS ? z : 0);
+            hw[z] = FastDiv::make(c.Hc * c.Wc); ww[z] = FastDiv::make(c.Wc);
         }
-        zero_vec(v);
+        dHW0 = hw[0]; dHW1 = hw[1]; dHW2 = hw[2]; dHW3 = hw[3];
+        dW0 = ww[0]; dW1 = ww[1]; dW2 = ww[2]; dW3 = ww[3];
+        M = max_m();
     }
-    HTS_HD void load_b(int c, int k, int kend, float (&v)[VB]) const
+    HTS_HD CtxA ctx_a(int m, int z) const
     {
-        if (c < N && k < kend) {
-            const int tap = k / Cout, n = k - tap * Cout, tk = ksz / stride, a = tap / tk, bb = tap - a * tk;
-            const int u = py + stride * a, vv = px + stride * bb;
-            load_vec(wd + ((long long)c * ksz * ksz + u * ksz + vv) * Cout + n, v);
-        } else zero_vec(v);
+        const Cls c = cls(z);
+        if (m >= c.M) return {-1, 0, 0};
+        const int b = c.dHW.div(m), p = m - b * (c.Hc * c.Wc), yy = c.dW.div(p), xx = p - yy * c.Wc;
+        return {(((long long)b * Ho + yy) * Wo + xx) * L::COUT, yy, xx};
     }
-    HTS_HD void store(int m, int c, float acc, int) const
+    HTS_HD CtxB ctx_b(int ch, int z) const
     {
-        const int b = m / (Hc * Wc), p = m - b * (Hc * Wc), yy = p / Wc, xx = p - yy * Wc;
-        const long long o = ((((long long)b * Hin + yy * stride + py) * Win) + xx * stride + px) * N + c;
+        const int py = z / L::STRIDE;
+        return {ch < N ? (long long)ch * L::KSZ * L::KSZ * L::COUT : -1, py, z - py * L::STRIDE};
+    }
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
+    {
+        if (c.off >= 0 && k < kend) {
+            const int tap = k / L::COUT, n = k - tap * L::COUT, a = tap / TK, bb = tap - a * TK;
+            const int oy = c.yy - a, ox = c.xx - bb;         // (y - u)/s with y = yy*s + py, u = py + s*a
+            if (oy >= 0 && ox >= 0 && oy < Ho && ox < Wo)
+                return load_vec<T, VA>(dy + c.off - (long long)(a * Wo + bb) * L::COUT + n);
+        }
+        return zero_vec<T, VA>();
+    }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
+    {
+        if (c.off < 0 || k >= kend) return zero_vec<T, VB>();
+        const int tap = k / L::COUT, n = k - tap * L::COUT, a = tap / TK, bb = tap - a * TK;
+        const int u = c.py + L::STRIDE * a, vv = c.px + L::STRIDE * bb;
+        return load_vec<T, VB>(wd + c.off + (u * L::KSZ + vv) * L::COUT + n);
+    }
+    HTS_HD void store(int m, int ch, float acc, int, int z) const
+    {
+        const Cls c = cls(z);
+        const int b = c.dHW.div(m), p = m - b * (c.Hc * c.Wc), yy = c.dW.div(p), xx = p - yy * c.Wc;
+        const long long o = ((((long long)b * Hin + yy * L::STRIDE + c.py) * Win) + xx * L::STRIDE + c.px) * N + ch;
         const float a = to_f32(act_in[o]);
         dy_in[o] = from_f32<T>(a > 0.0f ? acc : 0.0f);
     }
 };
 
 // ------------------------------------------------------------------------------------------------------------
-// conv weight gradient (layers 3 and 2), split over blockIdx.y along the B*Ho*Wo reduction:
+// conv weight gradient (layers 3 and 2), split along the B*Ho*Wo reduction:
 // part[z][n][kcol] = sum_{m in chunk z} dy[m][n] * (kcol < K ? im2col(in)[m][kcol] : 1); column K is the bias.
 // ------------------------------------------------------------------------------------------------------------
-template <typename T_> struct ConvWgrad {
+template <typename T_, class L> struct ConvWgrad {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = 32, WAVES_M = 2;
+    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
-    int M, N, K, klen;     // M = Cout (64), N = Kc + 1, K = B*Po
+    struct CtxA { int n; };
+    struct CtxB { long long goff; };   // offset of (u,v,c) inside a patch; -1: bias column; -2: beyond the last column
+    int M, N, K, klen;     // M = Cout (64), N = L::K + 1, K = B*Po
     const T *dy;           // [B*Po][Cout]
     const T *in;           // [B][Hin][Win][Cin]
     float *part;           // [nz][Cout][N]
-    int Kc, Cin, Hin, Win, ksz, stride, Wo, Po;
-    HTS_HD void load_a(int n, int m, int kend, float (&v)[VA]) const
+    int Hin, Win, Wo, Po;
+    FastDiv dPo, dWo;
+    HTS_HD CtxA ctx_a(int n) const { return {n}; }
+    HTS_HD CtxB ctx_b(int kcol) const
     {
-        if (m < kend) load_vec(dy + (long long)m * M + n, v); else zero_vec(v);       // M = 64 = BM
+        if (kcol >= L::K) return {kcol == L::K ? -1ll : -2ll};
+        const int u = kcol / (L::KSZ * L::CIN), r = kcol - u * (L::KSZ * L::CIN);
+        return {(long long)u * Win * L::CIN + r};
     }
-    HTS_HD void load_b(int kcol, int m, int kend, float (&v)[VB]) const
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int m, int kend) const
     {
-        if (m < kend && kcol < Kc) {
-            const int b = m / Po, p = m - b * Po, oy = p / Wo, ox = p - oy * Wo;
-            const int tap = kcol / Cin, c = kcol - tap * Cin, u = tap / ksz, vv = tap - u * ksz;
-            load_vec(in + (((long long)b * Hin + oy * stride + u) * Win + ox * stride + vv) * Cin + c, v);
-        } else { zero_vec(v); if (m < kend && kcol == Kc) v[0] = 1.0f; }
+        return m < kend ? load_vec<T, VA>(dy + (long long)m * L::COUT + c.n) : zero_vec<T, VA>();      // M = 64 = BM
+    }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int m, int kend) const
+    {
+        if (m < kend && c.goff >= 0) {
+            const int b = dPo.div(m), p = m - b * Po, oy = dWo.div(p), ox = p - oy * Wo;
+            return load_vec<T, VB>(in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN + c.goff);
+        }
+        Vec<T, VB> v = zero_vec<T, VB>();
+        if (m < kend && c.goff == -1) v[0] = from_f32<T>(1.0f);
+        return v;
     }
     HTS_HD void store(int n, int kcol, float acc, int z) const
     {
@@ -337,35 +431,40 @@ template <typename T_> struct ConvWgrad {
 // conv1 weight gradient: as above with the uint8 frames as the im2col source, kcol = (c,u,v)
 template <typename T_> struct Conv1Wgrad {
     using T = T_;
-    static constexpr int BM = 32, BN = 128, BK = 32, WAVES_M = 1;
+    static constexpr int BM = 32, BN = 128, BK = OperandTraits<T>::BK, WAVES_M = 1, WAVES_N = 4;
     static constexpr int VA = OperandTraits<T>::VEC, VB = 8;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
+    struct CtxA { int n; };
+    struct CtxB { long long goff; };
     int M, N, K, klen;     // M = 32, N = C*64 + 1, K = B*P1
     const T *dy;           // [B*P1][32]
     const uint8_t *obs;
     const int32_t *index;
     float *part;           // [nz][32][N]
     int Kc, C, H, W, W1, P1;
-    HTS_HD void load_a(int n, int m, int kend, float (&v)[VA]) const
+    FastDiv dP1, dW1;
+    HTS_HD CtxA ctx_a(int n) const { return {n}; }
+    HTS_HD CtxB ctx_b(int kcol) const
     {
-        if (m < kend) load_vec(dy + (long long)m * 32 + n, v); else zero_vec(v);
+        if (kcol >= Kc) return {kcol == Kc ? -1ll : -2ll};
+        const int c = kcol >> 6, u = (kcol >> 3) & 7;
+        return {((long long)c * H + u) * W};
     }
-    HTS_HD void load_b(int kcol, int m, int kend, float (&v)[VB]) const
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int m, int kend) const
     {
-        if (m < kend && kcol < Kc) {
-            const int b = m / P1, p = m - b * P1, oy = p / W1, ox = p - oy * W1;
-            const int c = kcol >> 6, u = (kcol >> 3) & 7;
+        return m < kend ? load_vec<T, VA>(dy + (long long)m * 32 + c.n) : zero_vec<T, VA>();
+    }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int m, int kend) const
+    {
+        if (m < kend && c.goff >= 0) {
+            const int b = dP1.div(m), p = m - b * P1, oy = dW1.div(p), ox = p - oy * W1;
             const long long row = index ? index[b] : b;
-            const uint8_t *src = obs + ((row * C + c) * H + (oy * 4 + u)) * (long long)W + ox * 4;
-            const uint32_t lo = *reinterpret_cast<const uint32_t *>(src);
-            const uint32_t hi = *reinterpret_cast<const uint32_t *>(src + 4);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[i] = (float)((lo >> (8 * i)) & 0xFFu);
-                v[4 + i] = (float)((hi >> (8 * i)) & 0xFFu);
-            }
-        } else { zero_vec(v); if (m < kend && kcol == Kc) v[0] = 255.0f; }   // the 1/255 of the input scaling is
-    }                                                                        // applied when partials are combined
+            return load_u8x8<T>(obs + row * C * H * W + (long long)(oy * 4) * W + ox * 4 + c.goff);
+        }
+        Vec<T, VB> v = zero_vec<T, VB>();
+        if (m < kend && c.goff == -1) v[0] = from_f32<T>(255.0f);   // the 1/255 of the input scaling is applied
+        return v;                                                    // when the partials are combined
+    }
     HTS_HD void store(int n, int kcol, float acc, int z) const
     {
         part[((long long)z * 32 + n) * N + kcol] = acc;

@@ -20,73 +20,115 @@
 namespace hts {
 
 template <class P, int WAVES, int SEG, bool PARTIAL>
-__global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p_in, const int spg)
+__global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int spg)
 {
-    P p = p_in;
-    if constexpr (HasBatch<P>::value) p.set_batch(blockIdx.z);
+    const int zb = blockIdx.z, M = rows_of(p, zb);
     using T = typename P::T;
     using Tr = OperandTraits<T>;
     constexpr int LS = SEG + Tr::PAD;
     constexpr int VA = P::VA, VB = P::VB;
-    constexpr int CA = 32 * SEG / VA, CB = 32 * SEG / VB;      // vectors per operand panel
+    // work items per operand panel: a k-contiguous vector (ALONG_K) or a V x V block to transpose (otherwise)
+    constexpr int CA = P::A_ALONG_K ? 32 * SEG / VA : (32 / VA) * (SEG / VA);
+    constexpr int CB = P::B_ALONG_K ? 32 * SEG / VB : (32 / VB) * (SEG / VB);
     constexpr int NA = (CA + 63) / 64, NB = (CB + 63) / 64;
+    constexpr int RA = P::A_ALONG_K ? 1 : VA, RB = P::B_ALONG_K ? 1 : VB;
     static_assert(SEG % Tr::KINST == 0 && SEG % VA == 0 && SEG % VB == 0 && 32 % VA == 0 && 32 % VB == 0, "segment shape");
+    constexpr size_t PANEL_BYTES = (size_t)2 * 32 * LS * sizeof(T);          // both operand panels of one wavefront
+    static_assert(PARTIAL || PANEL_BYTES >= 4096, "the fold reuses a wavefront's panels for its 32x32 partial tile");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T *panels = reinterpret_cast<T *>(smem);                                   // [WAVES][2][32*LS]
-    float *red = reinterpret_cast<float *>(smem + (size_t)WAVES * 2 * 32 * LS * sizeof(T));   // [WAVES][1024]
-
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    T *As = reinterpret_cast<T *>(smem + (size_t)w * PANEL_BYTES), *Bs = As + 32 * LS;
     const int tiles_n = (p.N + 31) / 32;
     const int m0 = (blockIdx.x / tiles_n) * 32, n0 = (blockIdx.x % tiles_n) * 32;
-    if (m0 >= p.M) return;
+    if (m0 >= M) return;
     const int nseg = (p.K + SEG - 1) / SEG;
-    T *As = panels + (size_t)w * 2 * 32 * LS, *Bs = As + 32 * LS;
     const int lrow = lane & 31, lk = lane >> 5;
+
+    // fixed assignment of panel items to lanes; the row part of every gather is resolved once per wavefront
+    typename P::CtxA ca[NA];
+    typename P::CtxB cb[NB];
+    int ka[NA], kb[NB], la[NA], lb[NB];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int id = lane + i * 64;
+        int r;
+        if constexpr (P::A_ALONG_K) { r = id / (SEG / VA); ka[i] = (id % (SEG / VA)) * VA; }
+        else { r = (id % (32 / VA)) * VA; ka[i] = (id / (32 / VA)) * VA; }
+        la[i] = r * LS + ka[i];
+        ca[i] = make_ctx_a(p, m0 + r, zb);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int id = lane + i * 64;
+        int r;
+        if constexpr (P::B_ALONG_K) { r = id / (SEG / VB); kb[i] = (id % (SEG / VB)) * VB; }
+        else { r = (id % (32 / VB)) * VB; kb[i] = (id / (32 / VB)) * VB; }
+        lb[i] = r * LS + kb[i];
+        cb[i] = make_ctx_b(p, n0 + r, zb);
+    }
+    constexpr bool VEC_LDS = sizeof(T) == 2;
 
     auto segment_sum = [&](int seg) -> f32x16 {
         const int kbeg = seg * SEG, kend = min(p.K, kbeg + SEG);
-        float ra[NA][VA], rb[NB][VB];
+        Vec<T, VA> ra[NA][RA];
+        Vec<T, VB> rb[NB][RB];
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+            if (CA % 64 == 0 || lane + i * 64 < CA)
+#pragma unroll
+                for (int q = 0; q < RA; ++q) ra[i][q] = p.load_a(ca[i], kbeg + ka[i] + q, kend);
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+            if (CB % 64 == 0 || lane + i * 64 < CB)
+#pragma unroll
+                for (int q = 0; q < RB; ++q) rb[i][q] = p.load_b(cb[i], kbeg + kb[i] + q, kend);
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            const int id = lane + i * 64;
-            if (CA % 64 != 0 && id >= CA) continue;
-            if constexpr (P::A_ALONG_K) p.load_a(m0 + id / (SEG / VA), kbeg + (id % (SEG / VA)) * VA, kend, ra[i]);
-            else                        p.load_a(m0 + (id % (32 / VA)) * VA, kbeg + id / (32 / VA), kend, ra[i]);
-        }
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int id = lane + i * 64;
-            if (CB % 64 != 0 && id >= CB) continue;
-            if constexpr (P::B_ALONG_K) p.load_b(n0 + id / (SEG / VB), kbeg + (id % (SEG / VB)) * VB, kend, rb[i]);
-            else                        p.load_b(n0 + (id % (32 / VB)) * VB, kbeg + id / (32 / VB), kend, rb[i]);
-        }
-#pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int id = lane + i * 64;
-            if (CA % 64 != 0 && id >= CA) continue;
+            if (CA % 64 != 0 && lane + i * 64 >= CA) continue;
+            T *d = As + la[i];
             if constexpr (P::A_ALONG_K) {
-                T *d = As + (id / (SEG / VA)) * LS + (id % (SEG / VA)) * VA;
+                if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VA> *>(d) = ra[i][0];
+                else {
 #pragma unroll
-                for (int j = 0; j < VA; ++j) d[j] = from_f32<T>(ra[i][j]);
+                    for (int j = 0; j < VA; ++j) d[j] = ra[i][0][j];
+                }
             } else {
-                T *d = As + ((id % (32 / VA)) * VA) * LS + id / (32 / VA);
 #pragma unroll
-                for (int j = 0; j < VA; ++j) d[j * LS] = from_f32<T>(ra[i][j]);
+                for (int j = 0; j < VA; ++j) {
+                    Vec<T, VA> t;
+#pragma unroll
+                    for (int q = 0; q < VA; ++q) t[q] = ra[i][q][j];
+                    if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VA> *>(d + j * LS) = t;
+                    else {
+#pragma unroll
+                        for (int q = 0; q < VA; ++q) d[j * LS + q] = t[q];
+                    }
+                }
             }
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int id = lane + i * 64;
-            if (CB % 64 != 0 && id >= CB) continue;
+            if (CB % 64 != 0 && lane + i * 64 >= CB) continue;
+            T *d = Bs + lb[i];
             if constexpr (P::B_ALONG_K) {
-                T *d = Bs + (id / (SEG / VB)) * LS + (id % (SEG / VB)) * VB;
+                if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VB> *>(d) = rb[i][0];
+                else {
 #pragma unroll
-                for (int j = 0; j < VB; ++j) d[j] = from_f32<T>(rb[i][j]);
+                    for (int j = 0; j < VB; ++j) d[j] = rb[i][0][j];
+                }
             } else {
-                T *d = Bs + ((id % (32 / VB)) * VB) * LS + id / (32 / VB);
 #pragma unroll
-                for (int j = 0; j < VB; ++j) d[j * LS] = from_f32<T>(rb[i][j]);
+                for (int j = 0; j < VB; ++j) {
+                    Vec<T, VB> t;
+#pragma unroll
+                    for (int q = 0; q < VB; ++q) t[q] = rb[i][q][j];
+                    if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VB> *>(d + j * LS) = t;
+                    else {
+#pragma unroll
+                        for (int q = 0; q < VB; ++q) d[j * LS + q] = t[q];
+                    }
+                }
             }
         }
         // the panels are private to this wavefront and a wavefront's LDS operations execute in order
@@ -114,7 +156,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p_in, const 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + 8 * (r / 4) + 4 * lk + (r % 4);
-            if (m < p.M && n < p.N) p.store(m, n, acc[r], seg);
+            if (m < M && n < p.N) do_store(p, m, n, acc[r], seg, zb);
         }
     } else {
         constexpr int PER = 1024 / (WAVES * 64);        // tile elements owned by each thread in the fold
@@ -128,14 +170,17 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p_in, const 
             const int seg = gbeg + rd * WAVES + w;
             if (seg < gend) {
                 const f32x16 acc = segment_sum(seg);
+                // this wavefront's panels are free again: they now carry its partial tile (r*64 + lane order)
+                float *mine = reinterpret_cast<float *>(smem + (size_t)w * PANEL_BYTES);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) red[w * 1024 + r * 64 + lane] = acc[r];
+                for (int r = 0; r < 16; ++r) mine[r * 64 + lane] = acc[r];
             }
             __syncthreads();
             const int live = min(WAVES, gend - gbeg - rd * WAVES);
 #pragma unroll
             for (int e = 0; e < PER; ++e)
-                for (int ww = 0; ww < live; ++ww) total[e] += red[ww * 1024 + e * (WAVES * 64) + tid];
+                for (int ww = 0; ww < live; ++ww)
+                    total[e] += reinterpret_cast<const float *>(smem + (size_t)ww * PANEL_BYTES)[e * (WAVES * 64) + tid];
             __syncthreads();
         }
 #pragma unroll
@@ -143,7 +188,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p_in, const 
             const int idx = e * (WAVES * 64) + tid;          // = r*64 + lane of the accumulator layout
             const int r = idx >> 6, l = idx & 63;
             const int m = m0 + 8 * (r / 4) + 4 * (l >> 5) + (r % 4), n = n0 + (l & 31);
-            if (m < p.M && n < p.N) p.store(m, n, total[e], (int)blockIdx.y);
+            if (m < M && n < p.N) do_store(p, m, n, total[e], (int)blockIdx.y, zb);
         }
     }
 }
@@ -155,7 +200,7 @@ inline hipError_t launch_wsgemm(const P &p, hipStream_t stream, int segs_per_gro
     const int tiles = ((grid_rows(p) + 31) / 32) * ((p.N + 31) / 32);
     const int nseg = (p.K + SEG - 1) / SEG;
     if (tiles <= 0 || nseg <= 0) return hipSuccess;
-    const size_t lds = (size_t)WAVES * 2 * 32 * (SEG + OperandTraits<T>::PAD) * sizeof(T) + (PARTIAL ? 0 : (size_t)WAVES * 4096);
+    const size_t lds = (size_t)WAVES * 2 * 32 * (SEG + OperandTraits<T>::PAD) * sizeof(T);
     auto kern = wsgemm_kernel<P, WAVES, SEG, PARTIAL>;
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
     if (!attr_set) {
