@@ -465,12 +465,67 @@ __global__ __launch_bounds__(64) void gae_kernel(const float *__restrict__ r, co
     }
 }
 
+// Time-chunked form for short-and-narrow storages (few environments): a workgroup owns 32 columns and cuts time into
+// TC chunks, one wavefront-row per chunk.  A_t = delta_t + c_t A_{t+1} is affine in the carry entering a chunk, so
+// pass 1 reduces every chunk to (S, P) with A_first = S + P * carry, the carries are chained through LDS in chunk
+// order, and pass 2 replays each chunk from its true carry and writes the outputs.  Double precision throughout, so
+// the result equals the one-lane-per-column recurrence to well below binary32 rounding.
+constexpr int GAE_COLS = 32, GAE_MAX_TC = 16;
+__global__ __launch_bounds__(GAE_COLS * GAE_MAX_TC) void gae_chunked_kernel(
+    const float *__restrict__ r, const float *__restrict__ v, const uint8_t *__restrict__ d, float gamma, float lambda,
+    int T, int N, int TC, int L, float *__restrict__ adv, float *__restrict__ ret)
+{
+    __shared__ double sS[GAE_MAX_TC][GAE_COLS], sP[GAE_MAX_TC][GAE_COLS];
+    const int cx = threadIdx.x % GAE_COLS, cc = threadIdx.x / GAE_COLS;
+    const int n = blockIdx.x * GAE_COLS + cx;
+    const int t0 = cc * L, t1 = min(T, t0 + L);                 // this thread's chunk [t0, t1)
+    const bool live = n < N && t0 < t1;
+    const double g = (double)gamma, gl = (double)gamma * (double)lambda;
+    double S = 0.0, P = 1.0;
+    if (live) {
+        double vnext = (double)v[(long long)t1 * N + n];
+        for (int t = t1 - 1; t >= t0; --t) {
+            const long long o = (long long)t * N + n;
+            const double vt = (double)v[o], nd = d[o] ? 0.0 : 1.0;
+            const double delta = (double)r[o] + g * nd * vnext - vt, ct = gl * nd;
+            S = delta + ct * S;
+            P = ct * P;
+            vnext = vt;
+        }
+    }
+    sS[cc][cx] = S; sP[cc][cx] = P;
+    __syncthreads();
+    if (!live) return;
+    double a = 0.0;                                              // advantage entering this chunk from later times
+    for (int q = TC - 1; q > cc; --q) a = sS[q][cx] + sP[q][cx] * a;
+    double vnext = (double)v[(long long)t1 * N + n];
+    for (int t = t1 - 1; t >= t0; --t) {
+        const long long o = (long long)t * N + n;
+        const double vt = (double)v[o], nd = d[o] ? 0.0 : 1.0;
+        const double delta = (double)r[o] + g * nd * vnext - vt;
+        a = delta + gl * nd * a;
+        adv[o] = (float)a;
+        ret[o] = (float)(a + vt);
+        vnext = vt;
+    }
+}
+
 hipError_t launch_gae(Ctx *c, hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda,
                       int T, int N, float *adv, float *ret)
 {
     Ctx dummy;
     SiteTimer tm(c ? *c : dummy, SITE_GAE);
-    hipLaunchKernelGGL(gae_kernel, dim3((N + 63) / 64), dim3(64), 0, s, r, v, d, gamma, lambda, T, N, adv, ret);
+    // enough columns to fill the chip with one lane each -> plain kernel; otherwise split time as well
+    if ((long long)N >= 16384 || T < 16) {
+        hipLaunchKernelGGL(gae_kernel, dim3((N + 63) / 64), dim3(64), 0, s, r, v, d, gamma, lambda, T, N, adv, ret);
+    } else {
+        int TC = T / 8;                       // chunks of at least 8 steps
+        if (TC > GAE_MAX_TC) TC = GAE_MAX_TC;
+        if (TC < 2) TC = 2;
+        const int L = (T + TC - 1) / TC;
+        hipLaunchKernelGGL(gae_chunked_kernel, dim3((N + GAE_COLS - 1) / GAE_COLS), dim3(GAE_COLS * TC), 0, s, r, v, d,
+                           gamma, lambda, T, N, TC, L, adv, ret);
+    }
     return hipGetLastError();
 }
 
