@@ -43,7 +43,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.dPo = FastDiv::make(g.P3); p.dWo = FastDiv::make(g.W3);
         {
             SiteTimer tm(c, SITE_CONV3_FWD);
-            e = small ? launch_wsgemm<ConvFwd<T, Layer3, true>, 4, ConvFwd<T, Layer3, true>::SEG, false>(p, c.stream)
+            e = small ? launch_wsgemm<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 8 : 4), ConvFwd<T, Layer3, true>::SEG, false, true>(p, c.stream)
                       : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;

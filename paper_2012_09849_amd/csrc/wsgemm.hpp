@@ -19,9 +19,13 @@
 
 namespace hts {
 
-template <class P, int WAVES, int SEG, bool PARTIAL>
+// BDIR = true (needs B_ALONG_K): the B operand (a weight matrix, rows contiguous in k) skips LDS -- every lane
+// loads the k-vectors of its own column straight into registers and picks the elements its MFMA slot needs.  That
+// halves the LDS footprint, so twice as many wavefronts (segments) fit in one workgroup.
+template <class P, int WAVES, int SEG, bool PARTIAL, bool BDIR = false>
 __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int spg)
 {
+    static_assert(!BDIR || P::B_ALONG_K, "direct B operands must be contiguous along k");
     const int zb = blockIdx.z, M = rows_of(p, zb);
     using T = typename P::T;
     using Tr = OperandTraits<T>;
@@ -33,7 +37,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
     constexpr int NA = (CA + 63) / 64, NB = (CB + 63) / 64;
     constexpr int RA = P::A_ALONG_K ? 1 : VA, RB = P::B_ALONG_K ? 1 : VB;
     static_assert(SEG % Tr::KINST == 0 && SEG % VA == 0 && SEG % VB == 0 && 32 % VA == 0 && 32 % VB == 0, "segment shape");
-    constexpr size_t PANEL_BYTES = (size_t)2 * 32 * LS * sizeof(T);          // both operand panels of one wavefront
+    constexpr size_t PANEL_BYTES = (size_t)(BDIR ? 1 : 2) * 32 * LS * sizeof(T);   // operand panel(s) of one wavefront
     static_assert(PARTIAL || PANEL_BYTES >= 4096, "the fold reuses a wavefront's panels for its 32x32 partial tile");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -68,21 +72,36 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         cb[i] = make_ctx_b(p, n0 + r, zb);
     }
     constexpr bool VEC_LDS = sizeof(T) == 2;
+    const typename P::CtxB cbd = make_ctx_b(p, n0 + lrow, zb);      // this lane's own column (direct B operands)
+    constexpr int NBD = BDIR ? (sizeof(T) == 4 ? SEG / VB : (SEG / 16) * (8 / VB)) : 1;
 
     auto segment_sum = [&](int seg) -> f32x16 {
         const int kbeg = seg * SEG, kend = min(p.K, kbeg + SEG);
         Vec<T, VA> ra[NA][RA];
-        Vec<T, VB> rb[NB][RB];
+        Vec<T, VB> rb[BDIR ? 1 : NB][RB];
+        Vec<T, VB> rbd[NBD];
+        if constexpr (BDIR) {
+            if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                for (int q = 0; q < NBD; ++q) rbd[q] = p.load_b(cbd, kbeg + q * VB, kend);
+            } else {        // slot t of this lane covers k = 16 t + 8 lk .. +7
+#pragma unroll
+                for (int q = 0; q < NBD; ++q)
+                    rbd[q] = p.load_b(cbd, kbeg + 16 * (q / (8 / VB)) + 8 * lk + VB * (q % (8 / VB)), kend);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < NA; ++i)
             if (CA % 64 == 0 || lane + i * 64 < CA)
 #pragma unroll
                 for (int q = 0; q < RA; ++q) ra[i][q] = p.load_a(ca[i], kbeg + ka[i] + q, kend);
+        if constexpr (!BDIR) {
 #pragma unroll
-        for (int i = 0; i < NB; ++i)
-            if (CB % 64 == 0 || lane + i * 64 < CB)
+            for (int i = 0; i < NB; ++i)
+                if (CB % 64 == 0 || lane + i * 64 < CB)
 #pragma unroll
-                for (int q = 0; q < RB; ++q) rb[i][q] = p.load_b(cb[i], kbeg + kb[i] + q, kend);
+                    for (int q = 0; q < RB; ++q) rb[i][q] = p.load_b(cb[i], kbeg + kb[i] + q, kend);
+        }
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             if (CA % 64 != 0 && lane + i * 64 >= CA) continue;
@@ -108,7 +127,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
             }
         }
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
+        for (int i = 0; i < (BDIR ? 0 : NB); ++i) {
             if (CB % 64 != 0 && lane + i * 64 >= CB) continue;
             T *d = Bs + lb[i];
             if constexpr (P::B_ALONG_K) {
@@ -137,13 +156,33 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
         const T *a = As + lrow * LS, *b = Bs + lrow * LS;
+        if constexpr (!BDIR) {
 #pragma unroll 8
-        for (int kk = 0; kk < SEG; kk += Tr::KINST) {
-            if constexpr (sizeof(T) == 4)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk + lk], b[kk + lk], acc, 0, 0, 0);
-            else
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(a + kk + lk * 8),
-                                                              *reinterpret_cast<const bf16x8 *>(b + kk + lk * 8), acc, 0, 0, 0);
+            for (int kk = 0; kk < SEG; kk += Tr::KINST) {
+                if constexpr (sizeof(T) == 4)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk + lk], b[kk + lk], acc, 0, 0, 0);
+                else
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(a + kk + lk * 8),
+                                                                  *reinterpret_cast<const bf16x8 *>(b + kk + lk * 8), acc, 0, 0, 0);
+            }
+        } else if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int t = 0; t < SEG / 2; ++t) {          // slot t needs k = 2 t + lk: one of two neighbours in a vector
+                const float b0 = rbd[(2 * t) / VB][(2 * t) % VB], b1 = rbd[(2 * t + 1) / VB][(2 * t + 1) % VB];
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2 * t + lk], lk ? b1 : b0, acc, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < SEG / 16; ++t) {
+                bf16x8 bv;
+                if constexpr (VB == 8) bv = rbd[t];
+                else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) bv[e] = rbd[t * (8 / VB) + e / VB][e % VB];
+                }
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(a + 16 * t + lk * 8), bv,
+                                                              acc, 0, 0, 0);
+            }
         }
         return acc;
     };
@@ -193,15 +232,15 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
     }
 }
 
-template <class P, int WAVES, int SEG, bool PARTIAL>
+template <class P, int WAVES, int SEG, bool PARTIAL, bool BDIR = false>
 inline hipError_t launch_wsgemm(const P &p, hipStream_t stream, int segs_per_group = 1 << 30)
 {
     using T = typename P::T;
     const int tiles = ((grid_rows(p) + 31) / 32) * ((p.N + 31) / 32);
     const int nseg = (p.K + SEG - 1) / SEG;
     if (tiles <= 0 || nseg <= 0) return hipSuccess;
-    const size_t lds = (size_t)WAVES * 2 * 32 * (SEG + OperandTraits<T>::PAD) * sizeof(T);
-    auto kern = wsgemm_kernel<P, WAVES, SEG, PARTIAL>;
+    const size_t lds = (size_t)WAVES * (BDIR ? 1 : 2) * 32 * (SEG + OperandTraits<T>::PAD) * sizeof(T);
+    auto kern = wsgemm_kernel<P, WAVES, SEG, PARTIAL, BDIR>;
     static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
