@@ -189,6 +189,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="atari_a2c_n16_t5_fp32", choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--site", default=None, help="time this launch site instead of discovering the dominant one")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="calibration for hardware counters: run a plain device copy of this many MiB and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); multi-GPU sharding is a design note, not code",
@@ -202,12 +205,28 @@ def main():
 
     cfg = CONFIGS[args.workload]
     torch.cuda.set_device(0)
+    if args.copy_probe > 0:
+        n = args.copy_probe * (1 << 20) // 4
+        src = torch.arange(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_MiB": args.copy_probe, "bytes_read": 4 * n, "bytes_written": 4 * n}))
+        return
     loop = Loop(cfg, hts, torch, syn)
     for _ in range(args.warmup):
         loop.step()
     torch.cuda.synchronize()
     work = site_work(cfg, loop)
-    dominant, per_step = find_dominant(loop, work)
+    if args.site:
+        dominant, per_step = args.site, {}
+        loop.ctx.hts_profile_begin(loop.ctx.profile_sites().index(dominant))
+        loop.step()
+        n1, ms1 = loop.ctx.hts_profile_end()
+        per_step[dominant] = (ms1, n1)
+    else:
+        dominant, per_step = find_dominant(loop, work)
     site_id = loop.ctx.profile_sites().index(dominant)
     torch.cuda.synchronize()
 
