@@ -79,7 +79,9 @@ class Loop:
         c, cfg = self.ctx, self.cfg
         base = self.iteration * (cfg["T"] + 1)
         for t in range(cfg["T"] + 1):
-            c.hts_act(self.obs[t], self.params, 20201209, base + t, 0, self.actions[t], self.logp[t], self.values[t])
+            # the actors keep one parameter version for a whole storage: it is loaded by the first call only
+            c.hts_act(self.obs[t], self.params if t == 0 else None, 20201209, base + t, 0, self.actions[t],
+                      self.logp[t], self.values[t])
 
     def returns(self):
         cfg = self.cfg

@@ -69,7 +69,12 @@ int32_t hts_destroy(hts_ctx *ctx);
 
 /* Actor step (Sec. 4.1 "Asynchronous actors and executors").
  *   obs      u8 [N,C,H,W]    the N observations grabbed in this poll
- *   params   f32 [P]         behaviour parameters
+ *   params   f32 [P] or NULL the behaviour parameters.  Non-NULL: the context first loads them (see hts_sync_params).
+ *                            NULL: the parameters loaded by the most recent hts_sync_params / hts_act(params) /
+ *                            hts_loss_and_grads on this context are used again -- the paper's actors keep one
+ *                            parameter version for a whole storage (Sec. 4.1 "Concurrent rollout and learning"), so
+ *                            only the first step of a rollout needs to pass them.  HTS_EINVAL if nothing is loaded,
+ *                            or if hts_learner_step / hts_adam_apply ran on this context since the last load.
  *   seed, step, env_offset   observation i belongs to environment env_offset+i; its action is drawn with the
  *                            uniform u = top 24 bits of word 0 of Philox4x32-10(key = seed lo/hi,
  *                            counter = (env, step, 0, 0)) * 2^-24, so the action does not depend on which call
@@ -79,6 +84,11 @@ int32_t hts_destroy(hts_ctx *ctx);
  * action = first j with c_j > u * c_{A-1}, else A-1. */
 int32_t hts_act(hts_ctx *ctx, const uint8_t *obs, const float *params, uint64_t seed, uint32_t step, int32_t N,
                 int32_t env_offset, int32_t *actions, float *logp, float *values, float *logits_or_null);
+
+/* Load a parameter vector f32 [P] into the context: the kernels read the network from a copy in the workspace
+ * (matrix operands converted to the context's precision and re-ordered for their gathers), refreshed by this call.
+ * The copy is what hts_act(params = NULL) uses.  The learner calls always load the vector they are given. */
+int32_t hts_sync_params(hts_ctx *ctx, const float *params);
 
 /* The sampling stage of hts_act alone, on caller-supplied logits f32 [N,A] (test hook for bit-exact parity). */
 int32_t hts_sample_from_logits(hts_ctx *ctx, const float *logits, uint64_t seed, uint32_t step, int32_t N,

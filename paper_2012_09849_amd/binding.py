@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libhts.so")
 PRECISION_FP32, PRECISION_BF16 = 0, 1
 ALGO_A2C, ALGO_PPO = 0, 1
 
-EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sample_from_logits", "hts_returns_gae",
+EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
            "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
            "hts_profile_end"]
@@ -73,6 +73,7 @@ def load_library():
         lib.hts_destroy.argtypes = [C.c_void_p]
         lib.hts_act.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.hts_sync_params.argtypes = [C.c_void_p, C.c_void_p]
         lib.hts_sample_from_logits.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
                                                C.c_void_p, C.c_void_p]
         lib.hts_returns_gae.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
@@ -151,6 +152,9 @@ class Context:
                                 _ptr(actions, torch.int32, "actions"), _ptr(logp, torch.float32, "logp"),
                                 _ptr(values, torch.float32, "values"), _ptr(logits, torch.float32, "logits")),
                "hts_act")
+
+    def hts_sync_params(self, params):
+        _check(self.lib.hts_sync_params(self._h, _ptr(params, torch.float32, "params")), "hts_sync_params")
 
     def hts_sample_from_logits(self, logits, seed, step, env_offset, actions, logp):
         N = logits.shape[0]

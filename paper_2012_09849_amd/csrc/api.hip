@@ -83,17 +83,16 @@ void carve(Ctx &c, Carver &cv)
     Workspace &w = c.ws;
     const size_t ts = c.desc.precision == HTS_PRECISION_BF16 ? 2 : 4;
     const size_t mb = (size_t)c.max_b, ml = (size_t)c.max_learn;
-    cv.take(w.wf2, 64 * 512 * ts); cv.take(w.wf3, 64 * 576 * ts);
-    cv.take(w.wd2, 32 * 1024 * ts); cv.take(w.wd3, 64 * 576 * ts);
+    cv.take(w.w1s, (size_t)32 * g.K1 * ts); cv.take(w.wf2, 64 * 512 * ts); cv.take(w.wf3, 64 * 576 * ts);
+    cv.take(w.wfc, (size_t)512 * g.F * ts); cv.take(w.hb, (size_t)c.sh.count * 4);
     cv.take(w.act1, mb * g.P1 * 32 * ts); cv.take(w.act2, mb * g.P2 * 64 * ts); cv.take(w.a3, mb * g.F * ts);
     cv.take(w.h, mb * 512 * 4); cv.take(w.logits, mb * g.A * 4); cv.take(w.val, mb * 4);
-    {
-        const size_t sb = (size_t)(c.small_b < c.max_b ? c.small_b : c.max_b);
-        cv.take(w.fc_part, (size_t)((g.F + 127) / 128) * sb * 512 * 4);
-    }
+    cv.take(w.fc_part, (size_t)c.fc_groups * mb * 512 * 4);
     cv.take(w.clip, 2 * 4);
     cv.take(w.norm_part, (size_t)((g.P + NORM_CHUNK - 1) / NORM_CHUNK) * 4);
     if (ml > 0) {
+        cv.take(w.wd2, 32 * 1024 * ts); cv.take(w.wd3, 64 * 576 * ts); cv.take(w.wfcd, (size_t)512 * g.F * ts);
+        cv.take(w.a3n, ml * g.F * ts);
         cv.take(w.dz, ml * (g.A + 1) * 4); cv.take(w.dh, ml * 512 * 4); cv.take(w.terms, ml * N_TERMS * 4);
         cv.take(w.dy3, ml * g.P3 * 64 * ts); cv.take(w.dy2, ml * g.P2 * 64 * ts); cv.take(w.dy1, ml * g.P1 * 32 * ts);
         cv.take(w.grads, (size_t)g.P * 4);
@@ -121,7 +120,15 @@ extern "C" int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, i
     c.desc = *desc; c.g = g; c.stream = (hipStream_t)hip_stream;
     c.max_act = max_act_batch; c.max_learn = max_learn_batch;
     c.max_b = max_act_batch > max_learn_batch ? max_act_batch : max_learn_batch;
-    c.small_b = 128; c.fc_nseg = 0;
+    c.small_b = 128;
+    c.fc_groups = (g.F + FC_GROUP_K - 1) / FC_GROUP_K;
+    c.synced = false; c.synced_learn = false;
+    {
+        auto pad4 = [](long long x) { return (x + 3) & ~3ll; };
+        ShadowOffsets &s = c.sh;
+        s.b1 = 0; s.b2 = 32; s.b3 = 96; s.fcb = 160; s.piw = 672;
+        s.pib = s.piw + 512ll * g.A; s.vw = pad4(s.pib + g.A); s.vb = s.vw + 512; s.count = pad4(s.vb + 1);
+    }
     if (const char *sb = getenv("HTS_SMALL_BATCH")) c.small_b = atoi(sb);   // tuning knob: 0 disables the small path
     c.ws = Workspace();
     Carver size_pass;
@@ -154,14 +161,23 @@ extern "C" int32_t hts_destroy(hts_ctx *ctx)
 extern "C" int32_t hts_act(hts_ctx *ctx, const uint8_t *obs, const float *params, uint64_t seed, uint32_t step, int32_t N,
                            int32_t env_offset, int32_t *actions, float *logp, float *values, float *logits_or_null)
 {
-    if (!ctx || !obs || !params || !actions || !logp || !values) return HTS_EINVAL;
+    if (!ctx || !obs || !actions || !logp || !values) return HTS_EINVAL;
     if (N <= 0 || env_offset < 0) return HTS_EINVAL;
     if (N > ctx->c.max_act) return HTS_ESHAPE;
     if (((uintptr_t)obs & 3u) || ((uintptr_t)params & 15u)) return HTS_EINVAL;
     Ctx &c = ctx->c;
-    HIP_TRY(launch_prep(c, params));
-    HIP_TRY(run_forward(c, obs, nullptr, params, N));
-    HIP_TRY(launch_heads_act(c, params, nullptr, seed, step, N, env_offset, actions, logp, values, logits_or_null));
+    if (params) HIP_TRY(launch_prep(c, params, false));
+    else if (!c.synced) return HTS_EINVAL;        // no parameters given and none loaded
+    HIP_TRY(run_forward(c, obs, nullptr, N, false));
+    HIP_TRY(launch_heads_act(c, nullptr, seed, step, N, env_offset, actions, logp, values, logits_or_null));
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_sync_params(hts_ctx *ctx, const float *params)
+{
+    if (!ctx || !params) return HTS_EINVAL;
+    if ((uintptr_t)params & 15u) return HTS_EINVAL;
+    HIP_TRY(launch_prep(ctx->c, params, ctx->c.max_learn > 0));
     return HTS_OK;
 }
 
@@ -170,7 +186,7 @@ extern "C" int32_t hts_sample_from_logits(hts_ctx *ctx, const float *logits, uin
 {
     if (!ctx || !logits || !actions || !logp) return HTS_EINVAL;
     if (N <= 0 || env_offset < 0) return HTS_EINVAL;
-    HIP_TRY(launch_heads_act(ctx->c, nullptr, logits, seed, step, N, env_offset, actions, logp, nullptr, nullptr));
+    HIP_TRY(launch_heads_act(ctx->c, logits, seed, step, N, env_offset, actions, logp, nullptr, nullptr));
     return HTS_OK;
 }
 
@@ -211,10 +227,10 @@ static int32_t loss_and_grads(Ctx &c, const hts_buffer *buf, const float *params
     la.actions = buf->actions; la.index = buf->index; la.old_logp = buf->old_logp;
     la.adv = buf->advantages; la.ret = buf->returns;
     la.algo = hp->algo; la.clip_eps = hp->clip_eps; la.vf_coef = hp->vf_coef; la.ent_coef = hp->ent_coef;
-    HIP_TRY(launch_prep(c, params));
-    HIP_TRY(run_forward(c, buf->obs, buf->index, params, buf->B));
-    HIP_TRY(launch_heads_learn(c, params, la, buf->B));
-    HIP_TRY(run_backward(c, buf->obs, buf->index, params, buf->B, grads));
+    HIP_TRY(launch_prep(c, params, true));
+    HIP_TRY(run_forward(c, buf->obs, buf->index, buf->B, true));
+    HIP_TRY(launch_heads_learn(c, la, buf->B));
+    HIP_TRY(run_backward(c, buf->obs, buf->index, buf->B, grads));
     return HTS_OK;
 }
 
@@ -245,6 +261,7 @@ static int32_t adam_apply(Ctx &c, float *params, const float *grads, hts_opt_sta
     HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, clip ? c.ws.clip : nullptr, hp->lr, hp->beta1, hp->beta2,
                         hp->adam_eps, bc1, bc2));
     opt->step = t;
+    c.synced = false; c.synced_learn = false;     // the caller's vector has moved on; the workspace copy has not
     return HTS_OK;
 }
 

@@ -6,8 +6,7 @@
 
 namespace hts {
 
-template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params,
-                                                   int B, float *grads)
+template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, const int32_t *index, int B, float *grads)
 {
     const Geom &g = c.g;
     hipError_t e;
@@ -43,8 +42,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     {   // d(conv3 pre-activation)
         FcDgrad<T> p;
         p.M = B; p.N = g.F; p.K = 512; p.klen = 512;
-        p.dh = c.ws.dh; p.w = params + g.fcw; p.a3 = (const T *)c.ws.a3; p.dy3 = (T *)c.ws.dy3; p.P3 = g.P3;
-        p.dP3 = FastDiv::make(g.P3);
+        p.dh = c.ws.dh; p.wfcd = (const T *)c.ws.wfcd; p.a3n = (const T *)c.ws.a3n; p.dy3 = (T *)c.ws.dy3;
         {
             SiteTimer tm(c, SITE_FC_DGRAD);
             e = small ? launch_wsgemm<FcDgrad<T>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
@@ -128,10 +126,10 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     return hipSuccess;
 }
 
-hipError_t run_backward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B, float *grads)
+hipError_t run_backward(Ctx &c, const uint8_t *obs, const int32_t *index, int B, float *grads)
 {
-    return c.desc.precision == HTS_PRECISION_BF16 ? backward_t<bf16_t>(c, obs, index, params, B, grads)
-                                                  : backward_t<float>(c, obs, index, params, B, grads);
+    return c.desc.precision == HTS_PRECISION_BF16 ? backward_t<bf16_t>(c, obs, index, B, grads)
+                                                  : backward_t<float>(c, obs, index, B, grads);
 }
 
 }  // namespace hts

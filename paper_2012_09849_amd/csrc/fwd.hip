@@ -4,16 +4,16 @@
 
 namespace hts {
 
-template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B)
+template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, const int32_t *index, int B, bool learn)
 {
     const Geom &g = c.g;
     hipError_t e;
     const bool small = B <= c.small_b;
-    c.fc_nseg = 0;
+    const float *hb = c.ws.hb;
     {
         Conv1Fwd<T> p;
         p.M = B * g.P1; p.N = 32; p.K = g.K1; p.klen = g.K1;
-        p.obs = obs; p.index = index; p.w = params + g.w1; p.bias = params + g.b1; p.out = (T *)c.ws.act1;
+        p.obs = obs; p.index = index; p.w = (const T *)c.ws.w1s; p.bias = hb + c.sh.b1; p.out = (T *)c.ws.act1;
         p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
         p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
         {
@@ -25,7 +25,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
     {
         ConvFwd<T, Layer2, false> p;
         p.M = B * g.P2; p.N = 64; p.K = 512; p.klen = 512;
-        p.in = (const T *)c.ws.act1; p.wf = (const T *)c.ws.wf2; p.bias = params + g.b2; p.out = (T *)c.ws.act2;
+        p.in = (const T *)c.ws.act1; p.wf = (const T *)c.ws.wf2; p.bias = hb + c.sh.b2; p.out = (T *)c.ws.act2; p.out2 = nullptr;
         p.Hin = g.H1; p.Win = g.W1; p.Wo = g.W2; p.Po = g.P2;
         p.dPo = FastDiv::make(g.P2); p.dWo = FastDiv::make(g.W2);
         {
@@ -38,7 +38,8 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
     {
         ConvFwd<T, Layer3, true> p;
         p.M = B * g.P3; p.N = 64; p.K = 576; p.klen = 576;
-        p.in = (const T *)c.ws.act2; p.wf = (const T *)c.ws.wf3; p.bias = params + g.b3; p.out = (T *)c.ws.a3;
+        p.in = (const T *)c.ws.act2; p.wf = (const T *)c.ws.wf3; p.bias = hb + c.sh.b3; p.out = (T *)c.ws.a3;
+        p.out2 = learn ? (T *)c.ws.a3n : nullptr;
         p.Hin = g.H2; p.Win = g.W2; p.Wo = g.W3; p.Po = g.P3;
         p.dPo = FastDiv::make(g.P3); p.dWo = FastDiv::make(g.W3);
         {
@@ -48,25 +49,25 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         }
         if (e != hipSuccess) return e;
     }
-    {
+    {   // groups of FC_GROUP_K inputs; the heads kernel adds them (same grouping and order on both paths)
         FcFwd<T> p;
-        p.M = B; p.N = 512; p.K = g.F; p.klen = g.F;
-        p.a3 = (const T *)c.ws.a3; p.w = params + g.fcw; p.bias = params + g.fcb; p.h = c.ws.h;
-        p.part = small ? c.ws.fc_part : nullptr;
+        p.M = B; p.N = 512; p.K = g.F; p.klen = FC_GROUP_K;
+        p.a3 = (const T *)c.ws.a3; p.w = (const T *)c.ws.wfc; p.part = c.ws.fc_part;
+        static_assert(FC_GROUP_K % FcFwd<T>::SEG == 0, "a group is a whole number of segments");
         {
             SiteTimer tm(c, SITE_FC_FWD);
-            e = small ? launch_wsgemm<FcFwd<T>, 4, FcFwd<T>::SEG, true>(p, c.stream) : launch_gemm(p, c.stream);
+            e = small ? launch_wsgemm<FcFwd<T>, 4, FcFwd<T>::SEG, false>(p, c.stream, FC_GROUP_K / FcFwd<T>::SEG)
+                      : launch_gemm(p, c.stream);
         }
-        if (small) c.fc_nseg = (g.F + FcFwd<T>::SEG - 1) / FcFwd<T>::SEG;
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-hipError_t run_forward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B)
+hipError_t run_forward(Ctx &c, const uint8_t *obs, const int32_t *index, int B, bool learn)
 {
-    return c.desc.precision == HTS_PRECISION_BF16 ? forward_t<bf16_t>(c, obs, index, params, B)
-                                                  : forward_t<float>(c, obs, index, params, B);
+    return c.desc.precision == HTS_PRECISION_BF16 ? forward_t<bf16_t>(c, obs, index, B, learn)
+                                                  : forward_t<float>(c, obs, index, B, learn);
 }
 
 template <typename T> static hipError_t plain_t(Ctx &c, const float *A, const float *Bm, float *C, int M, int N, int K)

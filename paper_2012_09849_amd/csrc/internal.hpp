@@ -11,16 +11,25 @@ namespace hts {
 
 constexpr int NORM_CHUNK = 8192;   // elements per workgroup in the gradient-norm pass (fixes the reduction shape)
 constexpr int N_TERMS = 5;         // per-sample loss terms: policy, value, entropy, clipped flag, kl
+constexpr int FC_GROUP_K = 512;    // the FC layer's reduction is cut into groups of this many inputs (4 segments of 128)
+
+// Offsets inside Workspace::hb.
+struct ShadowOffsets { long long b1, b2, b3, fcb, piw, pib, vw, vb, count; };
 
 struct Workspace {
     void *slab = nullptr;
     size_t bytes = 0;
-    // permuted conv weights (T)
-    void *wf2, *wf3, *wd2, *wd3;
+    // the network as the kernels read it, refreshed from the caller's fp32 vector by launch_prep (T = operand type):
+    void *w1s;                // conv1.w [32][(c,u,v)]
+    void *wf2, *wf3;          // conv2.w, conv3.w with taps outermost [64][(u,v,c)]
+    void *wfc;                // fc.w [512][F]
+    void *wd2, *wd3, *wfcd;   // learner only: conv weights for the input gradients; fc.w as [(p,c)][512]
+    float *hb;                // fp32 block: biases of all layers and the two heads (offsets in Ctx::sh)
     // forward activations
     void *act1, *act2, *a3;   // T
+    void *a3n;                // learner only: conv3 output once more, channel-innermost (ReLU mask of the FC input gradient)
     float *h, *logits, *val;
-    float *fc_part;           // [FC_NSEG_MAX][small_b][512] segment sums of the FC layer on the small-batch path
+    float *fc_part;           // [fc_groups][B][512] partial sums of the FC layer, one per group of FC_GROUP_K inputs
     // backward
     float *dz, *dh, *terms, *grads, *part, *norm_part, *clip;   // clip[0] = scale, clip[1] = ||g||
     void *dy3, *dy2, *dy1;    // T
@@ -48,7 +57,10 @@ struct Ctx {
     hipStream_t stream;
     int max_act, max_learn, max_b;
     int small_b;              // batches up to this size take the wave-per-segment forward kernels
-    int fc_nseg;              // FC segments on the small-batch path of the last forward (0: h already holds the output)
+    int fc_groups;            // ceil(F / FC_GROUP_K)
+    bool synced;              // the workspace's copy of the network matches the last parameter vector handed in
+    bool synced_learn;        // ... including the learner-only parts
+    ShadowOffsets sh;
     Workspace ws;
 };
 
@@ -88,15 +100,15 @@ struct LossArgs {
 };
 
 // fwd.hip
-hipError_t run_forward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B);
+hipError_t run_forward(Ctx &c, const uint8_t *obs, const int32_t *index, int B, bool learn);
 hipError_t run_plain_gemm(Ctx &c, int precision, const float *A, const float *B, float *C, int M, int N, int K);
 // bwd.hip
-hipError_t run_backward(Ctx &c, const uint8_t *obs, const int32_t *index, const float *params, int B, float *grads);
+hipError_t run_backward(Ctx &c, const uint8_t *obs, const int32_t *index, int B, float *grads);
 // misc.hip
-hipError_t launch_prep(Ctx &c, const float *params);
-hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in, uint64_t seed, uint32_t step, int N,
+hipError_t launch_prep(Ctx &c, const float *params, bool learn);
+hipError_t launch_heads_act(Ctx &c, const float *logits_in, uint64_t seed, uint32_t step, int N,
                             int env_offset, int32_t *actions, float *logp, float *values, float *logits_out);
-hipError_t launch_heads_learn(Ctx &c, const float *params, const LossArgs &la, int B);
+hipError_t launch_heads_learn(Ctx &c, const LossArgs &la, int B);
 hipError_t launch_stats(Ctx &c, int B, hts_stats *stats);
 hipError_t launch_wgrad_reduce(Ctx &c, const float *part, int nz, int rows, int ncol, int cin, int ksz, bool taps_outer,
                                float scale, float *g, long long w_off, long long b_off);

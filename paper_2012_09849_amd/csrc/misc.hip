@@ -18,38 +18,118 @@ __device__ __forceinline__ void load_vec(const float *p, float (&v)[8])
 }
 
 // ------------------------------------------------------------------------------------------------------------
-// conv weight permutation (run at the start of every call that needs the network: no cached state)
+// The network as the kernels read it: one launch copies the caller's fp32 parameter vector into the workspace,
+// converting to the operand type and re-ordering.  Workgroups are assigned to jobs by index range:
+//   [0, nb_fc)            64 x 64 tiles of fc.w -> wfc (same order) and, for the learner, wfcd (transposed, rows in
+//                         channel-innermost order f' = p*64 + c), through an LDS tile so both sides stay coalesced
+//   [nb_fc, +nb_conv)     conv2.w / conv3.w -> wf2, wf3 (taps outermost) and, for the learner, wd2, wd3
+//   [.., +nb_w1)          conv1.w -> w1s
+//   [.., +nb_hb)          biases and heads -> hb (fp32)
 // ------------------------------------------------------------------------------------------------------------
-template <typename T>
-__global__ void prep_kernel(const float *__restrict__ params, long long w2, long long w3, T *__restrict__ wf2,
-                            T *__restrict__ wf3, T *__restrict__ wd2, T *__restrict__ wd3)
+struct PrepArgs {
+    const float *params;
+    Geom g;
+    ShadowOffsets sh;
+    void *w1s, *wf2, *wf3, *wfc, *wd2, *wd3, *wfcd;
+    float *hb;
+    int nb_fc, nb_conv, nb_w1, nb_hb;
+    int learn;
+};
+
+template <typename T> __global__ __launch_bounds__(256) void prep_kernel(const PrepArgs a)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 64 * 32 * 16) {               // conv2.w[n][c][u][v], 64 x 32 x 4 x 4
-        const int n = i / 512, r = i % 512, c = r / 16, tap = r % 16;
-        const T w = from_f32<T>(params[w2 + i]);
-        wf2[n * 512 + tap * 32 + c] = w;
-        wd2[c * 1024 + tap * 64 + n] = w;
+    __shared__ float tile[64][65];
+    const int t = threadIdx.x;
+    int blk = blockIdx.x;
+    const float *__restrict__ params = a.params;
+    if (blk < a.nb_fc) {
+        const int F = a.g.F, tf = F / 64;
+        const int j0 = (blk / tf) * 64, f0 = (blk % tf) * 64;
+        const float *src = params + a.g.fcw;
+        T *wfc = (T *)a.wfc;
+        const int col = t & 63, r0 = t >> 6;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int r = r0 + 4 * i;
+            const float v = src[(long long)(j0 + r) * F + f0 + col];
+            wfc[(long long)(j0 + r) * F + f0 + col] = from_f32<T>(v);
+            tile[r][col] = v;
+        }
+        if (!a.learn) return;
+        __syncthreads();
+        T *wfcd = (T *)a.wfcd;
+        const int P3 = a.g.P3;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int fl = r0 + 4 * i, f = f0 + fl;
+            const int c = f / P3, p = f - c * P3;
+            wfcd[(long long)(p * 64 + c) * 512 + j0 + col] = from_f32<T>(tile[col][fl]);
+        }
+        return;
     }
-    if (i < 64 * 64 * 9) {                // conv3.w[n][c][u][v], 64 x 64 x 3 x 3
-        const int n = i / 576, r = i % 576, c = r / 9, tap = r % 9;
-        const T w = from_f32<T>(params[w3 + i]);
-        wf3[n * 576 + tap * 64 + c] = w;
-        wd3[c * 576 + tap * 64 + n] = w;
+    blk -= a.nb_fc;
+    if (blk < a.nb_conv) {
+        const int i = blk * 256 + t;
+        T *wf2 = (T *)a.wf2, *wf3 = (T *)a.wf3, *wd2 = (T *)a.wd2, *wd3 = (T *)a.wd3;
+        if (i < 64 * 32 * 16) {               // conv2.w[n][c][u][v], 64 x 32 x 4 x 4
+            const int n = i / 512, r = i % 512, c = r / 16, tap = r % 16;
+            const T w = from_f32<T>(params[a.g.w2 + i]);
+            wf2[n * 512 + tap * 32 + c] = w;
+            if (a.learn) wd2[c * 1024 + tap * 64 + n] = w;
+        }
+        if (i < 64 * 64 * 9) {                // conv3.w[n][c][u][v], 64 x 64 x 3 x 3
+            const int n = i / 576, r = i % 576, c = r / 9, tap = r % 9;
+            const T w = from_f32<T>(params[a.g.w3 + i]);
+            wf3[n * 576 + tap * 64 + c] = w;
+            if (a.learn) wd3[c * 576 + tap * 64 + n] = w;
+        }
+        return;
+    }
+    blk -= a.nb_conv;
+    if (blk < a.nb_w1) {
+        const int i = blk * 256 + t;
+        if (i < 32 * a.g.K1) ((T *)a.w1s)[i] = from_f32<T>(params[a.g.w1 + i]);
+        return;
+    }
+    blk -= a.nb_w1;
+    {
+        const int i = blk * 256 + t;
+        const int A = a.g.A;
+        // hb = b1 | b2 | b3 | fc.b | pi.w | pi.b | v.w | v.b, each part starting on a 16-byte boundary
+        long long src = -1;
+        if (i < 32) src = a.g.b1 + i;
+        else if (i >= a.sh.b2 && i < a.sh.b2 + 64) src = a.g.b2 + (i - a.sh.b2);
+        else if (i >= a.sh.b3 && i < a.sh.b3 + 64) src = a.g.b3 + (i - a.sh.b3);
+        else if (i >= a.sh.fcb && i < a.sh.fcb + 512) src = a.g.fcb + (i - a.sh.fcb);
+        else if (i >= a.sh.piw && i < a.sh.piw + 512 * A) src = a.g.piw + (i - a.sh.piw);
+        else if (i >= a.sh.pib && i < a.sh.pib + A) src = a.g.pib + (i - a.sh.pib);
+        else if (i >= a.sh.vw && i < a.sh.vw + 512) src = a.g.vw + (i - a.sh.vw);
+        else if (i == a.sh.vb) src = a.g.vb;
+        if (src < 0) return;
+        a.hb[i] = params[src];
     }
 }
 
-hipError_t launch_prep(Ctx &c, const float *params)
+hipError_t launch_prep(Ctx &c, const float *params, bool learn)
 {
     SiteTimer tm(c, SITE_PREP);
-    const int n = 64 * 64 * 9;
+    PrepArgs a;
+    a.params = params; a.g = c.g; a.sh = c.sh;
+    a.w1s = c.ws.w1s; a.wf2 = c.ws.wf2; a.wf3 = c.ws.wf3; a.wfc = c.ws.wfc;
+    a.wd2 = c.ws.wd2; a.wd3 = c.ws.wd3; a.wfcd = c.ws.wfcd; a.hb = c.ws.hb;
+    a.nb_fc = (512 / 64) * (c.g.F / 64);
+    a.nb_conv = (64 * 64 * 9 + 255) / 256;
+    a.nb_w1 = (32 * c.g.K1 + 255) / 256;
+    a.nb_hb = (int)((c.sh.count + 255) / 256);
+    a.learn = learn ? 1 : 0;
+    const int nb = a.nb_fc + a.nb_conv + a.nb_w1 + a.nb_hb;
     if (c.desc.precision == HTS_PRECISION_BF16)
-        hipLaunchKernelGGL(prep_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, c.stream, params, c.g.w2, c.g.w3,
-                           (bf16_t *)c.ws.wf2, (bf16_t *)c.ws.wf3, (bf16_t *)c.ws.wd2, (bf16_t *)c.ws.wd3);
+        hipLaunchKernelGGL(prep_kernel<bf16_t>, dim3(nb), dim3(256), 0, c.stream, a);
     else
-        hipLaunchKernelGGL(prep_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, c.stream, params, c.g.w2, c.g.w3,
-                           (float *)c.ws.wf2, (float *)c.ws.wf3, (float *)c.ws.wd2, (float *)c.ws.wd3);
-    return hipGetLastError();
+        hipLaunchKernelGGL(prep_kernel<float>, dim3(nb), dim3(256), 0, c.stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) { c.synced = true; c.synced_learn = learn; }
+    return e;
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -113,11 +193,10 @@ __device__ __forceinline__ float lane_value(float x, int src)
 // heads: one wavefront per sample.  Lane j (< A) ends up holding logit j; every lane holds the value.
 // ------------------------------------------------------------------------------------------------------------
 struct HeadsArgs {
-    const float *h;            // [B][512]
-    const float *fc_part;      // when nseg > 0: h = relu(fc_bias + sum_seg fc_part[seg][B][512]) is formed here ...
+    const float *fc_part;      // h = relu(fc_bias + sum_g fc_part[g][B][512]), groups added in order, is formed here ...
     const float *fc_bias;
-    float *h_out;              // ... and written back for the backward pass when not null
-    int nseg;
+    float *h_out;              // ... and written out for the backward pass when not null
+    int nseg;                  // number of groups
     const float *wpi, *bpi, *wv, *bv;
     const float *logits_in;    // optional: skip the head product and sample from these
     int B, A;
@@ -143,9 +222,9 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
     if (a.logits_in) {
         if (lane < A) mylogit = a.logits_in[(long long)b * A + lane];
     } else {
-        if (a.nseg > 0) {
-            // fold the FC layer's segment sums in segment order (the order the tile kernel uses), then bias + ReLU;
-            // five segments' loads are issued together so that their latencies overlap
+        {
+            // add the FC layer's group sums in group order, then bias + ReLU; five groups' loads are issued
+            // together so that their latencies overlap
 #pragma unroll
             for (int i = 0; i < 8; ++i) hv[i] = 0.0f;
             const float *src = a.fc_part + (long long)b * 512 + lane * 8;
@@ -177,7 +256,7 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
                 f32x4 *dst = reinterpret_cast<f32x4 *>(a.h_out + (long long)b * 512 + lane * 8);
                 dst[0] = o0; dst[1] = o1;
             }
-        } else load_vec(a.h + (long long)b * 512 + lane * 8, hv);
+        }
         // A dot products of length 512 for the logits: every lane forms its 8-element partial of each, the partials
         // go through this wavefront's LDS panel [A][65], and lane j adds row j in lane order (a fixed order; no
         // barrier is needed because a wavefront's LDS operations execute in order).  The value head is one more dot
@@ -298,15 +377,21 @@ static hipError_t raise_lds_limit(const void *fn, size_t bytes)
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in, uint64_t seed, uint32_t step, int N,
-                            int env_offset, int32_t *actions, float *logp, float *values, float *logits_out)
+static void heads_network(const Ctx &c, HeadsArgs &a)
+{
+    const float *hb = c.ws.hb;
+    a.wpi = hb + c.sh.piw; a.bpi = hb + c.sh.pib; a.wv = hb + c.sh.vw; a.bv = hb + c.sh.vb;
+    a.fc_part = c.ws.fc_part; a.fc_bias = hb + c.sh.fcb; a.nseg = c.fc_groups;
+}
+
+// logits_in != null: sample from these logits (no network involved); otherwise finish the forward pass first.
+hipError_t launch_heads_act(Ctx &c, const float *logits_in, uint64_t seed, uint32_t step, int N, int env_offset,
+                            int32_t *actions, float *logp, float *values, float *logits_out)
 {
     SiteTimer tm(c, SITE_HEADS_ACT);
     HeadsArgs a = {};
-    a.h = c.ws.h;
-    if (params) { a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb; }
     a.logits_in = logits_in;
-    if (params && c.fc_nseg > 0) { a.fc_part = c.ws.fc_part; a.fc_bias = params + c.g.fcb; a.nseg = c.fc_nseg; }
+    if (!logits_in) heads_network(c, a);
     a.B = N; a.A = c.g.A;
     a.seed = seed; a.step = step; a.env_offset = env_offset;
     a.actions = actions; a.logp = logp; a.values = values; a.logits_out = logits_out;
@@ -316,13 +401,12 @@ hipError_t launch_heads_act(Ctx &c, const float *params, const float *logits_in,
     return hipGetLastError();
 }
 
-hipError_t launch_heads_learn(Ctx &c, const float *params, const LossArgs &la, int B)
+hipError_t launch_heads_learn(Ctx &c, const LossArgs &la, int B)
 {
     SiteTimer tm(c, SITE_HEADS_LEARN);
     HeadsArgs a = {};
-    a.h = c.ws.h;
-    a.wpi = params + c.g.piw; a.bpi = params + c.g.pib; a.wv = params + c.g.vw; a.bv = params + c.g.vb;
-    if (c.fc_nseg > 0) { a.fc_part = c.ws.fc_part; a.fc_bias = params + c.g.fcb; a.nseg = c.fc_nseg; a.h_out = c.ws.h; }
+    heads_network(c, a);
+    a.h_out = c.ws.h;
     a.B = B; a.A = c.g.A;
     a.la = la;
     a.dz = c.ws.dz; a.dh = c.ws.dh; a.terms = c.ws.terms;

@@ -5,12 +5,16 @@
 // Layouts inside the library's workspace (T = float or bf16):
 //   act1 [B][H1][W1][32], act2 [B][H2][W2][64]   channel-innermost, post-ReLU
 //   a3   [B][F]           conv3 output flattened as (channel, y, x) = the order fc.w expects
+//   a3n  [B][H3][W3][64]  the same values channel-innermost (learner only)
+//   fc_part [G][B][512]   FC partial sums, one per group of 512 inputs; bias + ReLU when the heads kernel adds them
 //   h    [B][512] fp32    FC output, post-ReLU
 //   dz   [B][A+1] fp32    dL/dlogits followed by dL/dvalue
 //   dh   [B][512] fp32    dL/d(FC pre-activation)
 //   dy3 [B][H3][W3][64], dy2 [B][H2][W2][64], dy1 [B][H1][W1][32]   dL/d(conv pre-activation), T
+//   w1s [32][(c,u,v)], wfc [512][F]        conv1.w and fc.w in their own order, as T
 //   wf2 [64][(u,v,c)], wf3 [64][(u,v,c)]   conv weights with taps outermost, for the forward gathers
 //   wd2 [32][(u,v,n)], wd3 [64][(u,v,n)]   conv weights transposed for the input-gradient gathers
+//   wfcd [(p,c)][512]                      fc.w transposed, rows in channel-innermost order, for the FC input gradient
 //
 // Every gather is split into a row part (ctx_a / ctx_b: the batch / y / x decomposition, evaluated once per thread)
 // and a k part (load_a / load_b: taps and channels, with compile-time layer constants).
@@ -67,7 +71,7 @@ template <typename T_> struct PlainGemm {
 template <typename T_> struct Conv1Fwd {
     using T = T_;
     static constexpr int BM = 128, BN = 32, BK = OperandTraits<T>::BK, WAVES_M = 4, WAVES_N = 1;
-    static constexpr int VA = 8, VB = 4;
+    static constexpr int VA = 8, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 64;       // forward sums are segmented so every kernel variant returns the same bits
     typedef OffCtx CtxA;
@@ -75,7 +79,8 @@ template <typename T_> struct Conv1Fwd {
     int M, N, K, klen;
     const uint8_t *obs;
     const int32_t *index;
-    const float *w, *bias;
+    const T *w;
+    const float *bias;
     T *out;
     int C, H, W, W1, P1;
     FastDiv dP1, dW1;
@@ -121,6 +126,7 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     const T *wf;      // [Cout][K]
     const float *bias;
     T *out;
+    T *out2;          // FLAT_OUT only, optional: a second, channel-innermost copy of the output
     int Hin, Win, Wo, Po;
     FastDiv dPo, dWo;
     HTS_HD CtxA ctx_a(int m) const
@@ -147,26 +153,26 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
         if constexpr (FLAT_OUT) {
             const int b = dPo.div(m), p = m - b * Po;
             out[((long long)b * L::COUT + n) * Po + p] = r;
+            if (out2) out2[(long long)m * L::COUT + n] = r;
         } else out[(long long)m * L::COUT + n] = r;
     }
 };
 
 // ------------------------------------------------------------------------------------------------------------
-// FC forward: h = relu(a3 * fc.w^T + fc.b), fc.w read in its fp32 packing
+// FC forward, cut along the reduction into groups of klen inputs (blockIdx.y): part[g][b][j] = sum over group g of
+// a3[b][f] * fc.w[j][f].  The heads kernel adds the groups in order and applies bias and ReLU.
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcFwd {
     using T = T_;
-    static constexpr int BM = 64, BN = 32, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 1;   // 16 x B/64 workgroups
-    static constexpr int VA = OperandTraits<T>::VEC, VB = 4;
+    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
+    static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 128;
     typedef OffCtx CtxA;
     typedef OffCtx CtxB;
     int M, N, K, klen;
-    const T *a3;
-    const float *w, *bias;
-    float *h;
-    float *part;      // when set: segment sums go to part[seg][M][N]; bias and ReLU are applied by the consumer
+    const T *a3, *w;
+    float *part;      // [groups][M][N]
     HTS_HD CtxA ctx_a(int m) const { return {m < M ? (long long)m * K : -1}; }
     HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
@@ -177,12 +183,7 @@ template <typename T_> struct FcFwd {
     {
         return (c.off >= 0 && k < kend) ? load_vec<T, VB>(w + c.off + k) : zero_vec<T, VB>();
     }
-    HTS_HD void store(int m, int n, float acc, int seg) const
-    {
-        if (part) { part[((long long)seg * M + m) * N + n] = acc; return; }
-        const float y = acc + bias[n];
-        h[(long long)m * N + n] = y > 0.0f ? y : 0.0f;
-    }
+    HTS_HD void store(int m, int n, float acc, int grp) const { part[((long long)grp * M + m) * N + n] = acc; }
 };
 
 // ------------------------------------------------------------------------------------------------------------
@@ -259,37 +260,34 @@ template <typename T_> struct FcWgrad {
 };
 
 // ------------------------------------------------------------------------------------------------------------
-// FC input gradient, masked by conv3's ReLU and written channel-innermost:
-// D[b][f] = sum_j dh[b][j] fc.w[j][f];  dy3[b][p][c] = a3[b][f] > 0 ? D : 0,  f = c*P3 + p
+// FC input gradient, masked by conv3's ReLU, in channel-innermost order f' = p*64 + c throughout:
+// dy3[b][f'] = a3n[b][f'] > 0 ? sum_j dh[b][j] wfcd[f'][j] : 0
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcDgrad {
     using T = T_;
     static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
-    static constexpr int VA = 4, VB = 4;
-    static constexpr bool A_ALONG_K = true, B_ALONG_K = false;
+    static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
+    static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     typedef OffCtx CtxA;
-    struct CtxB { int f; };
+    typedef OffCtx CtxB;
     int M, N, K, klen;     // M = B, N = F, K = 512
-    const float *dh, *w;
-    const T *a3;
+    const float *dh;
+    const T *wfcd, *a3n;
     T *dy3;
-    int P3;
-    FastDiv dP3;
     HTS_HD CtxA ctx_a(int b) const { return {b < M ? (long long)b * 512 : -1}; }
-    HTS_HD CtxB ctx_b(int f) const { return {f}; }
+    HTS_HD CtxB ctx_b(int f) const { return {f < N ? (long long)f * 512 : -1}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
         return (c.off >= 0 && k < kend) ? load_vec<T, VA>(dh + c.off + k) : zero_vec<T, VA>();
     }
-    HTS_HD Vec<T, VB> load_b(const CtxB &c, int j, int kend) const
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        return (j < kend && c.f < N) ? load_vec<T, VB>(w + (long long)j * N + c.f) : zero_vec<T, VB>();   // F % 4 == 0
+        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(wfcd + c.off + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int b, int f, float acc, int) const
     {
-        const int c = dP3.div(f), p = f - c * P3;
-        const float a = to_f32(a3[(long long)b * N + f]);
-        dy3[((long long)b * P3 + p) * 64 + c] = from_f32<T>(a > 0.0f ? acc : 0.0f);
+        const long long o = (long long)b * N + f;
+        dy3[o] = from_f32<T>(to_f32(a3n[o]) > 0.0f ? acc : 0.0f);
     }
 };
 

@@ -202,6 +202,35 @@ def test_act_small_and_large_batch_kernels_agree_bitwise(hts, shape, A, prec, mo
         assert all(np.array_equal(x, y) for x, y in zip(o, outs[0]))
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+def test_act_with_loaded_parameters(hts, prec):
+    """hts_act(params = NULL) reuses the parameters loaded before (bitwise the same outputs); it is refused when
+    nothing is loaded, and after a learner update has moved the caller's vector on."""
+    Cc, H, W = ATARI
+    A, N = 6, 20
+    ctx = hts.Context(Cc, H, W, A, precision=prec, max_act_batch=N, max_learn_batch=N)
+    params = dev(syn.init_params(21, Cc, H, W, A, bias_scale=0.05))
+    other = dev(syn.init_params(22, Cc, H, W, A, bias_scale=0.05))
+    obs = dev(syn.obs_uniform(23, N, Cc, H, W))
+    with pytest.raises(hts.HtsError):
+        _act(ctx, obs, None, 5, 1, 0, A)
+    ref = _act(ctx, obs, params, 5, 1, 0, A)
+    again = _act(ctx, obs, None, 5, 1, 0, A)
+    assert all(np.array_equal(x, y) for x, y in zip(ref, again))
+    ctx.hts_sync_params(other)
+    o1 = _act(ctx, obs, None, 5, 1, 0, A)
+    o2 = _act(ctx, obs, other, 5, 1, 0, A)
+    assert all(np.array_equal(x, y) for x, y in zip(o1, o2))
+    assert not np.array_equal(o1[3], ref[3])
+    # an update through the library invalidates the loaded copy
+    P = params.numel()
+    opt = hts.OptState(torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda"))
+    ctx.hts_adam_apply(params, torch.ones(P, device="cuda"), opt, hts.HParams())
+    with pytest.raises(hts.HtsError):
+        _act(ctx, obs, None, 5, 1, 0, A)
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------------------------------
 # learner
 # ------------------------------------------------------------------------------------------------------------
