@@ -152,9 +152,22 @@ template <class P> HTS_HD typename P::CtxB make_ctx_b(const P &p, int col, int z
 {
     if constexpr (HasBatch<P>::value) return p.ctx_b(col, zb); else return p.ctx_b(col);
 }
-template <class P> HTS_HD void do_store(const P &p, int m, int n, float acc, int z, int zb)
+// Optional per-column epilogue data: a problem with `Col col(int n) const` (n < N) has it evaluated once per
+// output column held by a lane (e.g. the bias) and receives it as the last argument of store().
+template <class P, class = void> struct HasCol : std::false_type {};
+template <class P> struct HasCol<P, std::void_t<decltype(std::declval<const P &>().col(0))>> : std::true_type {};
+struct NoCol {};
+template <class P> HTS_HD auto make_col(const P &p, int n)
 {
-    if constexpr (HasBatch<P>::value) p.store(m, n, acc, z, zb); else p.store(m, n, acc, z);
+    if constexpr (HasCol<P>::value) return p.col(n); else return NoCol{};
+}
+template <class P, class C> HTS_HD void do_store(const P &p, int m, int n, float acc, int z, int zb, const C &col)
+{
+    if constexpr (HasCol<P>::value) {
+        if constexpr (HasBatch<P>::value) p.store(m, n, acc, z, zb, col); else p.store(m, n, acc, z, col);
+    } else {
+        if constexpr (HasBatch<P>::value) p.store(m, n, acc, z, zb); else p.store(m, n, acc, z);
+    }
 }
 
 // A problem type P provides:
@@ -171,6 +184,7 @@ template <class P> HTS_HD void do_store(const P &p, int m, int n, float acc, int
 //   Vec<T,VA> load_a(const CtxA &, int k, int kend) const     zero outside [0,M) x [.,kend)
 //   CtxB ctx_b(int col) const,  Vec<T,VB> load_b(const CtxB &, int k, int kend) const
 //   void store(int m, int n, float acc, int z) const          called only for m < M, n < N
+//   optionally Col col(int n) const and store(..., const Col &)   per-column epilogue data, fetched once per lane
 template <class P>
 __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(const P p)
 {
@@ -215,7 +229,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         const int id = tid + i * NT;
         int r;
         if constexpr (P::A_ALONG_K) { r = id / (BK / VA); ka[i] = (id % (BK / VA)) * VA; }
-        else { r = (id % (BM / VA)) * VA; ka[i] = (id / (BM / VA)) * VA; }
+        else { r = (id / (BK / VA)) * VA; ka[i] = (id % (BK / VA)) * VA; }     // neighbours write one LDS row
         la[i] = r * LS + ka[i];
         ca[i] = make_ctx_a(p, m0 + r, zb);
     }
@@ -224,7 +238,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         const int id = tid + i * NT;
         int r;
         if constexpr (P::B_ALONG_K) { r = id / (BK / VB); kb[i] = (id % (BK / VB)) * VB; }
-        else { r = (id % (BN / VB)) * VB; kb[i] = (id / (BN / VB)) * VB; }
+        else { r = (id / (BK / VB)) * VB; kb[i] = (id % (BK / VB)) * VB; }
         lb[i] = r * LS + kb[i];
         cb[i] = make_ctx_b(p, n0 + r, zb);
     }
@@ -294,29 +308,12 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         }
     };
 
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    f32x16 tot[SEG > 0 ? TM : 1][SEG > 0 ? TN : 1];
-    if constexpr (SEG > 0) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) tot[i][j][r] = 0.0f;
-    }
-
     const int lrow = lane & 31, lk = lane >> 5;
     const T *a_base = As + (wm * TM * 32 + lrow) * LS;
     const T *b_base = Bs + (wn * TN * 32 + lrow) * LS;
 
-    if (kbeg < kend) gload(kbeg);
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+    // one k-tile: registers -> LDS, start the next tile's global loads, multiply
+    auto step = [&](int k0, f32x16 (&acc)[TM][TN]) {
         sstore();
         __syncthreads();
         if (k0 + BK < kend) gload(k0 + BK);
@@ -348,36 +345,69 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
         }
-        if constexpr (SEG > 0) {
-            if ((k0 + BK) % SEG == 0 || k0 + BK >= kend) {      // end of a segment: fold it into the running total
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) { tot[i][j][r] += acc[i][j][r]; acc[i][j][r] = 0.0f; }
-            }
-        }
         __syncthreads();
-    }
-    if constexpr (SEG > 0) {
+    };
+    auto clear = [&](f32x16 (&x)[TM][TN]) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) acc[i][j] = tot[i][j];
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) x[i][j][r] = 0.0f;
+    };
+
+    f32x16 acc[TM][TN];
+    clear(acc);
+    if (kbeg < kend) gload(kbeg);
+    if constexpr (SEG > 0) {
+        // one fresh accumulator per segment (it only lives inside the segment), folded into the running total
+        constexpr int SPS = SEG / BK;            // k-tiles per segment
+        int k0 = kbeg;
+        for (; k0 + SEG <= kend; k0 += SEG) {
+            f32x16 sacc[TM][TN];
+            clear(sacc);
+#pragma unroll
+            for (int s = 0; s < SPS; ++s) step(k0 + s * BK, sacc);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += sacc[i][j][r];
+        }
+        if (k0 < kend) {                          // a last, shorter segment
+            f32x16 sacc[TM][TN];
+            clear(sacc);
+            for (; k0 < kend; k0 += BK) step(k0, sacc);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += sacc[i][j][r];
+        }
+    } else {
+        for (int k0 = kbeg; k0 < kend; k0 += BK) step(k0, acc);
     }
 
+    // Epilogue.  Tiles that lie wholly inside the output take a branch-free path (the compiler can then batch the
+    // loads an epilogue may need); edge tiles check every element.
+    auto epilogue = [&](auto full_tile) {
+        constexpr bool FULL = decltype(full_tile)::value;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + (wn * TN + j) * 32 + lrow;
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + (wn * TN + j) * 32 + lrow;
+                const auto col = make_col(p, FULL ? n : min(n, p.N - 1));
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (m < M && n < p.N) do_store(p, m, n, acc[i][j][r], z, zb);
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                    if (FULL || (m < M && n < p.N)) do_store(p, m, n, acc[i][j][r], z, zb, col);
+                }
             }
-        }
+    };
+    if (m0 + BM <= M && n0 + BN <= p.N) epilogue(std::true_type{}); else epilogue(std::false_type{});
 }
 
 template <class P> inline hipError_t launch_gemm(const P &p, hipStream_t stream)

@@ -102,9 +102,10 @@ template <typename T_> struct Conv1Fwd {
     {
         return (c.off >= 0 && k < kend) ? load_vec<T, VB>(w + c.off + k) : zero_vec<T, VB>();
     }
-    HTS_HD void store(int m, int n, float acc, int) const
+    HTS_HD float col(int n) const { return bias[n]; }
+    HTS_HD void store(int m, int n, float acc, int, const float &b) const
     {
-        const float y = acc * (1.0f / 255.0f) + bias[n];
+        const float y = acc * (1.0f / 255.0f) + b;
         out[(long long)m * 32 + n] = from_f32<T>(y > 0.0f ? y : 0.0f);
     }
 };
@@ -146,9 +147,10 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     {
         return (c.off >= 0 && k < kend) ? load_vec<T, VB>(wf + c.off + k) : zero_vec<T, VB>();
     }
-    HTS_HD void store(int m, int n, float acc, int) const
+    HTS_HD float col(int n) const { return bias[n]; }
+    HTS_HD void store(int m, int n, float acc, int, const float &bn) const
     {
-        const float y = acc + bias[n];
+        const float y = acc + bn;
         const T r = from_f32<T>(y > 0.0f ? y : 0.0f);
         if constexpr (FLAT_OUT) {
             const int b = dPo.div(m), p = m - b * Po;

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         const int id = lane + i * 64;
         int r;
         if constexpr (P::A_ALONG_K) { r = id / (SEG / VA); ka[i] = (id % (SEG / VA)) * VA; }
-        else { r = (id % (32 / VA)) * VA; ka[i] = (id / (32 / VA)) * VA; }
+        else { r = (id / (SEG / VA)) * VA; ka[i] = (id % (SEG / VA)) * VA; }   // neighbours write one LDS row
         la[i] = r * LS + ka[i];
         ca[i] = make_ctx_a(p, m0 + r, zb);
     }
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         const int id = lane + i * 64;
         int r;
         if constexpr (P::B_ALONG_K) { r = id / (SEG / VB); kb[i] = (id % (SEG / VB)) * VB; }
-        else { r = (id % (32 / VB)) * VB; kb[i] = (id / (32 / VB)) * VB; }
+        else { r = (id / (SEG / VB)) * VB; kb[i] = (id % (SEG / VB)) * VB; }
         lb[i] = r * LS + kb[i];
         cb[i] = make_ctx_b(p, n0 + r, zb);
     }
@@ -192,10 +192,16 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         if (seg >= nseg) return;
         const f32x16 acc = segment_sum(seg);
         const int n = n0 + lrow;
+        const auto col = make_col(p, min(n, p.N - 1));
+        if (m0 + 32 <= M && n0 + 32 <= p.N) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int m = m0 + 8 * (r / 4) + 4 * lk + (r % 4);
-            if (m < M && n < p.N) do_store(p, m, n, acc[r], seg, zb);
+            for (int r = 0; r < 16; ++r) do_store(p, m0 + 8 * (r / 4) + 4 * lk + (r % 4), n, acc[r], seg, zb, col);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + 8 * (r / 4) + 4 * lk + (r % 4);
+                if (m < M && n < p.N) do_store(p, m, n, acc[r], seg, zb, col);
+            }
         }
     } else {
         constexpr int PER = 1024 / (WAVES * 64);        // tile elements owned by each thread in the fold
@@ -222,12 +228,22 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
                     total[e] += reinterpret_cast<const float *>(smem + (size_t)ww * PANEL_BYTES)[e * (WAVES * 64) + tid];
             __syncthreads();
         }
+        // element e of this thread is accumulator register r = e*WAVES + w of lane `lane`: one column per thread
+        const int n = n0 + lrow;
+        const auto col = make_col(p, min(n, p.N - 1));
+        if (m0 + 32 <= M && n0 + 32 <= p.N) {
 #pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const int idx = e * (WAVES * 64) + tid;          // = r*64 + lane of the accumulator layout
-            const int r = idx >> 6, l = idx & 63;
-            const int m = m0 + 8 * (r / 4) + 4 * (l >> 5) + (r % 4), n = n0 + (l & 31);
-            if (m < M && n < p.N) do_store(p, m, n, total[e], (int)blockIdx.y, zb);
+            for (int e = 0; e < PER; ++e) {
+                const int r = e * WAVES + w;
+                do_store(p, m0 + 8 * (r / 4) + 4 * lk + (r % 4), n, total[e], (int)blockIdx.y, zb, col);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < PER; ++e) {
+                const int r = e * WAVES + w;
+                const int m = m0 + 8 * (r / 4) + 4 * lk + (r % 4);
+                if (m < M && n < p.N) do_store(p, m, n, total[e], (int)blockIdx.y, zb, col);
+            }
         }
     }
 }
