@@ -152,36 +152,93 @@ def find_dominant(loop, work):
     return ranked[0][1], per_step
 
 
-def cpu_baseline(cfg, loop, budget_s=20.0):
-    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+def cpu_baseline(cfg, loop, budget_s=16.0):
+    """The oracle as it stands, single thread, on a bounded sample of the same workload (about budget_s of CPU)."""
     import numpy as np
     import oracle
     h = loop.host
     N, T = cfg["N"], cfg["T"]
     net = oracle.make_net(cfg["C"], cfg["H"], cfg["W"], cfg["A"])
     p = h["params"].astype(np.float64)
+    hp = oracle.make_hparams(algo=cfg["algo"], clip_eps=cfg["clip"], lr=cfg["lr"], max_grad_norm=cfg["max_norm"])
+    all_obs = h["obs"][:T].reshape(N * T, cfg["C"], cfg["H"], cfg["W"])
+    # actor: whole hts_act steps (N frames each, cycling through the iteration's T+1) for 40% of the budget
     t0 = time.perf_counter()
-    # act on one step's N frames
-    logits, vals = oracle.forward(net, p, h["obs"][0])
-    oracle.sample(logits.astype(np.float32), 1, 0, 0)
-    t_act = time.perf_counter() - t0
-    rows = min(N * T, 16 if N * T > 80 else N * T)
-    obs = h["obs"][:T].reshape(N * T, cfg["C"], cfg["H"], cfg["W"])[:rows]
-    rng_act = np.zeros(rows, np.int32)
+    n_steps = 0
+    while n_steps == 0 or time.perf_counter() - t0 < 0.4 * budget_s:
+        logits, _ = oracle.forward(net, p, h["obs"][n_steps % (T + 1)])
+        oracle.sample(logits.astype(np.float32), 1, n_steps, 0)
+        n_steps += 1
+    t_act = (time.perf_counter() - t0) / n_steps
     t0 = time.perf_counter()
     oracle.gae(h["rew"], np.zeros((T + 1, N)), h["dones"], cfg["gamma"], cfg["lam"])
     t_gae = time.perf_counter() - t0
-    hp = oracle.make_hparams(algo=cfg["algo"], clip_eps=cfg["clip"], lr=cfg["lr"], max_grad_norm=cfg["max_norm"])
-    t0 = time.perf_counter()
-    oracle.learner_step(net, p, np.zeros(p.size), np.zeros(p.size), 1, obs, rng_act, np.zeros(rows), np.ones(rows),
-                        np.ones(rows), hp)
-    t_learn = time.perf_counter() - t0
+    # learner: one update on a calibration sample, then on as many rows as the rest of the budget allows
+    def learn(rows):
+        t = time.perf_counter()
+        oracle.learner_step(net, p, np.zeros(p.size), np.zeros(p.size), 1, all_obs[:rows], np.zeros(rows, np.int32),
+                            np.zeros(rows), np.ones(rows), np.ones(rows), hp)
+        return time.perf_counter() - t
+    rows0 = min(N * T, 16)
+    t_cal = learn(rows0)
+    mb_rows = N * T // cfg["minibatches"]
+    rows = int(min(mb_rows, max(rows0, 0.6 * budget_s * rows0 / t_cal)))
+    t_learn, reps = learn(rows), 1
+    while t_learn * (reps + 1) / reps < 0.6 * budget_s - t_cal:       # small workloads: repeat the whole update
+        t_learn += learn(rows)
+        reps += 1
+    t_learn /= reps
     learn_rows = N * T * cfg["epochs"]
     total = t_act * (T + 1) + t_gae + t_learn * (learn_rows / rows)
     return {"value": N * T / total, "unit": "env-frames/s", "cores": 1, "kind": "oracle",
-            "sample": f"hts_act on one step's {N} frames (x{T + 1}), GAE in full, learner on {rows} rows scaled "
-                      f"linearly to {learn_rows}; measured {t_act + t_gae + t_learn:.1f} s of CPU work",
+            "sample": f"{n_steps} hts_act steps of {N} frames (an iteration has {T + 1}), GAE in full, {reps} learner "
+                      f"update(s) on {rows} rows scaled linearly to the iteration's {learn_rows}; "
+                      f"{t_act * n_steps + t_gae + t_cal + t_learn * reps:.1f} s of CPU work",
             "learner_samples_per_s": rows / t_learn}
+
+
+def source_digest():
+    """SHA-256 over the kernel sources: hardware-counter figures are only reported for the sources they were taken on."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2012_09849_amd", "csrc")
+    for f in sorted(glob.glob(os.path.join(root, "*.hip")) + glob.glob(os.path.join(root, "*.hpp"))):
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+# HBM bytes per launch of a workload's dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per
+# dispatch, averaged over the run, each scaled by what the counter reads for a plain copy of known size):
+# workload -> (launch site, bytes per launch, digest of the kernel sources the counters were taken on).
+TRAFFIC = {}
+
+
+def streaming_rooflines(loop, per_step, work, torch, overhead_ms):
+    """Achieved bandwidth of the streaming kernels: Adam inside this workload, and returns/GAE at 128 x 4096."""
+    out = {}
+    if "adam" in per_step:
+        ms, n = per_step["adam"]
+        ms = max(ms - n * overhead_ms, 1e-6)
+        gbs = work["adam"][1] / (ms * 1e-3) / 1e9
+        out["adam"] = {"GB/s": gbs, "frac": gbs * 1e9 / PEAK["hbm"], "avg_launch_us": ms / n * 1e3}
+    T, N = 128, 4096
+    g = torch.Generator(device="cuda").manual_seed(1)
+    r, v = torch.randn(T, N, device="cuda", generator=g), torch.randn(T + 1, N, device="cuda", generator=g)
+    d = (torch.rand(T, N, device="cuda", generator=g) < 0.01).to(torch.uint8)
+    adv, ret = torch.empty_like(r), torch.empty_like(r)
+    ctx = loop.ctx
+    for _ in range(5):
+        ctx.hts_returns_gae(r, v, d, 0.99, 0.95, adv, ret)
+    ctx.hts_profile_begin(ctx.profile_sites().index("gae"))
+    for _ in range(200):
+        ctx.hts_returns_gae(r, v, d, 0.99, 0.95, adv, ret)
+    n, ms = ctx.hts_profile_end()
+    nbytes = 17.0 * T * N + 4.0 * N
+    us = max(ms / n - overhead_ms, 1e-6) * 1e3
+    out["gae_128x4096"] = {"GB/s": nbytes / (us * 1e-6) / 1e9, "frac": nbytes / (us * 1e-6) / PEAK["hbm"],
+                           "avg_launch_us": us}
+    return out
 
 
 def main():
@@ -269,19 +326,28 @@ def main():
     }
     kind, amount = work[dominant]
     launches_per_step = per_step[dominant][1]
-    avg_s = ms_timed / max(n_timed, 1) * 1e-3
+    # an event bracket also times the events themselves: subtract what an empty bracket reads
+    overhead_ms = loop.ctx.hts_profile_overhead(256)
+    avg_s = max(ms_timed / max(n_timed, 1) - overhead_ms, 1e-6) * 1e-3
+    traffic = None
+    if args.workload in TRAFFIC and TRAFFIC[args.workload][0] == dominant and TRAFFIC[args.workload][2] == source_digest():
+        traffic = TRAFFIC[args.workload][1]
     per_launch = amount / launches_per_step
     if kind == "flop":
         peak = PEAK["mfma_f32"] if cfg["precision"] == 0 else PEAK["mfma_bf16"]
         out["roofline"] = {"kernel": dominant, "bound": "mfma", "achieved": per_launch / avg_s / 1e12, "peak": peak / 1e12,
-                           "unit": "TFLOP/s", "frac": per_launch / avg_s / peak, "traffic": None,
-                           "avg_launch_us": avg_s * 1e6, "launches_timed": n_timed,
+                           "unit": "TFLOP/s", "frac": per_launch / avg_s / peak, "traffic": traffic,
+                           "avg_launch_us": avg_s * 1e6, "event_overhead_us": overhead_ms * 1e3,
+                           "launches_timed": n_timed,
                            "launches_per_step": launches_per_step}
     else:
         out["roofline"] = {"kernel": dominant, "bound": "hbm", "achieved": per_launch / avg_s / 1e9, "peak": 8000.0,
-                           "unit": "GB/s", "frac": per_launch / avg_s / PEAK["hbm"], "traffic": None,
-                           "avg_launch_us": avg_s * 1e6, "launches_timed": n_timed,
+                           "unit": "GB/s", "frac": per_launch / avg_s / PEAK["hbm"], "traffic": traffic,
+                           "avg_launch_us": avg_s * 1e6, "event_overhead_us": overhead_ms * 1e3,
+                           "launches_timed": n_timed,
                            "launches_per_step": launches_per_step}
+    if not args.site:
+        out["streaming"] = streaming_rooflines(loop, per_step, work, torch, overhead_ms)
     out["kernel_ms_per_step"] = {k: round(v[0], 5) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1][0])}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, loop)

@@ -167,6 +167,9 @@ int32_t     hts_profile_site_count(void);
 const char *hts_profile_site_name(int32_t site);
 int32_t     hts_profile_begin(hts_ctx *ctx, int32_t site);
 int32_t     hts_profile_end(hts_ctx *ctx, int32_t *launches, double *total_ms);
+/* Mean elapsed time (ms) of `reps` (1..4096) event pairs with nothing between them: the part of every bracket that
+ * the timer itself contributes.  Ends any open profiling window. */
+int32_t     hts_profile_overhead(hts_ctx *ctx, int32_t reps, double *mean_ms);
 
 int32_t     hts_last_hip_error(void);
 const char *hts_strerror(int32_t code);

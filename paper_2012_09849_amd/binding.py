@@ -15,7 +15,7 @@ ALGO_A2C, ALGO_PPO = 0, 1
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
            "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
-           "hts_profile_end"]
+           "hts_profile_end", "hts_profile_overhead"]
 
 
 class HtsError(RuntimeError):
@@ -91,6 +91,7 @@ def load_library():
         lib.hts_profile_site_name.argtypes = [C.c_int32]
         lib.hts_profile_begin.argtypes = [C.c_void_p, C.c_int32]
         lib.hts_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+        lib.hts_profile_overhead.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]
         _lib = lib
     return _lib
 
@@ -225,6 +226,12 @@ class Context:
         n, ms = C.c_int32(), C.c_double()
         _check(self.lib.hts_profile_end(self._h, C.byref(n), C.byref(ms)), "hts_profile_end")
         return n.value, ms.value
+
+    def hts_profile_overhead(self, reps=256):
+        """-> mean milliseconds of an empty event bracket."""
+        ms = C.c_double()
+        _check(self.lib.hts_profile_overhead(self._h, reps, C.byref(ms)), "hts_profile_overhead")
+        return ms.value
 
     @staticmethod
     def new_stats(device="cuda"):

@@ -301,6 +301,7 @@ extern "C" int32_t hts_test_gemm(hts_ctx *ctx, int32_t precision, const float *A
 }
 
 // ---- built-in event timer -------------------------------------------------------------------------------------
+extern "C" int32_t hts_profile_end(hts_ctx *ctx, int32_t *launches, double *total_ms);
 static const char *const k_site_names[SITE_COUNT] = {
     "prep", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc_fwd", "heads_act", "heads_learn", "heads_wgrad", "fc_wgrad",
     "fc_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "wgrad_reduce", "grad_norm",
@@ -330,6 +331,26 @@ extern "C" int32_t hts_profile_begin(hts_ctx *ctx, int32_t site)
         }
     }
     p.site = site; p.n = 0;
+    return HTS_OK;
+}
+
+// Mean elapsed time of an event pair with nothing between them: what the timer itself adds to every bracket.
+extern "C" int32_t hts_profile_overhead(hts_ctx *ctx, int32_t reps, double *mean_ms)
+{
+    if (!ctx || !mean_ms || reps <= 0 || reps > PROF_CAP) return HTS_EINVAL;
+    const int32_t rc = hts_profile_begin(ctx, 0);
+    if (rc != HTS_OK) return rc;
+    Profiler &p = ctx->c.prof;
+    for (int i = 0; i < reps; ++i) {
+        HIP_TRY(hipEventRecord(p.ev[2 * i], ctx->c.stream));
+        HIP_TRY(hipEventRecord(p.ev[2 * i + 1], ctx->c.stream));
+    }
+    p.n = reps;
+    int32_t n = 0;
+    double tot = 0.0;
+    const int32_t rc2 = hts_profile_end(ctx, &n, &tot);
+    if (rc2 != HTS_OK) return rc2;
+    *mean_ms = tot / reps;
     return HTS_OK;
 }
 
