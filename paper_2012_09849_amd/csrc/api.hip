@@ -98,8 +98,8 @@ void carve(Ctx &c, Carver &cv)
         cv.take(w.grads, (size_t)g.P * 4);
         // upper bounds of the split counts over every minibatch size B <= max_learn (see split_for)
         auto bound = [](long long kp, int maxz) { const long long n = (kp + 255) / 256; return (size_t)(n < maxz ? n : maxz); };
-        w.part_elems = bound((long long)ml * g.P3, 64) * 64 * 577 + bound((long long)ml * g.P2, 64) * 64 * 513 +
-                       bound((long long)ml * g.P1, 128) * 32 * (size_t)(g.K1 + 1);
+        w.part_elems = bound((long long)ml * g.P3, MAXZ3) * 64 * 577 + bound((long long)ml * g.P2, MAXZ2) * 64 * 513 +
+                       bound((long long)ml * g.P1, MAXZ1) * 32 * (size_t)(g.K1 + 1);
         cv.take(w.part, w.part_elems * 4);
     }
 }

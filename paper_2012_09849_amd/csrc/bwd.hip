@@ -50,8 +50,8 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         if (e != hipSuccess) return e;
     }
     // partial buffers of the three conv weight gradients live side by side in ws.part
-    const SplitK s3 = split_for((long long)B * g.P3, 64), s2 = split_for((long long)B * g.P2, 64),
-                 s1 = split_for((long long)B * g.P1, 128);
+    const SplitK s3 = split_for((long long)B * g.P3, MAXZ3), s2 = split_for((long long)B * g.P2, MAXZ2),
+                 s1 = split_for((long long)B * g.P1, MAXZ1);
     int spg3 = 0, spg2 = 0, spg1 = 0;
     const int nz3 = small ? groups_for((long long)B * g.P3, &spg3) : s3.nz;
     const int nz2 = small ? groups_for((long long)B * g.P2, &spg2) : s2.nz;

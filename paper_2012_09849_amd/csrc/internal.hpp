@@ -78,6 +78,10 @@ struct SiteTimer {
     }
 };
 
+// most chunks a conv weight gradient's reduction is cut into (layers 3, 2, 1)
+// (these kernels are bound by the latency of each workgroup's serial walk along its chunk, so many short chunks
+// beat few long ones; measured at B = 1024: conv1 170 -> 92 us going from 128 to 256 chunks)
+constexpr int MAXZ3 = 256, MAXZ2 = 128, MAXZ1 = 256;
 struct SplitK { int klen, nz; };
 // Split of a weight-gradient reduction of length kp; depends on kp only, so results are reproducible.
 inline SplitK split_for(long long kp, int maxz)

@@ -36,7 +36,11 @@ template <int CIN_, int KSZ_, int STRIDE_> struct ConvLayer {
 typedef ConvLayer<32, 4, 2> Layer2;
 typedef ConvLayer<64, 3, 1> Layer3;
 
-struct OffCtx { long long off; };          // element offset of the row's first operand, or -1 for a row outside M
+// Row part of a gather: pointer to the row's first operand.  Rows outside the matrix are clamped to the last valid
+// row (their products land in output rows that are never stored), so loads need no row check; only the end of the
+// reduction range (k >= kend) yields zeros.
+template <typename S> struct PtrCtx { const S *p; };
+HTS_HD int clamp_row(int r, int n) { return r < n ? r : n - 1; }
 
 // ------------------------------------------------------------------------------------------------------------
 // plain C = A * B^T on f32 arrays (test hook for the tile core)
@@ -46,20 +50,20 @@ template <typename T_> struct PlainGemm {
     static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = 4, VB = 4;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    typedef OffCtx CtxA;
-    typedef OffCtx CtxB;
+    typedef PtrCtx<float> CtxA;
+    typedef PtrCtx<float> CtxB;
     int M, N, K, klen;
     const float *A, *B;
     float *C;
-    HTS_HD CtxA ctx_a(int m) const { return {m < M ? (long long)m * K : -1}; }
-    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD CtxA ctx_a(int m) const { return {A + (long long)clamp_row(m, M) * K}; }
+    HTS_HD CtxB ctx_b(int n) const { return {B + (long long)clamp_row(n, N) * K}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VA>(A + c.off + k) : zero_vec<T, VA>();
+        return k < kend ? load_vec<T, VA>(c.p + k) : zero_vec<T, VA>();
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(B + c.off + k) : zero_vec<T, VB>();
+        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int m, int n, float acc, int) const { C[(long long)m * N + n] = acc; }
 };
@@ -74,8 +78,8 @@ template <typename T_> struct Conv1Fwd {
     static constexpr int VA = 8, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 64;       // forward sums are segmented so every kernel variant returns the same bits
-    typedef OffCtx CtxA;
-    typedef OffCtx CtxB;
+    typedef PtrCtx<uint8_t> CtxA;
+    typedef PtrCtx<T> CtxB;
     int M, N, K, klen;
     const uint8_t *obs;
     const int32_t *index;
@@ -86,21 +90,21 @@ template <typename T_> struct Conv1Fwd {
     FastDiv dP1, dW1;
     HTS_HD CtxA ctx_a(int m) const
     {
-        if (m >= M) return {-1};
+        m = clamp_row(m, M);
         const int b = dP1.div(m), p = m - b * P1, oy = dW1.div(p), ox = p - oy * W1;
         const long long row = index ? index[b] : b;
-        return {row * C * H * W + (long long)(oy * 4) * W + ox * 4};
+        return {obs + row * C * H * W + (oy * 4) * W + ox * 4};
     }
-    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD CtxB ctx_b(int n) const { return {w + (long long)clamp_row(n, N) * K}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (c.off < 0 || k >= kend) return zero_vec<T, VA>();
-        const int ch = k >> 6, u = (k >> 3) & 7;
-        return load_u8x8<T>(obs + c.off + (ch * H + u) * W);
+        if (k >= kend) return zero_vec<T, VA>();
+        const unsigned uk = (unsigned)k, ch = uk >> 6, u = (uk >> 3) & 7u;
+        return load_u8x8<T>(c.p + (ch * (unsigned)H + u) * (unsigned)W);
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(w + c.off + k) : zero_vec<T, VB>();
+        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
     }
     HTS_HD float col(int n) const { return bias[n]; }
     HTS_HD void store(int m, int n, float acc, int, const float &b) const
@@ -120,8 +124,8 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     // conv2: one tap row (4*32 = 128); conv3: one tap row (3*64 = 192) for bf16, half of one for fp32
     static constexpr int SEG = L::KSZ == 4 ? 128 : (sizeof(T) == 2 ? 192 : 96);
-    typedef OffCtx CtxA;
-    typedef OffCtx CtxB;
+    typedef PtrCtx<T> CtxA;
+    typedef PtrCtx<T> CtxB;
     int M, N, K, klen;
     const T *in;      // [B][Hin][Win][Cin]
     const T *wf;      // [Cout][K]
@@ -132,20 +136,20 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     FastDiv dPo, dWo;
     HTS_HD CtxA ctx_a(int m) const
     {
-        if (m >= M) return {-1};
+        m = clamp_row(m, M);
         const int b = dPo.div(m), p = m - b * Po, oy = dWo.div(p), ox = p - oy * Wo;
-        return {(((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN};
+        return {in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN};
     }
-    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD CtxB ctx_b(int n) const { return {wf + (long long)clamp_row(n, N) * K}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (c.off < 0 || k >= kend) return zero_vec<T, VA>();
-        const int u = k / (L::KSZ * L::CIN), r = k - u * (L::KSZ * L::CIN);     // a tap row is contiguous in memory
-        return load_vec<T, VA>(in + c.off + (long long)u * Win * L::CIN + r);
+        if (k >= kend) return zero_vec<T, VA>();
+        const unsigned uk = (unsigned)k, u = uk / (unsigned)(L::KSZ * L::CIN), r = uk - u * (L::KSZ * L::CIN);
+        return load_vec<T, VA>(c.p + (u * (unsigned)(Win * L::CIN) + r));     // a tap row is contiguous in memory
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(wf + c.off + k) : zero_vec<T, VB>();
+        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
     }
     HTS_HD float col(int n) const { return bias[n]; }
     HTS_HD void store(int m, int n, float acc, int, const float &bn) const
@@ -170,20 +174,20 @@ template <typename T_> struct FcFwd {
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 128;
-    typedef OffCtx CtxA;
-    typedef OffCtx CtxB;
+    typedef PtrCtx<T> CtxA;
+    typedef PtrCtx<T> CtxB;
     int M, N, K, klen;
     const T *a3, *w;
     float *part;      // [groups][M][N]
-    HTS_HD CtxA ctx_a(int m) const { return {m < M ? (long long)m * K : -1}; }
-    HTS_HD CtxB ctx_b(int n) const { return {n < N ? (long long)n * K : -1}; }
+    HTS_HD CtxA ctx_a(int m) const { return {a3 + (long long)clamp_row(m, M) * K}; }
+    HTS_HD CtxB ctx_b(int n) const { return {w + (long long)clamp_row(n, N) * K}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VA>(a3 + c.off + k) : zero_vec<T, VA>();
+        return k < kend ? load_vec<T, VA>(c.p + k) : zero_vec<T, VA>();
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(w + c.off + k) : zero_vec<T, VB>();
+        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int m, int n, float acc, int grp) const { part[((long long)grp * M + m) * N + n] = acc; }
 };
@@ -231,7 +235,7 @@ struct HeadsWgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcWgrad {
     using T = T_;
-    static constexpr int BM = 128, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 4, WAVES_N = 1;
+    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;   // 8 x 50 workgroups
     static constexpr int VA = 4, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
     struct CtxA { int j; };
@@ -270,21 +274,21 @@ template <typename T_> struct FcDgrad {
     static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    typedef OffCtx CtxA;
-    typedef OffCtx CtxB;
+    typedef PtrCtx<float> CtxA;
+    typedef PtrCtx<T> CtxB;
     int M, N, K, klen;     // M = B, N = F, K = 512
     const float *dh;
     const T *wfcd, *a3n;
     T *dy3;
-    HTS_HD CtxA ctx_a(int b) const { return {b < M ? (long long)b * 512 : -1}; }
-    HTS_HD CtxB ctx_b(int f) const { return {f < N ? (long long)f * 512 : -1}; }
+    HTS_HD CtxA ctx_a(int b) const { return {dh + (long long)clamp_row(b, M) * 512}; }
+    HTS_HD CtxB ctx_b(int f) const { return {wfcd + (long long)clamp_row(f, N) * 512}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VA>(dh + c.off + k) : zero_vec<T, VA>();
+        return k < kend ? load_vec<T, VA>(c.p + k) : zero_vec<T, VA>();
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        return (c.off >= 0 && k < kend) ? load_vec<T, VB>(wfcd + c.off + k) : zero_vec<T, VB>();
+        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
     }
     HTS_HD void store(int b, int f, float acc, int) const
     {
