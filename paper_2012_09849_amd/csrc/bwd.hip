@@ -119,10 +119,11 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         }
         if (e != hipSuccess) return e;
     }
-    if ((e = launch_wgrad_reduce(c, part3, nz3, 64, 577, 64, 3, true, 1.0f, grads, g.w3, g.b3)) != hipSuccess) return e;
-    if ((e = launch_wgrad_reduce(c, part2, nz2, 64, 513, 32, 4, true, 1.0f, grads, g.w2, g.b2)) != hipSuccess) return e;
-    if ((e = launch_wgrad_reduce(c, part1, nz1, 32, g.K1 + 1, g.C, 8, false, 1.0f / 255.0f, grads, g.w1, g.b1)) !=
-        hipSuccess) return e;
+    const ReduceSpec specs[3] = {
+        {part3, nz3, 64, 577, 64, 3, true, 1.0f, g.w3, g.b3},
+        {part2, nz2, 64, 513, 32, 4, true, 1.0f, g.w2, g.b2},
+        {part1, nz1, 32, g.K1 + 1, g.C, 8, false, 1.0f / 255.0f, g.w1, g.b1}};
+    if ((e = launch_wgrad_reduce(c, specs, grads)) != hipSuccess) return e;
     return hipSuccess;
 }
 

@@ -114,8 +114,14 @@ hipError_t launch_heads_act(Ctx &c, const float *logits_in, uint64_t seed, uint3
                             int env_offset, int32_t *actions, float *logp, float *values, float *logits_out);
 hipError_t launch_heads_learn(Ctx &c, const LossArgs &la, int B);
 hipError_t launch_stats(Ctx &c, int B, hts_stats *stats);
-hipError_t launch_wgrad_reduce(Ctx &c, const float *part, int nz, int rows, int ncol, int cin, int ksz, bool taps_outer,
-                               float scale, float *g, long long w_off, long long b_off);
+struct ReduceSpec {       // one layer's split weight gradient: part[nz][rows][ncol] -> g (see wgrad_reduce_kernel)
+    const float *part;
+    int nz, rows, ncol, cin, ksz;
+    bool taps_outer;
+    float scale;
+    long long w_off, b_off;
+};
+hipError_t launch_wgrad_reduce(Ctx &c, const ReduceSpec (&spec)[3], float *g);
 hipError_t launch_gae(Ctx *c, hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
                       int N, float *adv, float *ret);
 hipError_t launch_normalize(Ctx *c, hipStream_t s, float *adv, long long n);

@@ -461,44 +461,77 @@ hipError_t launch_stats(Ctx &c, int B, hts_stats *stats)
 }
 
 // ------------------------------------------------------------------------------------------------------------
-// split-K combine: g[dest(n,kcol)] = scale * sum_z part[z][n][kcol], z ascending
+// Combine of the split conv weight gradients, all three layers in one launch:
+// g[dest(n,kcol)] = scale * sum_z part[z][n][kcol].  A workgroup owns 32 consecutive outputs; its 8 lane groups sum
+// 8 contiguous ranges of z (loads in flight eight at a time, added in z order) and the 8 range sums are added in
+// range order -- a fixed shape, so the result is reproducible.
 // ------------------------------------------------------------------------------------------------------------
-__global__ void wgrad_reduce_kernel(const float *__restrict__ part, int nz, int rows, int ncol, int cin, int ksz,
-                                    int taps_outer, float scale, float *__restrict__ g, long long w_off,
-                                    long long b_off)
+struct ReduceJob {
+    const float *part;
+    int nz, rows, ncol, cin, ksz, taps_outer, first_block;
+    float scale;
+    long long w_off, b_off;
+};
+struct ReduceArgs { ReduceJob job[3]; float *g; };
+
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceArgs a)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows * ncol) return;
-    const int n = i / ncol, kcol = i - n * ncol;
+    __shared__ float red[8][33];
+    const int blk = blockIdx.x;
+    const int jn = blk >= a.job[2].first_block ? 2 : (blk >= a.job[1].first_block ? 1 : 0);
+    const ReduceJob &jb = a.job[jn];
+    const int e = threadIdx.x & 31, q = threadIdx.x >> 5;
+    const int n_el = jb.rows * jb.ncol;
+    const int i = (blk - jb.first_block) * 32 + e;
+    const long long zs = (long long)n_el;
+    const int chunk = (jb.nz + 7) / 8;
+    int z = q * chunk;
+    const int z1 = min(jb.nz, z + chunk);
     float s = 0.0f;
-    const long long zs = (long long)rows * ncol;
-    int z = 0;
-    for (; z + 8 <= nz; z += 8) {            // eight loads in flight, added in z order
-        float v[8];
+    if (i < n_el) {
+        const float *src = jb.part + i;
+        for (; z + 8 <= z1; z += 8) {
+            float v[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = part[(z + q) * zs + i];
+            for (int t = 0; t < 8; ++t) v[t] = src[(z + t) * zs];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) s += v[q];
+            for (int t = 0; t < 8; ++t) s += v[t];
+        }
+        for (; z < z1; ++z) s += src[z * zs];
     }
-    for (; z < nz; ++z) s += part[z * zs + i];
-    s *= scale;
-    const int kc = ncol - 1;
-    if (kcol == kc) { g[b_off + n] = s; return; }
+    red[q][e] = s;
+    __syncthreads();
+    if (q != 0 || i >= n_el) return;
+    float tot = red[0][e];
+#pragma unroll
+    for (int t = 1; t < 8; ++t) tot += red[t][e];
+    tot *= jb.scale;
+    const int n = i / jb.ncol, kcol = i - n * jb.ncol;
+    const int kc = jb.ncol - 1;
+    if (kcol == kc) { a.g[jb.b_off + n] = tot; return; }
     long long dst;
-    if (taps_outer) {                 // kcol = (tap, c)  ->  w[n][c][tap]
-        const int tap = kcol / cin, c = kcol - tap * cin;
-        dst = ((long long)n * cin + c) * (ksz * ksz) + tap;
+    if (jb.taps_outer) {              // kcol = (tap, c)  ->  w[n][c][tap]
+        const int tap = kcol / jb.cin, c = kcol - tap * jb.cin;
+        dst = ((long long)n * jb.cin + c) * (jb.ksz * jb.ksz) + tap;
     } else dst = (long long)n * kc + kcol;
-    g[w_off + dst] = s;
+    a.g[jb.w_off + dst] = tot;
 }
 
-hipError_t launch_wgrad_reduce(Ctx &c, const float *part, int nz, int rows, int ncol, int cin, int ksz, bool taps_outer,
-                               float scale, float *g, long long w_off, long long b_off)
+hipError_t launch_wgrad_reduce(Ctx &c, const ReduceSpec (&spec)[3], float *g)
 {
     SiteTimer tm(c, SITE_WGRAD_REDUCE);
-    const int n = rows * ncol;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, c.stream, part, nz, rows, ncol, cin,
-                       ksz, taps_outer ? 1 : 0, scale, g, w_off, b_off);
+    ReduceArgs a;
+    int blocks = 0;
+    for (int j = 0; j < 3; ++j) {
+        const ReduceSpec &sp = spec[j];
+        ReduceJob &jb = a.job[j];
+        jb.part = sp.part; jb.nz = sp.nz; jb.rows = sp.rows; jb.ncol = sp.ncol; jb.cin = sp.cin; jb.ksz = sp.ksz;
+        jb.taps_outer = sp.taps_outer ? 1 : 0; jb.scale = sp.scale; jb.w_off = sp.w_off; jb.b_off = sp.b_off;
+        jb.first_block = blocks;
+        blocks += (sp.rows * sp.ncol + 31) / 32;
+    }
+    a.g = g;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(256), 0, c.stream, a);
     return hipGetLastError();
 }
 
