@@ -107,6 +107,55 @@ class Loop:
         self.iteration += 1
 
 
+class OverlapLoop:
+    """The paper's schedule (Sec. 4.1 "Concurrent rollout and learning", "Delayed gradient") for workloads with one
+    update per storage: while the actors fill storage j with theta_j on one stream, the learner takes the gradient at
+    theta_{j-1} on storage j-1 on another stream and applies it to theta_j; the streams meet once per iteration.
+    Two contexts (calls on one context must not overlap), two storages, three parameter vectors in rotation."""
+
+    def __init__(self, base):
+        torch, hts, cfg = base.torch, base.hts, base.cfg
+        self.base, self.cfg, self.torch = base, cfg, torch
+        N, T = cfg["N"], cfg["T"]
+        self.s_roll, self.s_learn = torch.cuda.Stream(), torch.cuda.Stream()
+        mk = lambda **kw: hts.Context(cfg["C"], cfg["H"], cfg["W"], cfg["A"], precision=cfg["precision"], **kw)
+        self.ctx_act = mk(max_act_batch=N, stream=self.s_roll)
+        self.ctx_learn = mk(max_learn_batch=N * T, stream=self.s_learn)
+        z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device="cuda")
+        self.store = [dict(actions=z(T + 1, N, dt=torch.int32), logp=z(T + 1, N), values=z(T + 1, N), adv=z(T, N),
+                           ret=z(T, N)) for _ in range(2)]
+        self.theta = [base.params.clone() for _ in range(3)]        # prev, cur, next
+        P = base.params.numel()
+        self.opt = hts.OptState(z(P), z(P), 0)
+        self.ev_roll, self.ev_learn = torch.cuda.Event(), torch.cuda.Event()
+        self.j = 0
+        torch.cuda.synchronize()
+
+    def step(self):
+        torch, cfg, b = self.torch, self.cfg, self.base
+        T, N = cfg["T"], cfg["N"]
+        prev, cur, nxt = self.theta
+        st = self.store[self.j % 2]
+        for t in range(T + 1):
+            self.ctx_act.hts_act(b.obs[t], cur if t == 0 else None, 20201209, self.j * (T + 1) + t, 0, st["actions"][t],
+                                 st["logp"][t], st["values"][t])
+        self.ctx_act.hts_returns_gae(b.rew, st["values"], b.dones, cfg["gamma"], cfg["lam"], st["adv"], st["ret"])
+        self.ev_roll.record(self.s_roll)
+        with torch.cuda.stream(self.s_learn):
+            nxt.copy_(cur)
+            if self.j > 0:
+                old = self.store[(self.j - 1) % 2]
+                obs = b.obs[:T].reshape(T * N, cfg["C"], cfg["H"], cfg["W"])
+                self.ctx_learn.hts_learner_step_delayed(obs, old["actions"][:T].reshape(-1), old["logp"][:T].reshape(-1),
+                                                        old["adv"].reshape(-1), old["ret"].reshape(-1), prev, nxt,
+                                                        self.opt, b.hp)
+        self.ev_learn.record(self.s_learn)
+        self.s_roll.wait_event(self.ev_learn)
+        self.s_learn.wait_event(self.ev_roll)
+        self.theta = [cur, nxt, prev]
+        self.j += 1
+
+
 PEAK = {"mfma_f32": 157.3e12, "mfma_bf16": 2.5e15, "hbm": 8.0e12}
 
 
@@ -349,6 +398,21 @@ def main():
     if not args.site:
         out["streaming"] = streaming_rooflines(loop, per_step, work, torch, overhead_ms)
     out["kernel_ms_per_step"] = {k: round(v[0], 5) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1][0])}
+    if cfg["epochs"] * cfg["minibatches"] == 1:
+        ov = OverlapLoop(loop)
+        for _ in range(args.warmup):
+            ov.step()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            ov.step()
+        torch.cuda.synchronize()
+        ov_wall = time.perf_counter() - t2
+        out["overlapped"] = {"value": frames * args.steps / ov_wall, "unit": "env-frames/s",
+                             "ms_per_step": ov_wall / args.steps * 1e3,
+                             "schedule": "rollout with theta_j on one stream while the learner applies the gradient taken "
+                                         "at theta_{j-1} on the previous storage on a second stream (one-step-delayed "
+                                         "update); same work per step as `value`, which runs the three parts in sequence"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, loop)
     print(json.dumps(out))

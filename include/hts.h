@@ -144,6 +144,15 @@ typedef struct {
 int32_t hts_learner_step(hts_ctx *ctx, const hts_buffer *buf, float *params, hts_opt_state *opt,
                          const hts_hparams *hp, hts_stats *stats_or_null);
 
+/* The paper's update rule (Sec. 4.1 "Delayed gradient"): theta_{j+1} = theta_j + eta * grad J(theta_{j-1}; D^{theta_{j-1}}).
+ * The storage `buf` was collected with params_behaviour = theta_{j-1}; forward, loss and backward run at theta_{j-1};
+ * the clipped gradient goes through the optimiser into params_target = theta_j (in/out), which the forward pass never
+ * reads.  With one update per storage this lets the learner work on storage j-1 while the actors fill storage j with
+ * theta_j.  params_behaviour and params_target must be different vectors (HTS_EINVAL otherwise); both f32 [P]. */
+int32_t hts_learner_step_delayed(hts_ctx *ctx, const hts_buffer *buf, const float *params_behaviour,
+                                 float *params_target, hts_opt_state *opt, const hts_hparams *hp,
+                                 hts_stats *stats_or_null);
+
 /* The same forward/loss/backward without the update: grads f32 [P] receives dL/dparams (unclipped). */
 int32_t hts_loss_and_grads(hts_ctx *ctx, const hts_buffer *buf, const float *params, const hts_hparams *hp,
                            float *grads, hts_stats *stats_or_null);

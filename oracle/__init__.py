@@ -212,3 +212,14 @@ def learner_step(net: Net, params, m, v, t: int, obs, actions, old_logp, adv, re
                                 C.byref(st))
     assert rc == 0
     return th, m2, v2, g, st.as_dict()
+
+
+def learner_step_delayed(net: Net, params_behaviour, params_target, m, v, t: int, obs, actions, old_logp, adv, ret,
+                         hp: HParams, index=None):
+    """The paper's one-step-delayed update (Sec. 4.1 "Delayed gradient"): the gradient of the objective at the behaviour
+    parameters theta_{j-1}, on the storage collected with them, goes through clip + optimiser into the target
+    parameters theta_j.  -> (theta_{j+1}, m, v, grads, stats), new float64 arrays."""
+    g, st = loss_grads(net, params_behaviour, obs, actions, old_logp, adv, ret, hp, index=index)
+    scale = clip_coef(g, hp.max_grad_norm) if hp.max_grad_norm > 0 else 1.0
+    th, m2, v2 = adam(params_target, g, m, v, t, hp, gscale=scale)
+    return th, m2, v2, g, st

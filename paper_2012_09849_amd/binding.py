@@ -13,7 +13,7 @@ PRECISION_FP32, PRECISION_BF16 = 0, 1
 ALGO_A2C, ALGO_PPO = 0, 1
 
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
-           "hts_normalize_advantages", "hts_learner_step", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
+           "hts_normalize_advantages", "hts_learner_step", "hts_learner_step_delayed", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
            "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
            "hts_profile_end", "hts_profile_overhead"]
 
@@ -193,6 +193,17 @@ class Context:
         oc = _OptStateC(_ptr(opt.m, torch.float32, "m"), _ptr(opt.v, torch.float32, "v"), opt.step)
         _check(self.lib.hts_learner_step(self._h, C.byref(buf), _ptr(params, torch.float32, "params"), C.byref(oc),
                                          C.byref(hp), _ptr(stats, torch.float32, "stats")), "hts_learner_step")
+        opt.step = oc.step
+
+    def hts_learner_step_delayed(self, obs, actions, old_logp, advantages, returns, params_behaviour, params_target,
+                                 opt: OptState, hp: HParams, index=None, B=None, stats=None):
+        buf, _keep = self._buffer(obs, actions, old_logp, advantages, returns, index, B)
+        oc = _OptStateC(_ptr(opt.m, torch.float32, "m"), _ptr(opt.v, torch.float32, "v"), opt.step)
+        _check(self.lib.hts_learner_step_delayed(self._h, C.byref(buf),
+                                                 _ptr(params_behaviour, torch.float32, "params_behaviour"),
+                                                 _ptr(params_target, torch.float32, "params_target"), C.byref(oc),
+                                                 C.byref(hp), _ptr(stats, torch.float32, "stats")),
+               "hts_learner_step_delayed")
         opt.step = oc.step
 
     def hts_loss_and_grads(self, obs, actions, old_logp, advantages, returns, params, hp: HParams, grads, index=None,

@@ -265,19 +265,34 @@ static int32_t adam_apply(Ctx &c, float *params, const float *grads, hts_opt_sta
     return HTS_OK;
 }
 
-extern "C" int32_t hts_learner_step(hts_ctx *ctx, const hts_buffer *buf, float *params, hts_opt_state *opt,
-                                    const hts_hparams *hp, hts_stats *stats_or_null)
+static int32_t learner_step(hts_ctx *ctx, const hts_buffer *buf, const float *params_grad, float *params,
+                            hts_opt_state *opt, const hts_hparams *hp, hts_stats *stats_or_null)
 {
-    const int32_t rc = check_learn(ctx, buf, params, hp);
+    const int32_t rc = check_learn(ctx, buf, params_grad, hp);
     if (rc != HTS_OK) return rc;
+    if (!params || ((uintptr_t)params & 15u)) return HTS_EINVAL;
     if (!opt || !opt->m || !opt->v || opt->step < 0) return HTS_EINVAL;
     Ctx &c = ctx->c;
-    const int32_t rc2 = loss_and_grads(c, buf, params, hp, c.ws.grads);
+    const int32_t rc2 = loss_and_grads(c, buf, params_grad, hp, c.ws.grads);
     if (rc2 != HTS_OK) return rc2;
     const bool need_norm = hp->max_grad_norm > 0.0f || stats_or_null;
     if (need_norm) HIP_TRY(launch_grad_norm(c, c.ws.grads, c.g.P, hp->max_grad_norm, nullptr));
     if (stats_or_null) HIP_TRY(launch_stats(c, buf->B, stats_or_null));
     return adam_apply(c, params, c.ws.grads, opt, hp, c.g.P, need_norm);
+}
+
+extern "C" int32_t hts_learner_step(hts_ctx *ctx, const hts_buffer *buf, float *params, hts_opt_state *opt,
+                                    const hts_hparams *hp, hts_stats *stats_or_null)
+{
+    return learner_step(ctx, buf, params, params, opt, hp, stats_or_null);
+}
+
+extern "C" int32_t hts_learner_step_delayed(hts_ctx *ctx, const hts_buffer *buf, const float *params_behaviour,
+                                            float *params_target, hts_opt_state *opt, const hts_hparams *hp,
+                                            hts_stats *stats_or_null)
+{
+    if (params_behaviour == params_target) return HTS_EINVAL;     // that is hts_learner_step
+    return learner_step(ctx, buf, params_behaviour, params_target, opt, hp, stats_or_null);
 }
 
 extern "C" int32_t hts_adam_apply(hts_ctx *ctx, float *params, const float *grads, hts_opt_state *opt,

@@ -387,6 +387,34 @@ def test_learner_step_parity(hts, oracle, shape, A, count, B, algo, eps, max_nor
     ctx.close()
 
 
+@pytest.mark.parametrize("algo,max_norm", [(0, 0.0), (1, 0.5)])
+def test_delayed_gradient_step_parity(hts, oracle, algo, max_norm):
+    """hts_learner_step_delayed: gradient at the behaviour parameters, update applied to the target parameters."""
+    shape, A, count = ATARI, 18, 24
+    Cc, H, W = shape
+    net, p_b, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 500, algo == 1)
+    p_t = (p_b + 0.01 * syn.normal_f32(77, syn.S_MISC, p_b.shape)).astype(np.float32)
+    ctx = hts.Context(Cc, H, W, A, max_learn_batch=count)
+    hp = hts.HParams(algo=algo, max_grad_norm=max_norm, lr=7e-4)
+    P = ctx.P
+    pb_d, pt_d = dev(p_b), dev(p_t)
+    opt = hts.OptState(torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda"), 0)
+    args = (dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret))
+    ctx.hts_learner_step_delayed(*args, pb_d, pt_d, opt, hp)
+    torch.cuda.synchronize()
+    p_ref, m_ref, v_ref, _, _ = oracle.learner_step_delayed(net, p_b, p_t, np.zeros(P), np.zeros(P), 1, obs, actions,
+                                                            old_logp, adv, ret, oracle_hp(oracle, hp))
+    got = pt_d.cpu().numpy().astype(np.float64)
+    for name, pp in _split(got, shape, A).items():
+        assert_close(pp, _split(p_ref, shape, A)[name], 1e-5, f"param {name}")
+    assert_close(opt.m.cpu().numpy(), m_ref, 1e-4, "m")
+    assert torch.equal(pb_d, dev(p_b)), "behaviour parameters must not change"
+    assert opt.step == 1
+    with pytest.raises(hts.HtsError):          # one vector for both roles is the ordinary step, not this call
+        ctx.hts_learner_step_delayed(*args, pt_d, pt_d, opt, hp)
+    ctx.close()
+
+
 def test_learner_errors_launch_nothing(hts):
     ctx = hts.Context(4, 84, 84, 6, max_act_batch=4, max_learn_batch=4)
     obs = torch.zeros(8, 4, 84, 84, dtype=torch.uint8, device="cuda")

@@ -59,3 +59,35 @@ def test_learner_step_composes(oracle):
     p2, m2, v2 = oracle.adam(p, g2 * s, m0, v0, 1, hp)
     np.testing.assert_allclose(p1, p2, rtol=1e-14, atol=1e-16)
     np.testing.assert_allclose(m1, m2, rtol=1e-14, atol=1e-300)
+
+
+def test_delayed_gradient_step(oracle):
+    """Sec. 4.1 "Delayed gradient": theta_{j+1} = theta_j + step(grad J(theta_{j-1}; D)).
+    Pins: (i) with theta_{j-1} == theta_j it is the ordinary update; (ii) the gradient and the loss statistics depend on
+    the behaviour parameters only; (iii) from zero moments the displacement theta_{j+1} - theta_j is the same whichever
+    target it is applied to (Adam's first step is a function of g alone), and equals -lr*g/(|g|+eps)."""
+    import hts_synth as syn
+    kw = dict(convs=((3, 8, 4), (4, 3, 1), (4, 2, 1)), hidden=8)
+    net = oracle.make_net(2, 20, 20, 3, **kw)
+    rng = np.random.default_rng(5)
+    pb = syn.init_params(1, 2, 20, 20, 3, bias_scale=0.1, **kw).astype(np.float64)
+    pt1 = syn.init_params(2, 2, 20, 20, 3, bias_scale=0.1, **kw).astype(np.float64)
+    pt2 = syn.init_params(3, 2, 20, 20, 3, bias_scale=0.1, **kw).astype(np.float64)
+    B = 12
+    obs = rng.integers(0, 256, size=(B, 2, 20, 20), dtype=np.uint8)
+    act = rng.integers(0, 3, size=B).astype(np.int32)
+    adv, ret, olp = rng.normal(size=B), rng.normal(size=B), -np.ones(B)
+    hp = oracle.make_hparams(algo=0, lr=1e-2)
+    z = np.zeros(pb.size)
+    same = oracle.learner_step_delayed(net, pb, pb, z, z, 1, obs, act, olp, adv, ret, hp)
+    plain = oracle.learner_step(net, pb, z, z, 1, obs, act, olp, adv, ret, hp)
+    np.testing.assert_allclose(same[0], plain[0], rtol=1e-14, atol=1e-16)
+    a = oracle.learner_step_delayed(net, pb, pt1, z, z, 1, obs, act, olp, adv, ret, hp)
+    b = oracle.learner_step_delayed(net, pb, pt2, z, z, 1, obs, act, olp, adv, ret, hp)
+    assert np.array_equal(a[3], b[3]) and np.array_equal(a[3], plain[3]) and a[4] == b[4]
+    np.testing.assert_allclose(a[0] - pt1, b[0] - pt2, rtol=0, atol=1e-15)
+    g = a[3]
+    np.testing.assert_allclose(a[0] - pt1, -1e-2 * g / (np.abs(g) + 1e-5), rtol=1e-9, atol=1e-15)
+    # a gradient taken at the target instead would differ
+    g_t, _ = oracle.loss_grads(net, pt1, obs, act, olp, adv, ret, hp)
+    assert np.linalg.norm(g_t - g) > 1e-3 * np.linalg.norm(g)
