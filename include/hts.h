@@ -123,11 +123,20 @@ typedef struct {
  *   L = L_pi + vf_coef * mean((R - v)^2) - ent_coef * mean(H(pi(.|s)))
  *   A2C: L_pi = -mean(logp * adv);  PPO: L_pi = -mean(min(rho adv, clip(rho, 1-eps, 1+eps) adv)),
  *   rho = exp(logp - old_logp).   max_grad_norm > 0: gradients are scaled by min(1, c / (||g||_2 + 1e-6)).
- *   Adam: m <- b1 m + (1-b1) g; v <- b2 v + (1-b2) g^2; theta <- theta - lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps). */
+ *   optimizer = HTS_OPT_ADAM:
+ *     m <- b1 m + (1-b1) g; v <- b2 v + (1-b2) g^2; theta <- theta - lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps).
+ *   optimizer = HTS_OPT_RMSPROP (the optimiser of the paper's experiments, appendix "Implementation Details":
+ *     momentum 0, epsilon 1e-5; the decay constant is not given there, 0.99 is the usual choice):
+ *     v <- alpha v + (1-alpha) g^2; theta <- theta - lr g / (sqrt(v) + eps), eps = adam_eps, alpha = rms_alpha;
+ *     hts_opt_state.m is overwritten with the clipped gradient. */
+#define HTS_OPT_ADAM    0
+#define HTS_OPT_RMSPROP 1
 typedef struct {
     int32_t algo;
     float clip_eps, vf_coef, ent_coef, max_grad_norm;
     float lr, beta1, beta2, adam_eps;
+    int32_t optimizer;
+    float rms_alpha;
 } hts_hparams;
 
 /* Optimiser state: m, v device f32 [P]; step is a host counter of completed updates (the call uses t = step+1 and

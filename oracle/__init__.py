@@ -223,3 +223,12 @@ def learner_step_delayed(net: Net, params_behaviour, params_target, m, v, t: int
     scale = clip_coef(g, hp.max_grad_norm) if hp.max_grad_norm > 0 else 1.0
     th, m2, v2 = adam(params_target, g, m, v, t, hp, gscale=scale)
     return th, m2, v2, g, st
+
+
+def rmsprop(theta, g, v, lr: float, alpha: float, eps: float, gscale: float = 1.0):
+    """-> new (theta, v) float64 copies."""
+    th, v2 = _f64(theta).copy(), _f64(v).copy()
+    g = _f64(g)
+    lib().orc_rmsprop(_ptr(th), _ptr(g), _ptr(v2), C.c_int64(th.size), C.c_double(gscale), C.c_double(lr),
+                      C.c_double(alpha), C.c_double(eps))
+    return th, v2

@@ -26,7 +26,7 @@
  *                      entropy bonus) and the squared value loss J_V of the
  *                      "Policy Gradient" paragraph; PPO's clipped surrogate
  *                      for algo = 1.
- *   orc_adam, orc_clip_coef, orc_learner_step, orc_normalize_adv
+ *   orc_adam, orc_rmsprop, orc_clip_coef, orc_learner_step, orc_normalize_adv
  *                      the optimiser step applied to the estimator above.
  *
  * Parity pins for every function live in tests/test_oracle_*.py.
@@ -500,6 +500,19 @@ void orc_adam(double *theta, const double *g, double *m, double *v, int64_t P, i
         m[i] = hp->beta1 * m[i] + (1.0 - hp->beta1) * gi;
         v[i] = hp->beta2 * v[i] + (1.0 - hp->beta2) * gi * gi;
         theta[i] -= hp->lr * (m[i] / bc1) / (sqrt(v[i] / bc2) + hp->adam_eps);
+    }
+}
+
+/* One RMSProp step without momentum (the optimiser of the paper's experiments, appendix "Implementation Details":
+ * momentum 0, epsilon 1e-5); g is multiplied by gscale first.
+ *   v <- alpha v + (1-alpha) g^2;  theta <- theta - lr * g / (sqrt(v) + eps) */
+void orc_rmsprop(double *theta, const double *g, double *v, int64_t P, double gscale, double lr, double alpha,
+                 double eps)
+{
+    for (int64_t i = 0; i < P; ++i) {
+        const double gi = g[i] * gscale;
+        v[i] = alpha * v[i] + (1.0 - alpha) * gi * gi;
+        theta[i] -= lr * gi / (sqrt(v[i]) + eps);
     }
 }
 

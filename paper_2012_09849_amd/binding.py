@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(_HERE, "libhts.so")
 
 PRECISION_FP32, PRECISION_BF16 = 0, 1
 ALGO_A2C, ALGO_PPO = 0, 1
+OPT_ADAM, OPT_RMSPROP = 0, 1
 
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_learner_step_delayed", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
@@ -35,11 +36,12 @@ class Buffer(C.Structure):
 class HParams(C.Structure):
     _fields_ = [("algo", C.c_int32), ("clip_eps", C.c_float), ("vf_coef", C.c_float), ("ent_coef", C.c_float),
                 ("max_grad_norm", C.c_float), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("adam_eps", C.c_float)]
+                ("adam_eps", C.c_float), ("optimizer", C.c_int32), ("rms_alpha", C.c_float)]
 
     def __init__(self, algo=ALGO_A2C, clip_eps=0.1, vf_coef=0.5, ent_coef=0.01, max_grad_norm=0.0, lr=7e-4,
-                 beta1=0.9, beta2=0.999, adam_eps=1e-5):
-        super().__init__(algo, clip_eps, vf_coef, ent_coef, max_grad_norm, lr, beta1, beta2, adam_eps)
+                 beta1=0.9, beta2=0.999, adam_eps=1e-5, optimizer=OPT_ADAM, rms_alpha=0.99):
+        super().__init__(algo, clip_eps, vf_coef, ent_coef, max_grad_norm, lr, beta1, beta2, adam_eps, optimizer,
+                         rms_alpha)
 
 
 class _OptStateC(C.Structure):

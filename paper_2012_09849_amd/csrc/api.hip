@@ -213,6 +213,7 @@ static int32_t check_learn(hts_ctx *ctx, const hts_buffer *buf, const float *par
     if (!ctx || !buf || !params || !hp) return HTS_EINVAL;
     if (!buf->obs || !buf->actions || !buf->advantages || !buf->returns) return HTS_EINVAL;
     if (hp->algo != HTS_ALGO_A2C && hp->algo != HTS_ALGO_PPO) return HTS_EINVAL;
+    if (hp->optimizer != HTS_OPT_ADAM && hp->optimizer != HTS_OPT_RMSPROP) return HTS_EINVAL;
     if (hp->algo == HTS_ALGO_PPO && !buf->old_logp) return HTS_EINVAL;
     if (buf->B <= 0 || buf->count <= 0) return HTS_EINVAL;
     if (!buf->index && buf->B > buf->count) return HTS_EINVAL;
@@ -254,12 +255,16 @@ static int32_t adam_apply(Ctx &c, float *params, const float *grads, hts_opt_sta
                           long long P, bool have_norm)
 {
     const int64_t t = opt->step + 1;
-    const float bc1 = (float)(1.0 - pow((double)hp->beta1, (double)t));
-    const float bc2 = (float)(1.0 - pow((double)hp->beta2, (double)t));
+    if (hp->optimizer != HTS_OPT_ADAM && hp->optimizer != HTS_OPT_RMSPROP) return HTS_EINVAL;
+    // RMSProp without momentum is the same elementwise update with beta1 = 0 (m = g) and no bias corrections
+    const bool rms = hp->optimizer == HTS_OPT_RMSPROP;
+    const float b1 = rms ? 0.0f : hp->beta1, b2 = rms ? hp->rms_alpha : hp->beta2;
+    const float bc1 = rms ? 1.0f : (float)(1.0 - pow((double)hp->beta1, (double)t));
+    const float bc2 = rms ? 1.0f : (float)(1.0 - pow((double)hp->beta2, (double)t));
     const bool clip = hp->max_grad_norm > 0.0f;
     if (clip && !have_norm) HIP_TRY(launch_grad_norm(c, grads, P, hp->max_grad_norm, nullptr));
-    HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, clip ? c.ws.clip : nullptr, hp->lr, hp->beta1, hp->beta2,
-                        hp->adam_eps, bc1, bc2));
+    HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, clip ? c.ws.clip : nullptr, hp->lr, b1, b2, hp->adam_eps,
+                        bc1, bc2));
     opt->step = t;
     c.synced = false; c.synced_learn = false;     // the caller's vector has moved on; the workspace copy has not
     return HTS_OK;

@@ -415,6 +415,48 @@ def test_delayed_gradient_step_parity(hts, oracle, algo, max_norm):
     ctx.close()
 
 
+def test_rmsprop_parity(hts, oracle):
+    """The paper's optimiser: three RMSProp steps on random gradients (with and without the norm clip), then one whole
+    learner step with it."""
+    rng = np.random.default_rng(9)
+    ctx = hts.Context(4, 84, 84, 6, max_learn_batch=8)
+    P = ctx.P
+    th = rng.normal(size=P).astype(np.float32)
+    th_d, m_d, v_d = dev(th), torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    opt = hts.OptState(m_d, v_d, 0)
+    th_o, v_o = th.astype(np.float64), np.zeros(P)
+    for step, max_norm in enumerate((0.0, 0.5, 0.0)):
+        hp = hts.HParams(optimizer=hts.OPT_RMSPROP, rms_alpha=0.99, lr=7e-4, adam_eps=1e-5, max_grad_norm=max_norm)
+        g = (rng.normal(size=P) * 10.0 ** rng.uniform(-4, 0, size=P)).astype(np.float32)
+        ctx.hts_adam_apply(th_d, dev(g), opt, hp)
+        torch.cuda.synchronize()
+        sc = oracle.clip_coef(g, max_norm) if max_norm > 0 else 1.0
+        th_o, v_o = oracle.rmsprop(th_o, g, v_o, float(hp.lr), float(hp.rms_alpha), float(hp.adam_eps), gscale=sc)
+        np.testing.assert_allclose(th_d.cpu().numpy(), th_o, rtol=0, atol=2e-6)
+        np.testing.assert_allclose(v_d.cpu().numpy(), v_o, rtol=1e-5, atol=1e-12)
+        th_o = th_d.cpu().numpy().astype(np.float64); v_o = v_d.cpu().numpy().astype(np.float64)
+    assert opt.step == 3
+    ctx.close()
+    # whole learner step
+    shape, A, count = ATARI, 6, 8
+    net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 600, False)
+    ctx = hts.Context(*shape, A, max_learn_batch=count)
+    hp = hts.HParams(algo=0, optimizer=hts.OPT_RMSPROP, lr=7e-4)
+    p_d = dev(params)
+    opt = hts.OptState(torch.zeros(ctx.P, device="cuda"), torch.zeros(ctx.P, device="cuda"), 0)
+    ctx.hts_learner_step(dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret), p_d, opt, hp)
+    torch.cuda.synchronize()
+    g_ref, _ = oracle.loss_grads(net, params, obs, actions, old_logp, adv, ret, oracle_hp(oracle, hp))
+    p_ref, _ = oracle.rmsprop(params, g_ref, np.zeros(ctx.P), float(hp.lr), float(hp.rms_alpha), float(hp.adam_eps))
+    # From v = 0 the step is lr*g/(sqrt(1-alpha)|g| + eps): ten times Adam's first step, and sensitive to the
+    # gradient's rounding over a ten times wider band (|g| <~ eps/sqrt(1-alpha)); hence 1e-4 where Adam's test has 1e-5.
+    for name, pp in _split(p_d.cpu().numpy().astype(np.float64), shape, A).items():
+        assert_close(pp, _split(p_ref, shape, A)[name], 1e-4, f"param {name}")
+    with pytest.raises(hts.HtsError):
+        ctx.hts_adam_apply(p_d, p_d, opt, hts.HParams(optimizer=7))
+    ctx.close()
+
+
 def test_learner_errors_launch_nothing(hts):
     ctx = hts.Context(4, 84, 84, 6, max_act_batch=4, max_learn_batch=4)
     obs = torch.zeros(8, 4, 84, 84, dtype=torch.uint8, device="cuda")

@@ -91,3 +91,28 @@ def test_delayed_gradient_step(oracle):
     # a gradient taken at the target instead would differ
     g_t, _ = oracle.loss_grads(net, pt1, obs, act, olp, adv, ret, hp)
     assert np.linalg.norm(g_t - g) > 1e-3 * np.linalg.norm(g)
+
+
+def test_rmsprop(oracle):
+    """RMSProp without momentum: first step from v = 0 is -lr g / (sqrt(1-alpha)|g| + eps); g = 0 leaves theta alone;
+    a three-step scalar sequence worked by hand."""
+    rng = np.random.default_rng(3)
+    g = rng.normal(size=50)
+    th0 = rng.normal(size=50)
+    th, v = oracle.rmsprop(th0, g, np.zeros(50), 7e-4, 0.99, 1e-5)
+    np.testing.assert_allclose(th - th0, -7e-4 * g / (np.sqrt(0.01) * np.abs(g) + 1e-5), rtol=1e-12)
+    np.testing.assert_allclose(v, 0.01 * g * g, rtol=1e-14)
+    th2, v2 = oracle.rmsprop(th0, np.zeros(50), v, 7e-4, 0.99, 1e-5)
+    assert np.array_equal(th2, th0)
+    np.testing.assert_allclose(v2, 0.99 * v, rtol=1e-15)
+    # alpha = 0.5, lr = 0.1, eps = 0, g = 2, 0, 4:  v = 2, 1, 8.5
+    t, vv = np.array([1.0]), np.zeros(1)
+    want = [1.0 - 0.1 * 2 / np.sqrt(2.0), 1.0 - 0.1 * 2 / np.sqrt(2.0),
+            1.0 - 0.1 * 2 / np.sqrt(2.0) - 0.1 * 4 / np.sqrt(8.5)]
+    for k, gk in enumerate([2.0, 0.0, 4.0]):
+        t, vv = oracle.rmsprop(t, np.array([gk]), vv, 0.1, 0.5, 0.0 if gk else 1e-30)
+        np.testing.assert_allclose(t[0], want[k], rtol=1e-14)
+    # gscale is a plain factor on g
+    a = oracle.rmsprop(th0, g, np.zeros(50), 1e-3, 0.9, 1e-5, gscale=0.25)
+    b = oracle.rmsprop(th0, 0.25 * g, np.zeros(50), 1e-3, 0.9, 1e-5)
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-15)
