@@ -21,6 +21,11 @@
 #pragma once
 #include "gemm.hpp"
 
+// k per staged tile of the tile kernel for bf16 operands (fp32: 32 everywhere).  The weight gradients walk a long
+// reduction chunk per workgroup and are bound by the latency of each step, so they take deeper tiles (measured at
+// B = 1024: conv1 92 -> 53 us, conv2 50 -> 41 us); forward and input-gradient kernels measured no faster or slower.
+constexpr int BK_BF16 = 64, BK_BF16_WGRAD = 128;
+
 namespace hts {
 
 struct Geom {
@@ -74,7 +79,7 @@ template <typename T_> struct PlainGemm {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct Conv1Fwd {
     using T = T_;
-    static constexpr int BM = 128, BN = 32, BK = OperandTraits<T>::BK, WAVES_M = 4, WAVES_N = 1;
+    static constexpr int BM = 128, BN = 32, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 4, WAVES_N = 1;
     static constexpr int VA = 8, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 64;       // forward sums are segmented so every kernel variant returns the same bits
@@ -119,7 +124,7 @@ template <typename T_> struct Conv1Fwd {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
+    static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     // conv2: one tap row (4*32 = 128); conv3: one tap row (3*64 = 192) for bf16, half of one for fp32
@@ -170,7 +175,7 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcFwd {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
+    static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 128;
@@ -235,7 +240,7 @@ struct HeadsWgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcWgrad {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;   // 8 x 50 workgroups
+    static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 2, WAVES_N = 2;   // 8 x 50 workgroups
     static constexpr int VA = 4, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
     struct CtxA { int j; };
@@ -271,7 +276,7 @@ template <typename T_> struct FcWgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct FcDgrad {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
+    static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     typedef PtrCtx<float> CtxA;
@@ -307,7 +312,7 @@ template <typename T_> struct FcDgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_, class L> struct ConvDgrad {
     using T = T_;
-    static constexpr int BN = L::CIN, BM = (BN == 32 ? 128 : 64), BK = OperandTraits<T>::BK, WAVES_M = (BN == 32 ? 4 : 2),
+    static constexpr int BN = L::CIN, BM = (BN == 32 ? 128 : 64), BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = (BN == 32 ? 4 : 2),
                          WAVES_N = 4 / WAVES_M;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
@@ -394,7 +399,7 @@ template <typename T_, class L> struct ConvDgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_, class L> struct ConvWgrad {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = OperandTraits<T>::BK, WAVES_M = 2, WAVES_N = 2;
+    static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
     struct CtxA { int n; };
@@ -435,7 +440,7 @@ template <typename T_, class L> struct ConvWgrad {
 // conv1 weight gradient: as above with the uint8 frames as the im2col source, kcol = (c,u,v)
 template <typename T_> struct Conv1Wgrad {
     using T = T_;
-    static constexpr int BM = 32, BN = 128, BK = OperandTraits<T>::BK, WAVES_M = 1, WAVES_N = 4;
+    static constexpr int BM = 32, BN = 128, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 1, WAVES_N = 4;
     static constexpr int VA = OperandTraits<T>::VEC, VB = 8;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
     struct CtxA { int n; };
