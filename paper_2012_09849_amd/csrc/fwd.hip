@@ -30,7 +30,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.dPo = FastDiv::make(g.P2); p.dWo = FastDiv::make(g.W2);
         {
             SiteTimer tm(c, SITE_CONV2_FWD);
-            e = small ? launch_wsgemm<ConvFwd<T, Layer2, false>, 4, ConvFwd<T, Layer2, false>::SEG, false>(p, c.stream)
+            e = small ? launch_wsgemm<ConvFwd<T, Layer2, false>, 8, ConvFwd<T, Layer2, false>::SEG, false>(p, c.stream)
                       : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
@@ -56,7 +56,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         static_assert(FC_GROUP_K % FcFwd<T>::SEG == 0, "a group is a whole number of segments");
         {
             SiteTimer tm(c, SITE_FC_FWD);
-            e = small ? launch_wsgemm<FcFwd<T>, 4, FcFwd<T>::SEG, false>(p, c.stream, FC_GROUP_K / FcFwd<T>::SEG)
+            e = small ? launch_wsgemm<FcFwd<T>, 8, FcFwd<T>::SEG, false>(p, c.stream, FC_GROUP_K / FcFwd<T>::SEG)
                       : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;

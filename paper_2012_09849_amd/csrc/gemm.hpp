@@ -4,7 +4,7 @@
 // expressed as  D[m][n] = sum_k A(m,k) * B(n,k)  where a small "problem" object supplies the operand gathers
 // (implicit im2col, index gather, weight layouts) and the epilogue (bias, ReLU, masks, output layout).
 //
-// One workgroup = 256 threads = 4 wavefronts of 64 lanes; each wavefront owns a (TM*32) x (TN*32) block of D
+// One workgroup = WAVES_M x WAVES_N wavefronts of 64 lanes (2 to 8); each wavefront owns a (TM*32) x (TN*32) block of D
 // built from 32x32 MFMA accumulators:
 //   fp32 : v_mfma_f32_32x32x2_f32   (lane l supplies A[l%32][l/32] and B[l/32][l%32])
 //   bf16 : v_mfma_f32_32x32x16_bf16 (lane l supplies 8 consecutive k at k0 = 8*(l/32) for row/col l%32)

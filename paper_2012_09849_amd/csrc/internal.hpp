@@ -11,7 +11,7 @@ namespace hts {
 
 constexpr int NORM_CHUNK = 8192;   // elements per workgroup in the gradient-norm pass (fixes the reduction shape)
 constexpr int N_TERMS = 5;         // per-sample loss terms: policy, value, entropy, clipped flag, kl
-constexpr int FC_GROUP_K = 512;    // the FC layer's reduction is cut into groups of this many inputs (4 segments of 128)
+constexpr int FC_GROUP_K = 512;    // the FC layer's reduction is cut into groups of this many inputs (8 segments of 64)
 
 // Offsets inside Workspace::hb.
 struct ShadowOffsets { long long b1, b2, b3, fcb, piw, pib, vw, vb, count; };

@@ -223,27 +223,21 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         if (lane < A) mylogit = a.logits_in[(long long)b * A + lane];
     } else {
         {
-            // add the FC layer's group sums in group order, then bias + ReLU; five groups' loads are issued
-            // together so that their latencies overlap
+            // add the FC layer's group sums in group order, then bias + ReLU
 #pragma unroll
             for (int i = 0; i < 8; ++i) hv[i] = 0.0f;
             const float *src = a.fc_part + (long long)b * 512 + lane * 8;
             const long long sstride = (long long)a.B * 512;
-            int s = 0;
-            for (; s + 5 <= a.nseg; s += 5) {
-                float pv[5][8];
+            for (int s = 0; s < a.nseg; s += 8) {          // eight groups' loads in flight, added in group order
+                float pv[8][8];
 #pragma unroll
-                for (int q = 0; q < 5; ++q) load_vec(src + (s + q) * sstride, pv[q]);
+                for (int q = 0; q < 8; ++q)
+                    if (s + q < a.nseg) load_vec(src + (s + q) * sstride, pv[q]);
 #pragma unroll
-                for (int q = 0; q < 5; ++q)
+                for (int q = 0; q < 8; ++q)
+                    if (s + q < a.nseg)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) hv[i] += pv[q][i];
-            }
-            for (; s < a.nseg; ++s) {
-                float pv[8];
-                load_vec(src + s * sstride, pv);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) hv[i] += pv[i];
+                        for (int i = 0; i < 8; ++i) hv[i] += pv[q][i];
             }
             float bv8[8];
             load_vec(a.fc_bias + lane * 8, bv8);
@@ -262,30 +256,48 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         // barrier is needed because a wavefront's LDS operations execute in order).  The value head is one more dot
         // product, reduced by a butterfly.
         float *panel = heads_lds + (threadIdx.x >> 6) * A * 65;
-        for (int j = 0; j < A; ++j) {
-            float wv8[8];
-            load_vec(a.wpi + (long long)j * 512 + lane * 8, wv8);
-            float sj = 0.0f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) sj = __builtin_fmaf(hv[i], wv8[i], sj);
-            panel[j * 65 + lane] = sj;
-        }
         {
-            float wv8[8];
+            float wv8[8];                               // value head first: its butterfly overlaps the loads below
             load_vec(a.wv + lane * 8, wv8);
             float sv = 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) sv = __builtin_fmaf(hv[i], wv8[i], sv);
             value = wave_sum(sv) + a.bv[0];
         }
-        __builtin_amdgcn_wave_barrier();
-        if (lane < A) {
-            const float *row = panel + lane * 65;
-            float rowsum = 0.0f;
-#pragma unroll 16
-            for (int t = 0; t < 64; ++t) rowsum += row[t];
-            mylogit = rowsum + a.bpi[lane];
+        for (int j0 = 0; j0 < A; j0 += 6) {             // six weight rows' loads in flight
+            float w6[6][8];
+#pragma unroll
+            for (int q = 0; q < 6; ++q)
+                if (j0 + q < A) load_vec(a.wpi + (long long)(j0 + q) * 512 + lane * 8, w6[q]);
+#pragma unroll
+            for (int q = 0; q < 6; ++q)
+                if (j0 + q < A) {
+                    float sj = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) sj = __builtin_fmaf(hv[i], w6[q][i], sj);
+                    panel[(j0 + q) * 65 + lane] = sj;
+                }
         }
+        __builtin_amdgcn_wave_barrier();
+        // row sums: with A <= 32 (<= 16) rows, two (four) lanes share a row, each adding a contiguous half (quarter)
+        // in lane order; the parts are then added in part order
+        const int parts = A <= 16 ? 4 : (A <= 32 ? 2 : 1);
+        const int rows_per = 64 / parts, len = 64 / parts;
+        const int row = lane & (rows_per - 1), part = lane / rows_per;
+        float rowsum = 0.0f;
+        if (row < A) {
+            const float *rp = panel + row * 65 + part * len;
+            for (int t = 0; t < len; t += 16) {
+                float tv[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) tv[u] = rp[t + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) rowsum += tv[u];
+            }
+        }
+        float tot = rowsum;
+        for (int q = 1; q < parts; ++q) tot += __shfl(rowsum, row + q * rows_per, 64);
+        if (lane < A) mylogit = tot + a.bpi[lane];
     }
 
     float m = -INFINITY;

@@ -79,7 +79,7 @@ template <typename T_> struct PlainGemm {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_> struct Conv1Fwd {
     using T = T_;
-    static constexpr int BM = 128, BN = 32, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 4, WAVES_N = 1;
+    static constexpr int BM = 256, BN = 32, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 8, WAVES_N = 1;
     static constexpr int VA = 8, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 64;       // forward sums are segmented so every kernel variant returns the same bits
@@ -101,16 +101,13 @@ template <typename T_> struct Conv1Fwd {
         return {obs + row * C * H * W + (oy * 4) * W + ox * 4};
     }
     HTS_HD CtxB ctx_b(int n) const { return {w + (long long)clamp_row(n, N) * K}; }
-    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
+    // K = 64*C is a whole number of k-tiles and segments: no end-of-range checks
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int) const
     {
-        if (k >= kend) return zero_vec<T, VA>();
         const unsigned uk = (unsigned)k, ch = uk >> 6, u = (uk >> 3) & 7u;
         return load_u8x8<T>(c.p + (ch * (unsigned)H + u) * (unsigned)W);
     }
-    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
-    {
-        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
-    }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int) const { return load_vec<T, VB>(c.p + k); }
     HTS_HD float col(int n) const { return bias[n]; }
     HTS_HD void store(int m, int n, float acc, int, const float &b) const
     {
@@ -124,11 +121,11 @@ template <typename T_> struct Conv1Fwd {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     using T = T_;
-    static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 2, WAVES_N = 2;
+    static constexpr int BM = 128, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 4, WAVES_N = 1;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    // conv2: one tap row (4*32 = 128); conv3: one tap row (3*64 = 192) for bf16, half of one for fp32
-    static constexpr int SEG = L::KSZ == 4 ? 128 : (sizeof(T) == 2 ? 192 : 96);
+    // conv2: half a tap row (a tap row is 4*32 = 128); conv3: one tap row (3*64 = 192) for bf16, half of one for fp32
+    static constexpr int SEG = L::KSZ == 4 ? 64 : (sizeof(T) == 2 ? 192 : 96);
     typedef PtrCtx<T> CtxA;
     typedef PtrCtx<T> CtxB;
     int M, N, K, klen;
@@ -146,16 +143,13 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
         return {in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN};
     }
     HTS_HD CtxB ctx_b(int n) const { return {wf + (long long)clamp_row(n, N) * K}; }
-    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
+    // K (512, 576) is a whole number of k-tiles and segments: no end-of-range checks
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int) const
     {
-        if (k >= kend) return zero_vec<T, VA>();
         const unsigned uk = (unsigned)k, u = uk / (unsigned)(L::KSZ * L::CIN), r = uk - u * (L::KSZ * L::CIN);
         return load_vec<T, VA>(c.p + (u * (unsigned)(Win * L::CIN) + r));     // a tap row is contiguous in memory
     }
-    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
-    {
-        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
-    }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int) const { return load_vec<T, VB>(c.p + k); }
     HTS_HD float col(int n) const { return bias[n]; }
     HTS_HD void store(int m, int n, float acc, int, const float &bn) const
     {
@@ -178,7 +172,7 @@ template <typename T_> struct FcFwd {
     static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    static constexpr int SEG = 128;
+    static constexpr int SEG = 64;
     typedef PtrCtx<T> CtxA;
     typedef PtrCtx<T> CtxB;
     int M, N, K, klen;
@@ -186,14 +180,9 @@ template <typename T_> struct FcFwd {
     float *part;      // [groups][M][N]
     HTS_HD CtxA ctx_a(int m) const { return {a3 + (long long)clamp_row(m, M) * K}; }
     HTS_HD CtxB ctx_b(int n) const { return {w + (long long)clamp_row(n, N) * K}; }
-    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
-    {
-        return k < kend ? load_vec<T, VA>(c.p + k) : zero_vec<T, VA>();
-    }
-    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
-    {
-        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
-    }
+    // K = F = 64*P3 and the group length are whole numbers of k-tiles and segments: no end-of-range checks
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int) const { return load_vec<T, VA>(c.p + k); }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int) const { return load_vec<T, VB>(c.p + k); }
     HTS_HD void store(int m, int n, float acc, int grp) const { part[((long long)grp * M + m) * N + n] = acc; }
 };
 
@@ -287,14 +276,9 @@ template <typename T_> struct FcDgrad {
     T *dy3;
     HTS_HD CtxA ctx_a(int b) const { return {dh + (long long)clamp_row(b, M) * 512}; }
     HTS_HD CtxB ctx_b(int f) const { return {wfcd + (long long)clamp_row(f, N) * 512}; }
-    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
-    {
-        return k < kend ? load_vec<T, VA>(c.p + k) : zero_vec<T, VA>();
-    }
-    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
-    {
-        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
-    }
+    // K = 512 is a whole number of k-tiles and segments: no end-of-range checks
+    HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int) const { return load_vec<T, VA>(c.p + k); }
+    HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int) const { return load_vec<T, VB>(c.p + k); }
     HTS_HD void store(int b, int f, float acc, int) const
     {
         const long long o = (long long)b * N + f;
