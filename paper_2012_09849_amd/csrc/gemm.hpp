@@ -127,6 +127,24 @@ template <typename T> HTS_HD Vec<T, 8> load_u8x8(const uint8_t *p)
 template <class P, class = void> struct SegOf { static constexpr int value = 0; };
 template <class P> struct SegOf<P, std::void_t<decltype(P::SEG)>> { static constexpr int value = P::SEG; };
 
+// Optional prefetch depth: a problem that defines `static constexpr int STAGES = D` keeps the global loads of D k-tiles
+// in flight in registers (default 1: the next tile only).  The order of the arithmetic does not change.
+template <class P, class = void> struct StagesOf { static constexpr int value = 1; };
+template <class P> struct StagesOf<P, std::void_t<decltype(P::STAGES)>> { static constexpr int value = P::STAGES; };
+
+// Optional: a problem with `static constexpr bool STEADY = true` (and no SEG) gets a k loop whose whole groups of
+// steps load unconditionally, with the end-of-range checks folded away; the last steps keep the checks.
+template <class P, class = void> struct SteadyOf { static constexpr bool value = false; };
+template <class P> struct SteadyOf<P, std::void_t<decltype(P::STEADY)>> { static constexpr bool value = P::STEADY; };
+
+// Optional run loaders for operands that are contiguous along the reduction instead of along k: a problem with
+// `void load_a_run(const CtxA &, int k, int kend, Vec<T,VA> (&out)[VA]) const` (likewise load_b_run) fetches the VA
+// vectors of k, k+1, ..., k+VA-1 in one call, so the decomposition of k is done once and advanced incrementally.
+template <class P, class = void> struct HasRunA : std::false_type {};
+template <class P> struct HasRunA<P, std::void_t<decltype(&P::load_a_run)>> : std::true_type {};
+template <class P, class = void> struct HasRunB : std::false_type {};
+template <class P> struct HasRunB<P, std::void_t<decltype(&P::load_b_run)>> : std::true_type {};
+
 // Optional batching: a problem with `int batches() const`, `int max_m() const`, `int batch_m(int z) const` is
 // launched with gridDim.z = batches(); batch z has batch_m(z) rows and its own gathers: ctx_a(row, z),
 // ctx_b(col, z) and store(m, n, acc, split, z) receive the batch index (the problem object stays read-only).
@@ -243,21 +261,33 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         cb[i] = make_ctx_b(p, n0 + r, zb);
     }
 
-    Vec<T, VA> ra[NA][RA];
-    Vec<T, VB> rb[NB][RB];
-    auto gload = [&](int k0) {
+    constexpr int D = StagesOf<P>::value;
+    static_assert(D >= 1 && D <= 4, "prefetch depth");
+    Vec<T, VA> rra[D][NA][RA];
+    Vec<T, VB> rrb[D][NB][RB];
+    // lim = end of the reduction range for this load, or INT_MAX when the whole k-tile is known to lie inside it
+    // (the range checks then fold away and the loads are unconditional)
+    auto gload = [&](int k0, Vec<T, VA> (&ra)[NA][RA], Vec<T, VB> (&rb)[NB][RB], int lim) {
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-            if (CA % NT == 0 || tid + i * NT < CA)
+            if (CA % NT == 0 || tid + i * NT < CA) {
+                if constexpr (!P::A_ALONG_K && HasRunA<P>::value) p.load_a_run(ca[i], k0 + ka[i], lim, ra[i]);
+                else {
 #pragma unroll
-                for (int q = 0; q < RA; ++q) ra[i][q] = p.load_a(ca[i], k0 + ka[i] + q, kend);
+                    for (int q = 0; q < RA; ++q) ra[i][q] = p.load_a(ca[i], k0 + ka[i] + q, lim);
+                }
+            }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            if (CB % NT == 0 || tid + i * NT < CB)
+            if (CB % NT == 0 || tid + i * NT < CB) {
+                if constexpr (!P::B_ALONG_K && HasRunB<P>::value) p.load_b_run(cb[i], k0 + kb[i], lim, rb[i]);
+                else {
 #pragma unroll
-                for (int q = 0; q < RB; ++q) rb[i][q] = p.load_b(cb[i], k0 + kb[i] + q, kend);
+                    for (int q = 0; q < RB; ++q) rb[i][q] = p.load_b(cb[i], k0 + kb[i] + q, lim);
+                }
+            }
     };
-    auto sstore = [&]() {
+    auto sstore = [&](const Vec<T, VA> (&ra)[NA][RA], const Vec<T, VB> (&rb)[NB][RB]) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             if (CA % NT != 0 && tid + i * NT >= CA) continue;
@@ -312,11 +342,15 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     const T *a_base = As + (wm * TM * 32 + lrow) * LS;
     const T *b_base = Bs + (wn * TN * 32 + lrow) * LS;
 
-    // one k-tile: registers -> LDS, start the next tile's global loads, multiply
-    auto step = [&](int k0, f32x16 (&acc)[TM][TN]) {
-        sstore();
+    // one k-tile: registers -> LDS, refill this stage's registers with the tile D steps ahead, multiply.
+    // REFILL: 1 = always (steady state: an unconditional load lets the compiler wait for exactly the older stages),
+    // 0 = never, 2 = if that tile exists
+    auto step_s = [&](int k0, f32x16 (&acc)[TM][TN], Vec<T, VA> (&ra)[NA][RA], Vec<T, VB> (&rb)[NB][RB], auto refill) {
+        constexpr int REFILL = decltype(refill)::value;
+        sstore(ra, rb);
         __syncthreads();
-        if (k0 + BK < kend) gload(k0 + BK);
+        if constexpr (REFILL == 1) gload(k0 + D * BK, ra, rb, 0x7fffffff);
+        else if constexpr (REFILL == 2) { if (k0 + D * BK < kend) gload(k0 + D * BK, ra, rb, kend); }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += Tr::KINST) {
             if constexpr (sizeof(T) == 4) {
@@ -358,8 +392,45 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
 
     f32x16 acc[TM][TN];
     clear(acc);
-    if (kbeg < kend) gload(kbeg);
-    if constexpr (SEG > 0) {
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (kbeg + s * BK < kend) gload(kbeg + s * BK, rra[s], rrb[s], kend);
+    if constexpr (D > 1 || (SEG == 0 && SteadyOf<P>::value)) {
+        // the k loop is unrolled by the depth so that every stage has its own registers; whole groups of steps
+        // refill unconditionally
+        f32x16 sacc[TM][TN];
+        clear(sacc);
+        auto fold = [&](int k0) {
+            if (SEG == 0 ? k0 + BK >= kend : ((k0 + BK - kbeg) % (SEG > 0 ? SEG : 1) == 0 || k0 + BK >= kend)) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { acc[i][j][r] += sacc[i][j][r]; sacc[i][j][r] = 0.0f; }
+            }
+        };
+        int kg = kbeg;
+        // steady state: whole groups of D steps, each of which refills its stage
+        for (; kg + 2 * D * BK <= kend; kg += D * BK) {
+#pragma unroll
+            for (int s = 0; s < D; ++s) {
+                step_s(kg + s * BK, sacc, rra[s], rrb[s], std::integral_constant<int, 1>{});
+                fold(kg + s * BK);
+            }
+        }
+        // the last (at most 2 D) steps
+        for (; kg < kend; kg += D * BK) {
+#pragma unroll
+            for (int s = 0; s < D; ++s) {
+                const int k0 = kg + s * BK;
+                if (k0 >= kend) break;                 // uniform over the workgroup
+                step_s(k0, sacc, rra[s], rrb[s], std::integral_constant<int, 2>{});
+                fold(k0);
+            }
+        }
+    } else if constexpr (SEG > 0) {
+        auto step = [&](int k0, f32x16 (&a)[TM][TN]) { step_s(k0, a, rra[0], rrb[0], std::integral_constant<int, 2>{}); };
         // one fresh accumulator per segment (it only lives inside the segment), folded into the running total
         constexpr int SPS = SEG / BK;            // k-tiles per segment
         int k0 = kbeg;
@@ -387,7 +458,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
                     for (int r = 0; r < 16; ++r) acc[i][j][r] += sacc[i][j][r];
         }
     } else {
-        for (int k0 = kbeg; k0 < kend; k0 += BK) step(k0, acc);
+        for (int k0 = kbeg; k0 < kend; k0 += BK) step_s(k0, acc, rra[0], rrb[0], std::integral_constant<int, 2>{});
     }
 
     // Epilogue.  Tiles that lie wholly inside the output take a branch-free path (the compiler can then batch the

@@ -383,6 +383,7 @@ template <typename T_, class L> struct ConvDgrad {
 // ------------------------------------------------------------------------------------------------------------
 template <typename T_, class L> struct ConvWgrad {
     using T = T_;
+    static constexpr bool STEADY = true;
     static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
@@ -415,6 +416,33 @@ template <typename T_, class L> struct ConvWgrad {
         if (m < kend && c.goff == -1) v[0] = from_f32<T>(1.0f);
         return v;
     }
+    // VB consecutive reduction indices m, m+1, ...: one (b, oy, ox) decomposition, advanced position by position.
+    // Loads are issued for every column (the bias and padding columns read column 0 and discard it), so that a k-tile
+    // known to lie inside the range has only unconditional loads.
+    HTS_HD void load_b_run(const CtxB &c, int m, int kend, Vec<T, VB> (&out)[VB]) const
+    {
+        const int Ho = dWo.div(Po);
+        const int mm = m < K ? m : K - 1;
+        const int b = dPo.div(mm), p = mm - b * Po;
+        int oy = dWo.div(p), ox = p - oy * Wo;
+        const T *src = in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN + (c.goff >= 0 ? c.goff : 0);
+        const int row_adv = (L::STRIDE * Win - Wo * L::STRIDE) * L::CIN;      // from the end of an output row to the next
+        const int img_adv = (Hin - Ho * L::STRIDE) * Win * L::CIN;            // from the last output row to the next sample
+        const T one = from_f32<T>(c.goff == -1 ? 1.0f : 0.0f);
+#pragma unroll
+        for (int q = 0; q < VB; ++q) {
+            if (m + q < kend) {
+                const Vec<T, VB> v = load_vec<T, VB>(src);
+                if (c.goff >= 0) out[q] = v;
+                else { out[q] = zero_vec<T, VB>(); out[q][0] = one; }
+            } else out[q] = zero_vec<T, VB>();
+            src += L::STRIDE * L::CIN;
+            if (++ox == Wo) {
+                ox = 0; src += row_adv;
+                if (++oy == Ho) { oy = 0; src += img_adv; }
+            }
+        }
+    }
     HTS_HD void store(int n, int kcol, float acc, int z) const
     {
         part[((long long)z * M + n) * N + kcol] = acc;
@@ -424,6 +452,7 @@ template <typename T_, class L> struct ConvWgrad {
 // conv1 weight gradient: as above with the uint8 frames as the im2col source, kcol = (c,u,v)
 template <typename T_> struct Conv1Wgrad {
     using T = T_;
+    static constexpr bool STEADY = true;
     static constexpr int BM = 32, BN = 128, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 1, WAVES_N = 4;
     static constexpr int VA = OperandTraits<T>::VEC, VB = 8;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
@@ -457,6 +486,35 @@ template <typename T_> struct Conv1Wgrad {
         Vec<T, VB> v = zero_vec<T, VB>();
         if (m < kend && c.goff == -1) v[0] = from_f32<T>(255.0f);   // the 1/255 of the input scaling is applied
         return v;                                                    // when the partials are combined
+    }
+    // As ConvWgrad::load_b_run; a run of VB positions touches at most two samples (P1 >= 16), whose storage rows are
+    // both looked up before the loads.
+    HTS_HD void load_b_run(const CtxB &c, int m, int kend, Vec<T, VB> (&out)[VB]) const
+    {
+        const int H1 = dW1.div(P1), nb = dP1.div(K);
+        const int mm = m < K ? m : K - 1;
+        const int b = dP1.div(mm), p = mm - b * P1;
+        int oy = dW1.div(p), ox = p - oy * W1;
+        const int b1 = b + 1 < nb ? b + 1 : b;
+        const long long chw = (long long)C * H * W;
+        const long long r0 = index ? index[b] : b, r1 = index ? index[b1] : b1;
+        const long long goff = c.goff >= 0 ? c.goff : 0;
+        const uint8_t *src = obs + r0 * chw + (oy * 4) * W + ox * 4 + goff;
+        const uint8_t *next = obs + r1 * chw + goff;                            // position (0,0) of the next sample
+        const T one = from_f32<T>(c.goff == -1 ? 255.0f : 0.0f);              // the 1/255 of the input scaling is applied
+#pragma unroll                                                                  // when the partials are combined
+        for (int q = 0; q < VB; ++q) {
+            if (m + q < kend) {
+                const Vec<T, VB> v = load_u8x8<T>(src);
+                if (c.goff >= 0) out[q] = v;
+                else { out[q] = zero_vec<T, VB>(); out[q][0] = one; }
+            } else out[q] = zero_vec<T, VB>();
+            src += 4;
+            if (++ox == W1) {
+                ox = 0; src += 4 * W - 4 * W1;
+                if (++oy == H1) { oy = 0; src = next; }
+            }
+        }
     }
     HTS_HD void store(int n, int kcol, float acc, int z) const
     {
