@@ -644,8 +644,9 @@ hipError_t launch_gae(Ctx *c, hipStream_t s, const float *r, const float *v, con
 {
     Ctx dummy;
     SiteTimer tm(c ? *c : dummy, SITE_GAE);
-    // enough columns to fill the chip with one lane each -> plain kernel; otherwise split time as well
-    if ((long long)N >= 16384 || T < 16) {
+    // enough columns to hide each lane's serial walk behind other wavefronts -> plain kernel; otherwise split time as
+    // well (measured at T = 128: 16384 columns 27.7 us plain, 7.9 us chunked; break-even near 65536 columns)
+    if ((long long)N >= 65536 || T < 16) {
         hipLaunchKernelGGL(gae_kernel, dim3((N + 63) / 64), dim3(64), 0, s, r, v, d, gamma, lambda, T, N, adv, ret);
     } else {
         int TC = T / 8;                       // chunks of at least 8 steps
