@@ -274,22 +274,24 @@ def streaming_rooflines(loop, per_step, work, torch, overhead_ms):
         ms = max(ms - n * overhead_ms, 1e-6)
         gbs = work["adam"][1] / (ms * 1e-3) / 1e9
         out["adam"] = {"GB/s": gbs, "frac": gbs * 1e9 / PEAK["hbm"], "avg_launch_us": ms / n * 1e3}
-    T, N = 128, 4096
-    g = torch.Generator(device="cuda").manual_seed(1)
-    r, v = torch.randn(T, N, device="cuda", generator=g), torch.randn(T + 1, N, device="cuda", generator=g)
-    d = (torch.rand(T, N, device="cuda", generator=g) < 0.01).to(torch.uint8)
-    adv, ret = torch.empty_like(r), torch.empty_like(r)
     ctx = loop.ctx
-    for _ in range(5):
-        ctx.hts_returns_gae(r, v, d, 0.99, 0.95, adv, ret)
-    ctx.hts_profile_begin(ctx.profile_sites().index("gae"))
-    for _ in range(200):
-        ctx.hts_returns_gae(r, v, d, 0.99, 0.95, adv, ret)
-    n, ms = ctx.hts_profile_end()
-    nbytes = 17.0 * T * N + 4.0 * N
-    us = max(ms / n - overhead_ms, 1e-6) * 1e3
-    out["gae_128x4096"] = {"GB/s": nbytes / (us * 1e-6) / 1e9, "frac": nbytes / (us * 1e-6) / PEAK["hbm"],
-                           "avg_launch_us": us}
+    g = torch.Generator(device="cuda").manual_seed(1)
+    # the sweep size of the actor/returns configuration, and one wide enough to be bandwidth- rather than launch-bound
+    for T, N, reps in ((128, 4096, 200), (128, 262144, 20)):
+        r, v = torch.randn(T, N, device="cuda", generator=g), torch.randn(T + 1, N, device="cuda", generator=g)
+        d = (torch.rand(T, N, device="cuda", generator=g) < 0.01).to(torch.uint8)
+        adv, ret = torch.empty_like(r), torch.empty_like(r)
+        for _ in range(3):
+            ctx.hts_returns_gae(r, v, d, 0.99, 0.95, adv, ret)
+        ctx.hts_profile_begin(ctx.profile_sites().index("gae"))
+        for _ in range(reps):
+            ctx.hts_returns_gae(r, v, d, 0.99, 0.95, adv, ret)
+        n, ms = ctx.hts_profile_end()
+        nbytes = 17.0 * T * N + 4.0 * N
+        us = max(ms / n - overhead_ms, 1e-6) * 1e3
+        out[f"gae_{T}x{N}"] = {"GB/s": nbytes / (us * 1e-6) / 1e9, "frac": nbytes / (us * 1e-6) / PEAK["hbm"],
+                               "avg_launch_us": us}
+        del r, v, d, adv, ret
     return out
 
 

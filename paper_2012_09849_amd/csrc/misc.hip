@@ -222,6 +222,15 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
     if (a.logits_in) {
         if (lane < A) mylogit = a.logits_in[(long long)b * A + lane];
     } else {
+        // Everything this wavefront needs from the weights is requested before the FC partial sums are waited for
+        // (they are independent): value head, FC bias and the first HEAD_CHUNK rows of pi.w.
+        constexpr int HEAD_CHUNK = 20;
+        float wv8[8], bv8[8], wrow[HEAD_CHUNK][8];
+        load_vec(a.wv + lane * 8, wv8);
+        load_vec(a.fc_bias + lane * 8, bv8);
+#pragma unroll
+        for (int q = 0; q < HEAD_CHUNK; ++q)
+            if (q < A) load_vec(a.wpi + (long long)q * 512 + lane * 8, wrow[q]);
         {
             // add the FC layer's group sums in group order, then bias + ReLU
 #pragma unroll
@@ -239,8 +248,6 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
 #pragma unroll
                         for (int i = 0; i < 8; ++i) hv[i] += pv[q][i];
             }
-            float bv8[8];
-            load_vec(a.fc_bias + lane * 8, bv8);
 #pragma unroll
             for (int i = 0; i < 8; ++i) { const float y = hv[i] + bv8[i]; hv[i] = y > 0.0f ? y : 0.0f; }
             if (a.h_out) {
@@ -252,29 +259,28 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
             }
         }
         // A dot products of length 512 for the logits: every lane forms its 8-element partial of each, the partials
-        // go through this wavefront's LDS panel [A][65], and lane j adds row j in lane order (a fixed order; no
-        // barrier is needed because a wavefront's LDS operations execute in order).  The value head is one more dot
-        // product, reduced by a butterfly.
+        // go through this wavefront's LDS panel [A][65] and are added row by row in a fixed order (no barrier is
+        // needed because a wavefront's LDS operations execute in order).  The value head is one more dot product,
+        // reduced by a butterfly.
         float *panel = heads_lds + (threadIdx.x >> 6) * A * 65;
         {
-            float wv8[8];                               // value head first: its butterfly overlaps the loads below
-            load_vec(a.wv + lane * 8, wv8);
             float sv = 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) sv = __builtin_fmaf(hv[i], wv8[i], sv);
             value = wave_sum(sv) + a.bv[0];
         }
-        for (int j0 = 0; j0 < A; j0 += 6) {             // six weight rows' loads in flight
-            float w6[6][8];
+        for (int j0 = 0; j0 < A; j0 += HEAD_CHUNK) {
+            if (j0 > 0) {
 #pragma unroll
-            for (int q = 0; q < 6; ++q)
-                if (j0 + q < A) load_vec(a.wpi + (long long)(j0 + q) * 512 + lane * 8, w6[q]);
+                for (int q = 0; q < HEAD_CHUNK; ++q)
+                    if (j0 + q < A) load_vec(a.wpi + (long long)(j0 + q) * 512 + lane * 8, wrow[q]);
+            }
 #pragma unroll
-            for (int q = 0; q < 6; ++q)
+            for (int q = 0; q < HEAD_CHUNK; ++q)
                 if (j0 + q < A) {
                     float sj = 0.0f;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) sj = __builtin_fmaf(hv[i], w6[q][i], sj);
+                    for (int i = 0; i < 8; ++i) sj = __builtin_fmaf(hv[i], wrow[q][i], sj);
                     panel[(j0 + q) * 65 + lane] = sj;
                 }
         }
