@@ -12,12 +12,14 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     hipError_t e;
     // Small minibatches take the wave-per-segment kernels: many more, much shorter dependency chains.
     const bool small = B <= c.small_b;
-    // groups of 64-row segments for the split weight gradients on that path: at most 32 partial buffers per layer
-    auto groups_for = [](long long kp, int *spg) {
+    // groups of 64-row segments for the split weight gradients on that path: at most max_groups partial buffers per
+    // layer, at least min_segs segments per group (never more groups than the tile path's split_for allows for the
+    // same reduction length, which is what the partial buffers are sized for)
+    auto groups_for = [](long long kp, int *spg, int max_groups, int min_segs) {
         const int nseg = (int)((kp + 63) / 64);
-        int s = (nseg + 31) / 32;
+        int s = (nseg + max_groups - 1) / max_groups;
         s = ((s + 3) / 4) * 4;
-        if (s < 8) s = 8;
+        if (s < min_segs) s = min_segs;
         *spg = s;
         return (nseg + s - 1) / s;
     };
@@ -53,9 +55,9 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     const SplitK s3 = split_for((long long)B * g.P3, MAXZ3), s2 = split_for((long long)B * g.P2, MAXZ2),
                  s1 = split_for((long long)B * g.P1, MAXZ1);
     int spg3 = 0, spg2 = 0, spg1 = 0;
-    const int nz3 = small ? groups_for((long long)B * g.P3, &spg3) : s3.nz;
-    const int nz2 = small ? groups_for((long long)B * g.P2, &spg2) : s2.nz;
-    const int nz1 = small ? groups_for((long long)B * g.P1, &spg1) : s1.nz;
+    const int nz3 = small ? groups_for((long long)B * g.P3, &spg3, 32, 8) : s3.nz;
+    const int nz2 = small ? groups_for((long long)B * g.P2, &spg2, 32, 8) : s2.nz;
+    const int nz1 = small ? groups_for((long long)B * g.P1, &spg1, 128, 4) : s1.nz;   // long reduction, tiny output
     float *part3 = c.ws.part;
     float *part2 = part3 + (size_t)nz3 * 64 * 577;
     float *part1 = part2 + (size_t)nz2 * 64 * 513;
