@@ -226,6 +226,7 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         // (they are independent): value head, FC bias and the first HEAD_CHUNK rows of pi.w.
         constexpr int HEAD_CHUNK = 20;
         float wv8[8], bv8[8], wrow[HEAD_CHUNK][8];
+        const float head_bias = lane < A ? a.bpi[lane] : 0.0f, value_bias = a.bv[0];
         load_vec(a.wv + lane * 8, wv8);
         load_vec(a.fc_bias + lane * 8, bv8);
 #pragma unroll
@@ -267,7 +268,7 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
             float sv = 0.0f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) sv = __builtin_fmaf(hv[i], wv8[i], sv);
-            value = wave_sum(sv) + a.bv[0];
+            value = wave_sum(sv) + value_bias;
         }
         for (int j0 = 0; j0 < A; j0 += HEAD_CHUNK) {
             if (j0 > 0) {
@@ -303,22 +304,24 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         }
         float tot = rowsum;
         for (int q = 1; q < parts; ++q) tot += __shfl(rowsum, row + q * rows_per, 64);
-        if (lane < A) mylogit = tot + a.bpi[lane];
+        if (lane < A) mylogit = tot + head_bias;
     }
 
     float m = -INFINITY;
     for (int j = 0; j < A; ++j) m = fmaxf(m, lane_value(mylogit, j));
 
     if constexpr (!LEARN) {
-        // sequential binary32 inverse-CDF, evaluated identically by every lane
+        // binary32 inverse CDF: lane j evaluates e_j once; the running sums are formed sequentially in index order
+        // from those values (read lane by lane), identically in every lane
+        const float ej = sampler_exp((lane < A ? mylogit : m) - m);
         float total = 0.0f;
-        for (int j = 0; j < A; ++j) total = total + sampler_exp(lane_value(mylogit, j) - m);
+        for (int j = 0; j < A; ++j) total = total + lane_value(ej, j);
         const float u = seeded_uniform(a.seed, (uint32_t)(a.env_offset + b), a.step);
         const float thr = u * total;
         int act = A - 1;
         float run = 0.0f;
         for (int j = 0; j < A; ++j) {
-            run = run + sampler_exp(lane_value(mylogit, j) - m);
+            run = run + lane_value(ej, j);
             if (run > thr) { act = j; break; }
         }
         const float la = lane_value(mylogit, act);
