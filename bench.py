@@ -368,7 +368,7 @@ def main():
     ms = wall / args.steps * 1e3
     learn_rows = frames * cfg["epochs"]
     out = {
-        "metric": "env-frames/sec (act+GAE+learner update), 1xMI355X",
+        "metric": "env-frames/sec (act+GAE+PPO update) and learner samples/sec, 1\u00d7MI355X",
         "value": frames * args.steps / wall,
         "unit": "env-frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
