@@ -108,10 +108,14 @@ class Loop:
 
 
 class OverlapLoop:
-    """The paper's schedule (Sec. 4.1 "Concurrent rollout and learning", "Delayed gradient") for workloads with one
-    update per storage: while the actors fill storage j with theta_j on one stream, the learner takes the gradient at
-    theta_{j-1} on storage j-1 on another stream and applies it to theta_j; the streams meet once per iteration.
-    Two contexts (calls on one context must not overlap), two storages, three parameter vectors in rotation."""
+    """The paper's schedule (Sec. 4.1 "Concurrent rollout and learning"): while the actors fill storage j with theta_j
+    on one stream, the learner works on storage j-1 on another; the streams meet once per iteration.  Two contexts
+    (calls on one context must not overlap), two storages, three parameter vectors in rotation.
+
+    One update per storage (A2C): the paper's one-step-delayed rule -- gradient at theta_{j-1} on storage j-1, applied to
+    theta_j (hts_learner_step_delayed).  Several minibatch steps per storage (PPO): the paper states its rule for a
+    single gradient step only; here the learner runs its ordinary epochs on storage j-1 starting from theta_j, the
+    stored behaviour log-probabilities (of theta_{j-1}) entering through PPO's own probability ratio."""
 
     def __init__(self, base):
         torch, hts, cfg = base.torch, base.hts, base.cfg
@@ -120,7 +124,7 @@ class OverlapLoop:
         self.s_roll, self.s_learn = torch.cuda.Stream(), torch.cuda.Stream()
         mk = lambda **kw: hts.Context(cfg["C"], cfg["H"], cfg["W"], cfg["A"], precision=cfg["precision"], **kw)
         self.ctx_act = mk(max_act_batch=N, stream=self.s_roll)
-        self.ctx_learn = mk(max_learn_batch=N * T, stream=self.s_learn)
+        self.ctx_learn = mk(max_learn_batch=base.B, stream=self.s_learn)
         z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device="cuda")
         self.store = [dict(actions=z(T + 1, N, dt=torch.int32), logp=z(T + 1, N), values=z(T + 1, N), adv=z(T, N),
                            ret=z(T, N)) for _ in range(2)]
@@ -140,15 +144,24 @@ class OverlapLoop:
             self.ctx_act.hts_act(b.obs[t], cur if t == 0 else None, 20201209, self.j * (T + 1) + t, 0, st["actions"][t],
                                  st["logp"][t], st["values"][t])
         self.ctx_act.hts_returns_gae(b.rew, st["values"], b.dones, cfg["gamma"], cfg["lam"], st["adv"], st["ret"])
+        if cfg["algo"] == 1:
+            self.ctx_act.hts_normalize_advantages(st["adv"])
         self.ev_roll.record(self.s_roll)
+        single = cfg["epochs"] * cfg["minibatches"] == 1
         with torch.cuda.stream(self.s_learn):
             nxt.copy_(cur)
             if self.j > 0:
                 old = self.store[(self.j - 1) % 2]
                 obs = b.obs[:T].reshape(T * N, cfg["C"], cfg["H"], cfg["W"])
-                self.ctx_learn.hts_learner_step_delayed(obs, old["actions"][:T].reshape(-1), old["logp"][:T].reshape(-1),
-                                                        old["adv"].reshape(-1), old["ret"].reshape(-1), prev, nxt,
-                                                        self.opt, b.hp)
+                data = (obs, old["actions"][:T].reshape(-1), old["logp"][:T].reshape(-1), old["adv"].reshape(-1),
+                        old["ret"].reshape(-1))
+                if single:
+                    self.ctx_learn.hts_learner_step_delayed(*data, prev, nxt, self.opt, b.hp)
+                else:
+                    for e in range(cfg["epochs"]):
+                        for k in range(cfg["minibatches"]):
+                            self.ctx_learn.hts_learner_step(*data, nxt, self.opt, b.hp,
+                                                            index=b.perms[e][k * b.B:(k + 1) * b.B], B=b.B)
         self.ev_learn.record(self.s_learn)
         self.s_roll.wait_event(self.ev_learn)
         self.s_learn.wait_event(self.ev_roll)
@@ -405,21 +418,23 @@ def main():
     # per-site event-bracket sums, less what the brackets themselves read
     net = {k: max(v[0] - v[1] * overhead_ms, 0.0) for k, v in per_step.items()}
     out["kernel_ms_per_step"] = {k: round(v, 5) for k, v in sorted(net.items(), key=lambda kv: -kv[1])}
-    if cfg["epochs"] * cfg["minibatches"] == 1:
+    if not args.site:
         ov = OverlapLoop(loop)
-        for _ in range(args.warmup):
+        ov_steps = args.steps if cfg["epochs"] * cfg["minibatches"] == 1 else max(1, args.steps // 4)
+        for _ in range(min(args.warmup, 10)):
             ov.step()
         torch.cuda.synchronize()
         t2 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(ov_steps):
             ov.step()
         torch.cuda.synchronize()
         ov_wall = time.perf_counter() - t2
-        out["overlapped"] = {"value": frames * args.steps / ov_wall, "unit": "env-frames/s",
-                             "ms_per_step": ov_wall / args.steps * 1e3,
-                             "schedule": "rollout with theta_j on one stream while the learner applies the gradient taken "
-                                         "at theta_{j-1} on the previous storage on a second stream (one-step-delayed "
-                                         "update); same work per step as `value`, which runs the three parts in sequence"}
+        out["overlapped"] = {"value": frames * ov_steps / ov_wall, "unit": "env-frames/s",
+                             "ms_per_step": ov_wall / ov_steps * 1e3, "steps": ov_steps,
+                             "schedule": "rollout with theta_j on one stream while the learner works on the previous "
+                                         "storage on a second stream (one update per storage: the one-step-delayed "
+                                         "update; several: ordinary epochs from theta_j); same work per step as "
+                                         "`value`, which runs the three parts in sequence"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, loop)
     print(json.dumps(out))

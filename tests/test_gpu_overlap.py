@@ -55,3 +55,51 @@ def test_overlapped_schedule_equals_serial_schedule():
     # and the parameters did move
     assert not torch.equal(theta[1], base.params)
     ctx.close()
+
+
+def test_overlapped_ppo_schedule_equals_serial_schedule():
+    """Several minibatch steps per storage: the learner's epochs on storage j-1 run beside the rollout of storage j;
+    the serial replay of the same calls gives the same parameters and actions."""
+    import bench
+    import paper_2012_09849_amd as hts
+    cfg = dict(bench.CONFIGS["atari_ppo_n32_t128_bf16"], N=8, T=12, epochs=2, minibatches=2)
+    base = bench.Loop(cfg, hts, torch, syn)
+    ov = bench.OverlapLoop(base)
+    iters = 4
+    for _ in range(iters):
+        ov.step()
+    torch.cuda.synchronize()
+    N, T, B = cfg["N"], cfg["T"], base.B
+    ctx = hts.Context(cfg["C"], cfg["H"], cfg["W"], cfg["A"], precision=cfg["precision"], max_act_batch=N,
+                      max_learn_batch=B)
+    z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device="cuda")
+    store = [dict(actions=z(T + 1, N, dt=torch.int32), logp=z(T + 1, N), values=z(T + 1, N), adv=z(T, N), ret=z(T, N))
+             for _ in range(2)]
+    theta = [base.params.clone() for _ in range(3)]
+    P = base.params.numel()
+    opt = hts.OptState(z(P), z(P), 0)
+    obs_flat = base.obs[:T].reshape(T * N, cfg["C"], cfg["H"], cfg["W"])
+    for j in range(iters):
+        prev, cur, nxt = theta
+        st = store[j % 2]
+        for t in range(T + 1):
+            ctx.hts_act(base.obs[t], cur, 20201209, j * (T + 1) + t, 0, st["actions"][t], st["logp"][t], st["values"][t])
+        ctx.hts_returns_gae(base.rew, st["values"], base.dones, cfg["gamma"], cfg["lam"], st["adv"], st["ret"])
+        ctx.hts_normalize_advantages(st["adv"])
+        nxt.copy_(cur)
+        if j > 0:
+            old = store[(j - 1) % 2]
+            for e in range(cfg["epochs"]):
+                for k in range(cfg["minibatches"]):
+                    ctx.hts_learner_step(obs_flat, old["actions"][:T].reshape(-1), old["logp"][:T].reshape(-1),
+                                         old["adv"].reshape(-1), old["ret"].reshape(-1), nxt, opt, base.hp,
+                                         index=base.perms[e][k * B:(k + 1) * B], B=B)
+        theta = [cur, nxt, prev]
+    torch.cuda.synchronize()
+    for a, b in zip(ov.theta, theta):
+        assert torch.equal(a, b)
+    for a, b in zip(ov.store, store):
+        assert torch.equal(a["actions"], b["actions"])
+    assert opt.step == (iters - 1) * 4 and ov.opt.step == opt.step
+    assert not torch.equal(theta[1], base.params)
+    ctx.close()
