@@ -86,13 +86,12 @@ void carve(Ctx &c, Carver &cv)
     cv.take(w.w1s, (size_t)32 * g.K1 * ts); cv.take(w.wf2, 64 * 512 * ts); cv.take(w.wf3, 64 * 576 * ts);
     cv.take(w.wfc, (size_t)512 * g.F * ts); cv.take(w.hb, (size_t)c.sh.count * 4);
     cv.take(w.act1, mb * g.P1 * 32 * ts); cv.take(w.act2, mb * g.P2 * 64 * ts); cv.take(w.a3, mb * g.F * ts);
-    cv.take(w.h, mb * 512 * 4); cv.take(w.logits, mb * g.A * 4); cv.take(w.val, mb * 4);
     cv.take(w.fc_part, (size_t)c.fc_groups * mb * 512 * 4);
     cv.take(w.clip, 2 * 4);
     cv.take(w.norm_part, (size_t)((g.P + NORM_CHUNK - 1) / NORM_CHUNK) * 4);
     if (ml > 0) {
         cv.take(w.wd2, 32 * 1024 * ts); cv.take(w.wd3, 64 * 576 * ts); cv.take(w.wfcd, (size_t)512 * g.F * ts);
-        cv.take(w.a3n, ml * g.F * ts);
+        cv.take(w.a3n, ml * g.F * ts); cv.take(w.h, ml * 512 * 4);
         cv.take(w.dz, ml * (g.A + 1) * 4); cv.take(w.dh, ml * 512 * 4); cv.take(w.terms, ml * N_TERMS * 4);
         cv.take(w.dy3, ml * g.P3 * 64 * ts); cv.take(w.dy2, ml * g.P2 * 64 * ts); cv.take(w.dy1, ml * g.P1 * 32 * ts);
         cv.take(w.grads, (size_t)g.P * 4);

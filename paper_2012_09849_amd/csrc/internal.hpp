@@ -28,7 +28,7 @@ struct Workspace {
     // forward activations
     void *act1, *act2, *a3;   // T
     void *a3n;                // learner only: conv3 output once more, channel-innermost (ReLU mask of the FC input gradient)
-    float *h, *logits, *val;
+    float *h;                 // learner only: FC output [B][512], written by the heads kernel for the backward pass
     float *fc_part;           // [fc_groups][B][512] partial sums of the FC layer, one per group of FC_GROUP_K inputs
     // backward
     float *dz, *dh, *terms, *grads, *part, *norm_part, *clip;   // clip[0] = scale, clip[1] = ||g||

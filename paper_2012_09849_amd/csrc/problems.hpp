@@ -7,7 +7,7 @@
 //   a3   [B][F]           conv3 output flattened as (channel, y, x) = the order fc.w expects
 //   a3n  [B][H3][W3][64]  the same values channel-innermost (learner only)
 //   fc_part [G][B][512]   FC partial sums, one per group of 512 inputs; bias + ReLU when the heads kernel adds them
-//   h    [B][512] fp32    FC output, post-ReLU
+//   h    [B][512] fp32    FC output, post-ReLU (learner only; written by the heads kernel)
 //   dz   [B][A+1] fp32    dL/dlogits followed by dL/dvalue
 //   dh   [B][512] fp32    dL/d(FC pre-activation)
 //   dy3 [B][H3][W3][64], dy2 [B][H2][W2][64], dy1 [B][H1][W1][32]   dL/d(conv pre-activation), T
