@@ -4,6 +4,146 @@
 
 namespace hts {
 
+// ------------------------------------------------------------------------------------------------------------
+// conv1 for large batches of small 4-channel frames (bf16, image <= 64 KiB of LDS, e.g. 4x84x84): one workgroup per
+// observation.
+// The frame is converted to bf16 ONCE into an LDS image [(c,y)][Wp] (the tile kernel converts every pixel four times,
+// once per patch that contains it, and spends most of its issue slots on that and on gather addresses); the matrix
+// instruction's position operand is then read straight from the image -- 8 consecutive k of conv1.w's (c,u,v) order
+// are 8 neighbouring pixels of one row -- and the 32 x 64C weight operand lives in registers for the whole kernel.
+// Same k order, same 64-wide segments (one input channel each) and the same epilogue as Conv1Fwd, so the output bits
+// equal those of the other conv1 kernels.
+// ------------------------------------------------------------------------------------------------------------
+struct Conv1ImgArgs {
+    const uint8_t *obs;
+    const int32_t *index;
+    const bf16_t *w;        // [32][64*C]
+    const float *bias;
+    bf16_t *out;            // [B][P1][32]
+    int B, H, W, W1, P1, Wp;
+    FastDiv dGpr, dW1;      // division by W/4 (4-pixel groups per image row) and by W1
+};
+constexpr int C1IMG_THREADS = 512;        // 8 wavefronts: 13 position tiles of a 20x20 output spread 2,2,2,2,2,1,1,1
+constexpr int C1IMG_MAX_PASSES = 16;      // passes of a wavefront over its share of the image rows
+
+template <int C> __global__ __launch_bounds__(C1IMG_THREADS) void conv1_image_kernel(const Conv1ImgArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char c1_smem[];
+    bf16_t *img = reinterpret_cast<bf16_t *>(c1_smem);
+    constexpr int K = 64 * C;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lrow = lane & 31, lk = lane >> 5;
+    bf16x8 breg[K / 16];
+#pragma unroll
+    for (int t = 0; t < K / 16; ++t) breg[t] = *reinterpret_cast<const bf16x8 *>(a.w + lrow * K + 16 * t + 8 * lk);
+    const float bias = a.bias[lrow];
+    const int rows = C * a.H, gpr = a.W >> 2;
+    const int ntiles = (a.P1 + 31) >> 5;
+    // Frame -> image: a wavefront takes 64/gpr image rows per pass, one 4-pixel group per lane, so neighbouring lanes
+    // load neighbouring dwords and write neighbouring 8-byte LDS slots; a lane's (row-in-pass, group) never changes.
+    const int rpp = 64 / gpr;                                    // image rows per wavefront pass
+    const int lr = a.dGpr.div(lane), xg = lane - lr * gpr;
+    const bool lane_on = lr < rpp;
+    constexpr int NW = C1IMG_THREADS / 64;
+    uint32_t raw[C1IMG_MAX_PASSES];
+    auto fetch = [&](int b) {
+        const uint8_t *src = a.obs + (long long)(a.index ? a.index[b] : b) * rows * a.W + 4 * xg;
+#pragma unroll
+        for (int i = 0; i < C1IMG_MAX_PASSES; ++i) {
+            const int row = (w + i * NW) * rpp + lr;
+            if (lane_on && row < rows) raw[i] = *reinterpret_cast<const uint32_t *>(src + row * a.W);
+        }
+    };
+    if ((int)blockIdx.x < a.B) fetch(blockIdx.x);
+    for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
+#pragma unroll
+        for (int i = 0; i < C1IMG_MAX_PASSES; ++i) {
+            const int row = (w + i * NW) * rpp + lr;
+            if (!lane_on || row >= rows) continue;
+            Vec<bf16_t, 4> px;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) px[e] = from_f32<bf16_t>((float)((raw[i] >> (8 * e)) & 0xFFu));
+            *reinterpret_cast<Vec<bf16_t, 4> *>(img + row * a.Wp + 4 * xg) = px;
+        }
+        __syncthreads();
+        if (b + (int)gridDim.x < a.B) fetch(b + gridDim.x);      // the next frame travels while this one is multiplied
+        for (int mt = w; mt < ntiles; mt += C1IMG_THREADS / 64) {
+            const int m = mt * 32 + lrow, mc = m < a.P1 ? m : a.P1 - 1;
+            const int oy = a.dW1.div(mc), ox = mc - oy * a.W1;
+            const bf16_t *base = img + (4 * oy) * a.Wp + 4 * ox;
+            // One 64-long segment per input channel.  The C segment chains are independent until they are added, so
+            // their matrix instructions are interleaved (t outer, channel inner): no instruction waits for its
+            // predecessor, and within a segment k still ascends.
+            f32x16 acc[C];
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[c][r] = 0.0f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                bf16x8 av[C];
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const bf16_t *pa = base + (c * a.H + 2 * t + lk) * a.Wp;       // image row u = 2t + lk of the patch
+                    const Vec<bf16_t, 4> lo = *reinterpret_cast<const Vec<bf16_t, 4> *>(pa),
+                                         hi = *reinterpret_cast<const Vec<bf16_t, 4> *>(pa + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { av[c][e] = lo[e]; av[c][4 + e] = hi[e]; }
+                }
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[c], breg[c * 4 + t], acc[c], 0, 0, 0);
+            }
+            f32x16 tot;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tot[r] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tot[r] += acc[c][r];
+            bf16_t *dst = a.out + ((long long)b * a.P1 + mt * 32) * 32 + lrow;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int mm = 8 * (r / 4) + 4 * lk + (r % 4);
+                if (mt * 32 + mm < a.P1) {
+                    const float y = __builtin_fmaf(tot[r], 1.0f / 255.0f, bias);
+                    dst[mm * 32] = from_f32<bf16_t>(y > 0.0f ? y : 0.0f);
+                }
+            }
+        }
+        __syncthreads();          // the image is overwritten by the next observation
+    }
+}
+
+// Row pitch of the LDS image: a multiple of 4 pixels, and congruent to W1 modulo 32 so that a tile's positions keep
+// their 8-byte bank stride when they wrap from one output row to the next (4 image rows further down).
+static int conv1_image_pitch(const Geom &g)
+{
+    int wp = g.W;
+    while ((wp - g.W1) % 32 != 0) wp += 4;
+    return wp;
+}
+
+// true if the frame shape and pointers fit conv1_image_kernel
+static bool conv1_image_fits(const Geom &g, const uint8_t *obs)
+{
+    if (g.C != 4 || g.W > 256 || (((uintptr_t)obs) & 3u)) return false;
+    const int gpr = g.W / 4, rpp = 64 / gpr, rows = g.C * g.H;
+    return rows <= C1IMG_MAX_PASSES * rpp * (C1IMG_THREADS / 64) && (size_t)rows * conv1_image_pitch(g) * 2 <= 65536;
+}
+
+static hipError_t launch_conv1_image(Ctx &c, const uint8_t *obs, const int32_t *index, int B)
+{
+    const Geom &g = c.g;
+    Conv1ImgArgs a;
+    a.obs = obs; a.index = index; a.w = (const bf16_t *)c.ws.w1s; a.bias = c.ws.hb + c.sh.b1; a.out = (bf16_t *)c.ws.act1;
+    a.B = B; a.H = g.H; a.W = g.W; a.W1 = g.W1; a.P1 = g.P1; a.Wp = conv1_image_pitch(g);
+    a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
+    const size_t lds = (size_t)g.C * g.H * a.Wp * sizeof(bf16_t);
+    const int grid = B < 512 ? B : 512;          // resident workgroups walk the batch
+    hipLaunchKernelGGL(conv1_image_kernel<4>, dim3(grid), dim3(C1IMG_THREADS), lds, c.stream, a);
+    return hipGetLastError();
+}
+
 template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, const int32_t *index, int B, bool learn)
 {
     const Geom &g = c.g;
@@ -18,7 +158,9 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
         {
             SiteTimer tm(c, SITE_CONV1_FWD);
-            e = small ? launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream) : launch_gemm(p, c.stream);
+            if (small) e = launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream);
+            else if (sizeof(T) == 2 && conv1_image_fits(g, obs)) e = launch_conv1_image(c, obs, index, B);
+            else e = launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }

@@ -111,7 +111,7 @@ template <typename T_> struct Conv1Fwd {
     HTS_HD float col(int n) const { return bias[n]; }
     HTS_HD void store(int m, int n, float acc, int, const float &b) const
     {
-        const float y = acc * (1.0f / 255.0f) + b;
+        const float y = __builtin_fmaf(acc, 1.0f / 255.0f, b);     // explicit: every conv1 kernel rounds alike
         out[(long long)m * 32 + n] = from_f32<T>(y > 0.0f ? y : 0.0f);
     }
 };
