@@ -137,6 +137,14 @@ template <class P> struct StagesOf<P, std::void_t<decltype(P::STAGES)>> { static
 template <class P, class = void> struct SteadyOf { static constexpr bool value = false; };
 template <class P> struct SteadyOf<P, std::void_t<decltype(P::STEADY)>> { static constexpr bool value = P::STEADY; };
 
+// Optional "lane owns a row" orientation: a problem with `static constexpr bool LANE_OWNS_ROW = true` has the two
+// operands of the matrix instruction exchanged, so that a lane's 16 accumulator registers are 16 columns (four groups
+// of four neighbours) of ONE output row instead of 16 rows of one column.  Its epilogue then needs one row context
+// per lane (`Row row(int m[, int batch]) const`: e.g. a position decomposition) and stores four neighbouring columns
+// at a time (`store4(const Row &, int n, const float (&v)[4], int z[, int batch]) const`, n a multiple of 4, N too).
+template <class P, class = void> struct OwnsRow : std::false_type {};
+template <class P> struct OwnsRow<P, std::void_t<decltype(P::LANE_OWNS_ROW)>> : std::integral_constant<bool, P::LANE_OWNS_ROW> {};
+
 // Optional run loaders for operands that are contiguous along the reduction instead of along k: a problem with
 // `void load_a_run(const CtxA &, int k, int kend, Vec<T,VA> (&out)[VA]) const` (likewise load_b_run) fetches the VA
 // vectors of k, k+1, ..., k+VA-1 in one call, so the decomposition of k is done once and advanced incrementally.
@@ -262,6 +270,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     }
 
     constexpr int D = StagesOf<P>::value;
+    constexpr bool SWAP = OwnsRow<P>::value;
     static_assert(D >= 1 && D <= 4, "prefetch depth");
     Vec<T, VA> rra[D][NA][RA];
     Vec<T, VB> rrb[D][NB][RB];
@@ -363,7 +372,8 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x2f32(bv[j], av[i], acc[i][j], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
             } else {
                 bf16x8 av[TM], bv[TN];
 #pragma unroll
@@ -376,7 +386,8 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av[i], acc[i][j], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
         }
         __syncthreads();
@@ -465,18 +476,38 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     // loads an epilogue may need); edge tiles check every element.
     auto epilogue = [&](auto full_tile) {
         constexpr bool FULL = decltype(full_tile)::value;
+        if constexpr (SWAP) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + (wm * TM + i) * 32 + lrow;
+                const bool mok = FULL || m < M;
+                const int mr = mok ? m : M - 1;
+                auto rc = [&]() { if constexpr (HasBatch<P>::value) return p.row(mr, zb); else return p.row(mr); }();
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = n0 + (wn * TN + j) * 32 + lrow;
-                const auto col = make_col(p, FULL ? n : min(n, p.N - 1));
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
-                    if (FULL || (m < M && n < p.N)) do_store(p, m, n, acc[i][j][r], z, zb, col);
-                }
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = n0 + (wn * TN + j) * 32 + 8 * g + 4 * lk;
+                        const float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        if (FULL || (mok && n < p.N)) {
+                            if constexpr (HasBatch<P>::value) p.store4(rc, n, v, z, zb); else p.store4(rc, n, v, z);
+                        }
+                    }
             }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = n0 + (wn * TN + j) * 32 + lrow;
+                    const auto col = make_col(p, FULL ? n : min(n, p.N - 1));
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lk + (r % 4);
+                        if (FULL || (m < M && n < p.N)) do_store(p, m, n, acc[i][j][r], z, zb, col);
+                    }
+                }
+        }
     };
     if (m0 + BM <= M && n0 + BN <= p.N) epilogue(std::true_type{}); else epilogue(std::false_type{});
 }

@@ -150,6 +150,29 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
         return load_vec<T, VA>(c.p + (u * (unsigned)(Win * L::CIN) + r));     // a tap row is contiguous in memory
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int) const { return load_vec<T, VB>(c.p + k); }
+    // tile kernel, flattened output (conv3): a lane owns an output position, so the (sample, position) split of the
+    // row index is done once per lane instead of once per element (the plain layout measured no faster that way)
+    static constexpr bool LANE_OWNS_ROW = FLAT_OUT;
+    struct Row { long long o; long long o2; };
+    HTS_HD Row row(int m) const
+    {
+        if constexpr (FLAT_OUT) {
+            const int b = dPo.div(m), p = m - b * Po;
+            return {(long long)b * L::COUT * Po + p, (long long)m * L::COUT};
+        } else return {(long long)m * L::COUT, 0};
+    }
+    HTS_HD void store4(const Row &r, int n, const float (&v)[4], int) const
+    {
+        const f32x4 bn = *reinterpret_cast<const f32x4 *>(bias + n);
+        Vec<T, 4> y;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { const float t = v[q] + bn[q]; y[q] = from_f32<T>(t > 0.0f ? t : 0.0f); }
+        if constexpr (FLAT_OUT) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) out[r.o + (long long)(n + q) * Po] = y[q];
+            if (out2) *reinterpret_cast<Vec<T, 4> *>(out2 + r.o2 + n) = y;
+        } else *reinterpret_cast<Vec<T, 4> *>(out + r.o + n) = y;
+    }
     HTS_HD float col(int n) const { return bias[n]; }
     HTS_HD void store(int m, int n, float acc, int, const float &bn) const
     {
@@ -279,6 +302,17 @@ template <typename T_> struct FcDgrad {
     // K = 512 is a whole number of k-tiles and segments: no end-of-range checks
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int) const { return load_vec<T, VA>(c.p + k); }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int) const { return load_vec<T, VB>(c.p + k); }
+    static constexpr bool LANE_OWNS_ROW = true;
+    struct Row { long long o; };
+    HTS_HD Row row(int b) const { return {(long long)b * N}; }
+    HTS_HD void store4(const Row &r, int f, const float (&v)[4], int) const
+    {
+        const Vec<T, 4> a = *reinterpret_cast<const Vec<T, 4> *>(a3n + r.o + f);
+        Vec<T, 4> y;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) y[q] = from_f32<T>(to_f32(a[q]) > 0.0f ? v[q] : 0.0f);
+        *reinterpret_cast<Vec<T, 4> *>(dy3 + r.o + f) = y;
+    }
     HTS_HD void store(int b, int f, float acc, int) const
     {
         const long long o = (long long)b * N + f;
@@ -366,6 +400,22 @@ template <typename T_, class L> struct ConvDgrad {
         const int tap = k / L::COUT, n = k - tap * L::COUT, a = tap / TK, bb = tap - a * TK;
         const int u = c.py + L::STRIDE * a, vv = c.px + L::STRIDE * bb;
         return load_vec<T, VB>(wd + c.off + (u * L::KSZ + vv) * L::COUT + n);
+    }
+    static constexpr bool LANE_OWNS_ROW = true;
+    struct Row { long long o; };
+    HTS_HD Row row(int m, int z) const          // one position decomposition per lane
+    {
+        const Cls c = cls(z);
+        const int b = c.dHW.div(m), p = m - b * (c.Hc * c.Wc), yy = c.dW.div(p), xx = p - yy * c.Wc;
+        return {((((long long)b * Hin + yy * L::STRIDE + c.py) * Win) + xx * L::STRIDE + c.px) * N};
+    }
+    HTS_HD void store4(const Row &r, int ch, const float (&v)[4], int, int) const
+    {
+        const Vec<T, 4> a = *reinterpret_cast<const Vec<T, 4> *>(act_in + r.o + ch);
+        Vec<T, 4> y;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) y[q] = from_f32<T>(to_f32(a[q]) > 0.0f ? v[q] : 0.0f);
+        *reinterpret_cast<Vec<T, 4> *>(dy_in + r.o + ch) = y;
     }
     HTS_HD void store(int m, int ch, float acc, int, int z) const
     {
