@@ -23,20 +23,27 @@ struct Conv1ImgArgs {
     int B, H, W, W1, P1, Wp;
     FastDiv dGpr, dW1;      // division by W/4 (4-pixel groups per image row) and by W1
 };
-constexpr int C1IMG_THREADS = 512;        // 8 wavefronts: 13 position tiles of a 20x20 output spread 2,2,2,2,2,1,1,1
-constexpr int C1IMG_MAX_PASSES = 16;      // passes of a wavefront over its share of the image rows
+constexpr int C1IMG_THREADS = 256;        // 4 wavefronts (one per SIMD); two workgroups share a compute unit, one converting while the other multiplies
+constexpr int C1IMG_MAX_PASSES = 32;      // passes of a wavefront over its share of the image rows
 
-template <int C> __global__ __launch_bounds__(C1IMG_THREADS) void conv1_image_kernel(const Conv1ImgArgs a)
+// HC, WPC: frame height and image pitch as compile-time constants (0: taken from the arguments).  With them every
+// image offset of the multiply loop is an immediate of the LDS instruction.  NP: passes of a wavefront over its share
+// of the image rows (registers that hold the next frame while this one is multiplied).
+template <int C, int HC, int WPC, int NP> __global__ __launch_bounds__(C1IMG_THREADS, 2) void conv1_image_kernel(const Conv1ImgArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char c1_smem[];
     bf16_t *img = reinterpret_cast<bf16_t *>(c1_smem);
     constexpr int K = 64 * C;
+    const int H = HC ? HC : a.H, Wp = WPC ? WPC : a.Wp;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lrow = lane & 31, lk = lane >> 5;
     bf16x8 breg[K / 16];
 #pragma unroll
     for (int t = 0; t < K / 16; ++t) breg[t] = *reinterpret_cast<const bf16x8 *>(a.w + lrow * K + 16 * t + 8 * lk);
-    const float bias = a.bias[lrow];
-    const int rows = C * a.H, gpr = a.W >> 2;
+    // The weights are the FIRST operand of the matrix instruction, so a lane's accumulator registers are 16 output
+    // channels (8g + 4 lk + j, g and j < 4) of ONE position and leave as four 8-byte stores.
+    const int rows = C * H, gpr = a.W >> 2;
+    float *lbias = reinterpret_cast<float *>(img + ((rows * Wp + 7) & ~7));     // conv1.b behind the image, 16-byte aligned
+    if (tid < 32) lbias[tid] = a.bias[tid];
     const int ntiles = (a.P1 + 31) >> 5;
     // Frame -> image: a wavefront takes 64/gpr image rows per pass, one 4-pixel group per lane, so neighbouring lanes
     // load neighbouring dwords and write neighbouring 8-byte LDS slots; a lane's (row-in-pass, group) never changes.
@@ -44,11 +51,11 @@ template <int C> __global__ __launch_bounds__(C1IMG_THREADS) void conv1_image_ke
     const int lr = a.dGpr.div(lane), xg = lane - lr * gpr;
     const bool lane_on = lr < rpp;
     constexpr int NW = C1IMG_THREADS / 64;
-    uint32_t raw[C1IMG_MAX_PASSES];
+    uint32_t raw[NP];
     auto fetch = [&](int b) {
         const uint8_t *src = a.obs + (long long)(a.index ? a.index[b] : b) * rows * a.W + 4 * xg;
 #pragma unroll
-        for (int i = 0; i < C1IMG_MAX_PASSES; ++i) {
+        for (int i = 0; i < NP; ++i) {
             const int row = (w + i * NW) * rpp + lr;
             if (lane_on && row < rows) raw[i] = *reinterpret_cast<const uint32_t *>(src + row * a.W);
         }
@@ -56,57 +63,69 @@ template <int C> __global__ __launch_bounds__(C1IMG_THREADS) void conv1_image_ke
     if ((int)blockIdx.x < a.B) fetch(blockIdx.x);
     for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
 #pragma unroll
-        for (int i = 0; i < C1IMG_MAX_PASSES; ++i) {
+        for (int i = 0; i < NP; ++i) {
             const int row = (w + i * NW) * rpp + lr;
             if (!lane_on || row >= rows) continue;
             Vec<bf16_t, 4> px;
 #pragma unroll
             for (int e = 0; e < 4; ++e) px[e] = from_f32<bf16_t>((float)((raw[i] >> (8 * e)) & 0xFFu));
-            *reinterpret_cast<Vec<bf16_t, 4> *>(img + row * a.Wp + 4 * xg) = px;
+            *reinterpret_cast<Vec<bf16_t, 4> *>(img + row * Wp + 4 * xg) = px;
         }
         __syncthreads();
         if (b + (int)gridDim.x < a.B) fetch(b + gridDim.x);      // the next frame travels while this one is multiplied
         for (int mt = w; mt < ntiles; mt += C1IMG_THREADS / 64) {
             const int m = mt * 32 + lrow, mc = m < a.P1 ? m : a.P1 - 1;
             const int oy = a.dW1.div(mc), ox = mc - oy * a.W1;
-            const bf16_t *base = img + (4 * oy) * a.Wp + 4 * ox;
+            const bf16_t *base = img + (4 * oy + lk) * Wp + 4 * ox;      // image row u = 2t + lk of the patch, t = 0
             // One 64-long segment per input channel.  The C segment chains are independent until they are added, so
             // their matrix instructions are interleaved (t outer, channel inner): no instruction waits for its
             // predecessor, and within a segment k still ascends.
-            f32x16 acc[C];
-#pragma unroll
-            for (int c = 0; c < C; ++c)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[c][r] = 0.0f;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                bf16x8 av[C];
-#pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    const bf16_t *pa = base + (c * a.H + 2 * t + lk) * a.Wp;       // image row u = 2t + lk of the patch
-                    const Vec<bf16_t, 4> lo = *reinterpret_cast<const Vec<bf16_t, 4> *>(pa),
-                                         hi = *reinterpret_cast<const Vec<bf16_t, 4> *>(pa + 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { av[c][e] = lo[e]; av[c][4 + e] = hi[e]; }
-                }
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[c], breg[c * 4 + t], acc[c], 0, 0, 0);
-            }
+            // (Two chains at a time: enough to hide the instruction's latency, and half the accumulator registers.)
+            // The segment sums are added in channel order; a segment sum is never -0, so the total starts as the first.
+            static_assert(C % 2 == 0, "channel pairs");
             f32x16 tot;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) tot[r] = 0.0f;
+            for (int c0 = 0; c0 < C; c0 += 2) {
+                f32x16 acc[2];
 #pragma unroll
-            for (int c = 0; c < C; ++c)
+                for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) tot[r] += acc[c][r];
-            bf16_t *dst = a.out + ((long long)b * a.P1 + mt * 32) * 32 + lrow;
+                    for (int r = 0; r < 16; ++r) acc[c][r] = 0.0f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int mm = 8 * (r / 4) + 4 * lk + (r % 4);
-                if (mt * 32 + mm < a.P1) {
-                    const float y = __builtin_fmaf(tot[r], 1.0f / 255.0f, bias);
-                    dst[mm * 32] = from_f32<bf16_t>(y > 0.0f ? y : 0.0f);
+                for (int t = 0; t < 4; ++t) {
+                    bf16x8 av[2];
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        const bf16_t *pa = base + ((c0 + c) * H + 2 * t) * Wp;
+                        const Vec<bf16_t, 4> lo = *reinterpret_cast<const Vec<bf16_t, 4> *>(pa),
+                                             hi = *reinterpret_cast<const Vec<bf16_t, 4> *>(pa + 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { av[c][e] = lo[e]; av[c][4 + e] = hi[e]; }
+                    }
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(breg[(c0 + c) * 4 + t], av[c], acc[c], 0, 0, 0);
+                }
+                if (c0 == 0) tot = acc[0];
+                else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) tot[r] += acc[0][r];
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tot[r] += acc[1][r];
+            }
+            if (m < a.P1) {
+                bf16_t *dst = a.out + ((long long)b * a.P1 + m) * 32 + 4 * lk;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 bias = *reinterpret_cast<const f32x4 *>(lbias + 8 * g + 4 * lk);
+                    Vec<bf16_t, 4> o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float y = __builtin_fmaf(tot[4 * g + j], 1.0f / 255.0f, bias[j]);
+                        o[j] = from_f32<bf16_t>(y > 0.0f ? y : 0.0f);
+                    }
+                    *reinterpret_cast<Vec<bf16_t, 4> *>(dst + 8 * g) = o;
                 }
             }
         }
@@ -128,7 +147,7 @@ static bool conv1_image_fits(const Geom &g, const uint8_t *obs)
 {
     if (g.C != 4 || g.W > 256 || (((uintptr_t)obs) & 3u)) return false;
     const int gpr = g.W / 4, rpp = 64 / gpr, rows = g.C * g.H;
-    return rows <= C1IMG_MAX_PASSES * rpp * (C1IMG_THREADS / 64) && (size_t)rows * conv1_image_pitch(g) * 2 <= 65536;
+    return rows <= C1IMG_MAX_PASSES * rpp * (C1IMG_THREADS / 64) && (size_t)rows * conv1_image_pitch(g) * 2 + 16 + 128 <= 65536;
 }
 
 static hipError_t launch_conv1_image(Ctx &c, const uint8_t *obs, const int32_t *index, int B)
@@ -138,9 +157,12 @@ static hipError_t launch_conv1_image(Ctx &c, const uint8_t *obs, const int32_t *
     a.obs = obs; a.index = index; a.w = (const bf16_t *)c.ws.w1s; a.bias = c.ws.hb + c.sh.b1; a.out = (bf16_t *)c.ws.act1;
     a.B = B; a.H = g.H; a.W = g.W; a.W1 = g.W1; a.P1 = g.P1; a.Wp = conv1_image_pitch(g);
     a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
-    const size_t lds = (size_t)g.C * g.H * a.Wp * sizeof(bf16_t);
+    const size_t lds = (((size_t)g.C * g.H * a.Wp + 7) & ~(size_t)7) * sizeof(bf16_t) + 32 * sizeof(float);      // image + conv1.b
     const int grid = B < 512 ? B : 512;          // resident workgroups walk the batch
-    hipLaunchKernelGGL(conv1_image_kernel<4>, dim3(grid), dim3(C1IMG_THREADS), lds, c.stream, a);
+    if (g.H == 84 && g.W == 84 && a.Wp == 84)                 // the Atari frame of the paper's experiments
+        hipLaunchKernelGGL((conv1_image_kernel<4, 84, 84, 28>), dim3(grid), dim3(C1IMG_THREADS), lds, c.stream, a);
+    else
+        hipLaunchKernelGGL((conv1_image_kernel<4, 0, 0, C1IMG_MAX_PASSES>), dim3(grid), dim3(C1IMG_THREADS), lds, c.stream, a);
     return hipGetLastError();
 }
 
