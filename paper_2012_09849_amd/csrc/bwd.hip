@@ -110,15 +110,15 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         if (e != hipSuccess) return e;
     }
     {   // conv1.w, conv1.b
-        Conv1Wgrad<T> p;
-        p.M = 32; p.N = g.K1 + 1; p.K = B * g.P1; p.klen = s1.klen;
-        p.dy = (const T *)c.ws.dy1; p.obs = obs; p.index = index; p.part = part1;
-        p.Kc = g.K1; p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
-        p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
-        {
+        auto conv1_wgrad = [&](auto p) {
+            p.M = 32; p.N = g.K1 + 1; p.K = B * g.P1; p.klen = s1.klen;
+            p.dy = (const T *)c.ws.dy1; p.obs = obs; p.index = index; p.part = part1;
+            p.Kc = g.K1; p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
+            p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
             SiteTimer tm(c, SITE_CONV1_WGRAD);
-            e = small ? launch_wsgemm<Conv1Wgrad<T>, 4, 64, false>(p, c.stream, spg1) : launch_gemm(p, c.stream);
-        }
+            return small ? launch_wsgemm<decltype(p), 4, 64, false>(p, c.stream, spg1) : launch_gemm(p, c.stream);
+        };
+        e = index ? conv1_wgrad(Conv1Wgrad<T, true>{}) : conv1_wgrad(Conv1Wgrad<T, false>{});
         if (e != hipSuccess) return e;
     }
     const ReduceSpec specs[3] = {

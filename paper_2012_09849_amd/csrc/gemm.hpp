@@ -107,6 +107,27 @@ template <typename T, int V, typename S> HTS_HD Vec<T, V> load_vec(const S *p)
         return v;
     }
 }
+// v where keep, zeros otherwise, as selects on whole registers.  Loaders fetch from a clamped (always valid) address
+// and mask afterwards: a load inside a branch would have to be waited for before the next branch is entered, which
+// puts one memory round trip after the other.
+template <typename T, int V> HTS_HD Vec<T, V> keep_if(bool keep, const Vec<T, V> &v)
+{
+    if constexpr (V == 1) { Vec<T, V> r; r[0] = keep ? v[0] : from_f32<T>(0.0f); return r; }
+    else {
+        constexpr int N = V * (int)sizeof(T) / 4;
+        static_assert(N >= 1 && N * 4 == V * (int)sizeof(T), "whole registers");
+        if constexpr (N == 1) {
+            const uint32_t w = __builtin_bit_cast(uint32_t, v);
+            return __builtin_bit_cast(Vec<T, V>, keep ? w : 0u);
+        } else {
+            typedef uint32_t words __attribute__((ext_vector_type(N)));
+            words w = __builtin_bit_cast(words, v);
+#pragma unroll
+            for (int i = 0; i < N; ++i) w[i] = keep ? w[i] : 0u;
+            return __builtin_bit_cast(Vec<T, V>, w);
+        }
+    }
+}
 // 8 bytes (4-byte aligned) as 8 operands
 template <typename T> HTS_HD Vec<T, 8> load_u8x8(const uint8_t *p)
 {
@@ -144,6 +165,16 @@ template <class P> struct SteadyOf<P, std::void_t<decltype(P::STEADY)>> { static
 // at a time (`store4(const Row &, int n, const float (&v)[4], int z[, int batch]) const`, n a multiple of 4, N too).
 template <class P, class = void> struct OwnsRow : std::false_type {};
 template <class P> struct OwnsRow<P, std::void_t<decltype(P::LANE_OWNS_ROW)>> : std::integral_constant<bool, P::LANE_OWNS_ROW> {};
+
+// Optional natural staging of operands that are contiguous along the row index instead of along the reduction (the
+// weight gradients): a problem with `static constexpr bool NATURAL_LDS = true` has such an operand loaded by threads
+// whose neighbours take neighbouring row vectors at ONE reduction index (whole cache lines per load instruction), kept in
+// LDS as it lies in memory ([reduction][row], padded), and brought into the matrix instruction's lane layout by the
+// transposing LDS read (bf16) or by plain element reads (fp32).  No register transposes; same operand values in the
+// same lanes as the default staging, hence the same bits.
+template <class P, class = void> struct NaturalOf : std::false_type {};
+template <class P> struct NaturalOf<P, std::void_t<decltype(P::NATURAL_LDS)>> : std::integral_constant<bool, P::NATURAL_LDS> {};
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 // Optional run loaders for operands that are contiguous along the reduction instead of along k: a problem with
 // `void load_a_run(const CtxA &, int k, int kend, Vec<T,VA> (&out)[VA]) const` (likewise load_b_run) fetches the VA
@@ -222,11 +253,16 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int LS = BK + Tr::PAD;
     constexpr int VA = P::VA, VB = P::VB;
-    // work items per operand tile: a k-contiguous vector (ALONG_K) or a V x V block to transpose (otherwise)
-    constexpr int CA = P::A_ALONG_K ? BM * BK / VA : (BM / VA) * (BK / VA);
-    constexpr int CB = P::B_ALONG_K ? BN * BK / VB : (BN / VB) * (BK / VB);
+    // natural staging ([reduction][row + pad]); the pad keeps the row pitch at 64 bytes modulo 128 for bf16 (the four
+    // reduction rows a 16-lane group reads at once fall into different banks) and 128 modulo 256 for fp32
+    constexpr bool NAT_A = NaturalOf<P>::value && !P::A_ALONG_K, NAT_B = NaturalOf<P>::value && !P::B_ALONG_K;
+    constexpr int LSNA = BM + (BM % 64 == 0 ? 32 : 0), LSNB = BN + (BN % 64 == 0 ? 32 : 0);
+    // work items per operand tile: a k-contiguous vector (ALONG_K), a row-contiguous vector at one reduction index
+    // (natural staging) or a V x V block to transpose (otherwise)
+    constexpr int CA = P::A_ALONG_K ? BM * BK / VA : (NAT_A ? BK * (BM / VA) : (BM / VA) * (BK / VA));
+    constexpr int CB = P::B_ALONG_K ? BN * BK / VB : (NAT_B ? BK * (BN / VB) : (BN / VB) * (BK / VB));
     constexpr int NA = (CA + NT - 1) / NT, NB = (CB + NT - 1) / NT;     // items per thread (last one may be idle)
-    constexpr int RA = P::A_ALONG_K ? 1 : VA, RB = P::B_ALONG_K ? 1 : VB; // vectors held per item
+    constexpr int RA = (P::A_ALONG_K || NAT_A) ? 1 : VA, RB = (P::B_ALONG_K || NAT_B) ? 1 : VB; // vectors held per item
     static_assert(TM >= 1 && TN >= 1 && TM * 32 * WM == BM && TN * 32 * WN == BN, "tile shape");
     static_assert(BK % VA == 0 && BK % VB == 0 && BM % VA == 0 && BN % VB == 0, "loader shape");
     static_assert(BK % Tr::KINST == 0, "BK");
@@ -234,15 +270,27 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     static_assert(SEG % BK == 0, "SEG must be a multiple of BK");
     constexpr bool VEC_LDS = sizeof(T) == 2;      // bf16 rows are 16-byte aligned: whole vectors are stored at once
 
-    __shared__ __attribute__((aligned(16))) T As[BM * LS];
-    __shared__ __attribute__((aligned(16))) T Bs[BN * LS];
+    __shared__ __attribute__((aligned(16))) T As[NAT_A ? BK * LSNA : BM * LS];
+    __shared__ __attribute__((aligned(16))) T Bs[NAT_B ? BK * LSNB : BN * LS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int tiles_n = (p.N + BN - 1) / BN;
-    const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
+    int tile = blockIdx.x, z = blockIdx.y;
+    if constexpr (!HasBatch<P>::value) {
+        // A long split reduction is launched as a one-dimensional grid (see launch_gemm): workgroups go to the eight
+        // XCDs in turn, so workgroup h runs on XCD h % 8; all output tiles of reduction chunk z are given to XCD z % 8,
+        // whose L2 then serves the operand rows that those tiles share.
+        if (gridDim.y == 1 && p.klen < p.K) {
+            const int tiles = ((M + BM - 1) / BM) * tiles_n;
+            const int xcd = tile & 7, slot = tile >> 3;
+            z = (slot / tiles) * 8 + xcd;
+            tile = slot % tiles;
+            if ((long long)z * p.klen >= p.K) return;        // padding of the last round of eight chunks
+        }
+    }
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
     if (m0 >= M) return;                   // a batch smaller than the largest one: the whole workgroup leaves
-    const int z = blockIdx.y;
     const int kbeg = z * p.klen;
     const int kend = min(p.K, kbeg + p.klen);
 
@@ -255,8 +303,9 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         const int id = tid + i * NT;
         int r;
         if constexpr (P::A_ALONG_K) { r = id / (BK / VA); ka[i] = (id % (BK / VA)) * VA; }
+        else if constexpr (NAT_A) { r = (id % (BM / VA)) * VA; ka[i] = id / (BM / VA); }
         else { r = (id / (BK / VA)) * VA; ka[i] = (id % (BK / VA)) * VA; }     // neighbours write one LDS row
-        la[i] = r * LS + ka[i];
+        la[i] = NAT_A ? ka[i] * LSNA + r : r * LS + ka[i];
         ca[i] = make_ctx_a(p, m0 + r, zb);
     }
 #pragma unroll
@@ -264,8 +313,9 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         const int id = tid + i * NT;
         int r;
         if constexpr (P::B_ALONG_K) { r = id / (BK / VB); kb[i] = (id % (BK / VB)) * VB; }
+        else if constexpr (NAT_B) { r = (id % (BN / VB)) * VB; kb[i] = id / (BN / VB); }
         else { r = (id / (BK / VB)) * VB; kb[i] = (id % (BK / VB)) * VB; }
-        lb[i] = r * LS + kb[i];
+        lb[i] = NAT_B ? kb[i] * LSNB + r : r * LS + kb[i];
         cb[i] = make_ctx_b(p, n0 + r, zb);
     }
 
@@ -280,7 +330,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
 #pragma unroll
         for (int i = 0; i < NA; ++i)
             if (CA % NT == 0 || tid + i * NT < CA) {
-                if constexpr (!P::A_ALONG_K && HasRunA<P>::value) p.load_a_run(ca[i], k0 + ka[i], lim, ra[i]);
+                if constexpr (!P::A_ALONG_K && !NAT_A && HasRunA<P>::value) p.load_a_run(ca[i], k0 + ka[i], lim, ra[i]);
                 else {
 #pragma unroll
                     for (int q = 0; q < RA; ++q) ra[i][q] = p.load_a(ca[i], k0 + ka[i] + q, lim);
@@ -289,7 +339,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
 #pragma unroll
         for (int i = 0; i < NB; ++i)
             if (CB % NT == 0 || tid + i * NT < CB) {
-                if constexpr (!P::B_ALONG_K && HasRunB<P>::value) p.load_b_run(cb[i], k0 + kb[i], lim, rb[i]);
+                if constexpr (!P::B_ALONG_K && !NAT_B && HasRunB<P>::value) p.load_b_run(cb[i], k0 + kb[i], lim, rb[i]);
                 else {
 #pragma unroll
                     for (int q = 0; q < RB; ++q) rb[i][q] = p.load_b(cb[i], k0 + kb[i] + q, lim);
@@ -301,7 +351,8 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         for (int i = 0; i < NA; ++i) {
             if (CA % NT != 0 && tid + i * NT >= CA) continue;
             T *d = As + la[i];
-            if constexpr (P::A_ALONG_K) {
+            if constexpr (NAT_A) *reinterpret_cast<Vec<T, VA> *>(d) = ra[i][0];
+            else if constexpr (P::A_ALONG_K) {
                 if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VA> *>(d) = ra[i][0];
                 else {
 #pragma unroll
@@ -325,7 +376,8 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         for (int i = 0; i < NB; ++i) {
             if (CB % NT != 0 && tid + i * NT >= CB) continue;
             T *d = Bs + lb[i];
-            if constexpr (P::B_ALONG_K) {
+            if constexpr (NAT_B) *reinterpret_cast<Vec<T, VB> *>(d) = rb[i][0];
+            else if constexpr (P::B_ALONG_K) {
                 if constexpr (VEC_LDS) *reinterpret_cast<Vec<T, VB> *>(d) = rb[i][0];
                 else {
 #pragma unroll
@@ -350,6 +402,24 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     const int lrow = lane & 31, lk = lane >> 5;
     const T *a_base = As + (wm * TM * 32 + lrow) * LS;
     const T *b_base = Bs + (wn * TN * 32 + lrow) * LS;
+    // Natural staging, bf16: the transposing read works on groups of 16 lanes; lane 4j+q of a group points at 4 row
+    // entries (4q..4q+3 of the group's 16) of reduction index j (< 4) and receives the 4 reduction indices of row
+    // entry (lane % 16).  Groups 0,1 cover rows 0-15 and 16-31 at reduction 0-7 (two reads), groups 2,3 at 8-15.
+    // fp32: lane (row, k) reads its element.
+    const int nat_off_a = sizeof(T) == 2 ? (8 * (lane >> 5) + ((lane & 15) >> 2)) * LSNA + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)
+                                         : lk * LSNA + lrow;
+    const int nat_off_b = sizeof(T) == 2 ? (8 * (lane >> 5) + ((lane & 15) >> 2)) * LSNB + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)
+                                         : lk * LSNB + lrow;
+    const T *a_nat = As + wm * TM * 32 + nat_off_a;
+    const T *b_nat = Bs + wn * TN * 32 + nat_off_b;
+    auto tr8 = [](const T *q, int pitch) {      // 8 reduction indices of one row entry: two transposing reads
+        typedef i16x4 __attribute__((address_space(3))) *lds_ptr;
+        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q));
+        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q + 4 * pitch));
+        typedef short i16x8 __attribute__((ext_vector_type(8)));
+        const i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
+    };
 
     // one k-tile: registers -> LDS, refill this stage's registers with the tile D steps ahead, multiply.
     // REFILL: 1 = always (steady state: an unconditional load lets the compiler wait for exactly the older stages),
@@ -365,9 +435,9 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
             if constexpr (sizeof(T) == 4) {
                 float av[TM], bv[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) av[i] = a_base[i * 32 * LS + kk + lk];
+                for (int i = 0; i < TM; ++i) av[i] = NAT_A ? a_nat[kk * LSNA + i * 32] : a_base[i * 32 * LS + kk + lk];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bv[j] = b_base[j * 32 * LS + kk + lk];
+                for (int j = 0; j < TN; ++j) bv[j] = NAT_B ? b_nat[kk * LSNB + j * 32] : b_base[j * 32 * LS + kk + lk];
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -377,11 +447,15 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
             } else {
                 bf16x8 av[TM], bv[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    av[i] = *reinterpret_cast<const bf16x8 *>(a_base + i * 32 * LS + kk + lk * 8);
+                for (int i = 0; i < TM; ++i) {
+                    if constexpr (NAT_A) av[i] = tr8(a_nat + kk * LSNA + i * 32, LSNA);
+                    else av[i] = *reinterpret_cast<const bf16x8 *>(a_base + i * 32 * LS + kk + lk * 8);
+                }
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    bv[j] = *reinterpret_cast<const bf16x8 *>(b_base + j * 32 * LS + kk + lk * 8);
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (NAT_B) bv[j] = tr8(b_nat + kk * LSNB + j * 32, LSNB);
+                    else bv[j] = *reinterpret_cast<const bf16x8 *>(b_base + j * 32 * LS + kk + lk * 8);
+                }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -517,8 +591,11 @@ template <class P> inline hipError_t launch_gemm(const P &p, hipStream_t stream)
     const int tiles = ((grid_rows(p) + P::BM - 1) / P::BM) * ((p.N + P::BN - 1) / P::BN);
     const int nz = (p.K + p.klen - 1) / p.klen;
     if (tiles <= 0 || nz <= 0) return hipSuccess;
-    hipLaunchKernelGGL(gemm_kernel<P>, dim3(tiles, nz, grid_batches(p)), dim3(P::WAVES_M * P::WAVES_N * 64, 1, 1), 0,
-                       stream, p);
+    dim3 grid(tiles, nz, grid_batches(p));
+    if constexpr (!HasBatch<P>::value) {
+        if (nz >= 32) grid = dim3(((nz + 7) / 8) * 8 * tiles, 1, 1);      // XCD-aware order, decoded in the kernel
+    }
+    hipLaunchKernelGGL(gemm_kernel<P>, grid, dim3(P::WAVES_M * P::WAVES_N * 64, 1, 1), 0, stream, p);
     return hipGetLastError();
 }
 

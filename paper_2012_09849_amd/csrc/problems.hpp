@@ -64,11 +64,11 @@ template <typename T_> struct PlainGemm {
     HTS_HD CtxB ctx_b(int n) const { return {B + (long long)clamp_row(n, N) * K}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        return k < kend ? load_vec<T, VA>(c.p + k) : zero_vec<T, VA>();
+        return keep_if<T, VA>(k < kend, load_vec<T, VA>(c.p + (k < kend ? k : 0)));
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        return k < kend ? load_vec<T, VB>(c.p + k) : zero_vec<T, VB>();
+        return keep_if<T, VB>(k < kend, load_vec<T, VB>(c.p + (k < kend ? k : 0)));
     }
     HTS_HD void store(int m, int n, float acc, int) const { C[(long long)m * N + n] = acc; }
 };
@@ -230,14 +230,16 @@ struct HeadsWgrad {
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int b, int kend) const
     {
         Vec<T, VA> v;
-        v[0] = (c.j < M && b < kend) ? dz[(long long)b * M + c.j] : 0.0f;
+        const bool in = c.j < M && b < kend;
+        const float x = dz[in ? (long long)b * M + c.j : 0];
+        v[0] = in ? x : 0.0f;
         return v;
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int b, int kend) const
     {
-        if (b < kend && c.kk < 512) return load_vec<T, VB>(h + (long long)b * 512 + c.kk);
-        Vec<T, VB> v = zero_vec<T, VB>();
-        if (b < kend && c.kk == 512) v[0] = 1.0f;
+        const bool in = b < kend && c.kk < 512;
+        Vec<T, VB> v = keep_if<T, VB>(in, load_vec<T, VB>(h + (in ? (long long)b * 512 + c.kk : 0)));
+        v[0] = (b < kend && c.kk == 512) ? 1.0f : v[0];
         return v;
     }
     HTS_HD void store(int j, int kk, float acc, int) const
@@ -255,6 +257,7 @@ template <typename T_> struct FcWgrad {
     static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 2, WAVES_N = 2;   // 8 x 50 workgroups
     static constexpr int VA = 4, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
+    static constexpr bool NATURAL_LDS = true;
     struct CtxA { int j; };
     struct CtxB { int f; };
     int M, N, K, klen;     // M = 512, N = F+1, K = B
@@ -267,13 +270,13 @@ template <typename T_> struct FcWgrad {
     HTS_HD CtxB ctx_b(int f) const { return {f}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int b, int kend) const
     {
-        return b < kend ? load_vec<T, VA>(dh + (long long)b * 512 + c.j) : zero_vec<T, VA>();   // M = 512: no row tail
+        return keep_if<T, VA>(b < kend, load_vec<T, VA>(dh + (long long)(b < kend ? b : 0) * 512 + c.j));   // M = 512: no row tail
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int b, int kend) const
     {
-        if (b < kend && c.f < F) return load_vec<T, VB>(a3 + (long long)b * F + c.f);
-        Vec<T, VB> v = zero_vec<T, VB>();
-        if (b < kend && c.f == F) v[0] = from_f32<T>(1.0f);
+        const bool in = b < kend && c.f < F;
+        Vec<T, VB> v = keep_if<T, VB>(in, load_vec<T, VB>(a3 + (in ? (long long)b * F + c.f : 0)));
+        v[0] = (b < kend && c.f == F) ? from_f32<T>(1.0f) : v[0];
         return v;
     }
     HTS_HD void store(int j, int f, float acc, int) const
@@ -386,20 +389,17 @@ template <typename T_, class L> struct ConvDgrad {
     }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int k, int kend) const
     {
-        if (c.off >= 0 && k < kend) {
-            const int tap = k / L::COUT, n = k - tap * L::COUT, a = tap / TK, bb = tap - a * TK;
-            const int oy = c.yy - a, ox = c.xx - bb;         // (y - u)/s with y = yy*s + py, u = py + s*a
-            if (oy >= 0 && ox >= 0 && oy < Ho && ox < Wo)
-                return load_vec<T, VA>(dy + c.off - (long long)(a * Wo + bb) * L::COUT + n);
-        }
-        return zero_vec<T, VA>();
+        const int tap = k / L::COUT, n = k - tap * L::COUT, a = tap / TK, bb = tap - a * TK;
+        const int oy = c.yy - a, ox = c.xx - bb;         // (y - u)/s with y = yy*s + py, u = py + s*a
+        const bool in = c.off >= 0 && k < kend && oy >= 0 && ox >= 0 && oy < Ho && ox < Wo;
+        return keep_if<T, VA>(in, load_vec<T, VA>(dy + (in ? c.off - (long long)(a * Wo + bb) * L::COUT + n : 0)));
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int k, int kend) const
     {
-        if (c.off < 0 || k >= kend) return zero_vec<T, VB>();
         const int tap = k / L::COUT, n = k - tap * L::COUT, a = tap / TK, bb = tap - a * TK;
         const int u = c.py + L::STRIDE * a, vv = c.px + L::STRIDE * bb;
-        return load_vec<T, VB>(wd + c.off + (u * L::KSZ + vv) * L::COUT + n);
+        const bool in = c.off >= 0 && k < kend;
+        return keep_if<T, VB>(in, load_vec<T, VB>(wd + (in ? c.off + (u * L::KSZ + vv) * L::COUT + n : 0)));
     }
     static constexpr bool LANE_OWNS_ROW = true;
     struct Row { long long o; };
@@ -437,6 +437,7 @@ template <typename T_, class L> struct ConvWgrad {
     static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
+    static constexpr bool NATURAL_LDS = true;
     struct CtxA { int n; };
     struct CtxB { long long goff; };   // offset of (u,v,c) inside a patch; -1: bias column; -2: beyond the last column
     int M, N, K, klen;     // M = Cout (64), N = L::K + 1, K = B*Po
@@ -454,16 +455,16 @@ template <typename T_, class L> struct ConvWgrad {
     }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int m, int kend) const
     {
-        return m < kend ? load_vec<T, VA>(dy + (long long)m * L::COUT + c.n) : zero_vec<T, VA>();      // M = 64 = BM
+        return keep_if<T, VA>(m < kend, load_vec<T, VA>(dy + (long long)(m < kend ? m : 0) * L::COUT + c.n));      // M = 64 = BM
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int m, int kend) const
     {
-        if (m < kend && c.goff >= 0) {
-            const int b = dPo.div(m), p = m - b * Po, oy = dWo.div(p), ox = p - oy * Wo;
-            return load_vec<T, VB>(in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN + c.goff);
-        }
-        Vec<T, VB> v = zero_vec<T, VB>();
-        if (m < kend && c.goff == -1) v[0] = from_f32<T>(1.0f);
+        const bool inside = m < kend && c.goff >= 0;
+        const int mm = inside ? m : 0;
+        const int b = dPo.div(mm), p = mm - b * Po, oy = dWo.div(p), ox = p - oy * Wo;
+        Vec<T, VB> v = keep_if<T, VB>(inside, load_vec<T, VB>(in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN +
+                                                              (inside ? c.goff : 0)));
+        v[0] = (m < kend && c.goff == -1) ? from_f32<T>(1.0f) : v[0];
         return v;
     }
     // VB consecutive reduction indices m, m+1, ...: one (b, oy, ox) decomposition, advanced position by position.
@@ -476,16 +477,15 @@ template <typename T_, class L> struct ConvWgrad {
         const int b = dPo.div(mm), p = mm - b * Po;
         int oy = dWo.div(p), ox = p - oy * Wo;
         const T *src = in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN + (c.goff >= 0 ? c.goff : 0);
+        const T *first = src;                                                  // a valid address for positions past the range
         const int row_adv = (L::STRIDE * Win - Wo * L::STRIDE) * L::CIN;      // from the end of an output row to the next
         const int img_adv = (Hin - Ho * L::STRIDE) * Win * L::CIN;            // from the last output row to the next sample
         const T one = from_f32<T>(c.goff == -1 ? 1.0f : 0.0f);
 #pragma unroll
         for (int q = 0; q < VB; ++q) {
-            if (m + q < kend) {
-                const Vec<T, VB> v = load_vec<T, VB>(src);
-                if (c.goff >= 0) out[q] = v;
-                else { out[q] = zero_vec<T, VB>(); out[q][0] = one; }
-            } else out[q] = zero_vec<T, VB>();
+            const bool live = m + q < kend;
+            out[q] = keep_if<T, VB>(live && c.goff >= 0, load_vec<T, VB>(live ? src : first));
+            out[q][0] = (live && c.goff < 0) ? one : out[q][0];
             src += L::STRIDE * L::CIN;
             if (++ox == Wo) {
                 ox = 0; src += row_adv;
@@ -500,7 +500,8 @@ template <typename T_, class L> struct ConvWgrad {
 };
 
 // conv1 weight gradient: as above with the uint8 frames as the im2col source, kcol = (c,u,v)
-template <typename T_> struct Conv1Wgrad {
+// INDEXED: the frames are gathered through `index` (a template parameter so that the loader has no branch)
+template <typename T_, bool INDEXED> struct Conv1Wgrad {
     using T = T_;
     static constexpr bool STEADY = true;
     static constexpr int BM = 32, BN = 128, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 1, WAVES_N = 4;
@@ -524,18 +525,17 @@ template <typename T_> struct Conv1Wgrad {
     }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int m, int kend) const
     {
-        return m < kend ? load_vec<T, VA>(dy + (long long)m * 32 + c.n) : zero_vec<T, VA>();
+        return keep_if<T, VA>(m < kend, load_vec<T, VA>(dy + (long long)(m < kend ? m : 0) * 32 + c.n));
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int m, int kend) const
     {
-        if (m < kend && c.goff >= 0) {
-            const int b = dP1.div(m), p = m - b * P1, oy = dW1.div(p), ox = p - oy * W1;
-            const long long row = index ? index[b] : b;
-            return load_u8x8<T>(obs + row * C * H * W + (long long)(oy * 4) * W + ox * 4 + c.goff);
-        }
-        Vec<T, VB> v = zero_vec<T, VB>();
-        if (m < kend && c.goff == -1) v[0] = from_f32<T>(255.0f);   // the 1/255 of the input scaling is applied
-        return v;                                                    // when the partials are combined
+        const bool inside = m < kend && c.goff >= 0;
+        const int mm = inside ? m : 0;
+        const int b = dP1.div(mm), p = mm - b * P1, oy = dW1.div(p), ox = p - oy * W1;
+        const long long row = INDEXED ? (long long)index[b] : (long long)b;
+        Vec<T, VB> v = keep_if<T, VB>(inside, load_u8x8<T>(obs + row * C * H * W + (long long)(oy * 4) * W + ox * 4 + (inside ? c.goff : 0)));
+        v[0] = (m < kend && c.goff == -1) ? from_f32<T>(255.0f) : v[0];   // the 1/255 of the input scaling is applied
+        return v;                                                          // when the partials are combined
     }
     // As ConvWgrad::load_b_run; a run of VB positions touches at most two samples (P1 >= 16), whose storage rows are
     // both looked up before the loads.
@@ -547,18 +547,17 @@ template <typename T_> struct Conv1Wgrad {
         int oy = dW1.div(p), ox = p - oy * W1;
         const int b1 = b + 1 < nb ? b + 1 : b;
         const long long chw = (long long)C * H * W;
-        const long long r0 = index ? index[b] : b, r1 = index ? index[b1] : b1;
+        const long long r0 = INDEXED ? (long long)index[b] : (long long)b, r1 = INDEXED ? (long long)index[b1] : (long long)b1;
         const long long goff = c.goff >= 0 ? c.goff : 0;
         const uint8_t *src = obs + r0 * chw + (oy * 4) * W + ox * 4 + goff;
+        const uint8_t *first = src;                                             // a valid address for positions past the range
         const uint8_t *next = obs + r1 * chw + goff;                            // position (0,0) of the next sample
         const T one = from_f32<T>(c.goff == -1 ? 255.0f : 0.0f);              // the 1/255 of the input scaling is applied
 #pragma unroll                                                                  // when the partials are combined
         for (int q = 0; q < VB; ++q) {
-            if (m + q < kend) {
-                const Vec<T, VB> v = load_u8x8<T>(src);
-                if (c.goff >= 0) out[q] = v;
-                else { out[q] = zero_vec<T, VB>(); out[q][0] = one; }
-            } else out[q] = zero_vec<T, VB>();
+            const bool live = m + q < kend;
+            out[q] = keep_if<T, VB>(live && c.goff >= 0, load_u8x8<T>(live ? src : first));
+            out[q][0] = (live && c.goff < 0) ? one : out[q][0];
             src += 4;
             if (++ox == W1) {
                 ox = 0; src += 4 * W - 4 * W1;
