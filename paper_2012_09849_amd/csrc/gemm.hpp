@@ -74,17 +74,17 @@ struct FastDiv {
         while ((1ll << lg) < f.d) ++lg;
         const int p = 31 + lg;
         f.mul = (uint32_t)(((1ull << p) + (unsigned long long)f.d - 1) / (unsigned long long)f.d);
-        f.shr = p - 32;
+        f.shr = p - 32 < 0 ? 0 : p - 32;        // d == 1 (p = 31) is answered by the select below
         return f;
     }
-    HTS_HD int div(int x) const
-    {
-        if (d == 1) return x;
+    HTS_HD int div(int x) const                 // a select, not a branch: a branch would end the basic block and with it
+    {                                           // the window in which loads around the division can be issued together
 #if defined(__HIP_DEVICE_COMPILE__)
-        return (int)(__umulhi((uint32_t)x, mul) >> shr);
+        const int q = (int)(__umulhi((uint32_t)x, mul) >> shr);
 #else
-        return (int)((((unsigned long long)(uint32_t)x * mul) >> 32) >> shr);
+        const int q = (int)((((unsigned long long)(uint32_t)x * mul) >> 32) >> shr);
 #endif
+        return d == 1 ? x : q;
     }
 };
 
@@ -162,7 +162,9 @@ template <class P> struct SteadyOf<P, std::void_t<decltype(P::STEADY)>> { static
 // operands of the matrix instruction exchanged, so that a lane's 16 accumulator registers are 16 columns (four groups
 // of four neighbours) of ONE output row instead of 16 rows of one column.  Its epilogue then needs one row context
 // per lane (`Row row(int m[, int batch]) const`: e.g. a position decomposition) and stores four neighbouring columns
-// at a time (`store4(const Row &, int n, const float (&v)[4], int z[, int batch]) const`, n a multiple of 4, N too).
+// at a time: `Pre pre4(const Row &, int n) const` fetches what the store needs from memory (bias, mask) and
+// `store4(const Row &, int n, const float (&v)[4], int z[, int batch], const Pre &) const` finishes; n and N are
+// multiples of 4.
 template <class P, class = void> struct OwnsRow : std::false_type {};
 template <class P> struct OwnsRow<P, std::void_t<decltype(P::LANE_OWNS_ROW)>> : std::integral_constant<bool, P::LANE_OWNS_ROW> {};
 
@@ -551,23 +553,40 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     auto epilogue = [&](auto full_tile) {
         constexpr bool FULL = decltype(full_tile)::value;
         if constexpr (SWAP) {
+            // two passes: everything the stores need from memory (bias, ReLU masks) is fetched first, so those loads
+            // travel together instead of each waiting behind the store before it
+            auto row_of = [&](int mr) { if constexpr (HasBatch<P>::value) return p.row(mr, zb); else return p.row(mr); };
+            using RowT = decltype(row_of(0));
+            using PreT = decltype(p.pre4(std::declval<const RowT &>(), 0));
+            RowT rc[TM];
+            PreT pre[TM][TN][4];
+            bool mok[TM];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int m = m0 + (wm * TM + i) * 32 + lrow;
-                const bool mok = FULL || m < M;
-                const int mr = mok ? m : M - 1;
-                auto rc = [&]() { if constexpr (HasBatch<P>::value) return p.row(mr, zb); else return p.row(mr); }();
+                mok[i] = FULL || m < M;
+                rc[i] = row_of(mok[i] ? m : M - 1);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = n0 + (wn * TN + j) * 32 + 8 * g + 4 * lk;
+                        pre[i][j][g] = p.pre4(rc[i], FULL ? n : min(n, p.N - 4));
+                    }
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int n = n0 + (wn * TN + j) * 32 + 8 * g + 4 * lk;
                         const float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        if (FULL || (mok && n < p.N)) {
-                            if constexpr (HasBatch<P>::value) p.store4(rc, n, v, z, zb); else p.store4(rc, n, v, z);
+                        if (FULL || (mok[i] && n < p.N)) {
+                            if constexpr (HasBatch<P>::value) p.store4(rc[i], n, v, z, zb, pre[i][j][g]);
+                            else p.store4(rc[i], n, v, z, pre[i][j][g]);
                         }
                     }
-            }
         } else {
 #pragma unroll
             for (int i = 0; i < TM; ++i)

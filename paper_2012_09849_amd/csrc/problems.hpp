@@ -161,9 +161,9 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
             return {(long long)b * L::COUT * Po + p, (long long)m * L::COUT};
         } else return {(long long)m * L::COUT, 0};
     }
-    HTS_HD void store4(const Row &r, int n, const float (&v)[4], int) const
+    HTS_HD f32x4 pre4(const Row &, int n) const { return *reinterpret_cast<const f32x4 *>(bias + n); }
+    HTS_HD void store4(const Row &r, int n, const float (&v)[4], int, const f32x4 &bn) const
     {
-        const f32x4 bn = *reinterpret_cast<const f32x4 *>(bias + n);
         Vec<T, 4> y;
 #pragma unroll
         for (int q = 0; q < 4; ++q) { const float t = v[q] + bn[q]; y[q] = from_f32<T>(t > 0.0f ? t : 0.0f); }
@@ -308,9 +308,9 @@ template <typename T_> struct FcDgrad {
     static constexpr bool LANE_OWNS_ROW = true;
     struct Row { long long o; };
     HTS_HD Row row(int b) const { return {(long long)b * N}; }
-    HTS_HD void store4(const Row &r, int f, const float (&v)[4], int) const
+    HTS_HD Vec<T, 4> pre4(const Row &r, int f) const { return *reinterpret_cast<const Vec<T, 4> *>(a3n + r.o + f); }
+    HTS_HD void store4(const Row &r, int f, const float (&v)[4], int, const Vec<T, 4> &a) const
     {
-        const Vec<T, 4> a = *reinterpret_cast<const Vec<T, 4> *>(a3n + r.o + f);
         Vec<T, 4> y;
 #pragma unroll
         for (int q = 0; q < 4; ++q) y[q] = from_f32<T>(to_f32(a[q]) > 0.0f ? v[q] : 0.0f);
@@ -409,9 +409,9 @@ template <typename T_, class L> struct ConvDgrad {
         const int b = c.dHW.div(m), p = m - b * (c.Hc * c.Wc), yy = c.dW.div(p), xx = p - yy * c.Wc;
         return {((((long long)b * Hin + yy * L::STRIDE + c.py) * Win) + xx * L::STRIDE + c.px) * N};
     }
-    HTS_HD void store4(const Row &r, int ch, const float (&v)[4], int, int) const
+    HTS_HD Vec<T, 4> pre4(const Row &r, int ch) const { return *reinterpret_cast<const Vec<T, 4> *>(act_in + r.o + ch); }
+    HTS_HD void store4(const Row &r, int ch, const float (&v)[4], int, int, const Vec<T, 4> &a) const
     {
-        const Vec<T, 4> a = *reinterpret_cast<const Vec<T, 4> *>(act_in + r.o + ch);
         Vec<T, 4> y;
 #pragma unroll
         for (int q = 0; q < 4; ++q) y[q] = from_f32<T>(to_f32(a[q]) > 0.0f ? v[q] : 0.0f);
