@@ -81,7 +81,8 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.prepare();
         {
             SiteTimer tm(c, SITE_CONV3_DGRAD);
-            e = small ? launch_wsgemm<ConvDgrad<T, Layer3>, (sizeof(T) == 4 ? 8 : 4), (sizeof(T) == 2 ? 192 : 96), false, true>(p, c.stream) : launch_gemm(p, c.stream);
+            // fp32: eight segments of 72 for eight wavefronts, and panels small enough for two workgroups per compute unit
+            e = small ? launch_wsgemm<ConvDgrad<T, Layer3>, (sizeof(T) == 4 ? 8 : 4), (sizeof(T) == 2 ? 192 : 72), false, true>(p, c.stream) : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }
