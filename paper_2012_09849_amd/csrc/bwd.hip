@@ -6,6 +6,186 @@
 
 namespace hts {
 
+// ------------------------------------------------------------------------------------------------------------
+// conv1 weight gradient for large bf16 batches of small 4-channel frames (e.g. 4x84x84): one workgroup walks a share
+// of the observations.  For each one the frame is converted to bf16 ONCE into an LDS image [(c,y)][W] and the
+// sample's 32-channel output gradient [P1][32] is copied beside it; wavefront t then owns the 32 weight columns
+// (c = t/2, u = 4(t%2)..+3, v = 0..7) and adds  D[n][(c,u,v)] += sum_m dy[m][n] * image[c][4oy+u][4ox+v]  over the
+// sample's positions, 16 per matrix instruction.  Both operands have the reduction (the position) as their slow
+// index in LDS; the transposing LDS read hands each lane the 8 positions of its row / column -- for the image with a
+// per-lane address, so the im2col matrix is never materialised.  (The tile kernel converts every pixel four times and
+// fetches it in 8-byte pieces: it is bound by that.)  Wavefront 0 also forms the bias column against a constant 255
+// (the reduction scales every conv1 column by 1/255).  Partials part[workgroup][32][64C+1], combined in workgroup
+// order by the reduction kernel.
+// ------------------------------------------------------------------------------------------------------------
+struct Conv1WgImgArgs {
+    const uint8_t *obs;
+    const int32_t *index;
+    const bf16_t *dy;       // [B][P1][32]
+    float *part;
+    int B, H, W, W1, P1, N; // N = 64*C + 1
+    FastDiv dGpr, dW1;
+};
+constexpr int C1WG_THREADS = 512;          // 8 wavefronts = the 8 column tiles of a 4-channel conv1
+constexpr int C1WG_PASSES = 16;            // passes of a wavefront over its share of the image rows
+constexpr int C1WG_DYV = 4;                // 16-byte vectors of the sample's output gradient per thread
+
+template <int C> __global__ __launch_bounds__(C1WG_THREADS) void conv1_wgrad_image_kernel(const Conv1WgImgArgs a)
+{
+    static_assert(C == 4, "one wavefront per 32 weight columns");
+    extern __shared__ __attribute__((aligned(16))) unsigned char c1w_smem[];
+    bf16_t *img = reinterpret_cast<bf16_t *>(c1w_smem);
+    const int rows = C * a.H, Wp = a.W;
+    bf16_t *dyl = img + ((rows * Wp + 7) & ~7);                   // [P1][32]
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int kg = lane >> 5, g1 = (lane >> 4) & 1, jj = (lane & 15) >> 2, q = lane & 3;
+    // frame -> image, as in the forward image kernel: a wavefront takes 64/gpr image rows per pass
+    const int gpr = a.W >> 2, rpp = 64 / gpr;
+    const int lr = a.dGpr.div(lane), xg = lane - lr * gpr;
+    const bool lane_on = lr < rpp;
+    constexpr int NW = C1WG_THREADS / 64;
+    const int nvec = a.P1 * 4;                                    // 16-byte vectors in one sample's [P1][32]
+    uint32_t raw[C1WG_PASSES];
+    bf16x8 dyr[C1WG_DYV];
+    auto fetch = [&](int b) {
+        const uint8_t *src = a.obs + (long long)(a.index ? a.index[b] : b) * rows * a.W + 4 * xg;
+#pragma unroll
+        for (int i = 0; i < C1WG_PASSES; ++i) {
+            const int row = (w + i * NW) * rpp + lr;
+            if (lane_on && row < rows) raw[i] = *reinterpret_cast<const uint32_t *>(src + row * a.W);
+        }
+        const bf16_t *dsrc = a.dy + (long long)b * a.P1 * 32;
+#pragma unroll
+        for (int i = 0; i < C1WG_DYV; ++i) {
+            const int v = tid + i * C1WG_THREADS;
+            if (v < nvec) dyr[i] = *reinterpret_cast<const bf16x8 *>(dsrc + v * 8);
+        }
+    };
+    // this lane's part of the operand addresses.  Transposing read: lane 4j+q of a 16-lane group points at entries
+    // 4q..4q+3 (of the group's 16 rows / columns) at reduction index j and receives the four reduction indices of
+    // entry (lane % 16); groups 0,1 hold entries 0-15 and 16-31 at reduction 0-7 (two reads), groups 2,3 at 8-15.
+    const int col0 = 16 * g1 + 4 * q;                             // first of the four columns this lane points at
+    const int lane_img = ((w >> 1) * a.H + 4 * (w & 1) + (col0 >> 3)) * Wp + (col0 & 7);
+    const bf16_t *a_lane = dyl + (8 * kg + jj) * 32 + col0;
+    typedef i16x4 __attribute__((address_space(3))) *lds_ptr;
+    auto tr4 = [](const bf16_t *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p)); };
+    auto join = [](const i16x4 lo, const i16x4 hi) {
+        typedef short i16x8 __attribute__((ext_vector_type(8)));
+        const i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
+    };
+    bf16x8 ones;                                                  // bias column: 255 in column 0 of the tile
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = from_f32<bf16_t>((lane & 31) == 0 ? 255.0f : 0.0f);
+    f32x16 acc, accb;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc[r] = 0.0f; accb[r] = 0.0f; }
+    const int step_wrap = 64 + 4 * Wp - 4 * a.W1;                 // image offset from position m to m+16 across a row end
+
+    if ((int)blockIdx.x < a.B) fetch(blockIdx.x);
+    for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
+#pragma unroll
+        for (int i = 0; i < C1WG_PASSES; ++i) {
+            const int row = (w + i * NW) * rpp + lr;
+            if (!lane_on || row >= rows) continue;
+            Vec<bf16_t, 4> px;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) px[e] = from_f32<bf16_t>((float)((raw[i] >> (8 * e)) & 0xFFu));
+            *reinterpret_cast<Vec<bf16_t, 4> *>(img + row * Wp + 4 * xg) = px;
+        }
+#pragma unroll
+        for (int i = 0; i < C1WG_DYV; ++i) {
+            const int v = tid + i * C1WG_THREADS;
+            if (v < nvec) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
+        }
+        __syncthreads();
+        if (b + (int)gridDim.x < a.B) fetch(b + gridDim.x);      // the next sample travels while this one is multiplied
+        // positions m = 16 ks + 8 kg + jj (first read) and m + 4 (second read), walked incrementally (W1 >= 16)
+        int oya = a.dW1.div(8 * kg + jj), oxa = 8 * kg + jj - oya * a.W1;
+        int oyb = a.dW1.div(8 * kg + jj + 4), oxb = 8 * kg + jj + 4 - oyb * a.W1;
+        int offa = lane_img + 4 * oya * Wp + 4 * oxa, offb = lane_img + 4 * oyb * Wp + 4 * oxb;
+        const bf16_t *ap = a_lane;
+        const int nks = a.P1 >> 4;
+        // Software pipeline: the four reads of step k+1 are issued before the matrix instruction of step k (the
+        // transposing reads are not moved by the compiler).  Two straight-line bodies (with / without the bias
+        // column); whole groups of 5 steps are written out.
+        auto walk = [&](auto with_bias) {
+            i16x4 ra0, ra1, rb0, rb1;
+            auto read = [&]() {
+                ra0 = tr4(ap); ra1 = tr4(ap + 4 * 32); rb0 = tr4(img + offa); rb1 = tr4(img + offb);
+                ap += 16 * 32;
+                oxa += 16; { const bool wr = oxa >= a.W1; oxa -= wr ? a.W1 : 0; offa += wr ? step_wrap : 64; }
+                oxb += 16; { const bool wr = oxb >= a.W1; oxb -= wr ? a.W1 : 0; offb += wr ? step_wrap : 64; }
+            };
+            auto mult = [&](const bf16x8 av, const bf16x8 bv) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+                if constexpr (decltype(with_bias)::value) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, ones, accb, 0, 0, 0);
+            };
+            read();                                        // step 0 (P1 >= 16)
+            int ks = 0;
+            for (; ks + 5 < nks; ks += 5) {                // steps ks..ks+4; step ks+5 exists and is read in the last turn
+#pragma unroll
+                for (int u = 0; u < 5; ++u) {
+                    const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
+                    read();
+                    __builtin_amdgcn_sched_barrier(0);     // keep the reads of the next step ahead of this step's product
+                    mult(av, bv);
+                }
+            }
+            for (; ks < nks; ++ks) {
+                const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
+                if (ks + 1 < nks) read();
+                mult(av, bv);
+            }
+        };
+        if (w == 0) walk(std::true_type{}); else walk(std::false_type{});
+        __syncthreads();          // image and gradient are overwritten by the next sample
+    }
+    // accumulator register r of lane l is D[n = 8(r/4) + 4(l/32) + r%4][column l%32]
+    float *dst = a.part + (long long)blockIdx.x * 32 * a.N + w * 32 + (lane & 31);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dst[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = acc[r];
+    if (w == 0 && (lane & 31) == 0) {
+        float *bd = a.part + (long long)blockIdx.x * 32 * a.N + 64 * C;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) bd[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = accb[r];
+    }
+}
+
+// true if the frame shape and pointers fit conv1_wgrad_image_kernel
+static bool conv1_wgrad_image_fits(const Geom &g, const uint8_t *obs)
+{
+    if (g.C != 4 || g.W > 256 || (g.W & 3) || (((uintptr_t)obs) & 3u) || g.W1 < 16 || (g.P1 & 15)) return false;
+    const int gpr = g.W / 4, rpp = 64 / gpr, rows = g.C * g.H;
+    const size_t lds = (((size_t)rows * g.W + 7) & ~(size_t)7) * 2 + (size_t)g.P1 * 64;
+    return rows <= C1WG_PASSES * rpp * (C1WG_THREADS / 64) && g.P1 * 4 <= C1WG_DYV * C1WG_THREADS && lds <= 160 * 1024;
+}
+
+// nz: number of workgroups = number of partials written (at most max_parts)
+static hipError_t launch_conv1_wgrad_image(Ctx &c, const uint8_t *obs, const int32_t *index, int B, float *part, int max_parts,
+                                           int *nz)
+{
+    const Geom &g = c.g;
+    Conv1WgImgArgs a;
+    a.obs = obs; a.index = index; a.dy = (const bf16_t *)c.ws.dy1; a.part = part;
+    a.B = B; a.H = g.H; a.W = g.W; a.W1 = g.W1; a.P1 = g.P1; a.N = g.K1 + 1;
+    a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
+    const size_t lds = (((size_t)g.C * g.H * g.W + 7) & ~(size_t)7) * 2 + (size_t)g.P1 * 64;
+    auto kern = conv1_wgrad_image_kernel<4>;
+    static bool attr_set = false;       // raise the dynamic-LDS limit once
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int grid = B < max_parts ? B : max_parts;
+    *nz = grid;
+    SiteTimer tm(c, SITE_CONV1_WGRAD);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C1WG_THREADS), lds, c.stream, a);
+    return hipGetLastError();
+}
+
 template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, const int32_t *index, int B, float *grads)
 {
     const Geom &g = c.g;
@@ -57,7 +237,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     int spg3 = 0, spg2 = 0, spg1 = 0;
     const int nz3 = small ? groups_for((long long)B * g.P3, &spg3, 32, 8) : s3.nz;
     const int nz2 = small ? groups_for((long long)B * g.P2, &spg2, 32, 8) : s2.nz;
-    const int nz1 = small ? groups_for((long long)B * g.P1, &spg1, 128, 4) : s1.nz;   // long reduction, tiny output
+    int nz1 = small ? groups_for((long long)B * g.P1, &spg1, 128, 4) : s1.nz;   // long reduction, tiny output
     float *part3 = c.ws.part;
     float *part2 = part3 + (size_t)nz3 * 64 * 577;
     float *part1 = part2 + (size_t)nz2 * 64 * 513;
@@ -119,7 +299,8 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
             SiteTimer tm(c, SITE_CONV1_WGRAD);
             return small ? launch_wsgemm<decltype(p), 4, 64, false>(p, c.stream, spg1) : launch_gemm(p, c.stream);
         };
-        e = index ? conv1_wgrad(Conv1Wgrad<T, true>{}) : conv1_wgrad(Conv1Wgrad<T, false>{});
+        if (!small && sizeof(T) == 2 && conv1_wgrad_image_fits(g, obs)) e = launch_conv1_wgrad_image(c, obs, index, B, part1, s1.nz, &nz1);
+        else e = index ? conv1_wgrad(Conv1Wgrad<T, true>{}) : conv1_wgrad(Conv1Wgrad<T, false>{});
         if (e != hipSuccess) return e;
     }
     const ReduceSpec specs[3] = {
