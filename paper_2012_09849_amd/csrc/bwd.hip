@@ -3,6 +3,7 @@
 // each chunk writes its own partial, and wgrad_reduce adds the partials in chunk order -- no atomics, so the
 // gradient is bit-identical from run to run.
 #include "internal.hpp"
+#include "imgconv.hpp"
 
 namespace hts {
 
@@ -192,6 +193,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     hipError_t e;
     // Small minibatches take the wave-per-segment kernels: many more, much shorter dependency chains.
     const bool small = B <= c.small_b;
+    const bool atari_grid = g.H1 == 20 && g.W1 == 20;      // 84x84 frames: conv2 sees 20x20, conv3 9x9
     // groups of 64-row segments for the split weight gradients on that path: at most max_groups partial buffers per
     // layer, at least min_segs segments per group (never more groups than the tile path's split_for allows for the
     // same reduction length, which is what the partial buffers are sized for)
@@ -261,6 +263,12 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.prepare();
         {
             SiteTimer tm(c, SITE_CONV3_DGRAD);
+            if (!small && sizeof(T) == 2 && atari_grid) {      // large bf16 batch, 9x9 input: output gradients resident in LDS
+                ImgConvArgs a = {};
+                a.in = (const bf16_t *)c.ws.dy3; a.w = (const bf16_t *)c.ws.wd3; a.mask = (const bf16_t *)c.ws.act2;
+                a.out = (bf16_t *)c.ws.dy2; a.B = B;
+                e = launch_imgconv<ImgDgrad<64, 3, 1, 9, 9, 6>>(a, c.stream);
+            } else
             // fp32: eight segments of 72 for eight wavefronts, and panels small enough for two workgroups per compute unit
             e = small ? launch_wsgemm<ConvDgrad<T, Layer3>, (sizeof(T) == 4 ? 8 : 4), (sizeof(T) == 2 ? 192 : 72), false, true>(p, c.stream) : launch_gemm(p, c.stream);
         }
@@ -286,6 +294,12 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         p.prepare();
         {
             SiteTimer tm(c, SITE_CONV2_DGRAD);
+            if (!small && sizeof(T) == 2 && atari_grid) {
+                ImgConvArgs a = {};
+                a.in = (const bf16_t *)c.ws.dy2; a.w = (const bf16_t *)c.ws.wd2; a.mask = (const bf16_t *)c.ws.act1;
+                a.out = (bf16_t *)c.ws.dy1; a.B = B;
+                e = launch_imgconv<ImgDgrad<32, 4, 2, 20, 20, 4>>(a, c.stream);
+            } else
             e = small ? launch_wsgemm<ConvDgrad<T, Layer2>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;

@@ -1,6 +1,7 @@
 // Forward pass of the policy/value network (appendix "Implementation Details") as four tiled contractions:
 // conv1 (uint8 gather, 1/255 folded in), conv2, conv3, FC.  The heads run in misc.hip.
 #include "internal.hpp"
+#include "imgconv.hpp"
 
 namespace hts {
 
@@ -186,6 +187,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         }
         if (e != hipSuccess) return e;
     }
+    const bool atari_grid = g.H1 == 20 && g.W1 == 20;      // 84x84 frames: conv2 sees 20x20, conv3 9x9
     {
         ConvFwd<T, Layer2, false> p;
         p.M = B * g.P2; p.N = 64; p.K = 512; p.klen = 512;
@@ -194,6 +196,8 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.dPo = FastDiv::make(g.P2); p.dWo = FastDiv::make(g.W2);
         {
             SiteTimer tm(c, SITE_CONV2_FWD);
+            // (the LDS-resident kernel of imgconv.hpp measured slower here than the tile kernel: 20.4 vs 17.8 us at
+            // B = 1024 -- this layer streams the large conv1 output once either way)
             e = small ? launch_wsgemm<ConvFwd<T, Layer2, false>, 8, ConvFwd<T, Layer2, false>::SEG, false>(p, c.stream)
                       : launch_gemm(p, c.stream);
         }
@@ -208,8 +212,13 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.dPo = FastDiv::make(g.P3); p.dWo = FastDiv::make(g.W3);
         {
             SiteTimer tm(c, SITE_CONV3_FWD);
-            e = small ? launch_wsgemm<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 8 : 4), ConvFwd<T, Layer3, true>::SEG, false, true>(p, c.stream)
-                      : launch_gemm(p, c.stream);
+            if (small) e = launch_wsgemm<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 8 : 4), ConvFwd<T, Layer3, true>::SEG, false, true>(p, c.stream);
+            else if (sizeof(T) == 2 && atari_grid) {       // large bf16 batch, 9x9 input: activations resident in LDS
+                ImgConvArgs a = {};
+                a.in = (const bf16_t *)c.ws.act2; a.w = (const bf16_t *)c.ws.wf3; a.bias = hb + c.sh.b3;
+                a.out = (bf16_t *)c.ws.a3; a.out2 = learn ? (bf16_t *)c.ws.a3n : nullptr; a.B = B;
+                e = launch_imgconv<ImgFwd<64, 3, 1, 9, 9, 5, ConvFwd<bf16_t, Layer3, true>::SEG, true>>(a, c.stream);
+            } else e = launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }

@@ -79,9 +79,10 @@ struct SiteTimer {
 };
 
 // most chunks a conv weight gradient's reduction is cut into (layers 3, 2, 1)
-// (these kernels are bound by the latency of each workgroup's serial walk along its chunk, so many short chunks
-// beat few long ones; measured at B = 1024: conv1 170 -> 92 us going from 128 to 256 chunks)
-constexpr int MAXZ3 = 256, MAXZ2 = 128, MAXZ1 = 256;
+// (more chunks: more workgroups and shorter serial walks; fewer chunks: less partial-sum traffic for the reduction
+// kernel, which is bound by reading it.  Measured at B = 1024 with the chunks placed XCD by XCD: 64 chunks for
+// layers 3 and 2 beat 32, 128 and 256; layer 1 -- a tiny output, a long reduction -- keeps 256.)
+constexpr int MAXZ3 = 64, MAXZ2 = 64, MAXZ1 = 256;
 struct SplitK { int klen, nz; };
 // Split of a weight-gradient reduction of length kp; depends on kp only, so results are reproducible.
 inline SplitK split_for(long long kp, int maxz)
