@@ -181,7 +181,10 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
         {
             SiteTimer tm(c, SITE_CONV1_FWD);
-            if (small) e = launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream);
+            // one wavefront per 64-long segment (= per input channel): 4 for a 4-channel frame; a 16-channel frame
+            // gets 16, with the weight operand straight from memory so that their panels still fit in LDS
+            if (small) e = g.K1 >= 1024 ? launch_wsgemm<Conv1Fwd<T>, 16, Conv1Fwd<T>::SEG, false, true>(p, c.stream)
+                                        : launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream);
             else if (sizeof(T) == 2 && conv1_image_fits(g, obs)) e = launch_conv1_image(c, obs, index, B);
             else e = launch_gemm(p, c.stream);
         }
