@@ -239,7 +239,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     int spg3 = 0, spg2 = 0, spg1 = 0;
     const int nz3 = small ? groups_for((long long)B * g.P3, &spg3, 32, 8) : s3.nz;
     const int nz2 = small ? groups_for((long long)B * g.P2, &spg2, 32, 8) : s2.nz;
-    int nz1 = small ? groups_for((long long)B * g.P1, &spg1, 128, 4) : s1.nz;   // long reduction, tiny output
+    int nz1 = small ? groups_for((long long)B * g.P1, &spg1, 56, 4) : s1.nz;   // long reduction, tiny output
     float *part3 = c.ws.part;
     float *part2 = part3 + (size_t)nz3 * 64 * 577;
     float *part1 = part2 + (size_t)nz2 * 64 * 513;
