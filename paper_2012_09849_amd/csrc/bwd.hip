@@ -8,16 +8,17 @@
 namespace hts {
 
 // ------------------------------------------------------------------------------------------------------------
-// conv1 weight gradient for large bf16 batches of small 4-channel frames (e.g. 4x84x84): one workgroup walks a share
-// of the observations.  For each one the frame is converted to bf16 ONCE into an LDS image [(c,y)][W] and the
-// sample's 32-channel output gradient [P1][32] is copied beside it; wavefront t then owns the 32 weight columns
-// (c = t/2, u = 4(t%2)..+3, v = 0..7) and adds  D[n][(c,u,v)] += sum_m dy[m][n] * image[c][4oy+u][4ox+v]  over the
-// sample's positions, 16 per matrix instruction.  Both operands have the reduction (the position) as their slow
-// index in LDS; the transposing LDS read hands each lane the 8 positions of its row / column -- for the image with a
-// per-lane address, so the im2col matrix is never materialised.  (The tile kernel converts every pixel four times and
-// fetches it in 8-byte pieces: it is bound by that.)  Wavefront 0 also forms the bias column against a constant 255
-// (the reduction scales every conv1 column by 1/255).  Partials part[workgroup][32][64C+1], combined in workgroup
-// order by the reduction kernel.
+// conv1 weight gradient for large bf16 batches of small frames with 4, 8, 12 or 16 channels (4x84x84, 16x72x96):
+// one workgroup walks a share of the observations.  For each one the sample's 32-channel output gradient [P1][32] is
+// copied into LDS, and, four input channels at a time, the frame is converted to bf16 ONCE into an LDS image
+// [(c,y)][W]; wavefront t then owns the 32 weight columns (c = 4*group + t/2, u = 4(t%2)..+3, v = 0..7) and adds
+//   D[n][(c,u,v)] += sum_m dy[m][n] * image[c][4oy+u][4ox+v]
+// over the sample's positions, 16 per matrix instruction.  Both operands have the reduction (the position) as their
+// slow index in LDS; the transposing LDS read hands each lane the 8 positions of its row / column -- for the image
+// with a per-lane address, so the im2col matrix is never materialised.  (The tile kernel converts every pixel four
+// times and fetches it in 8-byte pieces: it is bound by that.)  Positions are padded to a multiple of 16 with zero
+// gradient rows.  Wavefront 0 also forms the bias column against a constant 255 (the reduction scales every conv1
+// column by 1/255).  Partials part[workgroup][32][64C+1], combined in workgroup order by the reduction kernel.
 // ------------------------------------------------------------------------------------------------------------
 struct Conv1WgImgArgs {
     const uint8_t *obs;
@@ -27,17 +28,18 @@ struct Conv1WgImgArgs {
     int B, H, W, W1, P1, N; // N = 64*C + 1
     FastDiv dGpr, dW1;
 };
-constexpr int C1WG_THREADS = 512;          // 8 wavefronts = the 8 column tiles of a 4-channel conv1
-constexpr int C1WG_PASSES = 16;            // passes of a wavefront over its share of the image rows
+constexpr int C1WG_THREADS = 512;          // 8 wavefronts = the 8 column tiles of four input channels
+constexpr int C1WG_PASSES = 20;            // passes of a wavefront over its share of a channel group's image rows
 constexpr int C1WG_DYV = 4;                // 16-byte vectors of the sample's output gradient per thread
 
-template <int C> __global__ __launch_bounds__(C1WG_THREADS) void conv1_wgrad_image_kernel(const Conv1WgImgArgs a)
+// PADDED: P1 is not a multiple of 16 (the last step has padding positions)
+template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) void conv1_wgrad_image_kernel(const Conv1WgImgArgs a)
 {
-    static_assert(C == 4, "one wavefront per 32 weight columns");
+    constexpr int C = 4 * NG;
     extern __shared__ __attribute__((aligned(16))) unsigned char c1w_smem[];
-    bf16_t *img = reinterpret_cast<bf16_t *>(c1w_smem);
-    const int rows = C * a.H, Wp = a.W;
-    bf16_t *dyl = img + ((rows * Wp + 7) & ~7);                   // [P1][32]
+    bf16_t *img = reinterpret_cast<bf16_t *>(c1w_smem);           // one channel group: [(c,y)][W]
+    const int rows = 4 * a.H, Wp = a.W;
+    bf16_t *dyl = img + ((rows * Wp + 7) & ~7);                   // [P1 padded to 16][32]
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int kg = lane >> 5, g1 = (lane >> 4) & 1, jj = (lane & 15) >> 2, q = lane & 3;
     // frame -> image, as in the forward image kernel: a wavefront takes 64/gpr image rows per pass
@@ -46,15 +48,18 @@ template <int C> __global__ __launch_bounds__(C1WG_THREADS) void conv1_wgrad_ima
     const bool lane_on = lr < rpp;
     constexpr int NW = C1WG_THREADS / 64;
     const int nvec = a.P1 * 4;                                    // 16-byte vectors in one sample's [P1][32]
+    const int nks = (a.P1 + 15) >> 4;                             // matrix-instruction steps per sample and group
     uint32_t raw[C1WG_PASSES];
     bf16x8 dyr[C1WG_DYV];
-    auto fetch = [&](int b) {
-        const uint8_t *src = a.obs + (long long)(a.index ? a.index[b] : b) * rows * a.W + 4 * xg;
+    auto fetch_image = [&](int b, int cg) {
+        const uint8_t *src = a.obs + ((long long)(a.index ? a.index[b] : b) * C + 4 * cg) * a.H * a.W + 4 * xg;
 #pragma unroll
         for (int i = 0; i < C1WG_PASSES; ++i) {
             const int row = (w + i * NW) * rpp + lr;
             if (lane_on && row < rows) raw[i] = *reinterpret_cast<const uint32_t *>(src + row * a.W);
         }
+    };
+    auto fetch_dy = [&](int b) {
         const bf16_t *dsrc = a.dy + (long long)b * a.P1 * 32;
 #pragma unroll
         for (int i = 0; i < C1WG_DYV; ++i) {
@@ -78,74 +83,94 @@ template <int C> __global__ __launch_bounds__(C1WG_THREADS) void conv1_wgrad_ima
     bf16x8 ones;                                                  // bias column: 255 in column 0 of the tile
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = from_f32<bf16_t>((lane & 31) == 0 ? 255.0f : 0.0f);
-    f32x16 acc, accb;
+    f32x16 acc[NG], accb;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { acc[r] = 0.0f; accb[r] = 0.0f; }
+    for (int r = 0; r < 16; ++r) {
+        accb[r] = 0.0f;
+#pragma unroll
+        for (int cg = 0; cg < NG; ++cg) acc[cg][r] = 0.0f;
+    }
     const int step_wrap = 64 + 4 * Wp - 4 * a.W1;                 // image offset from position m to m+16 across a row end
+    // positions m = 16 ks + 8 kg + jj (first read) and m + 4 (second read), walked incrementally (W1 >= 16); the
+    // padding positions of the last step (their gradient rows are zero) read position 0
+    const int ma0 = 8 * kg + jj, mb0 = ma0 + 4;
+    const int oya0 = a.dW1.div(ma0), oxa0 = ma0 - oya0 * a.W1, oyb0 = a.dW1.div(mb0), oxb0 = mb0 - oyb0 * a.W1;
+    const int offa0 = lane_img + 4 * oya0 * Wp + 4 * oxa0, offb0 = lane_img + 4 * oyb0 * Wp + 4 * oxb0;
+    // zero rows behind the sample's gradient (written once: the copies below never touch them)
+    for (int v = nvec + tid; v < nks * 64; v += C1WG_THREADS) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = zero_vec<bf16_t, 8>();
 
-    if ((int)blockIdx.x < a.B) fetch(blockIdx.x);
+    if ((int)blockIdx.x < a.B) { fetch_image(blockIdx.x, 0); fetch_dy(blockIdx.x); }
     for (int b = blockIdx.x; b < a.B; b += gridDim.x) {
 #pragma unroll
-        for (int i = 0; i < C1WG_PASSES; ++i) {
-            const int row = (w + i * NW) * rpp + lr;
-            if (!lane_on || row >= rows) continue;
-            Vec<bf16_t, 4> px;
+        for (int cg = 0; cg < NG; ++cg) {
+            if (cg > 0) __syncthreads();      // the previous group's image has been read
 #pragma unroll
-            for (int e = 0; e < 4; ++e) px[e] = from_f32<bf16_t>((float)((raw[i] >> (8 * e)) & 0xFFu));
-            *reinterpret_cast<Vec<bf16_t, 4> *>(img + row * Wp + 4 * xg) = px;
-        }
+            for (int i = 0; i < C1WG_PASSES; ++i) {
+                const int row = (w + i * NW) * rpp + lr;
+                if (!lane_on || row >= rows) continue;
+                Vec<bf16_t, 4> px;
 #pragma unroll
-        for (int i = 0; i < C1WG_DYV; ++i) {
-            const int v = tid + i * C1WG_THREADS;
-            if (v < nvec) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
-        }
-        __syncthreads();
-        if (b + (int)gridDim.x < a.B) fetch(b + gridDim.x);      // the next sample travels while this one is multiplied
-        // positions m = 16 ks + 8 kg + jj (first read) and m + 4 (second read), walked incrementally (W1 >= 16)
-        int oya = a.dW1.div(8 * kg + jj), oxa = 8 * kg + jj - oya * a.W1;
-        int oyb = a.dW1.div(8 * kg + jj + 4), oxb = 8 * kg + jj + 4 - oyb * a.W1;
-        int offa = lane_img + 4 * oya * Wp + 4 * oxa, offb = lane_img + 4 * oyb * Wp + 4 * oxb;
-        const bf16_t *ap = a_lane;
-        const int nks = a.P1 >> 4;
-        // Software pipeline: the four reads of step k+1 are issued before the matrix instruction of step k (the
-        // transposing reads are not moved by the compiler).  Two straight-line bodies (with / without the bias
-        // column); whole groups of 5 steps are written out.
-        auto walk = [&](auto with_bias) {
-            i16x4 ra0, ra1, rb0, rb1;
-            auto read = [&]() {
-                ra0 = tr4(ap); ra1 = tr4(ap + 4 * 32); rb0 = tr4(img + offa); rb1 = tr4(img + offb);
-                ap += 16 * 32;
-                oxa += 16; { const bool wr = oxa >= a.W1; oxa -= wr ? a.W1 : 0; offa += wr ? step_wrap : 64; }
-                oxb += 16; { const bool wr = oxb >= a.W1; oxb -= wr ? a.W1 : 0; offb += wr ? step_wrap : 64; }
-            };
-            auto mult = [&](const bf16x8 av, const bf16x8 bv) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
-                if constexpr (decltype(with_bias)::value) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, ones, accb, 0, 0, 0);
-            };
-            read();                                        // step 0 (P1 >= 16)
-            int ks = 0;
-            for (; ks + 5 < nks; ks += 5) {                // steps ks..ks+4; step ks+5 exists and is read in the last turn
+                for (int e = 0; e < 4; ++e) px[e] = from_f32<bf16_t>((float)((raw[i] >> (8 * e)) & 0xFFu));
+                *reinterpret_cast<Vec<bf16_t, 4> *>(img + row * Wp + 4 * xg) = px;
+            }
+            if (cg == 0) {
 #pragma unroll
-                for (int u = 0; u < 5; ++u) {
-                    const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
-                    read();
-                    __builtin_amdgcn_sched_barrier(0);     // keep the reads of the next step ahead of this step's product
-                    mult(av, bv);
+                for (int i = 0; i < C1WG_DYV; ++i) {
+                    const int v = tid + i * C1WG_THREADS;
+                    if (v < nvec) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
                 }
             }
-            for (; ks < nks; ++ks) {
-                const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
-                if (ks + 1 < nks) read();
-                mult(av, bv);
-            }
-        };
-        if (w == 0) walk(std::true_type{}); else walk(std::false_type{});
+            __syncthreads();
+            // the next image (and, with it, the next sample's gradient) travels while this one is multiplied
+            if (cg + 1 < NG) fetch_image(b, cg + 1);
+            else if (b + (int)gridDim.x < a.B) { fetch_image(b + gridDim.x, 0); fetch_dy(b + gridDim.x); }
+
+            int oxa = oxa0, oxb = oxb0, offa = offa0, offb = offb0;
+            const bf16_t *ap = a_lane;
+            // Software pipeline: the four reads of step k+1 are issued before the matrix instruction of step k (the
+            // transposing reads are not moved by the compiler).  Two straight-line bodies (with / without the bias
+            // column); whole groups of 5 steps are written out.
+            auto walk = [&](auto with_bias) {
+                i16x4 ra0, ra1, rb0, rb1;
+                auto read = [&](int m0) {                      // m0: first position of the step
+                    const bool pa = !PADDED || m0 + ma0 < a.P1, pb = !PADDED || m0 + mb0 < a.P1;
+                    ra0 = tr4(ap); ra1 = tr4(ap + 4 * 32); rb0 = tr4(img + (pa ? offa : lane_img)); rb1 = tr4(img + (pb ? offb : lane_img));
+                    ap += 16 * 32;
+                    oxa += 16; { const bool wr = oxa >= a.W1; oxa -= wr ? a.W1 : 0; offa += wr ? step_wrap : 64; }
+                    oxb += 16; { const bool wr = oxb >= a.W1; oxb -= wr ? a.W1 : 0; offb += wr ? step_wrap : 64; }
+                };
+                auto mult = [&](const bf16x8 av, const bf16x8 bv) {
+                    acc[cg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[cg], 0, 0, 0);
+                    if constexpr (decltype(with_bias)::value) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, ones, accb, 0, 0, 0);
+                };
+                read(0);
+                int ks = 0;
+                for (; ks + 5 < nks; ks += 5) {                // steps ks..ks+4; step ks+5 exists and is read in the last turn
+#pragma unroll
+                    for (int u = 0; u < 5; ++u) {
+                        const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
+                        read(16 * (ks + u + 1));
+                        __builtin_amdgcn_sched_barrier(0);     // keep the reads of the next step ahead of this step's product
+                        mult(av, bv);
+                    }
+                }
+                for (; ks < nks; ++ks) {
+                    const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
+                    if (ks + 1 < nks) read(16 * (ks + 1));
+                    mult(av, bv);
+                }
+            };
+            if (w == 0 && cg == 0) walk(std::true_type{}); else walk(std::false_type{});
+        }
         __syncthreads();          // image and gradient are overwritten by the next sample
     }
     // accumulator register r of lane l is D[n = 8(r/4) + 4(l/32) + r%4][column l%32]
-    float *dst = a.part + (long long)blockIdx.x * 32 * a.N + w * 32 + (lane & 31);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) dst[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = acc[r];
+    for (int cg = 0; cg < NG; ++cg) {
+        float *dst = a.part + (long long)blockIdx.x * 32 * a.N + cg * 256 + w * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dst[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = acc[cg][r];
+    }
     if (w == 0 && (lane & 31) == 0) {
         float *bd = a.part + (long long)blockIdx.x * 32 * a.N + 64 * C;
 #pragma unroll
@@ -153,13 +178,19 @@ template <int C> __global__ __launch_bounds__(C1WG_THREADS) void conv1_wgrad_ima
     }
 }
 
+static size_t conv1_wgrad_image_lds(const Geom &g)
+{
+    return (((size_t)4 * g.H * g.W + 7) & ~(size_t)7) * 2 + (size_t)((g.P1 + 15) / 16) * 16 * 64;
+}
+
 // true if the frame shape and pointers fit conv1_wgrad_image_kernel
 static bool conv1_wgrad_image_fits(const Geom &g, const uint8_t *obs)
 {
-    if (g.C != 4 || g.W > 256 || (g.W & 3) || (((uintptr_t)obs) & 3u) || g.W1 < 16 || (g.P1 & 15)) return false;
-    const int gpr = g.W / 4, rpp = 64 / gpr, rows = g.C * g.H;
-    const size_t lds = (((size_t)rows * g.W + 7) & ~(size_t)7) * 2 + (size_t)g.P1 * 64;
-    return rows <= C1WG_PASSES * rpp * (C1WG_THREADS / 64) && g.P1 * 4 <= C1WG_DYV * C1WG_THREADS && lds <= 160 * 1024;
+    if ((g.C != 4 && g.C != 8 && g.C != 12 && g.C != 16) || g.W > 256 || (g.W & 3) || (((uintptr_t)obs) & 3u) || g.W1 < 16 || g.P1 < 16)
+        return false;
+    const int gpr = g.W / 4, rpp = 64 / gpr, rows = 4 * g.H;
+    return rows <= C1WG_PASSES * rpp * (C1WG_THREADS / 64) && g.P1 * 4 <= C1WG_DYV * C1WG_THREADS &&
+           conv1_wgrad_image_lds(g) <= 160 * 1024;
 }
 
 // nz: number of workgroups = number of partials written (at most max_parts)
@@ -171,14 +202,19 @@ static hipError_t launch_conv1_wgrad_image(Ctx &c, const uint8_t *obs, const int
     a.obs = obs; a.index = index; a.dy = (const bf16_t *)c.ws.dy1; a.part = part;
     a.B = B; a.H = g.H; a.W = g.W; a.W1 = g.W1; a.P1 = g.P1; a.N = g.K1 + 1;
     a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
-    const size_t lds = (((size_t)g.C * g.H * g.W + 7) & ~(size_t)7) * 2 + (size_t)g.P1 * 64;
-    auto kern = conv1_wgrad_image_kernel<4>;
-    static bool attr_set = false;       // raise the dynamic-LDS limit once
-    if (!attr_set) {
+    const size_t lds = conv1_wgrad_image_lds(g);
+    const bool padded = (g.P1 & 15) != 0;
+    void (*kern)(const Conv1WgImgArgs);
+    if (padded) kern = g.C == 4 ? conv1_wgrad_image_kernel<1, true> : g.C == 8 ? conv1_wgrad_image_kernel<2, true>
+                       : g.C == 12 ? conv1_wgrad_image_kernel<3, true> : conv1_wgrad_image_kernel<4, true>;
+    else kern = g.C == 4 ? conv1_wgrad_image_kernel<1, false> : g.C == 8 ? conv1_wgrad_image_kernel<2, false>
+                : g.C == 12 ? conv1_wgrad_image_kernel<3, false> : conv1_wgrad_image_kernel<4, false>;
+    static bool attr_set[8] = {};       // raise the dynamic-LDS limit once per instantiation
+    if (!attr_set[g.C / 4 - 1 + (padded ? 4 : 0)]) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[g.C / 4 - 1 + (padded ? 4 : 0)] = true;
     }
     const int grid = B < max_parts ? B : max_parts;
     *nz = grid;
