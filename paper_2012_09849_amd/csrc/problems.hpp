@@ -83,6 +83,7 @@ template <typename T_> struct Conv1Fwd {
     static constexpr int VA = 8, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 64;       // forward sums are segmented so every kernel variant returns the same bits
+    static constexpr int STAGES = sizeof(T) == 2 ? 2 : 1;     // bf16: two k-tiles of loads in flight (16x72x96 frames: 169 -> 147 us at B = 2048)
     typedef PtrCtx<uint8_t> CtxA;
     typedef PtrCtx<T> CtxB;
     int M, N, K, klen;
