@@ -100,6 +100,7 @@ void carve(Ctx &c, Carver &cv)
         w.part_elems = bound((long long)ml * g.P3, MAXZ3) * 64 * 577 + bound((long long)ml * g.P2, MAXZ2) * 64 * 513 +
                        bound((long long)ml * g.P1, MAXZ1) * 32 * (size_t)(g.K1 + 1);
         cv.take(w.part, w.part_elems * 4);
+        cv.take(w.heads_part, (size_t)HEADS_MAXZ * (g.A + 1) * 513 * 4);
     }
 }
 }  // namespace

@@ -241,14 +241,24 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         *spg = s;
         return (nseg + s - 1) / s;
     };
-    {   // heads: pi.w, pi.b, v.w, v.b
+    // heads: pi.w, pi.b, v.w, v.b.  A tiny output and a reduction over the whole minibatch: beyond 512 rows it is cut
+    // into groups of 16 segments (one round of the 16 wavefronts) whose partials join the conv layers' reduction.
+    int nzh = 0;
+    {
         HeadsWgrad p;
         p.M = g.A + 1; p.N = 513; p.K = B; p.klen = B;
-        p.dz = c.ws.dz; p.h = c.ws.h; p.g = grads; p.A = g.A;
+        p.dz = c.ws.dz; p.h = c.ws.h; p.g = grads; p.A = g.A; p.part = nullptr;
         p.piw = g.piw; p.pib = g.pib; p.vw = g.vw; p.vb = g.vb;
+        const int nseg = (B + 31) / 32;
+        int spg = 1 << 30;
+        if (nseg > 16) {
+            spg = 16 * ((nseg + 16 * HEADS_MAXZ - 1) / (16 * HEADS_MAXZ));      // whole rounds, at most HEADS_MAXZ groups
+            nzh = (nseg + spg - 1) / spg;
+            p.part = c.ws.heads_part;
+        }
         {
-            SiteTimer tm(c, SITE_HEADS_WGRAD);        // tiny output, long reduction: 16 wavefronts share each tile
-            e = launch_wsgemm<HeadsWgrad, 16, 32, false>(p, c.stream);
+            SiteTimer tm(c, SITE_HEADS_WGRAD);        // 16 wavefronts share each tile
+            e = launch_wsgemm<HeadsWgrad, 16, 32, false>(p, c.stream, spg);
         }
         if (e != hipSuccess) return e;
     }
@@ -353,10 +363,13 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
         else e = index ? conv1_wgrad(Conv1Wgrad<T, true>{}) : conv1_wgrad(Conv1Wgrad<T, false>{});
         if (e != hipSuccess) return e;
     }
-    const ReduceSpec specs[3] = {
-        {part3, nz3, 64, 577, 64, 3, true, 1.0f, g.w3, g.b3},
-        {part2, nz2, 64, 513, 32, 4, true, 1.0f, g.w2, g.b2},
-        {part1, nz1, 32, g.K1 + 1, g.C, 8, false, 1.0f / 255.0f, g.w1, g.b1}};
+    const long long hstride = (long long)(g.A + 1) * 513;
+    const ReduceSpec specs[REDUCE_JOBS] = {
+        {part3, nz3, 64, 577, 64, 3, 0, true, 1.0f, g.w3, g.b3},
+        {part2, nz2, 64, 513, 32, 4, 0, true, 1.0f, g.w2, g.b2},
+        {part1, nz1, 32, g.K1 + 1, g.C, 8, 0, false, 1.0f / 255.0f, g.w1, g.b1},
+        {c.ws.heads_part, nzh, g.A, 513, 1, 1, hstride, false, 1.0f, g.piw, g.pib},
+        {c.ws.heads_part + (long long)g.A * 513, nzh, 1, 513, 1, 1, hstride, false, 1.0f, g.vw, g.vb}};
     if ((e = launch_wgrad_reduce(c, specs, grads)) != hipSuccess) return e;
     return hipSuccess;
 }

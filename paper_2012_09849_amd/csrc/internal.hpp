@@ -32,6 +32,7 @@ struct Workspace {
     float *fc_part;           // [fc_groups][B][512] partial sums of the FC layer, one per group of FC_GROUP_K inputs
     // backward
     float *dz, *dh, *terms, *grads, *part, *norm_part, *clip;   // clip[0] = scale, clip[1] = ||g||
+    float *heads_part;        // [HEADS_MAXZ][A+1][513] partials of the heads weight gradient (large minibatches)
     void *dy3, *dy2, *dy1;    // T
     size_t part_elems;
 };
@@ -117,12 +118,15 @@ hipError_t launch_heads_learn(Ctx &c, const LossArgs &la, int B);
 hipError_t launch_stats(Ctx &c, int B, hts_stats *stats);
 struct ReduceSpec {       // one layer's split weight gradient: part[nz][rows][ncol] -> g (see wgrad_reduce_kernel)
     const float *part;
-    int nz, rows, ncol, cin, ksz;
+    int nz, rows, ncol, cin, ksz;     // nz = 0: nothing to do
+    long long zstride;                // elements between consecutive partials (0: rows * ncol)
     bool taps_outer;
     float scale;
     long long w_off, b_off;
 };
-hipError_t launch_wgrad_reduce(Ctx &c, const ReduceSpec (&spec)[3], float *g);
+constexpr int REDUCE_JOBS = 5;
+hipError_t launch_wgrad_reduce(Ctx &c, const ReduceSpec (&spec)[REDUCE_JOBS], float *g);
+constexpr int HEADS_MAXZ = 16;      // most chunks the heads weight gradient's reduction over the batch is cut into
 hipError_t launch_gae(Ctx *c, hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
                       int N, float *adv, float *ret);
 hipError_t launch_normalize(Ctx *c, hipStream_t s, float *adv, long long n);

@@ -490,21 +490,24 @@ hipError_t launch_stats(Ctx &c, int B, hts_stats *stats)
 struct ReduceJob {
     const float *part;
     int nz, rows, ncol, cin, ksz, taps_outer, first_block;
+    long long zstride;
     float scale;
     long long w_off, b_off;
 };
-struct ReduceArgs { ReduceJob job[3]; float *g; };
+struct ReduceArgs { ReduceJob job[REDUCE_JOBS]; float *g; };
 
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceArgs a)
 {
     __shared__ float red[8][33];
     const int blk = blockIdx.x;
-    const int jn = blk >= a.job[2].first_block ? 2 : (blk >= a.job[1].first_block ? 1 : 0);
+    int jn = 0;
+#pragma unroll
+    for (int t = 1; t < REDUCE_JOBS; ++t) jn = blk >= a.job[t].first_block ? t : jn;       // first_block is non-decreasing
     const ReduceJob &jb = a.job[jn];
     const int e = threadIdx.x & 31, q = threadIdx.x >> 5;
     const int n_el = jb.rows * jb.ncol;
     const int i = (blk - jb.first_block) * 32 + e;
-    const long long zs = (long long)n_el;
+    const long long zs = jb.zstride;
     const int chunk = (jb.nz + 7) / 8;
     int z = q * chunk;
     const int z1 = min(jb.nz, z + chunk);
@@ -538,18 +541,19 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const ReduceArgs a)
     a.g[jb.w_off + dst] = tot;
 }
 
-hipError_t launch_wgrad_reduce(Ctx &c, const ReduceSpec (&spec)[3], float *g)
+hipError_t launch_wgrad_reduce(Ctx &c, const ReduceSpec (&spec)[REDUCE_JOBS], float *g)
 {
     SiteTimer tm(c, SITE_WGRAD_REDUCE);
     ReduceArgs a;
     int blocks = 0;
-    for (int j = 0; j < 3; ++j) {
+    for (int j = 0; j < REDUCE_JOBS; ++j) {
         const ReduceSpec &sp = spec[j];
         ReduceJob &jb = a.job[j];
         jb.part = sp.part; jb.nz = sp.nz; jb.rows = sp.rows; jb.ncol = sp.ncol; jb.cin = sp.cin; jb.ksz = sp.ksz;
         jb.taps_outer = sp.taps_outer ? 1 : 0; jb.scale = sp.scale; jb.w_off = sp.w_off; jb.b_off = sp.b_off;
+        jb.zstride = sp.zstride ? sp.zstride : (long long)sp.rows * sp.ncol;
         jb.first_block = blocks;
-        blocks += (sp.rows * sp.ncol + 31) / 32;
+        if (sp.nz > 0) blocks += (sp.rows * sp.ncol + 31) / 32;
     }
     a.g = g;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(blocks), dim3(256), 0, c.stream, a);

@@ -224,6 +224,7 @@ struct HeadsWgrad {
     int M, N, K, klen;     // M = A+1, N = 513, K = B
     const float *dz, *h;
     float *g;
+    float *part;           // not null: the reduction is cut into groups, group z writes part[z][M][513]
     int A;
     long long piw, pib, vw, vb;
     HTS_HD CtxA ctx_a(int j) const { return {j}; }
@@ -243,8 +244,9 @@ struct HeadsWgrad {
         v[0] = (b < kend && c.kk == 512) ? 1.0f : v[0];
         return v;
     }
-    HTS_HD void store(int j, int kk, float acc, int) const
+    HTS_HD void store(int j, int kk, float acc, int z) const
     {
+        if (part) { part[((long long)z * M + j) * 513 + kk] = acc; return; }
         if (j < A) { if (kk < 512) g[piw + (long long)j * 512 + kk] = acc; else g[pib + j] = acc; }
         else       { if (kk < 512) g[vw + kk] = acc; else g[vb] = acc; }
     }
