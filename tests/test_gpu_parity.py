@@ -95,7 +95,8 @@ def test_sampler_bit_exact(hts, oracle, A):
 @pytest.mark.parametrize("T,N,gamma,lam", [(5, 4, 0.99, 1.0), (5, 16, 0.99, 1.0), (128, 32, 0.99, 0.95),
                                            (512, 16, 0.993, 0.95), (1, 1, 0.9, 0.9), (7, 65, 0.99, 0.95),
                                            (33, 1000, 0.99, 0.95), (128, 4096, 0.99, 0.95),
-                                           (40, 70001, 0.99, 0.95), (17, 20000, 0.99, 0.95)])   # plain / chunked
+                                           (40, 70001, 0.99, 0.95), (17, 20000, 0.99, 0.95),    # plain / chunked
+                                           (11, 262144, 0.99, 0.95), (6, 262147, 0.99, 0.95)])   # very wide
 def test_gae_parity(hts, oracle, T, N, gamma, lam):
     ctx = hts.Context(4, 84, 84, 6, max_act_batch=1)
     seed = T * 131 + N
