@@ -147,6 +147,21 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) void imgconv_ke
                 ra[tap] = (r >= 0 ? g * PIN + r : ZR) * IP + 8 * kg;
             }
             const bf16_t *wrow = wl + (CLS * NCOL + lrow) * WP + 8 * kg;
+            const bool store_row = rvalid && g < ng;
+            const long long b = (long long)grp * G + (store_row ? g : 0);
+            // What the epilogue needs from memory (the ReLU masks of the input gradient) is requested now, so that it
+            // travels while the products are formed: fetched after them, every tile would end with a bare memory
+            // round trip.
+            const long long o = (b * S::POUT_ALL + S::out_pos(CLS, yy, xx)) * NCOL + 4 * kg;
+            Vec<bf16_t, 4> mk[TN][4];
+            if constexpr (!S::FWD) {
+                if (store_row) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) mk[j][q] = *reinterpret_cast<const Vec<bf16_t, 4> *>(a.mask + o + j * 32 + 8 * q);
+                }
+            }
             f32x16 acc[TN];
 #pragma unroll
             for (int j = 0; j < TN; ++j)
@@ -154,29 +169,22 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) void imgconv_ke
                 for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
             constexpr int CS = CIN / 16, STEPS = TAPS * CS, SEGS = S::SEGSTEPS;
             static_assert(SEGS == 0 || STEPS % SEGS == 0, "whole segments");
-            // software pipeline over the matrix-instruction steps: the operands of step ks+1 are read before the
-            // products of step ks are issued, and the scheduling barriers keep the reads from drifting further ahead
-            // (all of them at once would not fit the register file)
-            bf16x8 av_next, bv_next[TN];
-            auto read_step = [&](int ks) {
+            // Software pipeline over the matrix-instruction steps: the operands of step ks+PD are read before the
+            // products of step ks are issued (an LDS read takes a few hundred cycles to return when eight wavefronts
+            // read at once, a step's products 32-64), and the scheduling barriers keep the reads from drifting
+            // further ahead (all of them at once would not fit the register file).  The ring of PD operand sets is
+            // indexed at compile time: the step loops are written out.
+            constexpr int PD = 3;
+            static_assert(STEPS >= PD && (SEGS == 0 || SEGS % PD == 0), "pipeline depth");
+            bf16x8 av_q[PD], bv_q[PD][TN];
+            auto read_step = [&](int ks, int slot) {              // both compile-time constants after unrolling
                 const int tap = ks / CS, cs = ks % CS;
-                av_next = *reinterpret_cast<const bf16x8 *>(inl + ra[tap] + cs * 16);
+                av_q[slot] = *reinterpret_cast<const bf16x8 *>(inl + ra[tap] + cs * 16);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bv_next[j] = *reinterpret_cast<const bf16x8 *>(wrow + j * 32 * WP + tap * CIN + cs * 16);
+                for (int j = 0; j < TN; ++j) bv_q[slot][j] = *reinterpret_cast<const bf16x8 *>(wrow + j * 32 * WP + tap * CIN + cs * 16);
             };
-            read_step(0);
-            auto step = [&](int ks, f32x16 (&tgt)[TN]) {
-                const bf16x8 av = av_next;
-                bf16x8 bv[TN];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bv[j] = bv_next[j];
-                if (ks + 1 < STEPS) read_step(ks + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                // the weights are the first operand: a lane's accumulator registers are 16 output columns of ONE row
-#pragma unroll
-                for (int j = 0; j < TN; ++j) tgt[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av, tgt[j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            };
+            for (int q = 0; q < PD; ++q) read_step(q, q);
             if constexpr (SEGS > 0) {
                 // Forward: a fresh accumulator per segment, added in order.  The segment loop is a real loop (written
                 // out, the compiler moves all the additions to the end and runs out of registers); its step index
@@ -184,11 +192,11 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) void imgconv_ke
                 // a run-time index into registers.
                 static_assert(S::FWD, "segments are a forward-pass matter");
                 const int ra0 = ra[0];
-                auto read_rt = [&](int ks) {
+                auto read_rt = [&](int ks, int slot) {            // ks: run-time, wavefront-uniform
                     const int tap = ks / CS, cs = ks % CS;
-                    av_next = *reinterpret_cast<const bf16x8 *>(inl + ra0 + (S::in_row(0, 0, 0, tap) - S::in_row(0, 0, 0, 0)) * IP + cs * 16);
+                    av_q[slot] = *reinterpret_cast<const bf16x8 *>(inl + ra0 + (S::in_row(0, 0, 0, tap) - S::in_row(0, 0, 0, 0)) * IP + cs * 16);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) bv_next[j] = *reinterpret_cast<const bf16x8 *>(wrow + j * 32 * WP + ks * 16);
+                    for (int j = 0; j < TN; ++j) bv_q[slot][j] = *reinterpret_cast<const bf16x8 *>(wrow + j * 32 * WP + ks * 16);
                 };
 #pragma unroll 1
                 for (int sg = 0; sg < STEPS / SEGS; ++sg) {
@@ -199,11 +207,11 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) void imgconv_ke
                         for (int r = 0; r < 16; ++r) sacc[j][r] = 0.0f;
 #pragma unroll
                     for (int u = 0; u < SEGS; ++u) {
-                        const bf16x8 av = av_next;
+                        const bf16x8 av = av_q[u % PD];
                         bf16x8 bv[TN];
 #pragma unroll
-                        for (int j = 0; j < TN; ++j) bv[j] = bv_next[j];
-                        read_rt(min(sg * SEGS + u + 1, STEPS - 1));          // (the last step reads itself again)
+                        for (int j = 0; j < TN; ++j) bv[j] = bv_q[u % PD][j];
+                        read_rt(min(sg * SEGS + u + PD, STEPS - 1), u % PD);     // (past the end: the last step again)
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                         for (int j = 0; j < TN; ++j) sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av, sacc[j], 0, 0, 0);
@@ -216,10 +224,20 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) void imgconv_ke
                 }
             } else {
 #pragma unroll
-                for (int ks = 0; ks < STEPS; ++ks) step(ks, acc);
+                for (int ks = 0; ks < STEPS; ++ks) {
+                    const bf16x8 av = av_q[ks % PD];
+                    bf16x8 bv[TN];
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) bv[j] = bv_q[ks % PD][j];
+                    if (ks + PD < STEPS) read_step(ks + PD, ks % PD);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // the weights are the first operand: a lane's accumulator registers are 16 output columns of ONE row
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av, acc[j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            if (!(rvalid && g < ng)) return;
-            const long long b = (long long)grp * G + g;
+            if (!store_row) return;
             // register 4q+e of accumulator j is column j*32 + 8q + 4kg + e
             if constexpr (S::FWD) {
                 const long long m = b * S::POUT_ALL + p;
@@ -239,12 +257,6 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) void imgconv_ke
                         } else *reinterpret_cast<Vec<bf16_t, 4> *>(a.out + m * NCOL + ch) = y;
                     }
             } else {
-                const long long o = (b * S::POUT_ALL + S::out_pos(CLS, yy, xx)) * NCOL + 4 * kg;
-                Vec<bf16_t, 4> mk[TN][4];                                     // all masks first, then the stores
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) mk[j][q] = *reinterpret_cast<const Vec<bf16_t, 4> *>(a.mask + o + j * 32 + 8 * q);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
