@@ -229,6 +229,26 @@ template <class P, class C> HTS_HD void do_store(const P &p, int m, int n, float
     }
 }
 
+// Epilogue inputs of a "lane owns a row" problem (row contexts, and what pre4() fetches: bias, ReLU masks).  They
+// are requested BEFORE the k loop and held in registers, so that they travel while the products are formed; fetched
+// after the loop, every workgroup would end with a bare memory round trip.
+template <class P> HTS_HD auto epi_row(const P &p, int mr, int zb)
+{
+    if constexpr (HasBatch<P>::value) return p.row(mr, zb); else return p.row(mr);
+}
+// (A problem whose pre4() only reads a few hot bytes -- a bias -- opts out with `static constexpr bool
+// EPI_INPUTS_EARLY = false`: its registers are better left to the k loop, and the fetch then precedes the stores.)
+template <class P, class = void> struct EpiEarly : std::true_type {};
+template <class P> struct EpiEarly<P, std::void_t<decltype(P::EPI_INPUTS_EARLY)>> : std::integral_constant<bool, P::EPI_INPUTS_EARLY> {};
+template <class P, int TM, int TN, bool SWAP> struct EpiInputs {};
+template <class P, int TM, int TN> struct EpiInputs<P, TM, TN, true> {
+    using RowT = decltype(epi_row(std::declval<const P &>(), 0, 0));
+    using PreT = decltype(std::declval<const P &>().pre4(std::declval<const RowT &>(), 0));
+    RowT rc[TM];
+    PreT pre[TM][TN][4];
+    bool mok[TM];
+};
+
 // A problem type P provides:
 //   using T                          operand type in LDS / MFMA (float or bf16_t)
 //   static constexpr int BM, BN, BK  workgroup tile; WAVES_M x WAVES_N wavefronts (64 lanes each) share it
@@ -482,6 +502,23 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (kbeg + s * BK < kend) gload(kbeg + s * BK, rra[s], rrb[s], kend);
+    EpiInputs<P, TM, TN, SWAP> epi;
+    auto fetch_epi = [&]() {
+        if constexpr (SWAP) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + (wm * TM + i) * 32 + lrow;
+                epi.mok[i] = m < M;
+                epi.rc[i] = epi_row(p, epi.mok[i] ? m : M - 1, zb);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        epi.pre[i][j][g] = p.pre4(epi.rc[i], min(n0 + (wn * TN + j) * 32 + 8 * g + 4 * lk, p.N - 4));
+            }
+        }
+    };
+    if constexpr (SWAP && EpiEarly<P>::value) fetch_epi();
     if constexpr (D > 1 || (SEG == 0 && SteadyOf<P>::value)) {
         // the k loop is unrolled by the depth so that every stage has its own registers; whole groups of steps
         // refill unconditionally
@@ -553,27 +590,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     auto epilogue = [&](auto full_tile) {
         constexpr bool FULL = decltype(full_tile)::value;
         if constexpr (SWAP) {
-            // two passes: everything the stores need from memory (bias, ReLU masks) is fetched first, so those loads
-            // travel together instead of each waiting behind the store before it
-            auto row_of = [&](int mr) { if constexpr (HasBatch<P>::value) return p.row(mr, zb); else return p.row(mr); };
-            using RowT = decltype(row_of(0));
-            using PreT = decltype(p.pre4(std::declval<const RowT &>(), 0));
-            RowT rc[TM];
-            PreT pre[TM][TN][4];
-            bool mok[TM];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = m0 + (wm * TM + i) * 32 + lrow;
-                mok[i] = FULL || m < M;
-                rc[i] = row_of(mok[i] ? m : M - 1);
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = n0 + (wn * TN + j) * 32 + 8 * g + 4 * lk;
-                        pre[i][j][g] = p.pre4(rc[i], FULL ? n : min(n, p.N - 4));
-                    }
-            }
+            if constexpr (!EpiEarly<P>::value) fetch_epi();
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -582,9 +599,9 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
                     for (int g = 0; g < 4; ++g) {
                         const int n = n0 + (wn * TN + j) * 32 + 8 * g + 4 * lk;
                         const float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        if (FULL || (mok[i] && n < p.N)) {
-                            if constexpr (HasBatch<P>::value) p.store4(rc[i], n, v, z, zb, pre[i][j][g]);
-                            else p.store4(rc[i], n, v, z, pre[i][j][g]);
+                        if (FULL || (epi.mok[i] && n < p.N)) {
+                            if constexpr (HasBatch<P>::value) p.store4(epi.rc[i], n, v, z, zb, epi.pre[i][j][g]);
+                            else p.store4(epi.rc[i], n, v, z, epi.pre[i][j][g]);
                         }
                     }
         } else {

@@ -154,6 +154,7 @@ template <typename T_, class L, bool FLAT_OUT> struct ConvFwd {
     // tile kernel, flattened output (conv3): a lane owns an output position, so the (sample, position) split of the
     // row index is done once per lane instead of once per element (the plain layout measured no faster that way)
     static constexpr bool LANE_OWNS_ROW = FLAT_OUT;
+    static constexpr bool EPI_INPUTS_EARLY = false;      // pre4() is the bias: hot in L1, not worth registers during the k loop
     struct Row { long long o; long long o2; };
     HTS_HD Row row(int m) const
     {
