@@ -229,6 +229,18 @@ template <class P, class C> HTS_HD void do_store(const P &p, int m, int n, float
     }
 }
 
+// Optional element-wise form of the same idea for the wave-per-segment kernel: `Pre1 pre1(int m, int n[, int batch])`
+// fetches what one output element's store needs (its address, a ReLU mask) and `store1(const Pre1 &, float acc)`
+// finishes; pre1() is called at kernel start, store1() when the sums are ready.
+template <class P, class = void> struct HasPre1 : std::false_type {};
+template <class P> struct HasPre1<P, std::void_t<decltype(&P::store1)>> : std::true_type {};
+template <class P, bool> struct Pre1Type { typedef int type; };
+template <class P> struct Pre1Type<P, true> { typedef typename P::Pre1 type; };
+template <class P> HTS_HD auto epi_pre1(const P &p, int m, int n, int zb)
+{
+    if constexpr (HasBatch<P>::value) return p.pre1(m, n, zb); else return p.pre1(m, n);
+}
+
 // Epilogue inputs of a "lane owns a row" problem (row contexts, and what pre4() fetches: bias, ReLU masks).  They
 // are requested BEFORE the k loop and held in registers, so that they travel while the products are formed; fetched
 // after the loop, every workgroup would end with a bare memory round trip.

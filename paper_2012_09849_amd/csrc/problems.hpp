@@ -325,6 +325,9 @@ template <typename T_> struct FcDgrad {
         const long long o = (long long)b * N + f;
         dy3[o] = from_f32<T>(to_f32(a3n[o]) > 0.0f ? acc : 0.0f);
     }
+    struct Pre1 { long long o; float a; };
+    HTS_HD Pre1 pre1(int b, int f) const { const long long o = (long long)b * N + f; return {o, to_f32(a3n[o])}; }
+    HTS_HD void store1(const Pre1 &q, float acc) const { dy3[q.o] = from_f32<T>(q.a > 0.0f ? acc : 0.0f); }
 };
 
 // ------------------------------------------------------------------------------------------------------------
@@ -429,6 +432,15 @@ template <typename T_, class L> struct ConvDgrad {
         const float a = to_f32(act_in[o]);
         dy_in[o] = from_f32<T>(a > 0.0f ? acc : 0.0f);
     }
+    struct Pre1 { long long o; float a; };
+    HTS_HD Pre1 pre1(int m, int ch, int z) const
+    {
+        const Cls c = cls(z);
+        const int b = c.dHW.div(m), p = m - b * (c.Hc * c.Wc), yy = c.dW.div(p), xx = p - yy * c.Wc;
+        const long long o = ((((long long)b * Hin + yy * L::STRIDE + c.py) * Win) + xx * L::STRIDE + c.px) * N + ch;
+        return {o, to_f32(act_in[o])};
+    }
+    HTS_HD void store1(const Pre1 &q, float acc) const { dy_in[q.o] = from_f32<T>(q.a > 0.0f ? acc : 0.0f); }
 };
 
 // ------------------------------------------------------------------------------------------------------------

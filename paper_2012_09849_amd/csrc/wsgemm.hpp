@@ -48,6 +48,8 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
     if (m0 >= M) return;
     const int nseg = (p.K + SEG - 1) / SEG;
     const int lrow = lane & 31, lk = lane >> 5;
+    // per-column epilogue data (bias) is requested now, so that it has arrived when the sums are ready
+    const auto col = make_col(p, min(n0 + lrow, p.N - 1));
 
     // fixed assignment of panel items to lanes; the row part of every gather is resolved once per wavefront
     typename P::CtxA ca[NA];
@@ -192,7 +194,6 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         if (seg >= nseg) return;
         const f32x16 acc = segment_sum(seg);
         const int n = n0 + lrow;
-        const auto col = make_col(p, min(n, p.N - 1));
         if (m0 + 32 <= M && n0 + 32 <= p.N) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) do_store(p, m0 + 8 * (r / 4) + 4 * lk + (r % 4), n, acc[r], seg, zb, col);
@@ -206,6 +207,18 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
     } else {
         constexpr int PER = 1024 / (WAVES * 64);        // tile elements owned by each thread in the fold
         static_assert(PER * WAVES * 64 == 1024, "WAVES must divide 16");
+        // element e of this thread is accumulator register r = e*WAVES + w of lane `lane`.  What its store needs from
+        // memory (a ReLU mask) is requested now; it has arrived when the sums are ready.
+        constexpr bool PRE1 = HasPre1<P>::value;
+        using Pre1T = typename Pre1Type<P, PRE1>::type;
+        Pre1T pre[PER];
+        if constexpr (PRE1) {
+#pragma unroll
+            for (int e = 0; e < PER; ++e) {
+                const int r = e * WAVES + w;
+                pre[e] = epi_pre1(p, min(m0 + 8 * (r / 4) + 4 * lk + (r % 4), M - 1), min(n0 + lrow, p.N - 1), zb);
+            }
+        }
         float total[PER];
 #pragma unroll
         for (int e = 0; e < PER; ++e) total[e] = 0.0f;
@@ -230,19 +243,22 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         }
         // element e of this thread is accumulator register r = e*WAVES + w of lane `lane`: one column per thread
         const int n = n0 + lrow;
-        const auto col = make_col(p, min(n, p.N - 1));
         if (m0 + 32 <= M && n0 + 32 <= p.N) {
 #pragma unroll
             for (int e = 0; e < PER; ++e) {
                 const int r = e * WAVES + w;
-                do_store(p, m0 + 8 * (r / 4) + 4 * lk + (r % 4), n, total[e], (int)blockIdx.y, zb, col);
+                if constexpr (PRE1) p.store1(pre[e], total[e]);
+                else do_store(p, m0 + 8 * (r / 4) + 4 * lk + (r % 4), n, total[e], (int)blockIdx.y, zb, col);
             }
         } else {
 #pragma unroll
             for (int e = 0; e < PER; ++e) {
                 const int r = e * WAVES + w;
                 const int m = m0 + 8 * (r / 4) + 4 * lk + (r % 4);
-                if (m < M && n < p.N) do_store(p, m, n, total[e], (int)blockIdx.y, zb, col);
+                if (m < M && n < p.N) {
+                    if constexpr (PRE1) p.store1(pre[e], total[e]);
+                    else do_store(p, m, n, total[e], (int)blockIdx.y, zb, col);
+                }
             }
         }
     }
