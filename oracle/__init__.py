@@ -40,7 +40,7 @@ class Net(C.Structure):
 class HParams(C.Structure):
     _fields_ = [("algo", C.c_int32), ("clip_eps", C.c_double), ("vf_coef", C.c_double), ("ent_coef", C.c_double),
                 ("max_grad_norm", C.c_double), ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
-                ("adam_eps", C.c_double)]
+                ("adam_eps", C.c_double), ("rho_bar", C.c_double), ("value_clip", C.c_double)]
 
 
 class Stats(C.Structure):
@@ -62,9 +62,10 @@ def make_net(C_in, H, W, A, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=5
 
 
 def make_hparams(algo=0, clip_eps=0.1, vf_coef=0.5, ent_coef=0.01, max_grad_norm=0.0, lr=7e-4, beta1=0.9,
-                 beta2=0.999, adam_eps=1e-5) -> HParams:
-    algo_id = {"a2c": 0, "ppo": 1}.get(algo, algo)
-    return HParams(algo_id, clip_eps, vf_coef, ent_coef, max_grad_norm, lr, beta1, beta2, adam_eps)
+                 beta2=0.999, adam_eps=1e-5, rho_bar=1.0, value_clip=0.0) -> HParams:
+    algo_id = {"a2c": 0, "ppo": 1, "a2c_tis": 2}.get(algo, algo)
+    return HParams(algo_id, clip_eps, vf_coef, ent_coef, max_grad_norm, lr, beta1, beta2, adam_eps, rho_bar,
+                   value_clip)
 
 
 _lib = None
@@ -163,7 +164,7 @@ def normalize_adv(adv):
     return a
 
 
-def _buffer_args(net, obs, index, actions, old_logp, adv, ret):
+def _buffer_args(net, obs, index, actions, old_logp, adv, ret, old_values=None):
     obs = np.ascontiguousarray(obs, dtype=np.uint8).reshape(-1, net.C, net.H, net.W)
     count = obs.shape[0]
     idx = None if index is None else np.ascontiguousarray(index, dtype=np.int32)
@@ -172,17 +173,21 @@ def _buffer_args(net, obs, index, actions, old_logp, adv, ret):
     olp = _f64(old_logp if old_logp is not None else np.zeros(count)).reshape(-1)
     ad, rt = _f64(adv).reshape(-1), _f64(ret).reshape(-1)
     assert act.size == count and olp.size == count and ad.size == count and rt.size == count
-    return obs, idx, B, act, olp, ad, rt
+    olv = None if old_values is None else _f64(old_values).reshape(-1)
+    assert olv is None or olv.size == count
+    return obs, idx, B, act, olp, ad, rt, olv
 
 
-def loss_grads(net: Net, params, obs, actions, old_logp, adv, ret, hp: HParams, index=None, want_grads=True):
-    """-> (grads float64 [P] or None, stats dict)."""
+def loss_grads(net: Net, params, obs, actions, old_logp, adv, ret, hp: HParams, index=None, want_grads=True,
+               old_values=None):
+    """-> (grads float64 [P] or None, stats dict).  old_values is read only when hp.value_clip > 0."""
     p = _f64(params)
-    obs, idx, B, act, olp, ad, rt = _buffer_args(net, obs, index, actions, old_logp, adv, ret)
+    obs, idx, B, act, olp, ad, rt, olv = _buffer_args(net, obs, index, actions, old_logp, adv, ret, old_values)
+    assert hp.value_clip <= 0 or olv is not None
     g = np.empty(p.size) if want_grads else None
     st = Stats()
     rc = lib().orc_loss_grads(C.byref(net), _ptr(p), _ptr(obs), _ptr(idx), C.c_int32(B), _ptr(act), _ptr(olp),
-                              _ptr(ad), _ptr(rt), C.byref(hp), _ptr(g), C.byref(st))
+                              _ptr(olv), _ptr(ad), _ptr(rt), C.byref(hp), _ptr(g), C.byref(st))
     assert rc == 0
     return g, st.as_dict()
 
@@ -201,25 +206,27 @@ def adam(theta, g, m, v, t: int, hp: HParams, gscale: float = 1.0):
     return th, m2, v2
 
 
-def learner_step(net: Net, params, m, v, t: int, obs, actions, old_logp, adv, ret, hp: HParams, index=None):
+def learner_step(net: Net, params, m, v, t: int, obs, actions, old_logp, adv, ret, hp: HParams, index=None,
+                 old_values=None):
     """-> (params, m, v, grads, stats), all new float64 arrays."""
     th, m2, v2 = _f64(params).copy(), _f64(m).copy(), _f64(v).copy()
-    obs, idx, B, act, olp, ad, rt = _buffer_args(net, obs, index, actions, old_logp, adv, ret)
+    obs, idx, B, act, olp, ad, rt, olv = _buffer_args(net, obs, index, actions, old_logp, adv, ret, old_values)
+    assert hp.value_clip <= 0 or olv is not None
     g = np.empty(th.size)
     st = Stats()
     rc = lib().orc_learner_step(C.byref(net), _ptr(th), _ptr(m2), _ptr(v2), C.c_int64(t), _ptr(obs), _ptr(idx),
-                                C.c_int32(B), _ptr(act), _ptr(olp), _ptr(ad), _ptr(rt), C.byref(hp), _ptr(g),
-                                C.byref(st))
+                                C.c_int32(B), _ptr(act), _ptr(olp), _ptr(olv), _ptr(ad), _ptr(rt), C.byref(hp),
+                                _ptr(g), C.byref(st))
     assert rc == 0
     return th, m2, v2, g, st.as_dict()
 
 
 def learner_step_delayed(net: Net, params_behaviour, params_target, m, v, t: int, obs, actions, old_logp, adv, ret,
-                         hp: HParams, index=None):
+                         hp: HParams, index=None, old_values=None):
     """The paper's one-step-delayed update (Sec. 4.1 "Delayed gradient"): the gradient of the objective at the behaviour
     parameters theta_{j-1}, on the storage collected with them, goes through clip + optimiser into the target
     parameters theta_j.  -> (theta_{j+1}, m, v, grads, stats), new float64 arrays."""
-    g, st = loss_grads(net, params_behaviour, obs, actions, old_logp, adv, ret, hp, index=index)
+    g, st = loss_grads(net, params_behaviour, obs, actions, old_logp, adv, ret, hp, index=index, old_values=old_values)
     scale = clip_coef(g, hp.max_grad_norm) if hp.max_grad_norm > 0 else 1.0
     th, m2, v2 = adam(params_target, g, m, v, t, hp, gscale=scale)
     return th, m2, v2, g, st

@@ -25,7 +25,8 @@
  *   orc_loss_grads     Sec. 3 eq. (4) (mini-batch actor-critic estimator with
  *                      entropy bonus) and the squared value loss J_V of the
  *                      "Policy Gradient" paragraph; PPO's clipped surrogate
- *                      for algo = 1.
+ *                      for algo = 1; the truncated importance weights of
+ *                      the appendix's ablation "Delayed Gradient" for algo = 2.
  *   orc_adam, orc_rmsprop, orc_clip_coef, orc_learner_step, orc_normalize_adv
  *                      the optimiser step applied to the estimator above.
  *
@@ -53,9 +54,11 @@ typedef struct {
 } orc_net;
 
 typedef struct {
-    int32_t algo;                 /* 0 = A2C, 1 = PPO                                 */
+    int32_t algo;                 /* 0 = A2C, 1 = PPO, 2 = A2C with truncated importance weights */
     double clip_eps, vf_coef, ent_coef, max_grad_norm;
     double lr, beta1, beta2, adam_eps;
+    double rho_bar;               /* algo 2: truncation level of the importance weight          */
+    double value_clip;            /* > 0: clipped value loss around old_values with this radius */
 } orc_hparams;
 
 typedef struct {
@@ -342,10 +345,15 @@ void orc_normalize_adv(double *adv, int64_t n)
  *   L = L_pi + vf_coef * mean((R - v)^2) - ent_coef * mean(H)
  *   A2C: L_pi = -mean(logp * adv)                                     [eq. (4), sign flipped: a loss]
  *   PPO: L_pi = -mean(min(rho adv, clip(rho, 1-eps, 1+eps) adv)), rho = exp(logp - old_logp)
+ *   truncated importance sampling (one of the two alternatives to the delayed gradient in the appendix's
+ *   ablation "Delayed Gradient"; the paper names it without a formula, the usual form is taken):
+ *        L_pi = -mean(w logp adv), w = min(rho, rho_bar) held constant in the derivative
+ *   value_clip > 0 (old_values required): the value term of a row becomes
+ *        max((v - R)^2, (vc - R)^2), vc = old_v + clip(v - old_v, -value_clip, +value_clip)
  * adv and ret are constants.  grads (may be NULL) receives dL/dparams in the packing of params. */
 int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t *obs, const int32_t *index, int32_t B,
-                       const int32_t *actions, const double *old_logp, const double *adv, const double *ret,
-                       const orc_hparams *hp, double *grads, orc_stats *stats)
+                       const int32_t *actions, const double *old_logp, const double *old_values, const double *adv,
+                       const double *ret, const orc_hparams *hp, double *grads, orc_stats *stats)
 {
     orc_shape s; orc_shapes(n, &s);
     double *params = operand_params(n, &s, params_in);   /* the weights as the passes use them */
@@ -382,6 +390,13 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
         if (hp->algo == 0) {
             sum_pi += -logp * ad;
             dlogp = -ad * invB;
+        } else if (hp->algo == 2) {
+            const double rho = exp(logp - old_logp[row]);
+            const double w = rho < hp->rho_bar ? rho : hp->rho_bar;
+            sum_pi += -w * logp * ad;
+            dlogp = -w * ad * invB;
+            sum_clip += rho > hp->rho_bar ? 1.0 : 0.0;
+            sum_kl += old_logp[row] - logp;
         } else {
             const double rho = exp(logp - old_logp[row]);
             const double lo = 1.0 - hp->clip_eps, hi = 1.0 + hp->clip_eps;
@@ -393,7 +408,19 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
             sum_clip += (rho > hi || rho < lo) ? 1.0 : 0.0;
             sum_kl += old_logp[row] - logp;
         }
-        sum_v += (R - v) * (R - v);
+        double dv_row = 2.0 * (v - R);             /* d(value term of this row)/dv */
+        double v_term = (R - v) * (R - v);
+        if (hp->value_clip > 0.0) {
+            const double d = v - old_values[row];
+            const double dc = d < -hp->value_clip ? -hp->value_clip : (d > hp->value_clip ? hp->value_clip : d);
+            const double vc = old_values[row] + dc;
+            const double c_term = (vc - R) * (vc - R);
+            if (c_term > v_term) {
+                v_term = c_term;
+                dv_row = (dc == d) ? 2.0 * (vc - R) : 0.0;   /* the clipped value does not move with v */
+            }
+        }
+        sum_v += v_term;
         sum_h += ent;
         if (!grads) continue;
 
@@ -401,7 +428,7 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
             const double pj = exp(lp[j]);
             dl[j] = dlogp * ((j == a ? 1.0 : 0.0) - pj) + hp->ent_coef * invB * pj * (lp[j] + ent);
         }
-        const double dv = 2.0 * hp->vf_coef * (v - R) * invB;
+        const double dv = hp->vf_coef * dv_row * invB;
 
         /* heads */
         for (int j = 0; j < Hd; ++j) dh[j] = 0.0;
@@ -519,13 +546,13 @@ void orc_rmsprop(double *theta, const double *g, double *v, int64_t P, double gs
 /* loss + gradient at params, optional global-norm clip, Adam on params.  t is the 1-based step index. */
 int32_t orc_learner_step(const orc_net *n, double *params, double *m, double *v, int64_t t,
                          const uint8_t *obs, const int32_t *index, int32_t B, const int32_t *actions,
-                         const double *old_logp, const double *adv, const double *ret, const orc_hparams *hp,
-                         double *grads_out, orc_stats *stats)
+                         const double *old_logp, const double *old_values, const double *adv, const double *ret,
+                         const orc_hparams *hp, double *grads_out, orc_stats *stats)
 {
     const int64_t P = orc_param_count(n);
     double *g = grads_out ? grads_out : malloc(sizeof(double) * (size_t)P);
     if (!g) return -1;
-    const int32_t rc = orc_loss_grads(n, params, obs, index, B, actions, old_logp, adv, ret, hp, g, stats);
+    const int32_t rc = orc_loss_grads(n, params, obs, index, B, actions, old_logp, old_values, adv, ret, hp, g, stats);
     if (rc == 0) {
         const double sc = orc_clip_coef(g, P, hp->max_grad_norm);
         orc_adam(params, g, m, v, P, t, sc, hp);

@@ -27,7 +27,8 @@ def _torch_forward(p, obs, convs):
     return F.linear(h, p["pi.w"], p["pi.b"]), F.linear(h, p["v.w"], p["v.b"])[:, 0]
 
 
-def _torch_loss(p, obs, convs, actions, old_logp, adv, ret, algo, eps, cv, ce):
+def _torch_loss(p, obs, convs, actions, old_logp, adv, ret, algo, eps, cv, ce, rho_bar=1.0, old_values=None,
+                value_clip=0.0):
     logits, v = _torch_forward(p, obs, convs)
     lsm = F.log_softmax(logits, dim=1)
     logp = lsm.gather(1, torch.from_numpy(actions.astype(np.int64))[:, None])[:, 0]
@@ -35,10 +36,17 @@ def _torch_loss(p, obs, convs, actions, old_logp, adv, ret, algo, eps, cv, ce):
     adv_t, ret_t = torch.from_numpy(adv), torch.from_numpy(ret)
     if algo == 0:
         lpi = -(logp * adv_t).mean()
+    elif algo == 2:
+        w = (logp - torch.from_numpy(old_logp)).exp().clamp(max=rho_bar).detach()
+        lpi = -(w * logp * adv_t).mean()
     else:
         rho = (logp - torch.from_numpy(old_logp)).exp()
         lpi = -torch.minimum(rho * adv_t, rho.clamp(1 - eps, 1 + eps) * adv_t).mean()
-    lv = ((ret_t - v) ** 2).mean()
+    lv = (ret_t - v) ** 2
+    if value_clip > 0:
+        ov = torch.from_numpy(old_values)
+        lv = torch.maximum(lv, (ov + (v - ov).clamp(-value_clip, value_clip) - ret_t) ** 2)
+    lv = lv.mean()
     return lpi + cv * lv - ce * ent.mean(), lpi, lv, ent.mean()
 
 
@@ -114,7 +122,7 @@ def _problem(oracle, seed, B, algo, kw=TINY):
     adv, ret = rng.normal(size=B), rng.normal(size=B)
     logits, _ = oracle.forward(net, flat, obs)
     lsm = logits - logits.max(1, keepdims=True); lsm -= np.log(np.exp(lsm).sum(1, keepdims=True))
-    old_logp = lsm[np.arange(B), actions] + rng.normal(0, 0.15, size=B) * (algo == 1)
+    old_logp = lsm[np.arange(B), actions] + rng.normal(0, 0.15, size=B) * (algo != 0)
     return net, flat, obs, actions, old_logp, adv, ret
 
 
@@ -188,6 +196,77 @@ def test_ppo_ratio_one_is_a2c(oracle):
     rho = np.exp(old_logp - olp)
     ga2, _ = oracle.loss_grads(net, flat, obs, actions, old_logp, adv * rho, ret, oracle.make_hparams(algo=0))
     np.testing.assert_allclose(gp, ga2, rtol=1e-12, atol=1e-15)
+
+
+def _flat_grad(p, kw):
+    return np.concatenate([p[name].grad.numpy().ravel() for name, _ in
+                           syn.param_shapes(kw["C"], kw["H"], kw["W"], kw["A"], convs=kw["convs"], hidden=kw["hidden"])])
+
+
+@pytest.mark.parametrize("rho_bar", [1.0, 1.1, 1e9])
+def test_truncated_importance_weights(oracle, rho_bar):
+    """The alternative to the delayed gradient in the appendix's ablation ("Delayed Gradient"): importance weights
+    w = min(rho, rho_bar), constants in the derivative.  Pinned three ways: torch autograd with the weight detached,
+    A2C on advantages pre-multiplied by weights computed here from the forward pass, and the on-policy case."""
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 61, 16, 2)
+    hp = oracle.make_hparams(algo="a2c_tis", rho_bar=rho_bar)
+    g, st = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp)
+    p = _torch_params(flat, TINY, TINY["A"])
+    loss, lpi, lv, ent = _torch_loss(p, obs, TINY["convs"], actions, old_logp, adv, ret, 2, 0.0, 0.5, 0.01, rho_bar=rho_bar)
+    loss.backward()
+    np.testing.assert_allclose(st["total_loss"], loss.item(), rtol=1e-12)
+    np.testing.assert_allclose(st["policy_loss"], lpi.item(), rtol=1e-12)
+    np.testing.assert_allclose(g, _flat_grad(p, TINY), rtol=1e-9, atol=1e-13)
+    # the same gradient from the A2C branch with w folded into the advantages
+    logits, _ = oracle.forward(net, flat, obs)
+    lsm = logits - logits.max(1, keepdims=True); lsm -= np.log(np.exp(lsm).sum(1, keepdims=True))
+    rho = np.exp(lsm[np.arange(16), actions] - old_logp)
+    w = np.minimum(rho, rho_bar)
+    ga, _ = oracle.loss_grads(net, flat, obs, actions, old_logp, adv * w, ret, oracle.make_hparams(algo=0))
+    np.testing.assert_allclose(g, ga, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(st["clip_frac"], np.mean(rho > rho_bar), rtol=0, atol=1e-15)
+    if rho_bar == 1.1:
+        assert 0.0 < st["clip_frac"] < 1.0          # both truncated and untruncated rows occur
+    # on-policy data (rho == 1): the plain actor-critic gradient whenever rho_bar >= 1
+    net, flat, obs, actions, exact_logp, adv, ret = _problem(oracle, 62, 8, 0)
+    g1, _ = oracle.loss_grads(net, flat, obs, actions, exact_logp, adv, ret, hp)
+    g0, _ = oracle.loss_grads(net, flat, obs, actions, exact_logp, adv, ret, oracle.make_hparams(algo=0))
+    np.testing.assert_allclose(g1, g0, rtol=1e-12, atol=1e-15)
+
+
+def test_clipped_value_loss(oracle):
+    """max((v-R)^2, (old_v + clip(v - old_v, +-c) - R)^2) per row: torch autograd; a radius that never binds gives the
+    plain squared loss; rows whose clipped term wins while v is outside the radius send no gradient to the value head."""
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 71, 16, 1)
+    _, v = oracle.forward(net, flat, obs)
+    rng = np.random.default_rng(5)
+    old_values = v + rng.normal(0, 0.2, size=16)
+    c = 0.1
+    hp = oracle.make_hparams(algo=1, clip_eps=0.1, value_clip=c)
+    g, st = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp, old_values=old_values)
+    p = _torch_params(flat, TINY, TINY["A"])
+    loss, lpi, lv, ent = _torch_loss(p, obs, TINY["convs"], actions, old_logp, adv, ret, 1, 0.1, 0.5, 0.01,
+                                     old_values=old_values, value_clip=c)
+    loss.backward()
+    np.testing.assert_allclose(st["value_loss"], lv.item(), rtol=1e-12)
+    np.testing.assert_allclose(st["total_loss"], loss.item(), rtol=1e-12)
+    np.testing.assert_allclose(g, _flat_grad(p, TINY), rtol=1e-9, atol=1e-13)
+    vc = old_values + np.clip(v - old_values, -c, c)
+    wins = (vc - ret) ** 2 > (v - ret) ** 2
+    outside = np.abs(v - old_values) > c
+    assert (wins & outside).any() and (~wins).any()       # the case has rows of both kinds
+    # never binding: identical to the unclipped loss
+    g_big, s_big = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret,
+                                     oracle.make_hparams(algo=1, clip_eps=0.1, value_clip=1e9), old_values=old_values)
+    g_off, s_off = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, oracle.make_hparams(algo=1, clip_eps=0.1))
+    np.testing.assert_array_equal(g_big, g_off)
+    assert s_big["value_loss"] == s_off["value_loss"]
+    # every row clipped away from v with the clipped term winning: the value head gets no gradient at all
+    far, target = v + 10.0, v - 5.0             # clipped value v + 10 - c is further from the target than v is
+    g_far, s_far = oracle.loss_grads(net, flat, obs, actions, old_logp, np.zeros(16), target,
+                                     oracle.make_hparams(algo=0, ent_coef=0.0, value_clip=c), old_values=far)
+    assert not g_far.any(), "with adv = 0, no entropy term and a dead value term nothing has a gradient"
+    np.testing.assert_allclose(s_far["value_loss"], (15.0 - c) ** 2, rtol=1e-12)
 
 
 def test_uniform_policy_entropy_and_zero_sum(oracle):
