@@ -48,6 +48,7 @@ extern "C" {
 
 #define HTS_ALGO_A2C 0
 #define HTS_ALGO_PPO 1
+#define HTS_ALGO_A2C_TIS 2   /* actor-critic with truncated importance weights (see hts_hparams) */
 
 #define HTS_MAX_ACTIONS 64
 
@@ -106,12 +107,12 @@ int32_t hts_returns_gae(hts_ctx *ctx, const float *rewards, const float *values,
 int32_t hts_normalize_advantages(hts_ctx *ctx, float *adv, int64_t n);
 
 /* One storage as the learner reads it: `count` rows (= T*N, time-major), of which the minibatch is the B rows
- * index[0..B) (NULL = rows 0..B-1).  old_values is unused by the loss and may be NULL. */
+ * index[0..B) (NULL = rows 0..B-1).  old_values is read only when hts_hparams.value_clip > 0 and may be NULL otherwise. */
 typedef struct {
     const uint8_t *obs;        /* u8 [count,C,H,W] */
     const int32_t *actions;    /* i32 [count]      */
-    const float   *old_logp;   /* f32 [count]  log-prob under the behaviour policy (PPO; may be NULL for A2C) */
-    const float   *old_values; /* f32 [count]  unused                                                        */
+    const float   *old_logp;   /* f32 [count]  log-prob under the behaviour policy (PPO, A2C_TIS; may be NULL for A2C) */
+    const float   *old_values; /* f32 [count]  value estimates stored at collection time (value_clip > 0 only)         */
     const float   *advantages; /* f32 [count]  treated as constants                                           */
     const float   *returns;    /* f32 [count]                                                                 */
     int32_t        count;
@@ -123,6 +124,14 @@ typedef struct {
  *   L = L_pi + vf_coef * mean((R - v)^2) - ent_coef * mean(H(pi(.|s)))
  *   A2C: L_pi = -mean(logp * adv);  PPO: L_pi = -mean(min(rho adv, clip(rho, 1-eps, 1+eps) adv)),
  *   rho = exp(logp - old_logp).   max_grad_norm > 0: gradients are scaled by min(1, c / (||g||_2 + 1e-6)).
+ *   A2C_TIS (the appendix's ablation "Delayed Gradient" compares the one-step-delayed update with truncated importance
+ *     sampling and with no correction; the paper gives no formula, the usual truncated weight is taken):
+ *     L_pi = -mean(w logp adv), w = min(rho, rho_bar) held constant in the derivative.  "No correction" is HTS_ALGO_A2C
+ *     called with the current parameters on a storage collected with the previous ones.
+ *   value_clip > 0 (needs hts_buffer.old_values; the clipped value loss of the PPO code the paper's experiments build
+ *     on): a row's value term is max((v - R)^2, (vc - R)^2), vc = old_v + clip(v - old_v, -value_clip, +value_clip).
+ *   Statistics: clip_frac = share of rows with rho outside [1-eps, 1+eps] (PPO) or above rho_bar (A2C_TIS);
+ *     approx_kl = mean(old_logp - logp).
  *   optimizer = HTS_OPT_ADAM:
  *     m <- b1 m + (1-b1) g; v <- b2 v + (1-b2) g^2; theta <- theta - lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps).
  *   optimizer = HTS_OPT_RMSPROP (the optimiser of the paper's experiments, appendix "Implementation Details":
@@ -137,6 +146,8 @@ typedef struct {
     float lr, beta1, beta2, adam_eps;
     int32_t optimizer;
     float rms_alpha;
+    float rho_bar;       /* A2C_TIS: truncation level of the importance weight (> 0; 1 is the usual choice) */
+    float value_clip;    /* <= 0: plain squared value loss */
 } hts_hparams;
 
 /* Optimiser state: m, v device f32 [P]; step is a host counter of completed updates (the call uses t = step+1 and

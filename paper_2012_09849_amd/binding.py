@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhts.so")
 
 PRECISION_FP32, PRECISION_BF16 = 0, 1
-ALGO_A2C, ALGO_PPO = 0, 1
+ALGO_A2C, ALGO_PPO, ALGO_A2C_TIS = 0, 1, 2
 OPT_ADAM, OPT_RMSPROP = 0, 1
 
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
@@ -36,12 +36,14 @@ class Buffer(C.Structure):
 class HParams(C.Structure):
     _fields_ = [("algo", C.c_int32), ("clip_eps", C.c_float), ("vf_coef", C.c_float), ("ent_coef", C.c_float),
                 ("max_grad_norm", C.c_float), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("adam_eps", C.c_float), ("optimizer", C.c_int32), ("rms_alpha", C.c_float)]
+                ("adam_eps", C.c_float), ("optimizer", C.c_int32), ("rms_alpha", C.c_float), ("rho_bar", C.c_float),
+                ("value_clip", C.c_float)]
 
     def __init__(self, algo=ALGO_A2C, clip_eps=0.1, vf_coef=0.5, ent_coef=0.01, max_grad_norm=0.0, lr=7e-4,
-                 beta1=0.9, beta2=0.999, adam_eps=1e-5, optimizer=OPT_ADAM, rms_alpha=0.99):
+                 beta1=0.9, beta2=0.999, adam_eps=1e-5, optimizer=OPT_ADAM, rms_alpha=0.99, rho_bar=1.0,
+                 value_clip=0.0):
         super().__init__(algo, clip_eps, vf_coef, ent_coef, max_grad_norm, lr, beta1, beta2, adam_eps, optimizer,
-                         rms_alpha)
+                         rms_alpha, rho_bar, value_clip)
 
 
 class _OptStateC(C.Structure):
@@ -179,27 +181,27 @@ class Context:
         _check(self.lib.hts_normalize_advantages(self._h, _ptr(adv, torch.float32, "adv"), adv.numel()),
                "hts_normalize_advantages")
 
-    def _buffer(self, obs, actions, old_logp, advantages, returns, index, B):
+    def _buffer(self, obs, actions, old_logp, advantages, returns, index, B, old_values=None):
         count = obs.shape[0]
         if B is None:
             B = count if index is None else index.numel()
-        keep = (obs, actions, old_logp, advantages, returns, index)
+        keep = (obs, actions, old_logp, advantages, returns, index, old_values)
         return Buffer(_ptr(obs, torch.uint8, "obs"), _ptr(actions, torch.int32, "actions"),
-                      _ptr(old_logp, torch.float32, "old_logp"), None,
+                      _ptr(old_logp, torch.float32, "old_logp"), _ptr(old_values, torch.float32, "old_values"),
                       _ptr(advantages, torch.float32, "advantages"), _ptr(returns, torch.float32, "returns"), count,
                       _ptr(index, torch.int32, "index"), B), keep
 
     def hts_learner_step(self, obs, actions, old_logp, advantages, returns, params, opt: OptState, hp: HParams,
-                         index=None, B=None, stats=None):
-        buf, _keep = self._buffer(obs, actions, old_logp, advantages, returns, index, B)
+                         index=None, B=None, stats=None, old_values=None):
+        buf, _keep = self._buffer(obs, actions, old_logp, advantages, returns, index, B, old_values)
         oc = _OptStateC(_ptr(opt.m, torch.float32, "m"), _ptr(opt.v, torch.float32, "v"), opt.step)
         _check(self.lib.hts_learner_step(self._h, C.byref(buf), _ptr(params, torch.float32, "params"), C.byref(oc),
                                          C.byref(hp), _ptr(stats, torch.float32, "stats")), "hts_learner_step")
         opt.step = oc.step
 
     def hts_learner_step_delayed(self, obs, actions, old_logp, advantages, returns, params_behaviour, params_target,
-                                 opt: OptState, hp: HParams, index=None, B=None, stats=None):
-        buf, _keep = self._buffer(obs, actions, old_logp, advantages, returns, index, B)
+                                 opt: OptState, hp: HParams, index=None, B=None, stats=None, old_values=None):
+        buf, _keep = self._buffer(obs, actions, old_logp, advantages, returns, index, B, old_values)
         oc = _OptStateC(_ptr(opt.m, torch.float32, "m"), _ptr(opt.v, torch.float32, "v"), opt.step)
         _check(self.lib.hts_learner_step_delayed(self._h, C.byref(buf),
                                                  _ptr(params_behaviour, torch.float32, "params_behaviour"),
@@ -209,8 +211,8 @@ class Context:
         opt.step = oc.step
 
     def hts_loss_and_grads(self, obs, actions, old_logp, advantages, returns, params, hp: HParams, grads, index=None,
-                           B=None, stats=None):
-        buf, _keep = self._buffer(obs, actions, old_logp, advantages, returns, index, B)
+                           B=None, stats=None, old_values=None):
+        buf, _keep = self._buffer(obs, actions, old_logp, advantages, returns, index, B, old_values)
         _check(self.lib.hts_loss_and_grads(self._h, C.byref(buf), _ptr(params, torch.float32, "params"), C.byref(hp),
                                            _ptr(grads, torch.float32, "grads"), _ptr(stats, torch.float32, "stats")),
                "hts_loss_and_grads")

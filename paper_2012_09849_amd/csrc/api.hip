@@ -212,9 +212,11 @@ static int32_t check_learn(hts_ctx *ctx, const hts_buffer *buf, const float *par
 {
     if (!ctx || !buf || !params || !hp) return HTS_EINVAL;
     if (!buf->obs || !buf->actions || !buf->advantages || !buf->returns) return HTS_EINVAL;
-    if (hp->algo != HTS_ALGO_A2C && hp->algo != HTS_ALGO_PPO) return HTS_EINVAL;
+    if (hp->algo != HTS_ALGO_A2C && hp->algo != HTS_ALGO_PPO && hp->algo != HTS_ALGO_A2C_TIS) return HTS_EINVAL;
     if (hp->optimizer != HTS_OPT_ADAM && hp->optimizer != HTS_OPT_RMSPROP) return HTS_EINVAL;
-    if (hp->algo == HTS_ALGO_PPO && !buf->old_logp) return HTS_EINVAL;
+    if (hp->algo != HTS_ALGO_A2C && !buf->old_logp) return HTS_EINVAL;
+    if (hp->algo == HTS_ALGO_A2C_TIS && !(hp->rho_bar > 0.0f)) return HTS_EINVAL;
+    if (hp->value_clip > 0.0f && !buf->old_values) return HTS_EINVAL;
     if (buf->B <= 0 || buf->count <= 0) return HTS_EINVAL;
     if (!buf->index && buf->B > buf->count) return HTS_EINVAL;
     if (buf->B > ctx->c.max_learn) return HTS_ESHAPE;
@@ -226,8 +228,9 @@ static int32_t loss_and_grads(Ctx &c, const hts_buffer *buf, const float *params
 {
     LossArgs la;
     la.actions = buf->actions; la.index = buf->index; la.old_logp = buf->old_logp;
-    la.adv = buf->advantages; la.ret = buf->returns;
+    la.old_values = buf->old_values; la.adv = buf->advantages; la.ret = buf->returns;
     la.algo = hp->algo; la.clip_eps = hp->clip_eps; la.vf_coef = hp->vf_coef; la.ent_coef = hp->ent_coef;
+    la.rho_bar = hp->rho_bar; la.value_clip = hp->value_clip;
     HIP_TRY(launch_prep(c, params, true));
     HIP_TRY(run_forward(c, buf->obs, buf->index, buf->B, true));
     HIP_TRY(launch_heads_learn(c, la, buf->B));

@@ -100,9 +100,10 @@ inline SplitK split_for(long long kp, int maxz)
 
 struct LossArgs {
     const int32_t *actions, *index;
-    const float *old_logp, *adv, *ret;
+    const float *old_logp, *old_values, *adv, *ret;
     int algo;
     float clip_eps, vf_coef, ent_coef;
+    float rho_bar, value_clip;        // truncation level of the importance weight; radius of the clipped value loss (<= 0: off)
 };
 
 // fwd.hip

@@ -346,6 +346,15 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         if (a.la.algo == HTS_ALGO_A2C) {
             pi_term = -logp * adv;
             dlogp = -adv * invB;
+        } else if (a.la.algo == HTS_ALGO_A2C_TIS) {
+            // truncated importance weight, a constant in the derivative
+            const float old = a.la.old_logp[row];
+            const float rho = expf(logp - old);
+            const float w = fminf(rho, a.la.rho_bar);
+            pi_term = -w * logp * adv;
+            dlogp = -w * adv * invB;
+            clipped = rho > a.la.rho_bar ? 1.0f : 0.0f;
+            kl = old - logp;
         } else {
             const float old = a.la.old_logp[row];
             const float rho = expf(logp - old);
@@ -359,12 +368,26 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         }
         const float dl = lane < A ? dlogp * ((lane == act ? 1.0f : 0.0f) - p) + a.la.ent_coef * invB * p * (lsm + ent)
                                   : 0.0f;
-        const float dv = 2.0f * a.la.vf_coef * (value - R) * invB;
+        float v_term = (R - value) * (R - value), dv_row = 2.0f * (value - R);
+        if (a.la.value_clip > 0.0f) {
+            // clipped value loss: the larger of the plain term and the term of the value held within a radius of
+            // the stored estimate; a value held at the radius does not move with the network's output
+            const float ov = a.la.old_values[row];
+            const float d = value - ov;
+            const float dc = fminf(fmaxf(d, -a.la.value_clip), a.la.value_clip);
+            const float vc = ov + dc;
+            const float c_term = (vc - R) * (vc - R);
+            if (c_term > v_term) {
+                v_term = c_term;
+                dv_row = dc == d ? 2.0f * (vc - R) : 0.0f;
+            }
+        }
+        const float dv = a.la.vf_coef * dv_row * invB;
         if (lane < A) a.dz[(long long)b * (A + 1) + lane] = dl;
         if (lane == 0) {
             a.dz[(long long)b * (A + 1) + A] = dv;
             float *t = a.terms + (long long)b * N_TERMS;
-            t[0] = pi_term; t[1] = (R - value) * (R - value); t[2] = ent; t[3] = clipped; t[4] = kl;
+            t[0] = pi_term; t[1] = v_term; t[2] = ent; t[3] = clipped; t[4] = kl;
         }
         // dL/d(FC pre-activation) for this lane's 8 hidden units
         float acc[8];

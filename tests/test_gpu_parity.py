@@ -35,7 +35,8 @@ def oracle_hp(oracle, hp):
     """The oracle's hyper-parameters with exactly the binary32 values the GPU call receives."""
     return oracle.make_hparams(algo=hp.algo, clip_eps=float(hp.clip_eps), vf_coef=float(hp.vf_coef),
                                ent_coef=float(hp.ent_coef), max_grad_norm=float(hp.max_grad_norm), lr=float(hp.lr),
-                               beta1=float(hp.beta1), beta2=float(hp.beta2), adam_eps=float(hp.adam_eps))
+                               beta1=float(hp.beta1), beta2=float(hp.beta2), adam_eps=float(hp.adam_eps),
+                               rho_bar=float(hp.rho_bar), value_clip=float(hp.value_clip))
 
 
 def rel_err(got, want):
@@ -459,6 +460,86 @@ def test_rmsprop_parity(hts, oracle):
     ctx.close()
 
 
+@pytest.mark.parametrize("small_batch", ["128", "0"])
+@pytest.mark.parametrize("shape,A,count,B,algo,rho_bar,value_clip,prec", [
+    (ATARI, 18, 24, 17, 2, 1.0, 0.0, 0),            # truncated importance weights, about half the rows truncated
+    (ATARI, 18, 24, 17, 2, 1.05, 0.1, 0),           # ... with the clipped value loss as well
+    (ATARI, 6, 20, None, 1, 1.0, 0.15, 0),          # PPO with the clipped value loss
+    (FOOT, 19, 6, 5, 2, 1.0, 0.01, 0),
+    ((3, 44, 52), 7, 70, 67, 2, 1.0, 0.1, 0),
+])
+def test_loss_variants_parity(hts, oracle, shape, A, count, B, algo, rho_bar, value_clip, prec, small_batch, monkeypatch):
+    """Truncated importance weights (the alternative to the delayed gradient in the appendix's ablation) and the clipped
+    value loss, against the oracle; then one full optimiser step with them."""
+    monkeypatch.setenv("HTS_SMALL_BATCH", small_batch)
+    Cc, H, W = shape
+    net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 300 + count, True)
+    _, values = oracle.forward(net, params, obs)
+    old_values = (values + 0.2 * syn.normal(300 + count, syn.S_MISC + 2, count)).astype(np.float32)
+    index = None if B is None else syn.permutation(7, count)[:B]
+    nb = count if B is None else B
+    ctx = hts.Context(Cc, H, W, A, precision=prec, max_learn_batch=nb)
+    hp = hts.HParams(algo=algo, clip_eps=0.1, vf_coef=0.5, ent_coef=0.01, rho_bar=rho_bar, value_clip=value_clip,
+                     max_grad_norm=0.5, lr=2.5e-4)
+    ohp = oracle_hp(oracle, hp)
+    ov = old_values if value_clip > 0 else None
+    d_idx = None if index is None else dev(index)
+    d_ov = None if ov is None else dev(ov)
+    grads = torch.full((ctx.P,), float("nan"), device="cuda")
+    stats = ctx.new_stats()
+    d_params = dev(params)
+    ctx.hts_loss_and_grads(dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret), d_params, hp, grads, index=d_idx,
+                           stats=stats, old_values=d_ov)
+    torch.cuda.synchronize()
+    g_ref, st_ref = oracle.loss_grads(net, params, obs, actions, old_logp, adv, ret, ohp, index=index, old_values=ov)
+    rows = np.arange(count) if index is None else index
+    if algo == 2:
+        assert 0.0 < st_ref["clip_frac"] < 1.0, "the case should have truncated and untruncated rows"
+    if value_clip > 0:
+        d = values[rows] - old_values[rows]
+        wins = (old_values[rows] + np.clip(d, -value_clip, value_clip) - ret[rows]) ** 2 > (values[rows] - ret[rows]) ** 2
+        assert wins.any() and (~wins).any(), "the case should have rows on both sides of the maximum"
+    g = grads.cpu().numpy()
+    for name, gg in _split(g, shape, A).items():
+        assert_close(gg, _split(g_ref, shape, A)[name], 1e-4, f"grad {name}")
+    st = ctx.read_stats(stats)
+    for k in ("policy_loss", "value_loss", "entropy", "grad_norm"):
+        assert abs(st[k] - st_ref[k]) <= 1e-4 * max(1.0, abs(st_ref[k])), (k, st[k], st_ref[k])
+    assert abs(st["clip_frac"] - st_ref["clip_frac"]) < 1e-6 and abs(st["approx_kl"] - st_ref["approx_kl"]) < 1e-5
+    # one optimiser step
+    P = ctx.P
+    opt = hts.OptState(torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda"))
+    ctx.hts_learner_step(dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret), d_params, opt, hp, index=d_idx,
+                         old_values=d_ov)
+    torch.cuda.synchronize()
+    th, m, v, _, _ = oracle.learner_step(net, params, np.zeros(P), np.zeros(P), 1, obs, actions, old_logp, adv, ret, ohp,
+                                         index=index, old_values=ov)
+    assert_close(opt.m.cpu().numpy(), m, 1e-4, "m")
+    step_ref = th - params.astype(np.float64)
+    step = d_params.cpu().numpy().astype(np.float64) - params.astype(np.float64)
+    err = np.abs(step - step_ref)          # first Adam step: |step| ~ lr per entry, sensitive where |g| ~ adam_eps
+    assert err.max() <= 2.0 * float(hp.lr) and float(np.mean(err > 1e-2 * float(hp.lr))) < 5e-3
+    ctx.close()
+
+
+def test_no_correction_is_plain_actor_critic_on_a_stale_storage(hts, oracle):
+    """The ablation's third arm, "no correction": the plain actor-critic gradient at the current parameters on a storage
+    collected with the previous ones.  The stored log-probabilities play no part in it."""
+    net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, ATARI, 6, 20, 77, False)
+    stale = params + 1e-3 * syn.normal(78, syn.S_MISC, params.size).astype(np.float32)     # "current" parameters
+    ctx = hts.Context(4, 84, 84, 6, max_learn_batch=20)
+    hp = hts.HParams(algo=0)
+    g1, g2 = torch.zeros(ctx.P, device="cuda"), torch.zeros(ctx.P, device="cuda")
+    ctx.hts_loss_and_grads(dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret), dev(stale), hp, g1)
+    ctx.hts_loss_and_grads(dev(obs), dev(actions), None, dev(adv), dev(ret), dev(stale), hp, g2)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, g2)
+    g_ref, _ = oracle.loss_grads(net, stale, obs, actions, None, adv, ret, oracle_hp(oracle, hp))
+    for name, gg in _split(g1.cpu().numpy(), ATARI, 6).items():
+        assert_close(gg, _split(g_ref, ATARI, 6)[name], 1e-4, f"grad {name}")
+    ctx.close()
+
+
 def test_learner_errors_launch_nothing(hts):
     ctx = hts.Context(4, 84, 84, 6, max_act_batch=4, max_learn_batch=4)
     obs = torch.zeros(8, 4, 84, 84, dtype=torch.uint8, device="cuda")
@@ -468,6 +549,14 @@ def test_learner_errors_launch_nothing(hts):
         ctx.hts_act(obs, p, 1, 0, 0, a, lp, v)                 # N = 8 > max_act_batch
     with pytest.raises(hts.HtsError):
         ctx.hts_loss_and_grads(obs, a, None, lp, v, p, hts.HParams(algo=1), torch.zeros(ctx.P, device="cuda"))  # PPO needs old_logp
+    with pytest.raises(hts.HtsError):
+        ctx.hts_loss_and_grads(obs, a, None, lp, v, p, hts.HParams(algo=2), torch.zeros(ctx.P, device="cuda"), B=4)   # needs old_logp
+    with pytest.raises(hts.HtsError):
+        ctx.hts_loss_and_grads(obs, a, lp, lp, v, p, hts.HParams(algo=2, rho_bar=0.0), torch.zeros(ctx.P, device="cuda"), B=4)
+    with pytest.raises(hts.HtsError):
+        ctx.hts_loss_and_grads(obs, a, lp, lp, v, p, hts.HParams(algo=0, value_clip=0.1), torch.zeros(ctx.P, device="cuda"), B=4)  # needs old_values
+    with pytest.raises(hts.HtsError):
+        ctx.hts_loss_and_grads(obs, a, lp, lp, v, p, hts.HParams(algo=3), torch.zeros(ctx.P, device="cuda"), B=4)
     with pytest.raises(hts.HtsError):
         ctx.hts_loss_and_grads(obs, a, lp, lp, v, p, hts.HParams(algo=0), torch.zeros(ctx.P, device="cuda"))    # B = 8 > max
     torch.cuda.synchronize()
