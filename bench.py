@@ -27,6 +27,11 @@ CONFIGS = {
     "football_ppo_n16_t512_bf16": dict(C=16, H=72, W=96, A=19, N=16, T=512, precision=1, algo=1, gamma=0.993,
                                        lam=0.95, lr=3.4e-4, epochs=2, minibatches=4, clip=0.08, max_norm=0.0,
                                        ent=0.003, obs="football"),
+    # the paper's multi-agent football experiment controls three players per environment: every controlled player is
+    # one row of every call (16 environments x 3 players = 48 rows per step), unroll 128 as in the paper's runs
+    "football_multiagent_ppo_n16x3_t128_bf16": dict(C=16, H=72, W=96, A=19, N=48, T=128, precision=1, algo=1,
+                                                    gamma=0.993, lam=0.95, lr=3.4e-4, epochs=2, minibatches=4,
+                                                    clip=0.08, max_norm=0.0, ent=0.003, obs="football"),
 }
 FWD_FLOP = {"atari": 18.71e6, "football": 35.80e6}
 FWDBWD_FLOP = {"atari": 49.56e6, "football": 81.78e6}

@@ -130,6 +130,8 @@ extern "C" int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, i
         s.pib = s.piw + 512ll * g.A; s.vw = pad4(s.pib + g.A); s.vb = s.vw + 512; s.count = pad4(s.vb + 1);
     }
     if (const char *sb = getenv("HTS_SMALL_BATCH")) c.small_b = atoi(sb);   // tuning knob: 0 disables the small path
+    c.fc_fold_rows = 4096; c.fc_slices = c.fc_groups;
+    if (const char *fr = getenv("HTS_FC_FOLD_ROWS")) c.fc_fold_rows = atoi(fr);   // tuning knob, same bits either way
     c.ws = Workspace();
     Carver size_pass;
     carve(c, size_pass);

@@ -227,9 +227,14 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
     }
     {   // groups of FC_GROUP_K inputs; the heads kernel adds them (same grouping and order on both paths)
         FcFwd<T> p;
-        p.M = B; p.N = 512; p.K = g.F; p.klen = FC_GROUP_K;
+        // With enough rows to fill the machine the tile kernel adds the groups itself (same order, same bits) and the
+        // partial sums -- G x the FC output, written here and read back by the heads kernel -- shrink to one slice.
+        // Measured: slower than G x the workgroups at 2048 rows (54 vs 52 us for FC + heads), faster at 4096 (69 vs 77).
+        const bool fold = !small && B >= c.fc_fold_rows;
+        p.M = B; p.N = 512; p.K = g.F; p.klen = fold ? g.F : FC_GROUP_K;
+        c.fc_slices = fold ? 1 : c.fc_groups;
         p.a3 = (const T *)c.ws.a3; p.w = (const T *)c.ws.wfc; p.part = c.ws.fc_part;
-        static_assert(FC_GROUP_K % FcFwd<T>::SEG == 0, "a group is a whole number of segments");
+        static_assert(FC_GROUP_K % FcFwd<T>::SEG == 0 && FcFwd<T>::GROUP == FC_GROUP_K, "a group is a whole number of segments");
         {
             SiteTimer tm(c, SITE_FC_FWD);
             e = small ? launch_wsgemm<FcFwd<T>, 8, FcFwd<T>::SEG, false>(p, c.stream, FC_GROUP_K / FcFwd<T>::SEG)

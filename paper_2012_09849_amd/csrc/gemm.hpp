@@ -148,6 +148,14 @@ template <typename T> HTS_HD Vec<T, 8> load_u8x8(const uint8_t *p)
 template <class P, class = void> struct SegOf { static constexpr int value = 0; };
 template <class P> struct SegOf<P, std::void_t<decltype(P::SEG)>> { static constexpr int value = P::SEG; };
 
+// Optional second level: a problem that also defines `static constexpr int GROUP` (a multiple of SEG) has the segment
+// sums of each group of GROUP reduction indices added up first and the group sums then added in group order,
+//   D = (((0 + g_0) + g_1) + ...),  g_j = ((s_0 + s_1) + ...) over the segments of group j
+// -- what a consumer computes that receives one partial per group (klen = GROUP) and adds them in order, so a launch
+// may cover any whole number of groups per reduction chunk without changing a bit of the result.
+template <class P, class = void> struct GroupOf { static constexpr int value = 0; };
+template <class P> struct GroupOf<P, std::void_t<decltype(P::GROUP)>> { static constexpr int value = P::GROUP; };
+
 // Optional prefetch depth: a problem that defines `static constexpr int STAGES = D` keeps the global loads of D k-tiles
 // in flight in registers (default 1: the next tile only).  The order of the arithmetic does not change.
 template <class P, class = void> struct StagesOf { static constexpr int value = 1; };
@@ -569,6 +577,20 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         auto step = [&](int k0, f32x16 (&a)[TM][TN]) { step_s(k0, a, rra[0], rrb[0], std::integral_constant<int, 2>{}); };
         // one fresh accumulator per segment (it only lives inside the segment), folded into the running total
         constexpr int SPS = SEG / BK;            // k-tiles per segment
+        constexpr int GROUP = GroupOf<P>::value;
+        static_assert(GROUP % SEG == 0, "a group is a whole number of segments");
+        f32x16 tot[GROUP > 0 ? TM : 1][GROUP > 0 ? TN : 1];      // running sum of the finished groups
+        if constexpr (GROUP > 0) clear(tot);
+        auto close_group = [&]() {
+            if constexpr (GROUP > 0) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { tot[i][j][r] += acc[i][j][r]; acc[i][j][r] = 0.0f; }
+            }
+        };
         int k0 = kbeg;
         for (; k0 + SEG <= kend; k0 += SEG) {
             f32x16 sacc[TM][TN];
@@ -581,6 +603,9 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] += sacc[i][j][r];
+            if constexpr (GROUP > 0) {
+                if ((k0 + SEG - kbeg) % GROUP == 0) close_group();
+            }
         }
         if (k0 < kend) {                          // a last, shorter segment
             f32x16 sacc[TM][TN];
@@ -592,6 +617,13 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] += sacc[i][j][r];
+        }
+        if constexpr (GROUP > 0) {
+            if ((kend - kbeg) % GROUP != 0) close_group();      // a last, shorter group
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = tot[i][j];
         }
     } else {
         for (int k0 = kbeg; k0 < kend; k0 += BK) step_s(k0, acc, rra[0], rrb[0], std::integral_constant<int, 2>{});

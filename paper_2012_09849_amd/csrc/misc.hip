@@ -425,7 +425,7 @@ static void heads_network(const Ctx &c, HeadsArgs &a)
 {
     const float *hb = c.ws.hb;
     a.wpi = hb + c.sh.piw; a.bpi = hb + c.sh.pib; a.wv = hb + c.sh.vw; a.bv = hb + c.sh.vb;
-    a.fc_part = c.ws.fc_part; a.fc_bias = hb + c.sh.fcb; a.nseg = c.fc_groups;
+    a.fc_part = c.ws.fc_part; a.fc_bias = hb + c.sh.fcb; a.nseg = c.fc_slices;
 }
 
 // logits_in != null: sample from these logits (no network involved); otherwise finish the forward pass first.

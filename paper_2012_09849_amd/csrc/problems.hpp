@@ -198,11 +198,12 @@ template <typename T_> struct FcFwd {
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
     static constexpr int SEG = 64;
+    static constexpr int GROUP = 512;      // = FC_GROUP_K: klen may be any whole number of groups
     typedef PtrCtx<T> CtxA;
     typedef PtrCtx<T> CtxB;
     int M, N, K, klen;
     const T *a3, *w;
-    float *part;      // [groups][M][N]
+    float *part;      // [K chunks][M][N]
     HTS_HD CtxA ctx_a(int m) const { return {a3 + (long long)clamp_row(m, M) * K}; }
     HTS_HD CtxB ctx_b(int n) const { return {w + (long long)clamp_row(n, N) * K}; }
     // K = F = 64*P3 and the group length are whole numbers of k-tiles and segments: no end-of-range checks

@@ -192,8 +192,14 @@ def test_act_small_and_large_batch_kernels_agree_bitwise(hts, shape, A, prec, mo
     params = dev(syn.init_params(9, Cc, H, W, A, bias_scale=0.05))
     obs = dev(syn.obs_uniform(13, N, Cc, H, W))
     outs = []
-    for knob in ("128", "0", "16"):          # all small / all tile kernels / mixed (the 40-batch is "large", splits small)
+    # all small / all tile kernels / mixed (the 40-batch is "large", splits small) / tile kernels with the FC layer's
+    # groups added inside the FC kernel (the form large batches take) instead of by the heads kernel
+    for knob, fold in (("128", None), ("0", None), ("16", None), ("0", "1")):
         monkeypatch.setenv("HTS_SMALL_BATCH", knob)
+        if fold is None:
+            monkeypatch.delenv("HTS_FC_FOLD_ROWS", raising=False)
+        else:
+            monkeypatch.setenv("HTS_FC_FOLD_ROWS", fold)
         ctx = hts.Context(Cc, H, W, A, precision=prec, max_act_batch=N)
         full = _act(ctx, obs, params, 5, 1, 0, A)
         a = _act(ctx, obs[:16], params, 5, 1, 0, A)
@@ -618,8 +624,9 @@ def test_bf16_ragged_large_batch_agrees_with_small_batch_kernels(hts, oracle, sh
     net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 900 + count, True)
     index = syn.permutation(8, count)[:B]
     out = {}
-    for knob in ("128", "1000"):
+    for knob, fold in (("128", "1000000"), ("1000", "1000000"), ("128", "1")):
         monkeypatch.setenv("HTS_SMALL_BATCH", knob)
+        monkeypatch.setenv("HTS_FC_FOLD_ROWS", fold)     # "1": the FC kernel adds its K groups itself, as for large batches
         ctx = hts.Context(Cc, H, W, A, precision=1, max_learn_batch=B)
         hp = hts.HParams(algo=1, clip_eps=0.1)
         grads = torch.full((ctx.P,), float("nan"), device="cuda")
@@ -627,10 +634,11 @@ def test_bf16_ragged_large_batch_agrees_with_small_batch_kernels(hts, oracle, sh
         ctx.hts_loss_and_grads(dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret), dev(params), hp, grads,
                                index=dev(index), stats=stats)
         torch.cuda.synchronize()
-        out[knob] = (grads.cpu().numpy(), ctx.read_stats(stats))
+        out[knob, fold] = (grads.cpu().numpy(), ctx.read_stats(stats))
         ctx.close()
-    (g_large, st_large), (g_small, st_small) = out["128"], out["1000"]
+    (g_large, st_large), (g_small, st_small) = out["128", "1000000"], out["1000", "1000000"]
     assert np.all(np.isfinite(g_large))
+    assert np.array_equal(out["128", "1"][0], g_large) and out["128", "1"][1] == st_large     # same bits either way
     for k in ("policy_loss", "value_loss", "entropy"):
         assert st_large[k] == st_small[k], (k, st_large[k], st_small[k])          # forward bits are identical
     for name, gl in _split(g_large, shape, A).items():
