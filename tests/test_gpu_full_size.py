@@ -241,3 +241,77 @@ def test_gae_sweep_size(hts, oracle):
     np.testing.assert_allclose(adv.cpu().numpy(), a_ref, rtol=1e-6, atol=1e-6)
     np.testing.assert_allclose(ret.cpu().numpy(), r_ref, rtol=1e-6, atol=1e-6)
     ctx.close()
+
+
+MAX_BATCH = 65536          # the largest batch a context accepts
+
+
+@pytest.mark.parametrize("shape,A,prec", [(ATARI, 18, 1), (FOOT, 19, 1), (ATARI, 18, 0)])
+def test_maximum_batch_act(hts, oracle, shape, A, prec):
+    """hts_act at the largest batch a context accepts (offsets beyond 2^31 bytes in every activation).  The batch is
+    64 distinct frames repeated 1024 times: batch-partition invariance makes every copy's logits and value equal,
+    bit for bit, to those of the 64 frames served alone, which the oracle checks; actions and log-probabilities of all
+    65536 rows (every row has its own Philox counter) follow from the logits."""
+    Cc, H, W = shape
+    N, R = MAX_BATCH, 64
+    net = oracle.make_net(Cc, H, W, A)
+    params = syn.init_params(81, Cc, H, W, A, bias_scale=0.05)
+    frames = syn.obs_atari(82, 1, R)[0] if shape == ATARI else syn.obs_football(82, 1, R)[0]
+    ctx = hts.Context(Cc, H, W, A, precision=prec, max_act_batch=N)
+    z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device="cuda")
+    params_d, frames_d = dev(params), dev(frames)
+    a64, lp64, v64, lg64 = z(R, dt=torch.int32), z(R), z(R), z(R, A)
+    ctx.hts_act(frames_d, params_d, SEED, 3, 0, a64, lp64, v64, lg64)
+    obs_d = frames_d.repeat(N // R, 1, 1, 1)                  # row k*64 + i is frame i
+    actions, logp, values, logits = z(N, dt=torch.int32), z(N), z(N), z(N, A)
+    ctx.hts_act(obs_d, None, SEED, 3, 0, actions, logp, values, logits)
+    torch.cuda.synchronize()
+    assert torch.equal(logits.view(N // R, R, A), lg64.expand(N // R, R, A))
+    assert torch.equal(values.view(N // R, R), v64.expand(N // R, R))
+    l_ref, v_ref = oracle.forward(net, params, frames)
+    tol = 2e-2 if prec == 1 else 1e-4
+    assert_close(lg64.cpu().numpy(), l_ref, tol, "logits")
+    assert_close(v64.cpu().numpy(), v_ref, tol, "values")
+    a_ref, lp_ref, _ = oracle.sample(logits.cpu().numpy(), SEED, 3, 0)
+    assert np.array_equal(actions.cpu().numpy(), a_ref)
+    np.testing.assert_allclose(logp.cpu().numpy(), lp_ref, atol=1e-6, rtol=0)
+    ctx.close()
+
+
+@pytest.mark.parametrize("shape,A,prec,algo", [(ATARI, 18, 0, 0), (ATARI, 18, 1, 1), (FOOT, 19, 1, 1)])
+def test_maximum_minibatch_gradient(hts, oracle, shape, A, prec, algo):
+    """Forward, loss and backward on the largest minibatch a context accepts: 65536 rows gathered (through `index`)
+    from a 64-row storage, every row 1024 times.  The mean loss over the repeated rows is the mean over the 64, so the
+    oracle's gradient on the 64 rows is the expected value."""
+    Cc, H, W = shape
+    B, R = MAX_BATCH, 64
+    from test_gpu_parity import _rollout
+    net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, R, 500, algo == 1)
+    index = np.tile(np.arange(R, dtype=np.int32), B // R)
+    ctx = hts.Context(Cc, H, W, A, precision=prec, max_learn_batch=B)
+    hp = hts.HParams(algo=algo, clip_eps=0.1, vf_coef=0.5, ent_coef=0.01)
+    grads = torch.full((ctx.P,), float("nan"), device="cuda")
+    stats = ctx.new_stats()
+    args = (dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret), dev(params), hp)
+    ctx.hts_loss_and_grads(*args, grads, index=dev(index), stats=stats)
+    torch.cuda.synchronize()
+    if prec == 1:       # the oracle's operand-rounding model (same bf16 operands, exact sums): both sides open the same ReLU gates
+        net = oracle.make_net(Cc, H, W, A, operand_bf16=True)
+    g_ref, st_ref = oracle.loss_grads(net, params, obs, actions, old_logp, adv, ret, oracle_hp(oracle, hp))
+    g = grads.cpu().numpy()
+    assert np.all(np.isfinite(g))
+    # binary32 tolerance at this size: the FC and heads weight gradients are single accumulation chains over the 65536
+    # rows; with unit roundoff u = 6e-8 a chain of n additions errs by sqrt(n) u = 1.5e-5 for independent addends and by
+    # up to n u = 3.9e-3 in the worst case, and repeated rows (equal addends, partial sums growing linearly) lie in
+    # between (1.4e-4 observed on fc.w).  5e-4 is allowed here; the 1e-4 of the other tests stands for n <= 4096.
+    tol = 2e-2 if prec == 1 else 5e-4
+    for name, gg in _split(g, shape, A).items():
+        assert_close(gg, _split(g_ref, shape, A)[name], tol, f"grad {name}")
+    st = ctx.read_stats(stats)
+    for k in ("policy_loss", "value_loss", "entropy"):
+        assert abs(st[k] - st_ref[k]) <= tol * max(1.0, abs(st_ref[k])), (k, st[k], st_ref[k])
+    g2 = torch.zeros_like(grads)                                # run-to-run bit identity at this size
+    ctx.hts_loss_and_grads(*args, g2, index=dev(index))
+    torch.cuda.synchronize()
+    assert torch.equal(grads, g2)
+    ctx.close()
