@@ -131,6 +131,8 @@ extern "C" int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, i
     }
     if (const char *sb = getenv("HTS_SMALL_BATCH")) c.small_b = atoi(sb);   // tuning knob: 0 disables the small path
     c.fc_fold_rows = 4096; c.fc_slices = c.fc_groups;
+    c.tile16_below = 128;
+    if (const char *t16 = getenv("HTS_TILE16_BELOW")) c.tile16_below = atoi(t16);   // tuning knob, same bits either way
     if (const char *fr = getenv("HTS_FC_FOLD_ROWS")) c.fc_fold_rows = atoi(fr);   // tuning knob, same bits either way
     c.ws = Workspace();
     Carver size_pass;

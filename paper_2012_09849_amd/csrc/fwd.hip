@@ -173,6 +173,12 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
     hipError_t e;
     const bool small = B <= c.small_b;
     const float *hb = c.ws.hb;
+    // Small batches whose layer has fewer 32x32 output tiles (workgroups) than a threshold take 16x16 tiles: four
+    // times the workgroups, half the operand bytes per workgroup, the same bits.
+    // Measured (act call, 16 rows, binary32): 34.7 -> 26.7 us.  The gain ends between 100 and 200 workgroups (conv3
+    // at 32 rows, 98 workgroups: 12.6 -> 10.5 us; at 64 rows, 196: 13.2 -> 16.0 us); conv1 gains only with binary32
+    // operands (its frame operand is bytes either way), up to about 200 workgroups.
+    auto few32 = [&](int workgroups) { return workgroups < c.tile16_below; };
     {
         Conv1Fwd<T> p;
         p.M = B * g.P1; p.N = 32; p.K = g.K1; p.klen = g.K1;
@@ -183,7 +189,16 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
             SiteTimer tm(c, SITE_CONV1_FWD);
             // one wavefront per 64-long segment (= per input channel): 4 for a 4-channel frame; a 16-channel frame
             // gets 16, with the weight operand straight from memory so that their panels still fit in LDS
-            if (small) e = g.K1 >= 1024 ? launch_wsgemm<Conv1Fwd<T>, 16, Conv1Fwd<T>::SEG, false, true>(p, c.stream)
+            bool done = false;
+            if constexpr (sizeof(T) == 4) {
+                if (small && few32((p.M + 31) / 64)) {
+                    e = g.K1 >= 1024 ? launch_wsgemm16<Conv1Fwd<T>, 16, Conv1Fwd<T>::SEG>(p, c.stream)
+                                     : launch_wsgemm16<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG>(p, c.stream);
+                    done = true;
+                }
+            }
+            if (done) {}
+            else if (small) e = g.K1 >= 1024 ? launch_wsgemm<Conv1Fwd<T>, 16, Conv1Fwd<T>::SEG, false, true>(p, c.stream)
                                         : launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream);
             else if (sizeof(T) == 2 && conv1_image_fits(g, obs)) e = launch_conv1_image(c, obs, index, B);
             else e = launch_gemm(p, c.stream);
@@ -201,6 +216,9 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
             SiteTimer tm(c, SITE_CONV2_FWD);
             // (the LDS-resident kernel of imgconv.hpp measured slower here than the tile kernel: 20.4 vs 17.8 us at
             // B = 1024 -- this layer streams the large conv1 output once either way)
+            if (small && few32(((p.M + 31) / 32) * 2))
+                e = launch_wsgemm16<ConvFwd<T, Layer2, false>, 8, ConvFwd<T, Layer2, false>::SEG>(p, c.stream);
+            else
             e = small ? launch_wsgemm<ConvFwd<T, Layer2, false>, 8, ConvFwd<T, Layer2, false>::SEG, false>(p, c.stream)
                       : launch_gemm(p, c.stream);
         }
@@ -215,7 +233,9 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.dPo = FastDiv::make(g.P3); p.dWo = FastDiv::make(g.W3);
         {
             SiteTimer tm(c, SITE_CONV3_FWD);
-            if (small) e = launch_wsgemm<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 8 : 4), ConvFwd<T, Layer3, true>::SEG, false, true>(p, c.stream);
+            if (small && few32(((p.M + 31) / 32) * 2))     // binary32: 6 segments of 96; bfloat16: 3 of 192 (the fold needs 4 wavefronts)
+                e = launch_wsgemm16<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 6 : 4), ConvFwd<T, Layer3, true>::SEG>(p, c.stream);
+            else if (small) e = launch_wsgemm<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 8 : 4), ConvFwd<T, Layer3, true>::SEG, false, true>(p, c.stream);
             else if (sizeof(T) == 2 && atari_grid) {       // large bf16 batch, 9x9 input: activations resident in LDS
                 ImgConvArgs a = {};
                 a.in = (const bf16_t *)c.ws.act2; a.w = (const bf16_t *)c.ws.wf3; a.bias = hb + c.sh.b3;
@@ -237,6 +257,9 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         static_assert(FC_GROUP_K % FcFwd<T>::SEG == 0 && FcFwd<T>::GROUP == FC_GROUP_K, "a group is a whole number of segments");
         {
             SiteTimer tm(c, SITE_FC_FWD);
+            if (small && few32(((B + 31) / 32) * 16 * c.fc_groups))
+                e = launch_wsgemm16<FcFwd<T>, 8, FcFwd<T>::SEG>(p, c.stream, FC_GROUP_K / FcFwd<T>::SEG);
+            else
             e = small ? launch_wsgemm<FcFwd<T>, 8, FcFwd<T>::SEG, false>(p, c.stream, FC_GROUP_K / FcFwd<T>::SEG)
                       : launch_gemm(p, c.stream);
         }

@@ -59,6 +59,7 @@ struct Ctx {
     int max_act, max_learn, max_b;
     int small_b;              // batches up to this size take the wave-per-segment forward kernels
     int fc_groups;            // ceil(F / FC_GROUP_K)
+    int tile16_below;         // small-batch forward layers with fewer 32x32-tile workgroups than this use 16x16 tiles
     int fc_fold_rows;         // batches of at least this many rows add the FC groups inside the FC kernel (one slice of fc_part)
     int fc_slices;            // slices of fc_part the last forward pass wrote (fc_groups, or 1)
     bool synced;              // the workspace's copy of the network matches the last parameter vector handed in

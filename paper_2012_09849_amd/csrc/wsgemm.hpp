@@ -264,6 +264,141 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
     }
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The same scheme on 16x16 output tiles: four times the workgroups for the same problem.
+// With 16-32 observations a layer has fewer 32x32 tiles than the chip has compute units, and a workgroup's run time
+// is then the time its one compute unit needs to pull both 32 x K operand panels through its L1 (conv3, binary32,
+// K = 576: 147 KB per workgroup; about 60 % of the kernel's duration went into getting the loads issued at all).
+// Halving both tile edges halves the bytes per workgroup and spreads them over four times as many compute units.
+// Bits: on this hardware the matrix instructions of one operand type return the same bits for the same k order
+// whatever their tile shape (32x32x2 and 16x16x4 for binary32 -- both equal to a sequential fma chain --, 32x32x16
+// and 16x16x32 for bfloat16: checked on random operands of mixed magnitude, 51200 outputs each, and by the tests that
+// compare the kernel families bitwise), so with the same segments the results equal those of the other kernels.
+// Problems: A_ALONG_K and B_ALONG_K, plain store() epilogue (the forward layers).
+// ------------------------------------------------------------------------------------------------------------
+template <class P, int WAVES, int SEG>
+__global__ __launch_bounds__(WAVES * 64) void wsgemm16_kernel(const P p, const int spg)
+{
+    using T = typename P::T;
+    using Tr = OperandTraits<T>;
+    constexpr int VA = P::VA, VB = P::VB;
+    constexpr int KI = sizeof(T) == 4 ? 4 : 32;          // k per matrix instruction
+    static_assert(P::A_ALONG_K && P::B_ALONG_K, "k-contiguous operands");
+    static_assert(WAVES >= 4 && SEG % KI == 0 && (16 * SEG / VA) % 64 == 0 && (16 * SEG / VB) % 64 == 0,
+                  "four wavefronts own the fold; whole rounds of loads");
+    constexpr int LS = SEG + Tr::VEC;         // row pitch: a 16-byte step per row, so the 64 lanes of an operand read
+                                              // (row i, k slot q) spread evenly over the banks
+    constexpr int NA = 16 * SEG / VA / 64, NB = 16 * SEG / VB / 64;     // vectors per lane and panel
+    constexpr size_t PANEL_BYTES = (size_t)2 * 16 * LS * sizeof(T);
+    static_assert(PANEL_BYTES >= 1024, "the fold reuses a wavefront's panels for its 16x16 partial tile");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int zb = blockIdx.z, M = rows_of(p, zb);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    T *As = reinterpret_cast<T *>(smem + (size_t)w * PANEL_BYTES), *Bs = As + 16 * LS;
+    const int tiles_n = (p.N + 15) / 16;
+    const int m0 = (blockIdx.x / tiles_n) * 16, n0 = (blockIdx.x % tiles_n) * 16;
+    if (m0 >= M) return;
+    const int nseg = (p.K + SEG - 1) / SEG;
+    const int li = lane & 15, kq = lane >> 4;
+    // after the fold, thread (w < 4, lane) owns accumulator register w of lane `lane`: row 4 kq + w, column li
+    const auto col = make_col(p, min(n0 + li, p.N - 1));
+
+    typename P::CtxA ca[NA];
+    typename P::CtxB cb[NB];
+    int ka[NA], kb[NB], la[NA], lb[NB];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int id = lane + i * 64, r = id / (SEG / VA);
+        ka[i] = (id % (SEG / VA)) * VA;
+        la[i] = r * LS + ka[i];
+        ca[i] = make_ctx_a(p, m0 + r, zb);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int id = lane + i * 64, r = id / (SEG / VB);
+        kb[i] = (id % (SEG / VB)) * VB;
+        lb[i] = r * LS + kb[i];
+        cb[i] = make_ctx_b(p, n0 + r, zb);
+    }
+    auto segment_sum = [&](int seg) -> f32x4 {
+        const int kbeg = seg * SEG, kend = min(p.K, kbeg + SEG);
+        Vec<T, VA> ra[NA];
+        Vec<T, VB> rb[NB];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ra[i] = p.load_a(ca[i], kbeg + ka[i], kend);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) rb[i] = p.load_b(cb[i], kbeg + kb[i], kend);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<Vec<T, VA> *>(As + la[i]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<Vec<T, VB> *>(Bs + lb[i]) = rb[i];
+        // the panels are private to this wavefront and a wavefront's LDS operations execute in order
+        __builtin_amdgcn_wave_barrier();
+        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (sizeof(T) == 4) {        // slot t: lane (i, q) supplies k = 4 t + q
+            const T *a = As + li * LS + kq, *b = Bs + li * LS + kq;
+#pragma unroll
+            for (int t = 0; t < SEG / 4; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[4 * t], b[4 * t], acc, 0, 0, 0);
+        } else {                               // slot t: lane (i, q) supplies k = 32 t + 8 q .. + 7
+            const T *a = As + li * LS + 8 * kq, *b = Bs + li * LS + 8 * kq;
+#pragma unroll
+            for (int t = 0; t < SEG / 32; ++t)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8 *>(a + 32 * t),
+                                                              *reinterpret_cast<const bf16x8 *>(b + 32 * t), acc, 0, 0, 0);
+        }
+        return acc;
+    };
+
+    float total = 0.0f;
+    const int gbeg = blockIdx.y * spg, gend = min(nseg, gbeg + spg);
+    const int rounds = (gend - gbeg + WAVES - 1) / WAVES;
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int seg = gbeg + rd * WAVES + w;
+        if (seg < gend) {
+            const f32x4 acc = segment_sum(seg);
+            float *mine = reinterpret_cast<float *>(smem + (size_t)w * PANEL_BYTES);     // the panels are free again
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[r * 64 + lane] = acc[r];
+        }
+        __syncthreads();
+        const int live = min(WAVES, gend - gbeg - rd * WAVES);
+        if (w < 4) {
+            float v[WAVES];
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww)        // all reads first, then the additions in wave (= segment) order
+                v[ww] = reinterpret_cast<const float *>(smem + (size_t)ww * PANEL_BYTES)[tid];
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww)
+                if (ww < live) total += v[ww];
+        }
+        __syncthreads();
+    }
+    if (w < 4) {
+        const int m = m0 + 4 * kq + w, n = n0 + li;
+        if (m < M && n < p.N) do_store(p, m, n, total, (int)blockIdx.y, zb, col);
+    }
+}
+
+template <class P, int WAVES, int SEG> inline hipError_t launch_wsgemm16(const P &p, hipStream_t stream, int segs_per_group = 1 << 30)
+{
+    const int tiles = ((grid_rows(p) + 15) / 16) * ((p.N + 15) / 16);
+    const int nseg = (p.K + SEG - 1) / SEG;
+    if (tiles <= 0 || nseg <= 0) return hipSuccess;
+    using T = typename P::T;
+    const size_t lds = (size_t)WAVES * 2 * 16 * (SEG + OperandTraits<T>::VEC) * sizeof(T);
+    auto kern = wsgemm16_kernel<P, WAVES, SEG>;
+    static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int spg = segs_per_group < nseg ? segs_per_group : nseg;
+    hipLaunchKernelGGL(kern, dim3(tiles, (nseg + spg - 1) / spg, grid_batches(p)), dim3(WAVES * 64, 1, 1), lds, stream, p, spg);
+    return hipGetLastError();
+}
+
 template <class P, int WAVES, int SEG, bool PARTIAL, bool BDIR = false>
 inline hipError_t launch_wsgemm(const P &p, hipStream_t stream, int segs_per_group = 1 << 30)
 {

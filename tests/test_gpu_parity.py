@@ -194,8 +194,14 @@ def test_act_small_and_large_batch_kernels_agree_bitwise(hts, shape, A, prec, mo
     outs = []
     # all small / all tile kernels / mixed (the 40-batch is "large", splits small) / tile kernels with the FC layer's
     # groups added inside the FC kernel (the form large batches take) instead of by the heads kernel
-    for knob, fold in (("128", None), ("0", None), ("16", None), ("0", "1")):
+    # ... and the wave-per-segment kernels with 32x32 tiles only / with 16x16 tiles in every layer
+    for knob, fold, t16 in (("128", None, None), ("0", None, None), ("16", None, None), ("0", "1", None),
+                            ("128", None, "0"), ("128", None, "100000")):
         monkeypatch.setenv("HTS_SMALL_BATCH", knob)
+        if t16 is None:
+            monkeypatch.delenv("HTS_TILE16_BELOW", raising=False)
+        else:
+            monkeypatch.setenv("HTS_TILE16_BELOW", t16)
         if fold is None:
             monkeypatch.delenv("HTS_FC_FOLD_ROWS", raising=False)
         else:
