@@ -211,9 +211,9 @@ struct HeadsArgs {
 template <bool LEARN>
 __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
 {
-    extern __shared__ float heads_lds[];          // [4 wavefronts][A][65]
+    extern __shared__ float heads_lds[];          // [wavefronts of the workgroup][A][65]
     const int lane = threadIdx.x & 63;
-    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);     // one sample per wavefront
     if (b >= a.B) return;                        // whole wavefront leaves together; no block-level barrier below
     const int A = a.A;
 
@@ -415,7 +415,11 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
     }
 }
 
-static size_t heads_lds_bytes(int A) { return (size_t)4 * A * 65 * sizeof(float); }
+// Wavefronts per workgroup.  A wavefront fetches about 40 KB (the policy head's weights and its sample's FC partial
+// sums); with few samples one wavefront per workgroup spreads those fetches over as many compute units as there are
+// samples instead of queueing four wavefronts' worth behind one L1.
+static int heads_waves(int rows) { return rows <= 512 ? 1 : 4; }
+static size_t heads_lds_bytes(int A, int waves) { return (size_t)waves * A * 65 * sizeof(float); }
 static hipError_t raise_lds_limit(const void *fn, size_t bytes)
 {
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
@@ -439,9 +443,10 @@ hipError_t launch_heads_act(Ctx &c, const float *logits_in, uint64_t seed, uint3
     a.B = N; a.A = c.g.A;
     a.seed = seed; a.step = step; a.env_offset = env_offset;
     a.actions = actions; a.logp = logp; a.values = values; a.logits_out = logits_out;
-    const size_t lds = heads_lds_bytes(c.g.A);
+    const int wv = heads_waves(N);
+    const size_t lds = heads_lds_bytes(c.g.A, wv);
     if (lds > 65536) { const hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(heads_kernel<false>), lds); if (e != hipSuccess) return e; }
-    hipLaunchKernelGGL(heads_kernel<false>, dim3((N + 3) / 4), dim3(256), lds, c.stream, a);
+    hipLaunchKernelGGL(heads_kernel<false>, dim3((N + wv - 1) / wv), dim3(64 * wv), lds, c.stream, a);
     return hipGetLastError();
 }
 
@@ -454,9 +459,10 @@ hipError_t launch_heads_learn(Ctx &c, const LossArgs &la, int B)
     a.B = B; a.A = c.g.A;
     a.la = la;
     a.dz = c.ws.dz; a.dh = c.ws.dh; a.terms = c.ws.terms;
-    const size_t lds = heads_lds_bytes(c.g.A);
+    const int wv = heads_waves(B);
+    const size_t lds = heads_lds_bytes(c.g.A, wv);
     if (lds > 65536) { const hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(heads_kernel<true>), lds); if (e != hipSuccess) return e; }
-    hipLaunchKernelGGL(heads_kernel<true>, dim3((B + 3) / 4), dim3(256), lds, c.stream, a);
+    hipLaunchKernelGGL(heads_kernel<true>, dim3((B + wv - 1) / wv), dim3(64 * wv), lds, c.stream, a);
     return hipGetLastError();
 }
 
