@@ -315,8 +315,11 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
                 a.out = (bf16_t *)c.ws.dy2; a.B = B;
                 e = launch_imgconv<ImgDgrad<64, 3, 1, 9, 9, 6>>(a, c.stream);
             } else
-            // fp32: eight segments of 72 for eight wavefronts, and panels small enough for two workgroups per compute unit
-            e = small ? launch_wsgemm<ConvDgrad<T, Layer3>, (sizeof(T) == 4 ? 8 : 4), (sizeof(T) == 2 ? 192 : 72), false, true>(p, c.stream) : launch_gemm(p, c.stream);
+            // binary32: eight segments of 72 for eight wavefronts, both operands through LDS: a lane that fetches its own
+            // weight column touches 32 cache lines per load instruction, and with sixteen wavefronts on a compute unit
+            // the L1's address processing was the whole issue phase (24.2 -> 19.3 us at 80 rows).  bfloat16 rows are
+            // half as long and the direct form stays faster there (11.6 vs 17.2 us).
+            e = small ? launch_wsgemm<ConvDgrad<T, Layer3>, (sizeof(T) == 4 ? 8 : 4), (sizeof(T) == 2 ? 192 : 72), false, (sizeof(T) == 2)>(p, c.stream) : launch_gemm(p, c.stream);
         }
         if (e != hipSuccess) return e;
     }

@@ -31,11 +31,15 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
     using Tr = OperandTraits<T>;
     constexpr int LS = SEG + Tr::PAD;
     constexpr int VA = P::VA, VB = P::VB;
-    // work items per operand panel: a k-contiguous vector (ALONG_K) or a V x V block to transpose (otherwise)
-    constexpr int CA = P::A_ALONG_K ? 32 * SEG / VA : (32 / VA) * (SEG / VA);
-    constexpr int CB = P::B_ALONG_K ? 32 * SEG / VB : (32 / VB) * (SEG / VB);
+    // work items per operand panel: a k-contiguous vector (ALONG_K); otherwise (operand contiguous along its rows) a
+    // V x V block to transpose in registers (bfloat16: LDS rows are then written 16 bytes at a time), or for binary32 a
+    // single vector of V rows at ONE k -- neighbouring lanes then fetch neighbouring vectors of the same k, whole cache
+    // lines per load instruction instead of one line per lane (LDS rows are written element by element either way).
+    constexpr bool NAT_A = !P::A_ALONG_K && sizeof(T) == 4, NAT_B = !P::B_ALONG_K && sizeof(T) == 4;
+    constexpr int CA = P::A_ALONG_K ? 32 * SEG / VA : NAT_A ? (32 / VA) * SEG : (32 / VA) * (SEG / VA);
+    constexpr int CB = P::B_ALONG_K ? 32 * SEG / VB : NAT_B ? (32 / VB) * SEG : (32 / VB) * (SEG / VB);
     constexpr int NA = (CA + 63) / 64, NB = (CB + 63) / 64;
-    constexpr int RA = P::A_ALONG_K ? 1 : VA, RB = P::B_ALONG_K ? 1 : VB;
+    constexpr int RA = (P::A_ALONG_K || NAT_A) ? 1 : VA, RB = (P::B_ALONG_K || NAT_B) ? 1 : VB;
     static_assert(SEG % Tr::KINST == 0 && SEG % VA == 0 && SEG % VB == 0 && 32 % VA == 0 && 32 % VB == 0, "segment shape");
     constexpr size_t PANEL_BYTES = (size_t)(BDIR ? 1 : 2) * 32 * LS * sizeof(T);   // operand panel(s) of one wavefront
     static_assert(PARTIAL || PANEL_BYTES >= 4096, "the fold reuses a wavefront's panels for its 32x32 partial tile");
@@ -60,6 +64,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         const int id = lane + i * 64;
         int r;
         if constexpr (P::A_ALONG_K) { r = id / (SEG / VA); ka[i] = (id % (SEG / VA)) * VA; }
+        else if constexpr (NAT_A) { r = (id % (32 / VA)) * VA; ka[i] = id / (32 / VA); }
         else { r = (id / (SEG / VA)) * VA; ka[i] = (id % (SEG / VA)) * VA; }   // neighbours write one LDS row
         la[i] = r * LS + ka[i];
         ca[i] = make_ctx_a(p, m0 + r, zb);
@@ -69,6 +74,7 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
         const int id = lane + i * 64;
         int r;
         if constexpr (P::B_ALONG_K) { r = id / (SEG / VB); kb[i] = (id % (SEG / VB)) * VB; }
+        else if constexpr (NAT_B) { r = (id % (32 / VB)) * VB; kb[i] = id / (32 / VB); }
         else { r = (id / (SEG / VB)) * VB; kb[i] = (id % (SEG / VB)) * VB; }
         lb[i] = r * LS + kb[i];
         cb[i] = make_ctx_b(p, n0 + r, zb);
@@ -114,6 +120,9 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
 #pragma unroll
                     for (int j = 0; j < VA; ++j) d[j] = ra[i][0][j];
                 }
+            } else if constexpr (NAT_A) {
+#pragma unroll
+                for (int j = 0; j < VA; ++j) d[j * LS] = ra[i][0][j];
             } else {
 #pragma unroll
                 for (int j = 0; j < VA; ++j) {
@@ -138,6 +147,9 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
 #pragma unroll
                     for (int j = 0; j < VB; ++j) d[j] = rb[i][0][j];
                 }
+            } else if constexpr (NAT_B) {
+#pragma unroll
+                for (int j = 0; j < VB; ++j) d[j * LS] = rb[i][0][j];
             } else {
 #pragma unroll
                 for (int j = 0; j < VB; ++j) {
@@ -235,10 +247,19 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
             }
             __syncthreads();
             const int live = min(WAVES, gend - gbeg - rd * WAVES);
+            // all reads first (a panel that carries nothing this round is read and ignored), then the additions in
+            // wave (= segment) order: one LDS round trip instead of one per partial tile
+            float v[PER][WAVES];
 #pragma unroll
             for (int e = 0; e < PER; ++e)
-                for (int ww = 0; ww < live; ++ww)
-                    total[e] += reinterpret_cast<const float *>(smem + (size_t)ww * PANEL_BYTES)[e * (WAVES * 64) + tid];
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww)
+                    v[e][ww] = reinterpret_cast<const float *>(smem + (size_t)ww * PANEL_BYTES)[e * (WAVES * 64) + tid];
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww)
+                    if (ww < live) total[e] += v[e][ww];
             __syncthreads();
         }
         // element e of this thread is accumulator register r = e*WAVES + w of lane `lane`: one column per thread
