@@ -305,8 +305,8 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm16_kernel(const P p, const i
     constexpr int VA = P::VA, VB = P::VB;
     constexpr int KI = sizeof(T) == 4 ? 4 : 32;          // k per matrix instruction
     static_assert(P::A_ALONG_K && P::B_ALONG_K, "k-contiguous operands");
-    static_assert(WAVES >= 4 && SEG % KI == 0 && (16 * SEG / VA) % 64 == 0 && (16 * SEG / VB) % 64 == 0,
-                  "four wavefronts own the fold; whole rounds of loads");
+    static_assert(WAVES >= 4 && SEG % KI == 0 && SEG % (4 * VA) == 0 && SEG % (4 * VB) == 0,
+                  "four wavefronts own the fold; four lanes share a panel row");
     constexpr int LS = SEG + Tr::VEC;         // row pitch: a 16-byte step per row, so the 64 lanes of an operand read
                                               // (row i, k slot q) spread evenly over the banks
     constexpr int NA = 16 * SEG / VA / 64, NB = 16 * SEG / VB / 64;     // vectors per lane and panel
@@ -324,35 +324,24 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm16_kernel(const P p, const i
     // after the fold, thread (w < 4, lane) owns accumulator register w of lane `lane`: row 4 kq + w, column li
     const auto col = make_col(p, min(n0 + li, p.N - 1));
 
-    typename P::CtxA ca[NA];
-    typename P::CtxB cb[NB];
-    int ka[NA], kb[NB], la[NA], lb[NB];
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int id = lane + i * 64, r = id / (SEG / VA);
-        ka[i] = (id % (SEG / VA)) * VA;
-        la[i] = r * LS + ka[i];
-        ca[i] = make_ctx_a(p, m0 + r, zb);
-    }
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        const int id = lane + i * 64, r = id / (SEG / VB);
-        kb[i] = (id % (SEG / VB)) * VB;
-        lb[i] = r * LS + kb[i];
-        cb[i] = make_ctx_b(p, n0 + r, zb);
-    }
+    // Four lanes share a panel row and take its vectors in turn, so a lane resolves ONE row of each operand (the
+    // position decomposition of a gather is most of the arithmetic in front of the loads: with a different row per
+    // item the kernel spent 300 vector instructions between its first and its last load).
+    const int pr = lane >> 2, pq = lane & 3;
+    const typename P::CtxA ca = make_ctx_a(p, m0 + pr, zb);
+    const typename P::CtxB cb = make_ctx_b(p, n0 + pr, zb);
     auto segment_sum = [&](int seg) -> f32x4 {
         const int kbeg = seg * SEG, kend = min(p.K, kbeg + SEG);
         Vec<T, VA> ra[NA];
         Vec<T, VB> rb[NB];
 #pragma unroll
-        for (int i = 0; i < NA; ++i) ra[i] = p.load_a(ca[i], kbeg + ka[i], kend);
+        for (int i = 0; i < NA; ++i) ra[i] = p.load_a(ca, kbeg + (pq + 4 * i) * VA, kend);
 #pragma unroll
-        for (int i = 0; i < NB; ++i) rb[i] = p.load_b(cb[i], kbeg + kb[i], kend);
+        for (int i = 0; i < NB; ++i) rb[i] = p.load_b(cb, kbeg + (pq + 4 * i) * VB, kend);
 #pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<Vec<T, VA> *>(As + la[i]) = ra[i];
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<Vec<T, VA> *>(As + pr * LS + (pq + 4 * i) * VA) = ra[i];
 #pragma unroll
-        for (int i = 0; i < NB; ++i) *reinterpret_cast<Vec<T, VB> *>(Bs + lb[i]) = rb[i];
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<Vec<T, VB> *>(Bs + pr * LS + (pq + 4 * i) * VB) = rb[i];
         // the panels are private to this wavefront and a wavefront's LDS operations execute in order
         __builtin_amdgcn_wave_barrier();
         f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
