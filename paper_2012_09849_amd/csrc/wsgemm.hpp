@@ -59,25 +59,35 @@ __global__ __launch_bounds__(WAVES * 64) void wsgemm_kernel(const P p, const int
     typename P::CtxA ca[NA];
     typename P::CtxB cb[NB];
     int ka[NA], kb[NB], la[NA], lb[NB];
+    // k-contiguous operands: four lanes share a panel row and take its vectors in turn, a lane serves rows pr and
+    // pr + 16 -- two row contexts per lane instead of one per item (the position decomposition of a gather is most of
+    // the arithmetic in front of the loads).  Segments that do not split into four vectors per lane keep one
+    // context per item.
+    constexpr bool ROWS_A = P::A_ALONG_K && SEG % (4 * VA) == 0, ROWS_B = P::B_ALONG_K && SEG % (4 * VB) == 0;
+    const int pr = lane >> 2, pq = lane & 3;
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int id = lane + i * 64;
         int r;
-        if constexpr (P::A_ALONG_K) { r = id / (SEG / VA); ka[i] = (id % (SEG / VA)) * VA; }
+        if constexpr (ROWS_A) { r = pr + 16 * (i / (NA / 2)); ka[i] = (pq + 4 * (i % (NA / 2))) * VA; }
+        else if constexpr (P::A_ALONG_K) { r = id / (SEG / VA); ka[i] = (id % (SEG / VA)) * VA; }
         else if constexpr (NAT_A) { r = (id % (32 / VA)) * VA; ka[i] = id / (32 / VA); }
         else { r = (id / (SEG / VA)) * VA; ka[i] = (id % (SEG / VA)) * VA; }   // neighbours write one LDS row
         la[i] = r * LS + ka[i];
-        ca[i] = make_ctx_a(p, m0 + r, zb);
+        if (ROWS_A && i % (NA / 2 > 0 ? NA / 2 : 1) != 0) ca[i] = ca[i - 1];     // same row as the item before
+        else ca[i] = make_ctx_a(p, m0 + r, zb);
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int id = lane + i * 64;
         int r;
-        if constexpr (P::B_ALONG_K) { r = id / (SEG / VB); kb[i] = (id % (SEG / VB)) * VB; }
+        if constexpr (ROWS_B) { r = pr + 16 * (i / (NB / 2)); kb[i] = (pq + 4 * (i % (NB / 2))) * VB; }
+        else if constexpr (P::B_ALONG_K) { r = id / (SEG / VB); kb[i] = (id % (SEG / VB)) * VB; }
         else if constexpr (NAT_B) { r = (id % (32 / VB)) * VB; kb[i] = id / (32 / VB); }
         else { r = (id / (SEG / VB)) * VB; kb[i] = (id % (SEG / VB)) * VB; }
         lb[i] = r * LS + kb[i];
-        cb[i] = make_ctx_b(p, n0 + r, zb);
+        if (ROWS_B && i % (NB / 2 > 0 ? NB / 2 : 1) != 0) cb[i] = cb[i - 1];
+        else cb[i] = make_ctx_b(p, n0 + r, zb);
     }
     constexpr bool VEC_LDS = sizeof(T) == 2;
     const typename P::CtxB cbd = make_ctx_b(p, n0 + lrow, zb);      // this lane's own column (direct B operands)
