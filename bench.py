@@ -275,12 +275,13 @@ def source_digest():
     return h.hexdigest()[:16]
 
 
-# HBM bytes per launch of a workload's dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per
-# dispatch, averaged over the run, each scaled by what the counter reads for a plain copy of known size):
-# workload -> (launch site, bytes per launch, digest of the kernel sources the counters were taken on).
+# HBM bytes per launch of the launch sites that can come out as a workload's dominant kernel, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE (KiB per dispatch, averaged over the site's launches of the run, each scaled by what the
+# counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
+# sources the counters were taken on).
 TRAFFIC = {
-    "atari_a2c_n16_t5_fp32": ("conv3_fwd", 3654776, "965b5374c23cf160"),
-    "atari_ppo_n32_t128_bf16": ("conv1_fwd", 9858965, "965b5374c23cf160"),
+    "atari_a2c_n16_t5_fp32": ({"conv1_fwd": 4767392, "conv2_fwd": 6709976, "conv3_fwd": 3625334}, "ebc774ae549a6019"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 9854113}, "ebc774ae549a6019"),
 }
 
 
@@ -402,8 +403,8 @@ def main():
     launches_per_step = per_step[dominant][1]
     avg_s = max(ms_timed / max(n_timed, 1) - overhead_ms, 1e-6) * 1e-3
     traffic = None
-    if args.workload in TRAFFIC and TRAFFIC[args.workload][0] == dominant and TRAFFIC[args.workload][2] == source_digest():
-        traffic = TRAFFIC[args.workload][1]
+    if args.workload in TRAFFIC and dominant in TRAFFIC[args.workload][0] and TRAFFIC[args.workload][1] == source_digest():
+        traffic = TRAFFIC[args.workload][0][dominant]
     per_launch = amount / launches_per_step
     if kind == "flop":
         peak = PEAK["mfma_f32"] if cfg["precision"] == 0 else PEAK["mfma_bf16"]
