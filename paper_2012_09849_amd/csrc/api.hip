@@ -252,14 +252,15 @@ extern "C" int32_t hts_loss_and_grads(hts_ctx *ctx, const hts_buffer *buf, const
     const int32_t rc2 = loss_and_grads(c, buf, params, hp, grads);
     if (rc2 != HTS_OK) return rc2;
     if (stats_or_null) {
-        HIP_TRY(launch_grad_norm(c, grads, c.g.P, 0.0f, nullptr));
+        HIP_TRY(launch_grad_norm(c, grads, c.g.P, 0.0f, true));
         HIP_TRY(launch_stats(c, buf->B, stats_or_null));
     }
     return HTS_OK;
 }
 
+// have_norm: 0 = nothing computed yet, 1 = the per-chunk sums of squares are in the workspace, 2 = the clip factor too
 static int32_t adam_apply(Ctx &c, float *params, const float *grads, hts_opt_state *opt, const hts_hparams *hp,
-                          long long P, bool have_norm)
+                          long long P, int have_norm)
 {
     const int64_t t = opt->step + 1;
     if (hp->optimizer != HTS_OPT_ADAM && hp->optimizer != HTS_OPT_RMSPROP) return HTS_EINVAL;
@@ -269,9 +270,11 @@ static int32_t adam_apply(Ctx &c, float *params, const float *grads, hts_opt_sta
     const float bc1 = rms ? 1.0f : (float)(1.0 - pow((double)hp->beta1, (double)t));
     const float bc2 = rms ? 1.0f : (float)(1.0 - pow((double)hp->beta2, (double)t));
     const bool clip = hp->max_grad_norm > 0.0f;
-    if (clip && !have_norm) HIP_TRY(launch_grad_norm(c, grads, P, hp->max_grad_norm, nullptr));
-    HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, clip ? c.ws.clip : nullptr, hp->lr, b1, b2, hp->adam_eps,
-                        bc1, bc2));
+    // the optimiser kernel forms the clip factor from the per-chunk sums itself unless it already exists
+    if (clip && have_norm == 0) { HIP_TRY(launch_grad_norm(c, grads, P, hp->max_grad_norm, false)); have_norm = 1; }
+    HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, clip && have_norm == 2 ? c.ws.clip : nullptr,
+                        clip && have_norm == 1 ? c.ws.norm_part : nullptr, hp->max_grad_norm, hp->lr, b1, b2,
+                        hp->adam_eps, bc1, bc2));
     opt->step = t;
     c.synced = false; c.synced_learn = false;     // the caller's vector has moved on; the workspace copy has not
     return HTS_OK;
@@ -287,10 +290,11 @@ static int32_t learner_step(hts_ctx *ctx, const hts_buffer *buf, const float *pa
     Ctx &c = ctx->c;
     const int32_t rc2 = loss_and_grads(c, buf, params_grad, hp, c.ws.grads);
     if (rc2 != HTS_OK) return rc2;
+    // statistics need the norm itself; without them the optimiser kernel finishes the clip factor
     const bool need_norm = hp->max_grad_norm > 0.0f || stats_or_null;
-    if (need_norm) HIP_TRY(launch_grad_norm(c, c.ws.grads, c.g.P, hp->max_grad_norm, nullptr));
+    if (need_norm) HIP_TRY(launch_grad_norm(c, c.ws.grads, c.g.P, hp->max_grad_norm, stats_or_null != nullptr));
     if (stats_or_null) HIP_TRY(launch_stats(c, buf->B, stats_or_null));
-    return adam_apply(c, params, c.ws.grads, opt, hp, c.g.P, need_norm);
+    return adam_apply(c, params, c.ws.grads, opt, hp, c.g.P, need_norm ? (stats_or_null ? 2 : 1) : 0);
 }
 
 extern "C" int32_t hts_learner_step(hts_ctx *ctx, const hts_buffer *buf, float *params, hts_opt_state *opt,

@@ -134,8 +134,9 @@ constexpr int HEADS_MAXZ = 16;      // most chunks the heads weight gradient's r
 hipError_t launch_gae(Ctx *c, hipStream_t s, const float *r, const float *v, const uint8_t *d, float gamma, float lambda, int T,
                       int N, float *adv, float *ret);
 hipError_t launch_normalize(Ctx *c, hipStream_t s, float *adv, long long n);
-hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, hts_stats *stats);
+hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, bool finalize);
 hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale_or_null,
-                       float lr, float b1, float b2, float eps, float bc1, float bc2);
+                       const float *norm_part_or_null, float max_norm, float lr, float b1, float b2, float eps, float bc1,
+                       float bc2);
 
 }  // namespace hts

@@ -784,10 +784,9 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const float *__restrict__ g,
     if (t == 0) part[blockIdx.x] = red[0];
 }
 
-__global__ __launch_bounds__(256) void clip_finalize_kernel(const float *__restrict__ part, int nparts, float max_norm,
-                                                            float *__restrict__ clip)
+// ||g|| from the per-chunk sums, added in a fixed order by one workgroup of 256 threads (every thread gets the result)
+__device__ __forceinline__ float norm_from_parts(const float *__restrict__ part, int nparts, float *red)
 {
-    __shared__ float red[256];
     const int t = threadIdx.x;
     float s = 0.0f;
     for (int i = t; i < nparts; i += 256) s += part[i];
@@ -797,22 +796,34 @@ __global__ __launch_bounds__(256) void clip_finalize_kernel(const float *__restr
         if (t < w) red[t] += red[t + w];
         __syncthreads();
     }
-    if (t == 0) {
-        const float nrm = sqrtf(red[0]);
-        float sc = 1.0f;
-        if (max_norm > 0.0f) sc = fminf(1.0f, max_norm / (nrm + 1e-6f));
-        clip[0] = sc;
+    return sqrtf(red[0]);
+}
+__device__ __forceinline__ float clip_scale(float nrm, float max_norm)
+{
+    return max_norm > 0.0f ? fminf(1.0f, max_norm / (nrm + 1e-6f)) : 1.0f;
+}
+
+__global__ __launch_bounds__(256) void clip_finalize_kernel(const float *__restrict__ part, int nparts, float max_norm,
+                                                            float *__restrict__ clip)
+{
+    __shared__ float red[256];
+    const float nrm = norm_from_parts(part, nparts, red);
+    if (threadIdx.x == 0) {
+        clip[0] = clip_scale(nrm, max_norm);
         clip[1] = nrm;
     }
 }
 
-hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, hts_stats *)
+// finalize = false leaves the per-chunk sums in the workspace for the optimiser kernel, which then forms the norm and the
+// clip factor itself (the same additions in the same order, in every workgroup): one launch less per update
+hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, bool finalize)
 {
     SiteTimer tm(c, SITE_GRAD_NORM);
     const int nparts = (int)((P + NORM_CHUNK - 1) / NORM_CHUNK);
     hipLaunchKernelGGL(sumsq_kernel, dim3(nparts), dim3(256), 0, c.stream, g, P, c.ws.norm_part);
-    hipLaunchKernelGGL(clip_finalize_kernel, dim3(1), dim3(256), 0, c.stream, c.ws.norm_part, nparts, max_norm,
-                       c.ws.clip);
+    if (finalize)
+        hipLaunchKernelGGL(clip_finalize_kernel, dim3(1), dim3(256), 0, c.stream, c.ws.norm_part, nparts, max_norm,
+                           c.ws.clip);
     return hipGetLastError();
 }
 
@@ -831,10 +842,15 @@ __device__ __forceinline__ void adam_one(float &th, float g, float &m, float &v,
 template <bool VEC4>
 __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ theta, const float *__restrict__ g,
                                                    float *__restrict__ m, float *__restrict__ v, long long P,
-                                                   const float *__restrict__ scale, float lr, float b1, float b2,
+                                                   const float *__restrict__ scale, const float *__restrict__ norm_part,
+                                                   int nparts, float max_norm, float lr, float b1, float b2,
                                                    float eps, float ibc1, float ibc2)
 {
-    const float gs = scale ? scale[0] : 1.0f;
+    // the clip factor: given (scale), or formed here from the per-chunk sums of squares (norm_part), or none
+    __shared__ float red[256];
+    float gs = 1.0f;
+    if (norm_part) gs = clip_scale(norm_from_parts(norm_part, nparts, red), max_norm);
+    else if (scale) gs = scale[0];
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if constexpr (VEC4) {
         const long long o = i * 4;
@@ -860,18 +876,19 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ theta, co
 }
 
 hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale,
-                       float lr, float b1, float b2, float eps, float bc1, float bc2)
+                       const float *norm_part, float max_norm, float lr, float b1, float b2, float eps, float bc1, float bc2)
 {
+    const int nparts = (int)((P + NORM_CHUNK - 1) / NORM_CHUNK);
     SiteTimer tm(c, SITE_ADAM);
     const bool aligned = (((uintptr_t)theta | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15u) == 0;
     const float ibc1 = 1.0f / bc1, ibc2 = 1.0f / bc2;
     if (aligned) {
         const long long nthreads = (P + 3) / 4;
         hipLaunchKernelGGL(adam_kernel<true>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, c.stream, theta, g,
-                           m, v, P, scale, lr, b1, b2, eps, ibc1, ibc2);
+                           m, v, P, scale, norm_part, nparts, max_norm, lr, b1, b2, eps, ibc1, ibc2);
     } else {
         hipLaunchKernelGGL(adam_kernel<false>, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, c.stream, theta, g, m, v,
-                           P, scale, lr, b1, b2, eps, ibc1, ibc2);
+                           P, scale, norm_part, nparts, max_norm, lr, b1, b2, eps, ibc1, ibc2);
     }
     return hipGetLastError();
 }
