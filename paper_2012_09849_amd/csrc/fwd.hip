@@ -170,7 +170,7 @@ static hipError_t launch_conv1_image(Ctx &c, const uint8_t *obs, const int32_t *
 template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, const int32_t *index, int B, bool learn)
 {
     const Geom &g = c.g;
-    hipError_t e;
+    hipError_t e = hipSuccess;
     const bool small = B <= c.small_b;
     const float *hb = c.ws.hb;
     // Small batches whose layer has fewer 32x32 output tiles (workgroups) than a threshold take 16x16 tiles: four
