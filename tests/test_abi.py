@@ -51,3 +51,13 @@ def test_null_arguments_rejected_without_gpu():
     assert lib.hts_destroy(None) == -1
     assert lib.hts_returns_gae(None, None, None, None, 0.99, 0.95, 4, 4, None, None) == -1
     assert lib.hts_act(None, None, None, 0, 0, 1, 0, None, None, None, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more exits with a message before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
