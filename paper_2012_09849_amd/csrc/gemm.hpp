@@ -341,8 +341,13 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     typename P::CtxB cb[NB];
     int ka[NA], kb[NB], la[NA], lb[NB];          // k offset inside the tile, LDS offset
 #pragma unroll
+    // When an operand tile has fewer items than the workgroup has threads (or a last, partial round of them), the
+    // spare threads repeat other threads' items -- same loads, same LDS stores of the same values -- instead of
+    // sitting out: an `if (owns an item)` around a store puts the store in a branch, and in a branch the compiler
+    // waits for EVERY outstanding load, the prefetched tile's included (conv1 on 16-channel frames, whose weight tile
+    // has 256 items for 512 threads, stalled 1600 cycles every second k-tile that way).
     for (int i = 0; i < NA; ++i) {
-        const int id = tid + i * NT;
+        const int id = CA % NT == 0 ? tid + i * NT : (tid + i * NT) % CA;
         int r;
         if constexpr (P::A_ALONG_K) { r = id / (BK / VA); ka[i] = (id % (BK / VA)) * VA; }
         else if constexpr (NAT_A) { r = (id % (BM / VA)) * VA; ka[i] = id / (BM / VA); }
@@ -352,7 +357,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-        const int id = tid + i * NT;
+        const int id = CB % NT == 0 ? tid + i * NT : (tid + i * NT) % CB;
         int r;
         if constexpr (P::B_ALONG_K) { r = id / (BK / VB); kb[i] = (id % (BK / VB)) * VB; }
         else if constexpr (NAT_B) { r = (id % (BN / VB)) * VB; kb[i] = id / (BN / VB); }
@@ -371,7 +376,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     auto gload = [&](int k0, Vec<T, VA> (&ra)[NA][RA], Vec<T, VB> (&rb)[NB][RB], int lim) {
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-            if (CA % NT == 0 || tid + i * NT < CA) {
+            {
                 if constexpr (!P::A_ALONG_K && !NAT_A && HasRunA<P>::value) p.load_a_run(ca[i], k0 + ka[i], lim, ra[i]);
                 else {
 #pragma unroll
@@ -380,7 +385,7 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
             }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            if (CB % NT == 0 || tid + i * NT < CB) {
+            {
                 if constexpr (!P::B_ALONG_K && !NAT_B && HasRunB<P>::value) p.load_b_run(cb[i], k0 + kb[i], lim, rb[i]);
                 else {
 #pragma unroll
@@ -391,7 +396,6 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
     auto sstore = [&](const Vec<T, VA> (&ra)[NA][RA], const Vec<T, VB> (&rb)[NB][RB]) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            if (CA % NT != 0 && tid + i * NT >= CA) continue;
             T *d = As + la[i];
             if constexpr (NAT_A) *reinterpret_cast<Vec<T, VA> *>(d) = ra[i][0];
             else if constexpr (P::A_ALONG_K) {
@@ -416,7 +420,6 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            if (CB % NT != 0 && tid + i * NT >= CB) continue;
             T *d = Bs + lb[i];
             if constexpr (NAT_B) *reinterpret_cast<Vec<T, VB> *>(d) = rb[i][0];
             else if constexpr (P::B_ALONG_K) {
@@ -519,9 +522,14 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
 
     f32x16 acc[TM][TN];
     clear(acc);
+    // (unconditional: a stage beyond the end of a short reduction range fetches the range's last k-tile once more and
+    // is never consumed -- a branch here leaves the compiler unsure how many loads are outstanding when the k loop
+    // starts, and it then waits for all of them at the top of every iteration)
 #pragma unroll
-    for (int s = 0; s < D; ++s)
-        if (kbeg + s * BK < kend) gload(kbeg + s * BK, rra[s], rrb[s], kend);
+    for (int s = 0; s < D; ++s) {
+        const int last = kbeg + ((kend - kbeg - 1) / BK) * BK;
+        gload(min(kbeg + s * BK, last), rra[s], rrb[s], kend);
+    }
     EpiInputs<P, TM, TN, SWAP> epi;
     auto fetch_epi = [&]() {
         if constexpr (SWAP) {
