@@ -20,12 +20,18 @@ _SRC = os.path.join(_HERE, "hts_oracle.c")
 _LIB = os.path.join(_HERE, "libhts_oracle.so")
 
 MAX_CONV = 4
+GRAD_SLOTS = 32       # slots of the threaded gradient (fixed, so that its result does not depend on the thread count)
+
+
+def host_threads() -> int:
+    """Worker threads for the threaded variants: the host's cores, at most 16."""
+    return max(1, min(16, os.cpu_count() or 1))
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
                "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
@@ -34,7 +40,7 @@ def build(force: bool = False) -> str:
 class Net(C.Structure):
     _fields_ = [("C", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("nconv", C.c_int32),
                 ("cout", C.c_int32 * MAX_CONV), ("ksz", C.c_int32 * MAX_CONV), ("stride", C.c_int32 * MAX_CONV),
-                ("hidden", C.c_int32), ("A", C.c_int32), ("operand_bf16", C.c_int32)]
+                ("hidden", C.c_int32), ("A", C.c_int32), ("operand_bf16", C.c_int32), ("gates_exact", C.c_int32)]
 
 
 class HParams(C.Structure):
@@ -52,9 +58,13 @@ class Stats(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
-def make_net(C_in, H, W, A, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512, operand_bf16=False) -> Net:
+def make_net(C_in, H, W, A, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512, operand_bf16=False,
+             gates_exact=False) -> Net:
+    """operand_bf16: every operand of a conv/FC matrix product (forward and backward) rounded to bfloat16;
+    gates_exact (with operand_bf16): the backward pass takes its ReLU gates from an unrounded forward pass."""
     n = Net()
     n.operand_bf16 = 1 if operand_bf16 else 0
+    n.gates_exact = 1 if gates_exact else 0
     n.C, n.H, n.W, n.A, n.hidden, n.nconv = C_in, H, W, A, hidden, len(convs)
     for i, (co, k, s) in enumerate(convs):
         n.cout[i], n.ksz[i], n.stride[i] = co, k, s
@@ -119,8 +129,8 @@ def round_bf16(x: float) -> float:
     return float(lib().orc_round_bf16(C.c_double(float(x))))
 
 
-def forward(net: Net, params, obs, index=None, B=None):
-    """-> logits float64 [B,A], values float64 [B]."""
+def forward(net: Net, params, obs, index=None, B=None, threads=1):
+    """-> logits float64 [B,A], values float64 [B].  threads > 1: rows spread over host threads (same values)."""
     p = _f64(params)
     obs = np.ascontiguousarray(obs, dtype=np.uint8).reshape(-1, net.C, net.H, net.W)
     idx = None if index is None else np.ascontiguousarray(index, dtype=np.int32)
@@ -128,7 +138,11 @@ def forward(net: Net, params, obs, index=None, B=None):
         B = obs.shape[0] if idx is None else idx.size
     logits = np.empty((B, net.A), dtype=np.float64)
     values = np.empty(B, dtype=np.float64)
-    rc = lib().orc_forward(C.byref(net), _ptr(p), _ptr(obs), _ptr(idx), C.c_int32(B), _ptr(logits), _ptr(values))
+    if threads > 1:
+        rc = lib().orc_forward_mt(C.byref(net), _ptr(p), _ptr(obs), _ptr(idx), C.c_int32(B), _ptr(logits),
+                                  _ptr(values), C.c_int32(threads))
+    else:
+        rc = lib().orc_forward(C.byref(net), _ptr(p), _ptr(obs), _ptr(idx), C.c_int32(B), _ptr(logits), _ptr(values))
     assert rc == 0
     return logits, values
 
@@ -179,15 +193,21 @@ def _buffer_args(net, obs, index, actions, old_logp, adv, ret, old_values=None):
 
 
 def loss_grads(net: Net, params, obs, actions, old_logp, adv, ret, hp: HParams, index=None, want_grads=True,
-               old_values=None):
-    """-> (grads float64 [P] or None, stats dict).  old_values is read only when hp.value_clip > 0."""
+               old_values=None, threads=1):
+    """-> (grads float64 [P] or None, stats dict).  old_values is read only when hp.value_clip > 0.
+    threads > 1: the rows are cut into GRAD_SLOTS slots, each a plain call, combined in slot order."""
     p = _f64(params)
     obs, idx, B, act, olp, ad, rt, olv = _buffer_args(net, obs, index, actions, old_logp, adv, ret, old_values)
     assert hp.value_clip <= 0 or olv is not None
     g = np.empty(p.size) if want_grads else None
     st = Stats()
-    rc = lib().orc_loss_grads(C.byref(net), _ptr(p), _ptr(obs), _ptr(idx), C.c_int32(B), _ptr(act), _ptr(olp),
-                              _ptr(olv), _ptr(ad), _ptr(rt), C.byref(hp), _ptr(g), C.byref(st))
+    if threads > 1:
+        rc = lib().orc_loss_grads_mt(C.byref(net), _ptr(p), _ptr(obs), _ptr(idx), C.c_int32(B), _ptr(act), _ptr(olp),
+                                     _ptr(olv), _ptr(ad), _ptr(rt), C.byref(hp), _ptr(g), C.byref(st),
+                                     C.c_int32(GRAD_SLOTS), C.c_int32(threads))
+    else:
+        rc = lib().orc_loss_grads(C.byref(net), _ptr(p), _ptr(obs), _ptr(idx), C.c_int32(B), _ptr(act), _ptr(olp),
+                                  _ptr(olv), _ptr(ad), _ptr(rt), C.byref(hp), _ptr(g), C.byref(st))
     assert rc == 0
     return g, st.as_dict()
 
@@ -207,8 +227,15 @@ def adam(theta, g, m, v, t: int, hp: HParams, gscale: float = 1.0):
 
 
 def learner_step(net: Net, params, m, v, t: int, obs, actions, old_logp, adv, ret, hp: HParams, index=None,
-                 old_values=None):
-    """-> (params, m, v, grads, stats), all new float64 arrays."""
+                 old_values=None, threads=1):
+    """-> (params, m, v, grads, stats), all new float64 arrays.  threads > 1: the threaded gradient, then the same
+    clip and optimiser step."""
+    if threads > 1:
+        g, st = loss_grads(net, params, obs, actions, old_logp, adv, ret, hp, index=index, old_values=old_values,
+                           threads=threads)
+        scale = clip_coef(g, hp.max_grad_norm) if hp.max_grad_norm > 0 else 1.0
+        th, m2, v2 = adam(params, g, m, v, t, hp, gscale=scale)
+        return th, m2, v2, g, st
     th, m2, v2 = _f64(params).copy(), _f64(m).copy(), _f64(v).copy()
     obs, idx, B, act, olp, ad, rt, olv = _buffer_args(net, obs, index, actions, old_logp, adv, ret, old_values)
     assert hp.value_clip <= 0 or olv is not None

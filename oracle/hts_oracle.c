@@ -47,10 +47,19 @@ typedef struct {
     int32_t stride[ORC_MAX_CONV]; /* stride                                           */
     int32_t hidden;               /* width of the fully connected layer               */
     int32_t A;                    /* number of actions                                */
-    int32_t operand_bf16;         /* 0: exact operands.  1: model of a reduced-precision matrix path -- conv and FC
-                                     weights and the stored outputs of the three conv layers are rounded to bfloat16
-                                     (round to nearest even) before use; sums, biases, FC output, heads and loss stay
-                                     exact.  Gradients treat the rounding as the identity.                          */
+    int32_t operand_bf16;         /* 0: exact operands.  1: model of a reduced-precision matrix path -- EVERY operand of
+                                     a matrix product of the conv and FC layers, in the forward and in the backward
+                                     pass, is rounded to bfloat16 (round to nearest even) before use: the conv and FC
+                                     weights, the outputs of the conv layers (inputs of the next product; pixels are
+                                     exact in bfloat16), and in the backward pass the gradients with respect to the
+                                     pre-activations of the FC and conv layers (operands of the weight-gradient and
+                                     input-gradient products, bias gradients included).  Sums, biases, the FC output,
+                                     heads, loss and optimiser stay exact.  Derivatives treat a rounding as the
+                                     identity.                                                                        */
+    int32_t gates_exact;          /* diagnostic, with operand_bf16 = 1 only: the ReLU gates of the backward pass are
+                                     those of an unrounded forward pass of the same sample, so that the difference to
+                                     the unrounded gradient is the accumulated operand rounding alone and the
+                                     difference to the operand_bf16 = 1 gradient is the effect of flipped gates.      */
 } orc_net;
 
 typedef struct {
@@ -365,6 +374,16 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
            *dh = malloc(sizeof(double) * Hd), *logits = malloc(sizeof(double) * A),
            *lp = malloc(sizeof(double) * A), *dl = malloc(sizeof(double) * A);
     if (!x || !act || !dact || !h || !dh || !logits || !lp || !dl) return -1;
+    /* gates_exact: outputs of an unrounded forward pass, consulted for the ReLU gates only */
+    const int exact_gates = n->operand_bf16 && n->gates_exact;
+    double *act_g = act, *h_g = h, *logits_g = NULL;
+    orc_net plain = *n; plain.operand_bf16 = 0;
+    if (exact_gates) {
+        act_g = malloc(sizeof(double) * s.act_total); h_g = malloc(sizeof(double) * Hd);
+        logits_g = malloc(sizeof(double) * A);
+        if (!act_g || !h_g || !logits_g) return -1;
+    }
+    const int rq = n->operand_bf16;           /* round the backward pass's matrix operands */
     if (grads) memset(grads, 0, sizeof(double) * (size_t)s.total);
 
     double sum_pi = 0.0, sum_v = 0.0, sum_h = 0.0, sum_clip = 0.0, sum_kl = 0.0;
@@ -373,6 +392,7 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
     for (int b = 0; b < B; ++b) {
         const int64_t row = index ? index[b] : b;
         double v;
+        if (exact_gates) { double v_g; forward_one(&plain, &s, params_in, obs + row * in_sz, x, act_g, h_g, logits_g, &v_g); }
         forward_one(n, &s, params, obs + row * in_sz, x, act, h, logits, &v);
 
         /* log-softmax, entropy */
@@ -450,8 +470,8 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
         double *dfin = L > 0 ? dact + s.act_off[L - 1] : NULL;
         if (dfin) for (int f = 0; f < s.F; ++f) dfin[f] = 0.0;
         for (int j = 0; j < Hd; ++j) {
-            if (!(h[j] > 0.0)) continue;          /* ReLU gate: pre-activation > 0 */
-            const double g = dh[j];
+            if (!(h_g[j] > 0.0)) continue;        /* ReLU gate: pre-activation > 0 */
+            const double g = rq ? orc_round_bf16(dh[j]) : dh[j];
             grads[s.fcb + j] += g;
             for (int f = 0; f < s.F; ++f) {
                 grads[s.fcw + (int64_t)j * s.F + f] += g * fin[f];
@@ -465,7 +485,7 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
             const int ho = s.hout[l], wo = s.wout[l];
             const double *in = l > 0 ? act + s.act_off[l - 1] : x;
             double *din = l > 0 ? dact + s.act_off[l - 1] : NULL;
-            const double *out = act + s.act_off[l];
+            const double *out = act_g + s.act_off[l];      /* consulted for the gate only */
             const double *dout = dact + s.act_off[l];
             const double *wgt = params + s.w_off[l];
             if (din) for (int i = 0; i < ci * hi * wi; ++i) din[i] = 0.0;
@@ -473,7 +493,7 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
                 for (int i = 0; i < ho; ++i)
                     for (int j = 0; j < wo; ++j) {
                         if (!(out[(o * ho + i) * wo + j] > 0.0)) continue;
-                        const double g = dout[(o * ho + i) * wo + j];
+                        const double g = rq ? orc_round_bf16(dout[(o * ho + i) * wo + j]) : dout[(o * ho + i) * wo + j];
                         grads[s.b_off[l] + o] += g;
                         for (int c = 0; c < ci; ++c)
                             for (int u = 0; u < k; ++u)
@@ -497,8 +517,78 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
         if (grads) for (int64_t i = 0; i < s.total; ++i) ss += grads[i] * grads[i];
         stats->grad_norm = sqrt(ss);
     }
+    if (exact_gates) { free(act_g); free(h_g); free(logits_g); }
     free(x); free(act); free(dact); free(h); free(dh); free(logits); free(lp); free(dl); free(params);
     return 0;
+}
+
+/* The same loss and gradient with the rows spread over host threads (used for full-size minibatches and for the
+ * all-core timing).  The B rows are cut into `nslots` contiguous slots (a fixed number: the result does not depend on
+ * the thread count); every slot is a plain orc_loss_grads call on its rows, and the slot results -- each a mean over
+ * its own rows -- are combined in slot order with weights B_slot / B.  Needs nslots gradient buffers. */
+int32_t orc_loss_grads_mt(const orc_net *n, const double *params, const uint8_t *obs, const int32_t *index, int32_t B,
+                          const int32_t *actions, const double *old_logp, const double *old_values, const double *adv,
+                          const double *ret, const orc_hparams *hp, double *grads, orc_stats *stats, int32_t nslots,
+                          int32_t nthreads)
+{
+    if (nslots > B) nslots = B;
+    if (nslots < 1) nslots = 1;
+    const int64_t P = orc_param_count(n);
+    int32_t *rows = malloc(sizeof(int32_t) * (size_t)B);
+    double *gs = grads ? malloc(sizeof(double) * (size_t)P * (size_t)nslots) : NULL;
+    orc_stats *ss = malloc(sizeof(orc_stats) * (size_t)nslots);
+    int32_t *rcs = malloc(sizeof(int32_t) * (size_t)nslots);
+    if (!rows || (grads && !gs) || !ss || !rcs) return -1;
+    for (int b = 0; b < B; ++b) rows[b] = index ? index[b] : b;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+    for (int sl = 0; sl < nslots; ++sl) {
+        const int b0 = (int)((int64_t)sl * B / nslots), b1 = (int)((int64_t)(sl + 1) * B / nslots);
+        rcs[sl] = orc_loss_grads(n, params, obs, rows + b0, b1 - b0, actions, old_logp, old_values, adv, ret, hp,
+                                 gs ? gs + (int64_t)sl * P : NULL, &ss[sl]);
+    }
+    int32_t rc = 0;
+    for (int sl = 0; sl < nslots; ++sl) if (rcs[sl] != 0) rc = rcs[sl];
+    if (rc == 0) {
+        if (grads) memset(grads, 0, sizeof(double) * (size_t)P);
+        orc_stats tot; memset(&tot, 0, sizeof tot);
+        for (int sl = 0; sl < nslots; ++sl) {
+            const int b0 = (int)((int64_t)sl * B / nslots), b1 = (int)((int64_t)(sl + 1) * B / nslots);
+            const double w = (double)(b1 - b0) / (double)B;
+            if (grads) for (int64_t i = 0; i < P; ++i) grads[i] += w * gs[(int64_t)sl * P + i];
+            tot.policy_loss += w * ss[sl].policy_loss; tot.value_loss += w * ss[sl].value_loss;
+            tot.entropy += w * ss[sl].entropy; tot.clip_frac += w * ss[sl].clip_frac;
+            tot.approx_kl += w * ss[sl].approx_kl;
+        }
+        tot.total_loss = tot.policy_loss + hp->vf_coef * tot.value_loss - hp->ent_coef * tot.entropy;
+        double sq = 0.0;
+        if (grads) for (int64_t i = 0; i < P; ++i) sq += grads[i] * grads[i];
+        tot.grad_norm = sqrt(sq);
+        if (stats) *stats = tot;
+    }
+    free(rows); free(gs); free(ss); free(rcs);
+    return rc;
+}
+
+/* orc_forward with the rows spread over host threads (every row is independent): contiguous chunks of rows, each a
+ * plain orc_forward call. */
+int32_t orc_forward_mt(const orc_net *n, const double *params, const uint8_t *obs, const int32_t *index, int32_t B,
+                       double *logits, double *values, int32_t nthreads)
+{
+    int32_t nchunks = nthreads > 0 ? 4 * nthreads : 1;
+    if (nchunks > B) nchunks = B;
+    if (nchunks < 1) nchunks = 1;
+    int32_t *rows = malloc(sizeof(int32_t) * (size_t)B), *rcs = malloc(sizeof(int32_t) * (size_t)nchunks);
+    if (!rows || !rcs) return -1;
+    for (int b = 0; b < B; ++b) rows[b] = index ? index[b] : b;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+    for (int c = 0; c < nchunks; ++c) {
+        const int b0 = (int)((int64_t)c * B / nchunks), b1 = (int)((int64_t)(c + 1) * B / nchunks);
+        rcs[c] = orc_forward(n, params, obs, rows + b0, b1 - b0, logits + (int64_t)b0 * n->A, values + b0);
+    }
+    int32_t rc = 0;
+    for (int c = 0; c < nchunks; ++c) if (rcs[c] != 0) rc = rcs[c];
+    free(rows); free(rcs);
+    return rc;
 }
 
 /* ------------------------------------------------------------------------- */

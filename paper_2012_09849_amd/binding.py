@@ -158,6 +158,34 @@ class Context:
                                 _ptr(values, torch.float32, "values"), _ptr(logits, torch.float32, "logits")),
                "hts_act")
 
+    def act_rows(self, obs, actions, logp, values, logits=None):
+        """Pre-marshalled hts_act arguments, one entry per leading index s of obs [S,N,C,H,W], actions / logp / values
+        [S,N] (and logits [S,N,A]): the tensors are checked once and only raw device addresses are kept."""
+        S, N = obs.shape[0], obs.shape[1]
+        for t, dt, nm in ((obs, torch.uint8, "obs"), (actions, torch.int32, "actions"), (logp, torch.float32, "logp"),
+                          (values, torch.float32, "values"), (logits, torch.float32, "logits")):
+            if t is not None:
+                _ptr(t, dt, nm)
+                if t.shape[0] != S or t.shape[1] != N:
+                    raise HtsError(f"{nm}: leading dimensions must be [{S},{N}]")
+        ob, so = obs.data_ptr(), obs[0].numel()
+        ab, lb, vb = actions.data_ptr(), logp.data_ptr(), values.data_ptr()
+        gb, sg = (logits.data_ptr(), 4 * logits[0].numel()) if logits is not None else (0, 0)
+        rows = [(ob + s * so, ab + 4 * s * N, lb + 4 * s * N, vb + 4 * s * N, (gb + s * sg) if gb else None)
+                for s in range(S)]
+        return (N, rows, (obs, actions, logp, values, logits))
+
+    def hts_act_rows(self, act_rows, params, seed, step0, env_offset):
+        """One hts_act call per entry of act_rows (see act_rows), steps step0, step0+1, ...; the parameters are passed
+        to the first call only (the actors keep one parameter version for a whole storage)."""
+        N, rows, _keep = act_rows
+        fn, h = self.lib.hts_act, self._h
+        pp = _ptr(params, torch.float32, "params")
+        for s, (o, a, l, v, g) in enumerate(rows):
+            rc = fn(h, o, pp if s == 0 else None, seed, step0 + s, N, env_offset, a, l, v, g)
+            if rc != 0:
+                _check(rc, "hts_act")
+
     def hts_sync_params(self, params):
         _check(self.lib.hts_sync_params(self._h, _ptr(params, torch.float32, "params")), "hts_sync_params")
 

@@ -300,34 +300,141 @@ def test_round_bf16_against_torch_and_ties(oracle):
     assert oracle.round_bf16(255.0) == 255.0 and oracle.round_bf16(257.0) == 256.0
 
 
+class _RoundGrad(torch.autograd.Function):
+    """Identity whose derivative rounds the incoming gradient to bfloat16 (placed on a pre-activation, it rounds the
+    gradient with respect to that pre-activation before any product of the backward pass uses it)."""
+
+    @staticmethod
+    def forward(ctx, x):
+        return x.view_as(x)
+
+    @staticmethod
+    def backward(ctx, g):
+        return g.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+
+def _rb(t):
+    q = t.detach().to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    return t + (q - t).detach()
+
+
+def _rounded_model_torch(kw, p, obs, gate_masks=None, round_grads=True):
+    """Forward pass with every operand of a conv/FC product rounded to bfloat16 (straight-through); with round_grads
+    the gradients of the pre-activations are rounded too.  gate_masks: ReLU gates to use in the derivative instead of
+    the pass's own.  -> (logits, values, list of pre-activations)."""
+    def relu(pre, li):
+        if gate_masks is None:
+            return F.relu(pre)
+        y = pre * gate_masks[li]
+        return F.relu(pre).detach() + (y - y.detach())
+
+    rg = _RoundGrad.apply if round_grads else (lambda t: t)
+    pres = []
+    x = torch.from_numpy(obs.astype(np.float64)) / 255.0
+    for i, (co, k, s) in enumerate(kw["convs"]):
+        pre = rg(F.conv2d(x, _rb(p[f"conv{i + 1}.w"]), p[f"conv{i + 1}.b"], stride=s))
+        pres.append(pre)
+        x = _rb(relu(pre, i))
+    pre = rg(F.linear(x.flatten(1), _rb(p["fc.w"]), p["fc.b"]))
+    pres.append(pre)
+    h = relu(pre, len(kw["convs"]))
+    return F.linear(h, p["pi.w"], p["pi.b"]), F.linear(h, p["v.w"], p["v.b"])[:, 0], pres
+
+
+def _ppo_loss_torch(logits, v, actions, old_logp, adv, ret):
+    lsm = F.log_softmax(logits, dim=1)
+    logp = lsm.gather(1, torch.from_numpy(actions.astype(np.int64))[:, None])[:, 0]
+    rho = (logp - torch.from_numpy(old_logp)).exp()
+    ad = torch.from_numpy(adv)
+    return (-torch.minimum(rho * ad, rho.clamp(0.9, 1.1) * ad).mean() + 0.5 * ((torch.from_numpy(ret) - v) ** 2).mean()
+            - 0.01 * (-(lsm.exp() * lsm).sum(1)).mean())
+
+
+_QKW = dict(C=3, H=44, W=52, A=5, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512)
+
+
+def _qflat_grad(p):
+    return np.concatenate([p[name].grad.numpy().ravel() for name, _ in syn.param_shapes(3, 44, 52, 5)])
+
+
 def test_operand_model_matches_torch_with_rounded_operands(oracle):
-    """Forward and gradients in the operand-rounding model vs autograd through the same roundings (straight-through)."""
-    def rb(t):
-        q = t.detach().to(torch.float32).to(torch.bfloat16).to(torch.float64)
-        return t + (q - t).detach()
-    kw = dict(C=3, H=44, W=52, A=5, convs=((32, 8, 4), (64, 4, 2), (64, 3, 1)), hidden=512)
+    """Forward and gradients in the operand-rounding model vs autograd through the same roundings: weights and layer
+    outputs rounded straight-through in the forward pass, pre-activation gradients rounded in the backward pass."""
+    kw = _QKW
     net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 61, 4, 1, kw)
     flat = flat.astype(np.float32).astype(np.float64)
     qnet = oracle.make_net(3, 44, 52, 5, operand_bf16=True)
     p = _torch_params(flat, kw, 5)
-    x = torch.from_numpy(obs.astype(np.float64)) / 255.0
-    for i, (co, k, s) in enumerate(kw["convs"]):
-        x = rb(F.relu(F.conv2d(x, rb(p[f"conv{i + 1}.w"]), p[f"conv{i + 1}.b"], stride=s)))
-    h = F.relu(F.linear(x.flatten(1), rb(p["fc.w"]), p["fc.b"]))
-    logits, v = F.linear(h, p["pi.w"], p["pi.b"]), F.linear(h, p["v.w"], p["v.b"])[:, 0]
+    logits, v, _ = _rounded_model_torch(kw, p, obs)
     ql, qv = oracle.forward(qnet, flat, obs)
     np.testing.assert_allclose(ql, logits.detach().numpy(), rtol=1e-9, atol=1e-12)
     np.testing.assert_allclose(qv, v.detach().numpy(), rtol=1e-9, atol=1e-12)
     el, _ = oracle.forward(net, flat, obs)
     assert 1e-5 < np.abs(ql - el).max() < 0.1 * np.abs(el).max()       # the rounding is really applied
-    lsm = F.log_softmax(logits, dim=1)
-    logp = lsm.gather(1, torch.from_numpy(actions.astype(np.int64))[:, None])[:, 0]
-    rho = (logp - torch.from_numpy(old_logp)).exp()
-    ad = torch.from_numpy(adv)
-    loss = (-torch.minimum(rho * ad, rho.clamp(0.9, 1.1) * ad).mean() + 0.5 * ((torch.from_numpy(ret) - v) ** 2).mean()
-            - 0.01 * (-(lsm.exp() * lsm).sum(1)).mean())
+    loss = _ppo_loss_torch(logits, v, actions, old_logp, adv, ret)
     loss.backward()
-    tg = np.concatenate([p[name].grad.numpy().ravel() for name, _ in syn.param_shapes(3, 44, 52, 5)])
+    tg = _qflat_grad(p)
     g, st = oracle.loss_grads(qnet, flat, obs, actions, old_logp, adv, ret, oracle.make_hparams(algo=1, clip_eps=0.1))
     np.testing.assert_allclose(st["total_loss"], loss.item(), rtol=1e-11)
     np.testing.assert_allclose(g, tg, rtol=1e-8, atol=1e-13)
+    # the backward roundings are really applied: with the forward roundings alone the gradient differs, a little
+    p2 = _torch_params(flat, kw, 5)
+    l2, v2, _ = _rounded_model_torch(kw, p2, obs, round_grads=False)
+    _ppo_loss_torch(l2, v2, actions, old_logp, adv, ret).backward()
+    fg = _qflat_grad(p2)
+    rel = np.linalg.norm(g - fg) / np.linalg.norm(fg)
+    assert 1e-5 < rel < 2e-2
+
+
+def test_exact_gate_diagnostic_matches_torch(oracle):
+    """gates_exact: rounded operands, but the derivative's ReLU gates come from the unrounded forward pass."""
+    kw = _QKW
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 62, 6, 1, kw)
+    flat = flat.astype(np.float32).astype(np.float64)
+    pe = _torch_params(flat, kw, 5)                                   # unrounded forward pass: its gates
+    x = torch.from_numpy(obs.astype(np.float64)) / 255.0
+    masks = []
+    with torch.no_grad():
+        for i, (co, k, s) in enumerate(kw["convs"]):
+            pre = F.conv2d(x, pe[f"conv{i + 1}.w"], pe[f"conv{i + 1}.b"], stride=s)
+            masks.append((pre > 0).to(torch.float64))
+            x = F.relu(pre)
+        masks.append((F.linear(x.flatten(1), pe["fc.w"], pe["fc.b"]) > 0).to(torch.float64))
+    p = _torch_params(flat, kw, 5)
+    logits, v, pres = _rounded_model_torch(kw, p, obs, gate_masks=masks)
+    flips = sum(int(((pr.detach() > 0).to(torch.float64) != mk).sum()) for pr, mk in zip(pres, masks))
+    assert flips > 0                                                   # otherwise the case tests nothing
+    _ppo_loss_torch(logits, v, actions, old_logp, adv, ret).backward()
+    tg = _qflat_grad(p)
+    hp = oracle.make_hparams(algo=1, clip_eps=0.1)
+    gnet = oracle.make_net(3, 44, 52, 5, operand_bf16=True, gates_exact=True)
+    g, st = oracle.loss_grads(gnet, flat, obs, actions, old_logp, adv, ret, hp)
+    np.testing.assert_allclose(g, tg, rtol=1e-8, atol=1e-13)
+    gq, stq = oracle.loss_grads(oracle.make_net(3, 44, 52, 5, operand_bf16=True), flat, obs, actions, old_logp, adv,
+                                ret, hp)
+    assert st["total_loss"] == stq["total_loss"]                       # the losses are those of the rounded pass
+    assert np.abs(g - gq).max() > 0                                    # and the flipped gates do change the gradient
+
+
+def test_threaded_variants_equal_the_plain_calls(oracle):
+    """The threaded gradient is the slot-ordered combination of plain calls: equal to the plain call up to the
+    reassociation of its float64 sums, and independent of the number of threads; the threaded forward is identical."""
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 63, 37, 1, _QKW)
+    hp = oracle.make_hparams(algo=1, clip_eps=0.1)
+    idx = np.array([5, 3, 36, 0, 7, 7, 12, 30, 2, 1, 35], np.int32)
+    for index in (None, idx):
+        g1, s1 = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp, index=index)
+        g2, s2 = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp, index=index, threads=2)
+        g3, s3 = oracle.loss_grads(net, flat, obs, actions, old_logp, adv, ret, hp, index=index, threads=5)
+        assert np.array_equal(g2, g3) and s2 == s3
+        np.testing.assert_allclose(g2, g1, rtol=1e-11, atol=1e-15)
+        for k in s1:
+            np.testing.assert_allclose(s2[k], s1[k], rtol=1e-12, atol=1e-15)
+        l1, v1 = oracle.forward(net, flat, obs, index=index)
+        l2, v2 = oracle.forward(net, flat, obs, index=index, threads=3)
+        assert np.array_equal(l1, l2) and np.array_equal(v1, v2)
+    z = np.zeros(flat.size)
+    th1 = oracle.learner_step(net, flat, z, z, 1, obs, actions, old_logp, adv, ret, hp)
+    th2 = oracle.learner_step(net, flat, z, z, 1, obs, actions, old_logp, adv, ret, hp, threads=4)
+    big = np.abs(th1[3]) > 1e-4 * np.abs(th1[3]).max()    # Adam's first step is ~lr*sign(g): compare where g is not ~0
+    np.testing.assert_allclose(th2[0][big], th1[0][big], rtol=0, atol=1e-10)
