@@ -1,13 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the whole hot path on one MI355X.
 
-One step = one training iteration of the Atari-shaped A2C configuration (N=16 environments, unroll T=5, fp32,
-18 actions): T batched hts_act calls with seeded sampling + one bootstrap hts_act, hts_returns_gae (gamma=0.99,
-lambda=1) and one hts_learner_step (A2C loss, Adam) on the 80 collected rows -- all enqueued back to back on one
-stream, no host synchronisation inside the timed region, inputs resident in HBM.
+One step = one training iteration of a workload: T batched hts_act calls with seeded sampling plus the bootstrap call,
+hts_returns_gae (and the advantage normalisation of the PPO workloads), and every learner minibatch step of the
+iteration -- all enqueued back to back on one stream, no host synchronisation inside the timed region, inputs resident
+in HBM.  The default workload is the largest single-GPU configuration, the Football-shaped PPO iteration (16x72x96
+observations, 16 environments, unroll 512, 2 epochs x 4 minibatches of 2048, bf16 operands).
 
-Prints ONE JSON line: env-frames/s (N*T per step over wall time), plus learner samples/s, a roofline entry for the
-dominant kernel (timed live with HIP events inside the library) and the CPU oracle timed on the host beside it.
+Prints ONE JSON line: env-frames/s (N*T per step over wall time) and learner samples/s of that workload, a roofline
+entry for its dominant kernel (timed live with HIP events inside the library, a sample of its launches inside the
+timed region), the other workloads (Atari-shaped PPO and A2C, the large-batch actor / returns sweep) in
+`other_workloads`, and the CPU oracle timed on the host beside it (one core, and all cores).
 """
 import argparse
 import json
@@ -18,209 +21,80 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-CONFIGS = {
-    # name: (C, H, W, A, N, T, precision, algo, gamma, lambda, lr, epochs, minibatches, clip, max_grad_norm, ent)
-    "atari_a2c_n16_t5_fp32": dict(C=4, H=84, W=84, A=18, N=16, T=5, precision=0, algo=0, gamma=0.99, lam=1.0,
-                                  lr=7e-4, epochs=1, minibatches=1, clip=0.1, max_norm=0.0, ent=0.01, obs="atari"),
-    "atari_ppo_n32_t128_bf16": dict(C=4, H=84, W=84, A=18, N=32, T=128, precision=1, algo=1, gamma=0.99, lam=0.95,
-                                    lr=2.5e-4, epochs=4, minibatches=4, clip=0.1, max_norm=0.5, ent=0.01, obs="atari"),
-    "football_ppo_n16_t512_bf16": dict(C=16, H=72, W=96, A=19, N=16, T=512, precision=1, algo=1, gamma=0.993,
-                                       lam=0.95, lr=3.4e-4, epochs=2, minibatches=4, clip=0.08, max_norm=0.0,
-                                       ent=0.003, obs="football"),
-    # the paper's multi-agent football experiment controls three players per environment: every controlled player is
-    # one row of every call (16 environments x 3 players = 48 rows per step), unroll 128 as in the paper's runs
-    "football_multiagent_ppo_n16x3_t128_bf16": dict(C=16, H=72, W=96, A=19, N=48, T=128, precision=1, algo=1,
-                                                    gamma=0.993, lam=0.95, lr=3.4e-4, epochs=2, minibatches=4,
-                                                    clip=0.08, max_norm=0.0, ent=0.003, obs="football"),
-}
-FWD_FLOP = {"atari": 18.71e6, "football": 35.80e6}
-FWDBWD_FLOP = {"atari": 49.56e6, "football": 81.78e6}
+from paper_2012_09849_amd.schedule import CONFIGS, Loop, OverlapLoop  # noqa: E402  (no GPU needed to import)
 
-
-def make_inputs(cfg, torch, syn):
-    N, T = cfg["N"], cfg["T"]
-    if cfg["obs"] == "atari":
-        obs = syn.obs_atari(syn.MASTER_SEED, T + 1, N)
-        rew = syn.rewards_ternary(syn.MASTER_SEED, T, N) if cfg["algo"] == 0 else syn.rewards_score_clipped(syn.MASTER_SEED, T, N)
-        dones = syn.dones_bernoulli(syn.MASTER_SEED, T, N, 0.05 if cfg["algo"] == 0 else 0.01)
-    else:
-        obs = syn.obs_football(syn.MASTER_SEED, T + 1, N)
-        rew = syn.rewards_ternary(syn.MASTER_SEED, T, N, p_nonzero=0.002)
-        dones = ((rew != 0) | (syn.dones_bernoulli(syn.MASTER_SEED, T, N, 0.001) != 0)).astype("uint8")
-    params = syn.init_params(syn.MASTER_SEED, cfg["C"], cfg["H"], cfg["W"], cfg["A"])
-    return obs, rew, dones, params
-
-
-class Loop:
-    """Device buffers of one storage plus the calls of one iteration."""
-
-    def __init__(self, cfg, hts, torch, syn):
-        self.cfg, self.hts, self.torch = cfg, hts, torch
-        N, T, A = cfg["N"], cfg["T"], cfg["A"]
-        obs, rew, dones, params = make_inputs(cfg, torch, syn)
-        self.host = dict(obs=obs, rew=rew, dones=dones, params=params)
-        dev = "cuda"
-        self.obs = torch.from_numpy(obs).to(dev)                      # [T+1, N, C, H, W]
-        self.rew = torch.from_numpy(rew).to(dev)
-        self.dones = torch.from_numpy(dones).to(dev)
-        self.params = torch.from_numpy(params).to(dev)
-        B = N * T // cfg["minibatches"]
-        self.B = B
-        self.ctx = hts.Context(cfg["C"], cfg["H"], cfg["W"], A, precision=cfg["precision"], max_act_batch=N,
-                               max_learn_batch=B)
-        P = self.ctx.P
-        self.opt = hts.OptState(torch.zeros(P, device=dev), torch.zeros(P, device=dev), 0)
-        self.actions = torch.zeros(T + 1, N, dtype=torch.int32, device=dev)
-        self.logp = torch.zeros(T + 1, N, device=dev)
-        self.values = torch.zeros(T + 1, N, device=dev)
-        self.adv = torch.zeros(T, N, device=dev)
-        self.ret = torch.zeros(T, N, device=dev)
-        self.hp = hts.HParams(algo=cfg["algo"], clip_eps=cfg["clip"], vf_coef=0.5, ent_coef=cfg["ent"],
-                              max_grad_norm=cfg["max_norm"], lr=cfg["lr"])
-        self.perms = [torch.from_numpy(syn.permutation(syn.MASTER_SEED, N * T, e)).to(dev) for e in range(cfg["epochs"])]
-        self.iteration = 0
-
-    def rollout(self):
-        c, cfg = self.ctx, self.cfg
-        base = self.iteration * (cfg["T"] + 1)
-        for t in range(cfg["T"] + 1):
-            # the actors keep one parameter version for a whole storage: it is loaded by the first call only
-            c.hts_act(self.obs[t], self.params if t == 0 else None, 20201209, base + t, 0, self.actions[t],
-                      self.logp[t], self.values[t])
-
-    def returns(self):
-        cfg = self.cfg
-        self.ctx.hts_returns_gae(self.rew, self.values, self.dones, cfg["gamma"], cfg["lam"], self.adv, self.ret)
-        if cfg["algo"] == 1:
-            self.ctx.hts_normalize_advantages(self.adv)
-
-    def learn(self):
-        cfg, T, N = self.cfg, self.cfg["T"], self.cfg["N"]
-        obs = self.obs[:T].reshape(T * N, cfg["C"], cfg["H"], cfg["W"])
-        actions, logp = self.actions[:T].reshape(-1), self.logp[:T].reshape(-1)
-        adv, ret = self.adv.reshape(-1), self.ret.reshape(-1)
-        for e in range(cfg["epochs"]):
-            for k in range(cfg["minibatches"]):
-                idx = None if cfg["minibatches"] == 1 and cfg["epochs"] == 1 else self.perms[e][k * self.B:(k + 1) * self.B]
-                self.ctx.hts_learner_step(obs, actions, logp, adv, ret, self.params, self.opt, self.hp, index=idx,
-                                          B=self.B)
-
-    def step(self):
-        self.rollout()
-        self.returns()
-        self.learn()
-        self.iteration += 1
-
-
-class OverlapLoop:
-    """The paper's schedule (Sec. 4.1 "Concurrent rollout and learning"): while the actors fill storage j with theta_j
-    on one stream, the learner works on storage j-1 on another; the streams meet once per iteration.  Two contexts
-    (calls on one context must not overlap), two storages, three parameter vectors in rotation.
-
-    One update per storage (A2C): the paper's one-step-delayed rule -- gradient at theta_{j-1} on storage j-1, applied to
-    theta_j (hts_learner_step_delayed).  Several minibatch steps per storage (PPO): the paper states its rule for a
-    single gradient step only; here the learner runs its ordinary epochs on storage j-1 starting from theta_j, the
-    stored behaviour log-probabilities (of theta_{j-1}) entering through PPO's own probability ratio."""
-
-    def __init__(self, base):
-        torch, hts, cfg = base.torch, base.hts, base.cfg
-        self.base, self.cfg, self.torch = base, cfg, torch
-        N, T = cfg["N"], cfg["T"]
-        self.s_roll, self.s_learn = torch.cuda.Stream(), torch.cuda.Stream()
-        mk = lambda **kw: hts.Context(cfg["C"], cfg["H"], cfg["W"], cfg["A"], precision=cfg["precision"], **kw)
-        self.ctx_act = mk(max_act_batch=N, stream=self.s_roll)
-        self.ctx_learn = mk(max_learn_batch=base.B, stream=self.s_learn)
-        z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device="cuda")
-        self.store = [dict(actions=z(T + 1, N, dt=torch.int32), logp=z(T + 1, N), values=z(T + 1, N), adv=z(T, N),
-                           ret=z(T, N)) for _ in range(2)]
-        self.theta = [base.params.clone() for _ in range(3)]        # prev, cur, next
-        P = base.params.numel()
-        self.opt = hts.OptState(z(P), z(P), 0)
-        self.ev_roll, self.ev_learn = torch.cuda.Event(), torch.cuda.Event()
-        self.j = 0
-        torch.cuda.synchronize()
-
-    def step(self):
-        torch, cfg, b = self.torch, self.cfg, self.base
-        T, N = cfg["T"], cfg["N"]
-        prev, cur, nxt = self.theta
-        st = self.store[self.j % 2]
-        for t in range(T + 1):
-            self.ctx_act.hts_act(b.obs[t], cur if t == 0 else None, 20201209, self.j * (T + 1) + t, 0, st["actions"][t],
-                                 st["logp"][t], st["values"][t])
-        self.ctx_act.hts_returns_gae(b.rew, st["values"], b.dones, cfg["gamma"], cfg["lam"], st["adv"], st["ret"])
-        if cfg["algo"] == 1:
-            self.ctx_act.hts_normalize_advantages(st["adv"])
-        self.ev_roll.record(self.s_roll)
-        single = cfg["epochs"] * cfg["minibatches"] == 1
-        with torch.cuda.stream(self.s_learn):
-            nxt.copy_(cur)
-            if self.j > 0:
-                old = self.store[(self.j - 1) % 2]
-                obs = b.obs[:T].reshape(T * N, cfg["C"], cfg["H"], cfg["W"])
-                data = (obs, old["actions"][:T].reshape(-1), old["logp"][:T].reshape(-1), old["adv"].reshape(-1),
-                        old["ret"].reshape(-1))
-                if single:
-                    self.ctx_learn.hts_learner_step_delayed(*data, prev, nxt, self.opt, b.hp)
-                else:
-                    for e in range(cfg["epochs"]):
-                        for k in range(cfg["minibatches"]):
-                            self.ctx_learn.hts_learner_step(*data, nxt, self.opt, b.hp,
-                                                            index=b.perms[e][k * b.B:(k + 1) * b.B], B=b.B)
-        self.ev_learn.record(self.s_learn)
-        self.s_roll.wait_event(self.ev_learn)
-        self.s_learn.wait_event(self.ev_roll)
-        self.theta = [cur, nxt, prev]
-        self.j += 1
-
-
+DEFAULT_WORKLOAD = "football_ppo_n16_t512_bf16"
+METRIC = "env-frames/sec (act+GAE+PPO update) and learner samples/sec, 1×MI355X"
 PEAK = {"mfma_f32": 157.3e12, "mfma_bf16": 2.5e15, "hbm": 8.0e12}
 
 
-def site_work(cfg, loop):
-    """Algorithmic work of one step per launch site: name -> (kind, amount per step); kind is 'flop' or 'byte'.
-
-    FLOPs are 2*MACs of the unpadded contraction; bytes are the arrays each streaming kernel must read and write once.
-    """
-    C, H, W, A, N, T = (cfg[k] for k in ("C", "H", "W", "A", "N", "T"))
+def layer_flops(cfg):
+    """2*MACs per observation of the four contractions (unpadded)."""
+    C, H, W = cfg["C"], cfg["H"], cfg["W"]
     H1, W1 = (H - 8) // 4 + 1, (W - 8) // 4 + 1
     H2, W2 = (H1 - 4) // 2 + 1, (W1 - 4) // 2 + 1
     P1, P2, P3 = H1 * W1, H2 * W2, (H2 - 2) * (W2 - 2)
-    F, K1 = 64 * P3, C * 64
-    act_rows = N * (T + 1)
-    learn_rows = N * T * cfg["epochs"]
-    steps = cfg["epochs"] * cfg["minibatches"]
-    c1, c2, c3, fc = 2.0 * P1 * 32 * K1, 2.0 * P2 * 64 * 512, 2.0 * P3 * 64 * 576, 2.0 * 512 * F
-    P = loop.ctx.P
-    return {
-        "conv1_fwd": ("flop", (act_rows + learn_rows) * c1), "conv2_fwd": ("flop", (act_rows + learn_rows) * c2),
-        "conv3_fwd": ("flop", (act_rows + learn_rows) * c3), "fc_fwd": ("flop", (act_rows + learn_rows) * fc),
-        "fc_wgrad": ("flop", learn_rows * fc), "fc_dgrad": ("flop", learn_rows * fc),
-        "conv3_wgrad": ("flop", learn_rows * c3), "conv3_dgrad": ("flop", learn_rows * c3),
-        "conv2_wgrad": ("flop", learn_rows * c2), "conv2_dgrad": ("flop", learn_rows * c2),
-        "conv1_wgrad": ("flop", learn_rows * c1),
-        "adam": ("byte", steps * 28.0 * P), "grad_norm": ("byte", steps * 4.0 * P),
-        "gae": ("byte", 17.0 * T * N + 4.0 * N),
-    }
+    return {"conv1": 2.0 * P1 * 32 * 64 * C, "conv2": 2.0 * P2 * 64 * 512, "conv3": 2.0 * P3 * 64 * 576,
+            "fc": 2.0 * 512 * 64 * P3}
 
 
-def find_dominant(loop, work, overhead_ms):
-    """Time every launch site with the library's event timer over a few steps; return per-site ms per step."""
+def site_work(cfg, P):
+    """Algorithmic work PER LAUNCH of every launch site: name -> (kind, amount, rows per launch).
+
+    FLOPs are 2*MACs of the unpadded contraction times the rows one launch processes (N for an actor call, the
+    minibatch size for a learner call); bytes are the arrays a streaming kernel must read and write once."""
+    N, T = cfg["N"], cfg["T"]
+    B = N * T // cfg["minibatches"]
+    f = layer_flops(cfg)
+    w = {}
+    for layer in ("conv1", "conv2", "conv3", "fc"):
+        w[f"{layer}_fwd"] = ("flop", N * f[layer], N)
+        w[f"{layer}_fwd_learn"] = ("flop", B * f[layer], B)
+    for layer in ("conv3", "conv2"):
+        w[f"{layer}_wgrad"] = ("flop", B * f[layer], B)
+        w[f"{layer}_dgrad"] = ("flop", B * f[layer], B)
+    w["conv1_wgrad"] = ("flop", B * f["conv1"], B)
+    w["fc_wgrad"] = ("flop", B * f["fc"], B)
+    w["fc_dgrad"] = ("flop", B * f["fc"], B)
+    w["adam"] = ("byte", 28.0 * P, B)
+    w["grad_norm"] = ("byte", 4.0 * P, B)
+    w["gae"] = ("byte", 17.0 * T * N + 4.0 * N, N)
+    return w
+
+
+def time_sites(loop, steps=2):
+    """Every launch site bracketed in turn over a few steps: name -> (bracket ms per step, launches per step)."""
     names = loop.ctx.profile_sites()
     per_step = {}
     for i, nm in enumerate(names):
         loop.ctx.hts_profile_begin(i)
-        for _ in range(3):
+        for _ in range(steps):
             loop.step()
         n, ms = loop.ctx.hts_profile_end()
         if n:
-            per_step[nm] = (ms / 3.0, n // 3)
-    ranked = sorted(((v[0] - v[1] * overhead_ms, k) for k, v in per_step.items() if k in work), reverse=True)
-    return ranked[0][1], per_step
+            per_step[nm] = (ms / steps, n / steps)
+    return per_step
 
 
-def cpu_baseline(cfg, loop, budget_s=16.0):
-    """The oracle as it stands, single thread, on a bounded sample of the same workload (about budget_s of CPU)."""
+def roofline_entry(cfg, name, kind, per_launch, rows, avg_bracket_s, overhead_s, n_timed, launches_per_step, traffic):
+    """The dominant kernel against its roofline.  `achieved` uses the event bracket less what an empty bracket reads;
+    both raw figures are printed beside it."""
+    net_s = max(avg_bracket_s - overhead_s, 1e-9)
+    if kind == "flop":
+        peak = PEAK["mfma_f32"] if cfg["precision"] == 0 else PEAK["mfma_bf16"]
+        ach, unit, scale, bound = per_launch / net_s, "TFLOP/s", 1e12, "mfma"
+    else:
+        peak, ach, unit, scale, bound = PEAK["hbm"], per_launch / net_s, "GB/s", 1e9, "hbm"
+    return {"kernel": name, "bound": bound, "achieved": ach / scale, "peak": peak / scale, "unit": unit,
+            "frac": ach / peak, "traffic": traffic, "rows_per_launch": rows, "work_per_launch": per_launch,
+            "avg_launch_us": net_s * 1e6, "raw_bracket_us": avg_bracket_s * 1e6, "event_overhead_us": overhead_s * 1e6,
+            "frac_from_raw_bracket": per_launch / avg_bracket_s / peak,
+            "launches_timed": n_timed, "launches_per_step": launches_per_step}
+
+
+def cpu_baseline(cfg, loop, budget_s=14.0, threads=1):
+    """The oracle as it stands on a bounded sample of the same workload (about budget_s of wall time).
+    threads > 1: its threaded variants (rows spread over host threads, fixed-order combination)."""
     import numpy as np
     import oracle
     h = loop.host
@@ -233,7 +107,7 @@ def cpu_baseline(cfg, loop, budget_s=16.0):
     t0 = time.perf_counter()
     n_steps = 0
     while n_steps == 0 or time.perf_counter() - t0 < 0.4 * budget_s:
-        logits, _ = oracle.forward(net, p, h["obs"][n_steps % (T + 1)])
+        logits, _ = oracle.forward(net, p, h["obs"][n_steps % (T + 1)], threads=threads)
         oracle.sample(logits.astype(np.float32), 1, n_steps, 0)
         n_steps += 1
     t_act = (time.perf_counter() - t0) / n_steps
@@ -241,12 +115,13 @@ def cpu_baseline(cfg, loop, budget_s=16.0):
     oracle.gae(h["rew"], np.zeros((T + 1, N)), h["dones"], cfg["gamma"], cfg["lam"])
     t_gae = time.perf_counter() - t0
     # learner: one update on a calibration sample, then on as many rows as the rest of the budget allows
+
     def learn(rows):
         t = time.perf_counter()
         oracle.learner_step(net, p, np.zeros(p.size), np.zeros(p.size), 1, all_obs[:rows], np.zeros(rows, np.int32),
-                            np.zeros(rows), np.ones(rows), np.ones(rows), hp)
+                            np.zeros(rows), np.ones(rows), np.ones(rows), hp, threads=threads)
         return time.perf_counter() - t
-    rows0 = min(N * T, 16)
+    rows0 = min(N * T, 16 * max(1, threads))
     t_cal = learn(rows0)
     mb_rows = N * T // cfg["minibatches"]
     rows = int(min(mb_rows, max(rows0, 0.6 * budget_s * rows0 / t_cal)))
@@ -257,11 +132,11 @@ def cpu_baseline(cfg, loop, budget_s=16.0):
     t_learn /= reps
     learn_rows = N * T * cfg["epochs"]
     total = t_act * (T + 1) + t_gae + t_learn * (learn_rows / rows)
-    return {"value": N * T / total, "unit": "env-frames/s", "cores": 1, "kind": "oracle",
+    return {"value": N * T / total, "unit": "env-frames/s", "cores": threads, "kind": "oracle",
             "sample": f"{n_steps} hts_act steps of {N} frames (an iteration has {T + 1}), GAE in full, {reps} learner "
                       f"update(s) on {rows} rows scaled linearly to the iteration's {learn_rows}; "
-                      f"{t_act * n_steps + t_gae + t_cal + t_learn * reps:.1f} s of CPU work",
-            "learner_samples_per_s": rows / t_learn}
+                      f"{t_act * n_steps + t_gae + t_cal + t_learn * reps:.1f} s of wall time on {threads} thread(s)",
+            "learner_samples_per_s": rows / t_learn, "host_cores": os.cpu_count()}
 
 
 def source_digest():
@@ -269,7 +144,7 @@ def source_digest():
     import glob
     import hashlib
     h = hashlib.sha256()
-    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2012_09849_amd", "csrc")
+    root = os.path.join(ROOT, "paper_2012_09849_amd", "csrc")
     for f in sorted(glob.glob(os.path.join(root, "*.hip")) + glob.glob(os.path.join(root, "*.hpp"))):
         h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
@@ -279,23 +154,83 @@ def source_digest():
 # FETCH_SIZE / WRITE_SIZE (KiB per dispatch, averaged over the site's launches of the run, each scaled by what the
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
-TRAFFIC = {
-    "atari_a2c_n16_t5_fp32": ({"conv1_fwd": 4770809, "conv2_fwd": 6707252, "conv3_fwd": 3632676}, "146048e642115fd3"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 9854484}, "146048e642115fd3"),
-}
+TRAFFIC = {}
 
 
-def streaming_rooflines(loop, per_step, work, torch, overhead_ms):
-    """Achieved bandwidth of the streaming kernels: Adam inside this workload, and returns/GAE at 128 x 4096."""
+def run_iterations(loop, torch, steps, warmup, sample_site=None, sample_every=1):
+    """warmup untimed steps, then `steps` timed ones between two synchronisations.  sample_site: bracket every
+    sample_every-th launch of that site with events during the timed steps."""
+    for _ in range(warmup):
+        loop.step()
+    torch.cuda.synchronize()
+    if sample_site is not None:
+        loop.ctx.hts_profile_begin_sampled(sample_site, sample_every)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        loop.step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    timed = loop.ctx.hts_profile_end() if sample_site is not None else (0, 0.0)
+    return wall, timed
+
+
+def time_learner(loop, torch, n):
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(n):
+        loop.learn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t1) / n
+
+
+def workload_summary(name, steps, warmup, hts, torch, syn):
+    """One of the other workloads, timed the same way (no brackets)."""
+    cfg = CONFIGS[name]
+    loop = Loop(cfg, hts, torch, syn)
+    wall, _ = run_iterations(loop, torch, steps, warmup)
+    t_learn = time_learner(loop, torch, max(1, steps // 4))
+    frames = cfg["N"] * cfg["T"]
+    out = {"value": frames * steps / wall, "unit": "env-frames/s", "ms_per_step": wall / steps * 1e3, "steps": steps,
+           "warmup": warmup, "dtype": "f32" if cfg["precision"] == 0 else "bf16",
+           "learner_samples_per_s": frames * cfg["epochs"] / t_learn, "learner_ms_per_step": t_learn * 1e3,
+           "config": {"envs": cfg["N"], "unroll": cfg["T"], "obs": [cfg["C"], cfg["H"], cfg["W"]],
+                      "epochs": cfg["epochs"], "minibatches": cfg["minibatches"]}}
+    loop.ctx.close()
+    del loop
+    torch.cuda.empty_cache()
+    return out
+
+
+def act_sweep(hts, torch, syn):
+    """Large-batch actor / returns sweep: hts_act over N in {256, 1024, 4096} Atari-shaped observations (bf16, 18
+    actions, seeded sampling), frames/s per call with the parameters already loaded; returns/GAE at 128 x 4096 and,
+    for a bandwidth- rather than launch-bound figure, at 128 x 262144."""
+    import numpy as np
     out = {}
-    if "adam" in per_step:
-        ms, n = per_step["adam"]
-        ms = max(ms - n * overhead_ms, 1e-6)
-        gbs = work["adam"][1] / (ms * 1e-3) / 1e9
-        out["adam"] = {"GB/s": gbs, "frac": gbs * 1e9 / PEAK["hbm"], "avg_launch_us": ms / n * 1e3}
-    ctx = loop.ctx
+    params = torch.from_numpy(syn.init_params(syn.MASTER_SEED, 4, 84, 84, 18)).cuda()
+    base = syn.obs_atari(syn.MASTER_SEED, 1, 256)[0]                 # 256 distinct environments, tiled to N
+    for N in (256, 1024, 4096):
+        obs = torch.from_numpy(np.ascontiguousarray(np.tile(base, (N // 256, 1, 1, 1)))).cuda()
+        ctx = hts.Context(4, 84, 84, 18, precision=1, max_act_batch=N)
+        actions = torch.zeros(N, dtype=torch.int32, device="cuda")
+        logp, values = torch.zeros(N, device="cuda"), torch.zeros(N, device="cuda")
+        ctx.hts_act(obs, params, 7, 0, 0, actions, logp, values)
+        reps = 200 if N <= 1024 else 60
+        for s in range(5):
+            ctx.hts_act(obs, None, 7, s, 0, actions, logp, values)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(reps):
+            ctx.hts_act(obs, None, 7, s, 0, actions, logp, values)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        out[f"act_n{N}"] = {"frames_per_s": N / dt, "us_per_call": dt * 1e6,
+                            "frac_of_bf16_mfma_peak": N * sum(layer_flops(dict(C=4, H=84, W=84)).values()) / dt / PEAK["mfma_bf16"]}
+        ctx.close()
+        del obs
+    ctx = hts.Context(4, 84, 84, 18, precision=1, max_act_batch=1)
+    overhead_ms = ctx.hts_profile_overhead(256)
     g = torch.Generator(device="cuda").manual_seed(1)
-    # the sweep size of the actor/returns configuration, and one wide enough to be bandwidth- rather than launch-bound
     for T, N, reps in ((128, 4096, 200), (128, 262144, 20)):
         r, v = torch.randn(T, N, device="cuda", generator=g), torch.randn(T + 1, N, device="cuda", generator=g)
         d = (torch.rand(T, N, device="cuda", generator=g) < 0.01).to(torch.uint8)
@@ -307,21 +242,25 @@ def streaming_rooflines(loop, per_step, work, torch, overhead_ms):
             ctx.hts_returns_gae(r, v, d, 0.99, 0.95, adv, ret)
         n, ms = ctx.hts_profile_end()
         nbytes = 17.0 * T * N + 4.0 * N
-        us = max(ms / n - overhead_ms, 1e-6) * 1e3
-        out[f"gae_{T}x{N}"] = {"GB/s": nbytes / (us * 1e-6) / 1e9, "frac": nbytes / (us * 1e-6) / PEAK["hbm"],
-                               "avg_launch_us": us}
+        raw_us = ms / n * 1e3
+        us = max(raw_us - overhead_ms * 1e3, 1e-3)
+        out[f"gae_{T}x{N}"] = {"GB/s": nbytes / (us * 1e-6) / 1e9, "frac_of_hbm_peak": nbytes / (us * 1e-6) / PEAK["hbm"],
+                               "avg_launch_us": us, "raw_bracket_us": raw_us, "event_overhead_us": overhead_ms * 1e3}
         del r, v, d, adv, ret
+    ctx.close()
+    torch.cuda.empty_cache()
     return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="atari_a2c_n16_t5_fp32", choices=sorted(CONFIGS))
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--site", default=None, help="time this launch site instead of discovering the dominant one")
+    ap.add_argument("--no-others", action="store_true", help="skip the other workloads and the overlapped schedule")
+    ap.add_argument("--site", default=None, help="bracket this launch site instead of discovering the dominant one")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="calibration for hardware counters: run a plain device copy of this many MiB and exit")
     args = ap.parse_args()
@@ -350,84 +289,68 @@ def main():
     for _ in range(args.warmup):
         loop.step()
     torch.cuda.synchronize()
-    work = site_work(cfg, loop)
-    # an event bracket also times the events themselves: what an empty bracket reads is subtracted everywhere
-    overhead_ms = loop.ctx.hts_profile_overhead(256)
+    work = site_work(cfg, loop.ctx.P)
+    names = loop.ctx.profile_sites()
+    overhead_ms = loop.ctx.hts_profile_overhead(256)     # what an empty event bracket reads
     if args.site:
         dominant, per_step = args.site, {}
-        loop.ctx.hts_profile_begin(loop.ctx.profile_sites().index(dominant))
+        loop.ctx.hts_profile_begin(names.index(dominant))
         loop.step()
         n1, ms1 = loop.ctx.hts_profile_end()
         per_step[dominant] = (ms1, n1)
     else:
-        dominant, per_step = find_dominant(loop, work, overhead_ms)
-    site_id = loop.ctx.profile_sites().index(dominant)
+        per_step = time_sites(loop)
+        ranked = sorted(((v[0] - v[1] * overhead_ms, k) for k, v in per_step.items() if k in work), reverse=True)
+        dominant = ranked[0][1]
+    launches_per_step = per_step[dominant][1]
+    # about 64 brackets per step: a bracket costs the stream about as much as a small kernel
+    every = max(1, int(launches_per_step // 64))
     torch.cuda.synchronize()
 
-    # timed region: the dominant kernel's launches are bracketed by HIP events on the library's stream
-    loop.ctx.hts_profile_begin(site_id)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        loop.step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    n_timed, ms_timed = loop.ctx.hts_profile_end()
-
-    # learner part alone
-    torch.cuda.synchronize()
-    nl = max(1, args.steps // 4)
-    t1 = time.perf_counter()
-    for _ in range(nl):
-        loop.learn()
-    torch.cuda.synchronize()
-    learn_wall = time.perf_counter() - t1
+    # timed region: a sample of the dominant kernel's launches is bracketed by HIP events on the library's stream
+    wall, (n_timed, ms_timed) = run_iterations(loop, torch, args.steps, 0, names.index(dominant), every)
+    t_learn = time_learner(loop, torch, max(1, args.steps // 4))
 
     N, T = cfg["N"], cfg["T"]
     frames = N * T
-    ms = wall / args.steps * 1e3
     learn_rows = frames * cfg["epochs"]
     out = {
-        "metric": "env-frames/sec (act+GAE+PPO update) and learner samples/sec, 1\u00d7MI355X",
+        "metric": METRIC,
         "value": frames * args.steps / wall,
         "unit": "env-frames/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if cfg["precision"] == 0 else "bf16",
         "data": "synthetic",
         "config": {"workload": args.workload, "envs": N, "unroll": T, "actions": cfg["A"],
-                   "obs": [cfg["C"], cfg["H"], cfg["W"]], "learner_rows_per_step": learn_rows},
-        "learner_samples_per_s": learn_rows * nl / learn_wall,
-        "learner_ms_per_step": learn_wall / nl * 1e3,
+                   "obs": [cfg["C"], cfg["H"], cfg["W"]], "epochs": cfg["epochs"], "minibatches": cfg["minibatches"],
+                   "minibatch_rows": loop.B, "learner_rows_per_step": learn_rows},
+        "learner_samples_per_s": learn_rows / t_learn,
+        "learner_ms_per_step": t_learn * 1e3,
     }
-    kind, amount = work[dominant]
-    launches_per_step = per_step[dominant][1]
-    avg_s = max(ms_timed / max(n_timed, 1) - overhead_ms, 1e-6) * 1e-3
+    kind, per_launch, rows = work[dominant]
     traffic = None
     if args.workload in TRAFFIC and dominant in TRAFFIC[args.workload][0] and TRAFFIC[args.workload][1] == source_digest():
         traffic = TRAFFIC[args.workload][0][dominant]
-    per_launch = amount / launches_per_step
-    if kind == "flop":
-        peak = PEAK["mfma_f32"] if cfg["precision"] == 0 else PEAK["mfma_bf16"]
-        out["roofline"] = {"kernel": dominant, "bound": "mfma", "achieved": per_launch / avg_s / 1e12, "peak": peak / 1e12,
-                           "unit": "TFLOP/s", "frac": per_launch / avg_s / peak, "traffic": traffic,
-                           "avg_launch_us": avg_s * 1e6, "event_overhead_us": overhead_ms * 1e3,
-                           "launches_timed": n_timed,
-                           "launches_per_step": launches_per_step}
-    else:
-        out["roofline"] = {"kernel": dominant, "bound": "hbm", "achieved": per_launch / avg_s / 1e9, "peak": 8000.0,
-                           "unit": "GB/s", "frac": per_launch / avg_s / PEAK["hbm"], "traffic": traffic,
-                           "avg_launch_us": avg_s * 1e6, "event_overhead_us": overhead_ms * 1e3,
-                           "launches_timed": n_timed,
-                           "launches_per_step": launches_per_step}
-    if not args.site:
-        out["streaming"] = streaming_rooflines(loop, per_step, work, torch, overhead_ms)
-    # per-site event-bracket sums, less what the brackets themselves read
-    net = {k: max(v[0] - v[1] * overhead_ms, 0.0) for k, v in per_step.items()}
-    out["kernel_ms_per_step"] = {k: round(v, 5) for k, v in sorted(net.items(), key=lambda kv: -kv[1])}
-    if not args.site:
+    out["roofline"] = roofline_entry(cfg, dominant, kind, per_launch, rows, ms_timed / max(n_timed, 1) * 1e-3,
+                                     overhead_ms * 1e-3, n_timed, launches_per_step, traffic)
+    # every launch site of this workload: event-bracket time per launch (raw, and less the empty bracket) and its share
+    kernels = {}
+    for k, (ms, n) in sorted(per_step.items(), key=lambda kv: -(kv[1][0] - kv[1][1] * overhead_ms)):
+        raw_us = ms / n * 1e3
+        e = {"launches_per_step": n, "raw_bracket_us": round(raw_us, 3),
+             "avg_launch_us": round(max(raw_us - overhead_ms * 1e3, 0.0), 3),
+             "ms_per_step": round(max(ms - n * overhead_ms, 0.0), 5)}
+        if k in work:
+            wk, amount, _ = work[k]
+            pk = PEAK["hbm"] if wk == "byte" else (PEAK["mfma_f32"] if cfg["precision"] == 0 else PEAK["mfma_bf16"])
+            e["frac_of_peak"] = round(amount / max((raw_us - overhead_ms * 1e3) * 1e-6, 1e-9) / pk, 5)
+        kernels[k] = e
+    out["kernels"] = kernels
+    if not args.site and not args.no_others:
         ov = OverlapLoop(loop)
-        ov_steps = args.steps if cfg["epochs"] * cfg["minibatches"] == 1 else max(1, args.steps // 4)
-        for _ in range(min(args.warmup, 10)):
+        ov_steps = max(1, args.steps // 2)
+        for _ in range(2):
             ov.step()
         torch.cuda.synchronize()
         t2 = time.perf_counter()
@@ -441,8 +364,23 @@ def main():
                                          "storage on a second stream (one update per storage: the one-step-delayed "
                                          "update; several: ordinary epochs from theta_j); same work per step as "
                                          "`value`, which runs the three parts in sequence"}
+        ov.ctx_act.close()
+        ov.ctx_learn.close()
+        del ov
     if not args.no_cpu_baseline:
+        import oracle
         out["cpu_baseline"] = cpu_baseline(cfg, loop)
+        out["cpu_baseline_all_cores"] = cpu_baseline(cfg, loop, budget_s=8.0, threads=oracle.host_threads())
+    loop.ctx.close()
+    del loop
+    torch.cuda.empty_cache()
+    if not args.site and not args.no_others:
+        others = {}
+        for name, steps, warmup in (("atari_ppo_n32_t128_bf16", 40, 3), ("atari_a2c_n16_t5_fp32", 1000, 50)):
+            if name != args.workload:
+                others[name] = workload_summary(name, steps, warmup, hts, torch, syn)
+        others["act_sweep_bf16"] = act_sweep(hts, torch, syn)
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 

@@ -195,6 +195,10 @@ int32_t hts_test_gemm(hts_ctx *ctx, int32_t precision, const float *A, const flo
 int32_t     hts_profile_site_count(void);
 const char *hts_profile_site_name(int32_t site);
 int32_t     hts_profile_begin(hts_ctx *ctx, int32_t site);
+/* The same with only every `every`-th launch of the site bracketed (every >= 1): a site with hundreds of short launches
+ * per iteration can then be timed inside a throughput measurement without stretching it (a bracket costs the stream
+ * about as much as a small kernel). */
+int32_t     hts_profile_begin_sampled(hts_ctx *ctx, int32_t site, int32_t every);
 int32_t     hts_profile_end(hts_ctx *ctx, int32_t *launches, double *total_ms);
 /* Mean elapsed time (ms) of `reps` (1..4096) event pairs with nothing between them: the part of every bracket that
  * the timer itself contributes.  Ends any open profiling window. */

@@ -16,7 +16,7 @@ OPT_ADAM, OPT_RMSPROP = 0, 1
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_learner_step_delayed", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
            "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
-           "hts_profile_end", "hts_profile_overhead"]
+           "hts_profile_end", "hts_profile_overhead", "hts_profile_begin_sampled"]
 
 
 class HtsError(RuntimeError):
@@ -94,6 +94,7 @@ def load_library():
         lib.hts_profile_site_name.restype = C.c_char_p
         lib.hts_profile_site_name.argtypes = [C.c_int32]
         lib.hts_profile_begin.argtypes = [C.c_void_p, C.c_int32]
+        lib.hts_profile_begin_sampled.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         lib.hts_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         lib.hts_profile_overhead.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]
         _lib = lib
@@ -263,6 +264,9 @@ class Context:
 
     def hts_profile_begin(self, site: int):
         _check(self.lib.hts_profile_begin(self._h, site), "hts_profile_begin")
+
+    def hts_profile_begin_sampled(self, site: int, every: int):
+        _check(self.lib.hts_profile_begin_sampled(self._h, site, every), "hts_profile_begin_sampled")
 
     def hts_profile_end(self):
         """-> (timed launches, total milliseconds)."""

@@ -336,7 +336,7 @@ extern "C" int32_t hts_profile_end(hts_ctx *ctx, int32_t *launches, double *tota
 static const char *const k_site_names[SITE_COUNT] = {
     "prep", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc_fwd", "heads_act", "heads_learn", "heads_wgrad", "fc_wgrad",
     "fc_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "wgrad_reduce", "grad_norm",
-    "adam", "gae", "normalize", "stats"};
+    "adam", "gae", "normalize", "stats", "conv1_fwd_learn", "conv2_fwd_learn", "conv3_fwd_learn", "fc_fwd_learn"};
 
 extern "C" int32_t hts_profile_site_count(void) { return SITE_COUNT; }
 
@@ -345,9 +345,12 @@ extern "C" const char *hts_profile_site_name(int32_t site)
     return (site >= 0 && site < SITE_COUNT) ? k_site_names[site] : "";
 }
 
-extern "C" int32_t hts_profile_begin(hts_ctx *ctx, int32_t site)
+extern "C" int32_t hts_profile_begin_sampled(hts_ctx *ctx, int32_t site, int32_t every);
+extern "C" int32_t hts_profile_begin(hts_ctx *ctx, int32_t site) { return hts_profile_begin_sampled(ctx, site, 1); }
+
+extern "C" int32_t hts_profile_begin_sampled(hts_ctx *ctx, int32_t site, int32_t every)
 {
-    if (!ctx || site < 0 || site >= SITE_COUNT) return HTS_EINVAL;
+    if (!ctx || site < 0 || site >= SITE_COUNT || every < 1) return HTS_EINVAL;
     Profiler &p = ctx->c.prof;
     if (!p.ev) {
         p.ev = new (std::nothrow) hipEvent_t[2 * PROF_CAP];
@@ -361,7 +364,7 @@ extern "C" int32_t hts_profile_begin(hts_ctx *ctx, int32_t site)
             }
         }
     }
-    p.site = site; p.n = 0;
+    p.site = site; p.n = 0; p.every = every; p.seen = 0;
     return HTS_OK;
 }
 

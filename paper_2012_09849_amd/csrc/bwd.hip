@@ -209,12 +209,12 @@ static hipError_t launch_conv1_wgrad_image(Ctx &c, const uint8_t *obs, const int
                        : g.C == 12 ? conv1_wgrad_image_kernel<3, true> : conv1_wgrad_image_kernel<4, true>;
     else kern = g.C == 4 ? conv1_wgrad_image_kernel<1, false> : g.C == 8 ? conv1_wgrad_image_kernel<2, false>
                 : g.C == 12 ? conv1_wgrad_image_kernel<3, false> : conv1_wgrad_image_kernel<4, false>;
-    static bool attr_set[8] = {};       // raise the dynamic-LDS limit once per instantiation
-    if (!attr_set[g.C / 4 - 1 + (padded ? 4 : 0)]) {
+    static std::atomic<bool> attr_set[8] = {};       // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
+    if (!attr_set[g.C / 4 - 1 + (padded ? 4 : 0)].load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_set[g.C / 4 - 1 + (padded ? 4 : 0)] = true;
+        attr_set[g.C / 4 - 1 + (padded ? 4 : 0)].store(true, std::memory_order_release);
     }
     const int grid = B < max_parts ? B : max_parts;
     *nz = grid;

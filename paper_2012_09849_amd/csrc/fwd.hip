@@ -186,7 +186,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.C = g.C; p.H = g.H; p.W = g.W; p.W1 = g.W1; p.P1 = g.P1;
         p.dP1 = FastDiv::make(g.P1); p.dW1 = FastDiv::make(g.W1);
         {
-            SiteTimer tm(c, SITE_CONV1_FWD);
+            SiteTimer tm(c, learn ? SITE_CONV1_FWD_LEARN : SITE_CONV1_FWD);
             // one wavefront per 64-long segment (= per input channel): 4 for a 4-channel frame; a 16-channel frame
             // gets 16 (binary32: with the weight operand straight from memory so that their panels still fit in LDS;
             // bfloat16 panels fit, and staging the weights is faster: 9.7 -> 8.3 us at 16 rows of 16x72x96)
@@ -214,7 +214,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.Hin = g.H1; p.Win = g.W1; p.Wo = g.W2; p.Po = g.P2;
         p.dPo = FastDiv::make(g.P2); p.dWo = FastDiv::make(g.W2);
         {
-            SiteTimer tm(c, SITE_CONV2_FWD);
+            SiteTimer tm(c, learn ? SITE_CONV2_FWD_LEARN : SITE_CONV2_FWD);
             // (the LDS-resident kernel of imgconv.hpp measured slower here than the tile kernel: 20.4 vs 17.8 us at
             // B = 1024 -- this layer streams the large conv1 output once either way)
             if (small && few32(((p.M + 31) / 32) * 2))
@@ -233,7 +233,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.Hin = g.H2; p.Win = g.W2; p.Wo = g.W3; p.Po = g.P3;
         p.dPo = FastDiv::make(g.P3); p.dWo = FastDiv::make(g.W3);
         {
-            SiteTimer tm(c, SITE_CONV3_FWD);
+            SiteTimer tm(c, learn ? SITE_CONV3_FWD_LEARN : SITE_CONV3_FWD);
             if (small && few32(((p.M + 31) / 32) * 2))     // binary32: 6 segments of 96; bfloat16: 3 of 192 (the fold needs 4 wavefronts)
                 e = launch_wsgemm16<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 6 : 4), ConvFwd<T, Layer3, true>::SEG>(p, c.stream);
             else if (small) e = launch_wsgemm<ConvFwd<T, Layer3, true>, (sizeof(T) == 4 ? 8 : 4), ConvFwd<T, Layer3, true>::SEG, false, true>(p, c.stream);
@@ -257,7 +257,7 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
         p.a3 = (const T *)c.ws.a3; p.w = (const T *)c.ws.wfc; p.part = c.ws.fc_part;
         static_assert(FC_GROUP_K % FcFwd<T>::SEG == 0 && FcFwd<T>::GROUP == FC_GROUP_K, "a group is a whole number of segments");
         {
-            SiteTimer tm(c, SITE_FC_FWD);
+            SiteTimer tm(c, learn ? SITE_FC_FWD_LEARN : SITE_FC_FWD);
             // (also when 16-row tiles leave fewer padded rows: 80 rows are five tiles of 16 but three of 32; 13.8 -> 10.9 us)
             const bool less_padding = c.tile16_below > 0 && ((B + 15) / 16) * 16 < ((B + 31) / 32) * 32;
             if (small && (few32(((B + 31) / 32) * 16 * c.fc_groups) || less_padding))

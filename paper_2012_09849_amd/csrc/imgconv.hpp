@@ -285,12 +285,12 @@ template <class S> inline hipError_t launch_imgconv(const ImgConvArgs &a, hipStr
 {
     if (a.B <= 0) return hipSuccess;
     auto kern = imgconv_kernel<S>;
-    static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};       // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
+    if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)imgconv_lds_bytes<S>());
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int ngroups = (a.B + S::G - 1) / S::G;
     const int grid = ngroups < 256 ? ngroups : 256;          // one workgroup per compute unit walks the groups

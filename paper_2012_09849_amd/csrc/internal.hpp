@@ -42,12 +42,15 @@ enum Site {
     SITE_PREP = 0, SITE_CONV1_FWD, SITE_CONV2_FWD, SITE_CONV3_FWD, SITE_FC_FWD, SITE_HEADS_ACT, SITE_HEADS_LEARN,
     SITE_HEADS_WGRAD, SITE_FC_WGRAD, SITE_FC_DGRAD, SITE_CONV3_WGRAD, SITE_CONV3_DGRAD, SITE_CONV2_WGRAD,
     SITE_CONV2_DGRAD, SITE_CONV1_WGRAD, SITE_WGRAD_REDUCE, SITE_GRAD_NORM, SITE_ADAM, SITE_GAE, SITE_NORMALIZE,
-    SITE_STATS, SITE_COUNT
+    SITE_STATS,
+    // the learner's forward pass runs other kernels than an actor call of a few rows: its launches are sites of their own
+    SITE_CONV1_FWD_LEARN, SITE_CONV2_FWD_LEARN, SITE_CONV3_FWD_LEARN, SITE_FC_FWD_LEARN, SITE_COUNT
 };
 constexpr int PROF_CAP = 4096;     // event pairs kept per profiling window
 
 struct Profiler {
     int site = -1, n = 0;
+    int every = 1, seen = 0;       // only every `every`-th launch of the site is bracketed; launches of the site seen so far
     hipEvent_t *ev = nullptr;      // 2*PROF_CAP events, created on first use
 };
 
@@ -74,6 +77,7 @@ struct SiteTimer {
     bool on;
     SiteTimer(Ctx &ctx, int site) : c(ctx), on(ctx.prof.site == site && ctx.prof.ev && ctx.prof.n < PROF_CAP)
     {
+        if (on) on = (c.prof.seen++ % c.prof.every) == 0;
         if (on) (void)hipEventRecord(c.prof.ev[2 * c.prof.n], c.stream);
     }
     ~SiteTimer()

@@ -407,12 +407,12 @@ template <class P, int WAVES, int SEG> inline hipError_t launch_wsgemm16(const P
     using T = typename P::T;
     const size_t lds = (size_t)WAVES * 2 * 16 * (SEG + OperandTraits<T>::VEC) * sizeof(T);
     auto kern = wsgemm16_kernel<P, WAVES, SEG>;
-    static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};       // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
+    if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int spg = segs_per_group < nseg ? segs_per_group : nseg;
     hipLaunchKernelGGL(kern, dim3(tiles, (nseg + spg - 1) / spg, grid_batches(p)), dim3(WAVES * 64, 1, 1), lds, stream, p, spg);
@@ -428,12 +428,12 @@ inline hipError_t launch_wsgemm(const P &p, hipStream_t stream, int segs_per_gro
     if (tiles <= 0 || nseg <= 0) return hipSuccess;
     const size_t lds = (size_t)WAVES * (BDIR ? 1 : 2) * 32 * (SEG + OperandTraits<T>::PAD) * sizeof(T);
     auto kern = wsgemm_kernel<P, WAVES, SEG, PARTIAL, BDIR>;
-    static bool attr_set = false;       // raise the dynamic-LDS limit once per instantiation
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};       // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
+    if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int spg = segs_per_group < nseg ? segs_per_group : nseg;
     const int gy = PARTIAL ? (nseg + WAVES - 1) / WAVES : (nseg + spg - 1) / spg;

@@ -1,4 +1,4 @@
-"""The concurrent schedule of bench.py (rollout on one stream, one-step-delayed learner update on another) must give
+"""The concurrent schedule of the package (schedule.OverlapLoop: rollout on one stream, one-step-delayed learner update on another) must give
 the same bits as the same calls issued one after the other on a single stream: concurrency changes when things run,
 never what they compute (the paper's determinism claim, Sec. 4.1)."""
 
@@ -11,11 +11,11 @@ pytestmark = pytest.mark.gpu
 
 
 def test_overlapped_schedule_equals_serial_schedule():
-    import bench
     import paper_2012_09849_amd as hts
-    cfg = dict(bench.CONFIGS["atari_a2c_n16_t5_fp32"])
-    base = bench.Loop(cfg, hts, torch, syn)
-    ov = bench.OverlapLoop(base)
+    from paper_2012_09849_amd import schedule
+    cfg = dict(schedule.CONFIGS["atari_a2c_n16_t5_fp32"])
+    base = schedule.Loop(cfg, hts, torch, syn)
+    ov = schedule.OverlapLoop(base)
     iters = 5
     for _ in range(iters):
         ov.step()
@@ -60,11 +60,11 @@ def test_overlapped_schedule_equals_serial_schedule():
 def test_overlapped_ppo_schedule_equals_serial_schedule():
     """Several minibatch steps per storage: the learner's epochs on storage j-1 run beside the rollout of storage j;
     the serial replay of the same calls gives the same parameters and actions."""
-    import bench
     import paper_2012_09849_amd as hts
-    cfg = dict(bench.CONFIGS["atari_ppo_n32_t128_bf16"], N=8, T=12, epochs=2, minibatches=2)
-    base = bench.Loop(cfg, hts, torch, syn)
-    ov = bench.OverlapLoop(base)
+    from paper_2012_09849_amd import schedule
+    cfg = dict(schedule.CONFIGS["atari_ppo_n32_t128_bf16"], N=8, T=12, epochs=2, minibatches=2)
+    base = schedule.Loop(cfg, hts, torch, syn)
+    ov = schedule.OverlapLoop(base)
     iters = 4
     for _ in range(iters):
         ov.step()
