@@ -181,6 +181,20 @@ int32_t hts_loss_and_grads(hts_ctx *ctx, const hts_buffer *buf, const float *par
 int32_t hts_adam_apply(hts_ctx *ctx, float *params, const float *grads, hts_opt_state *opt, const hts_hparams *hp,
                        int64_t P);
 
+/* Clip + optimiser step for callers that cannot allocate and hold no context: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The same kernels and the same results as hts_adam_apply, but the
+ * scratch memory of the gradient-norm reduction (one partial sum per 8192 parameters) is a static device array of the
+ * library instead of a context's workspace: the call allocates nothing, creates nothing and needs no hts_create.
+ *   params, grads, opt->m, opt->v   device f32 [P], caller-owned;  hp, opt  host structs as for hts_adam_apply
+ *   P           1 .. HTS_STATIC_MAX_PARAMS (HTS_ESHAPE beyond: the static array is sized for that many)
+ *   hip_stream  hipStream_t to enqueue on (NULL = the default stream); not synchronised
+ * The array belongs to the GPU that is current when the call is made (every GPU has its own copy, held until the
+ * process ends) and is shared by all calls on that GPU: calls that overlap in time on one GPU race on it -- issue them
+ * on one stream, or otherwise order them.  Nothing in it has to be cleared between calls. */
+#define HTS_STATIC_MAX_PARAMS 16777216
+int32_t hts_adam_apply_static(float *params, const float *grads, hts_opt_state *opt, const hts_hparams *hp, int64_t P,
+                              void *hip_stream);
+
 /* Test hook for the tiled matrix-multiply core every layer is built on: C[M,N] = A[M,K] * B[N,K]^T, all f32
  * row-major device arrays; operands are rounded to bf16 first when precision = HTS_PRECISION_BF16.  K % 8 == 0. */
 int32_t hts_test_gemm(hts_ctx *ctx, int32_t precision, const float *A, const float *B, float *Cout, int32_t M,

@@ -16,7 +16,7 @@ OPT_ADAM, OPT_RMSPROP = 0, 1
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_learner_step_delayed", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
            "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
-           "hts_profile_end", "hts_profile_overhead", "hts_profile_begin_sampled"]
+           "hts_profile_end", "hts_profile_overhead", "hts_profile_begin_sampled", "hts_adam_apply_static"]
 
 
 class HtsError(RuntimeError):
@@ -89,6 +89,8 @@ def load_library():
                                            C.c_void_p]
         lib.hts_adam_apply.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_OptStateC), C.POINTER(HParams),
                                        C.c_int64]
+        lib.hts_adam_apply_static.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_OptStateC), C.POINTER(HParams),
+                                              C.c_int64, C.c_void_p]
         lib.hts_test_gemm.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_int32]
         lib.hts_profile_site_name.restype = C.c_char_p
@@ -121,6 +123,17 @@ def _ptr(t, dtype, name):
     if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise HtsError(f"{name}: expected a contiguous {dtype} device tensor")
     return C.c_void_p(t.data_ptr())
+
+
+def hts_adam_apply_static(params, grads, opt: OptState, hp: HParams, stream=None):
+    """Clip + optimiser step through the library's static scratch array: no context, no allocation."""
+    lib = load_library()
+    stream = stream if stream is not None else torch.cuda.current_stream()
+    oc = _OptStateC(_ptr(opt.m, torch.float32, "m"), _ptr(opt.v, torch.float32, "v"), opt.step)
+    _check(lib.hts_adam_apply_static(_ptr(params, torch.float32, "params"), _ptr(grads, torch.float32, "grads"),
+                                     C.byref(oc), C.byref(hp), params.numel(), C.c_void_p(stream.cuda_stream)),
+           "hts_adam_apply_static")
+    opt.step = oc.step
 
 
 class Context:

@@ -16,6 +16,7 @@ static int32_t hip_fail(hipError_t e)
     g_last_hip = (int32_t)e;
     return HTS_EHIP;
 }
+void hts::note_hip_error(hipError_t e) { g_last_hip = (int32_t)e; }
 #define HIP_TRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
 
 static int32_t make_geom(const hts_net_desc *d, Geom *g)

@@ -113,6 +113,8 @@ struct LossArgs {
     float rho_bar, value_clip;        // truncation level of the importance weight; radius of the clipped value loss (<= 0: off)
 };
 
+// api.hip: remembers a HIP error code for hts_last_hip_error()
+void note_hip_error(hipError_t e);
 // fwd.hip
 hipError_t run_forward(Ctx &c, const uint8_t *obs, const int32_t *index, int B, bool learn);
 hipError_t run_plain_gemm(Ctx &c, int precision, const float *A, const float *B, float *C, int M, int N, int K);

@@ -3,6 +3,10 @@
 //
 // This file is compiled with floating-point contraction off: the sampler's decision rule is a fixed sequence of
 // binary32 operations (see hts_act in hts.h) and must not be re-associated or fused.
+#include <math.h>
+
+#include <mutex>
+
 #include "internal.hpp"
 
 #pragma clang fp contract(off)
@@ -814,13 +818,19 @@ __global__ __launch_bounds__(256) void clip_finalize_kernel(const float *__restr
     }
 }
 
+static void enqueue_sumsq(hipStream_t stream, const float *g, long long P, float *norm_part)
+{
+    const int nparts = (int)((P + NORM_CHUNK - 1) / NORM_CHUNK);
+    hipLaunchKernelGGL(sumsq_kernel, dim3(nparts), dim3(256), 0, stream, g, P, norm_part);
+}
+
 // finalize = false leaves the per-chunk sums in the workspace for the optimiser kernel, which then forms the norm and the
 // clip factor itself (the same additions in the same order, in every workgroup): one launch less per update
 hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm, bool finalize)
 {
     SiteTimer tm(c, SITE_GRAD_NORM);
     const int nparts = (int)((P + NORM_CHUNK - 1) / NORM_CHUNK);
-    hipLaunchKernelGGL(sumsq_kernel, dim3(nparts), dim3(256), 0, c.stream, g, P, c.ws.norm_part);
+    enqueue_sumsq(c.stream, g, P, c.ws.norm_part);
     if (finalize)
         hipLaunchKernelGGL(clip_finalize_kernel, dim3(1), dim3(256), 0, c.stream, c.ws.norm_part, nparts, max_norm,
                            c.ws.clip);
@@ -875,22 +885,92 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ theta, co
     }
 }
 
-hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale,
-                       const float *norm_part, float max_norm, float lr, float b1, float b2, float eps, float bc1, float bc2)
+static void enqueue_adam(hipStream_t stream, float *theta, const float *g, float *m, float *v, long long P,
+                         const float *scale, const float *norm_part, float max_norm, float lr, float b1, float b2,
+                         float eps, float bc1, float bc2)
 {
     const int nparts = (int)((P + NORM_CHUNK - 1) / NORM_CHUNK);
-    SiteTimer tm(c, SITE_ADAM);
     const bool aligned = (((uintptr_t)theta | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15u) == 0;
     const float ibc1 = 1.0f / bc1, ibc2 = 1.0f / bc2;
     if (aligned) {
         const long long nthreads = (P + 3) / 4;
-        hipLaunchKernelGGL(adam_kernel<true>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, c.stream, theta, g,
+        hipLaunchKernelGGL(adam_kernel<true>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, stream, theta, g,
                            m, v, P, scale, norm_part, nparts, max_norm, lr, b1, b2, eps, ibc1, ibc2);
     } else {
-        hipLaunchKernelGGL(adam_kernel<false>, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, c.stream, theta, g, m, v,
+        hipLaunchKernelGGL(adam_kernel<false>, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, stream, theta, g, m, v,
                            P, scale, norm_part, nparts, max_norm, lr, b1, b2, eps, ibc1, ibc2);
     }
+}
+
+hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale,
+                       const float *norm_part, float max_norm, float lr, float b1, float b2, float eps, float bc1, float bc2)
+{
+    SiteTimer tm(c, SITE_ADAM);
+    enqueue_adam(c.stream, theta, g, m, v, P, scale, norm_part, max_norm, lr, b1, b2, eps, bc1, bc2);
     return hipGetLastError();
 }
 
 }  // namespace hts
+
+// ------------------------------------------------------------------------------------------------------------
+// Clip + optimiser step without a context and without any allocation: the per-chunk sums of squares of the gradient
+// norm live in a file-scope device array instead of a context's workspace.  For callers that cannot allocate (code
+// under graph capture, tight serving loops).  Every GPU holds its own copy of the array; its device address is looked
+// up once per device and only that address is handed to kernels.
+// ------------------------------------------------------------------------------------------------------------
+namespace {
+constexpr long long STATIC_MAX_PARAMS = HTS_STATIC_MAX_PARAMS;
+constexpr int STATIC_PARTS = (int)((STATIC_MAX_PARAMS + hts::NORM_CHUNK - 1) / hts::NORM_CHUNK);
+static __device__ __align__(256) float scratch[STATIC_PARTS];       // 8 KiB per GPU, held until the process ends
+
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[STATIC_MAX_DEVICES] = {};                      // device address of `scratch`, per device
+
+// Device address of the scratch array on the current device (looked up on first use, under a lock).
+hipError_t scratch_on_current_device(float **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+extern "C" int32_t hts_adam_apply_static(float *params, const float *grads, hts_opt_state *opt, const hts_hparams *hp,
+                                         int64_t P, void *hip_stream)
+{
+    using namespace hts;
+    if (!params || !grads || !opt || !opt->m || !opt->v || !hp) return HTS_EINVAL;
+    if (P <= 0 || opt->step < 0) return HTS_EINVAL;
+    if (P > STATIC_MAX_PARAMS) return HTS_ESHAPE;          // the static array holds one partial sum per 8192 parameters
+    if (hp->optimizer != HTS_OPT_ADAM && hp->optimizer != HTS_OPT_RMSPROP) return HTS_EINVAL;
+    float *part = nullptr;
+    hipError_t e = scratch_on_current_device(&part);
+    if (e != hipSuccess) { note_hip_error(e); return HTS_EHIP; }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t t = opt->step + 1;
+    const bool rms = hp->optimizer == HTS_OPT_RMSPROP;
+    const float b1 = rms ? 0.0f : hp->beta1, b2 = rms ? hp->rms_alpha : hp->beta2;
+    const float bc1 = rms ? 1.0f : (float)(1.0 - pow((double)hp->beta1, (double)t));
+    const float bc2 = rms ? 1.0f : (float)(1.0 - pow((double)hp->beta2, (double)t));
+    const bool clip = hp->max_grad_norm > 0.0f;
+    // every partial sum the optimiser kernel reads is written by the pass before it: nothing has to start at zero
+    if (clip) enqueue_sumsq(stream, grads, P, part);
+    enqueue_adam(stream, params, grads, opt->m, opt->v, P, nullptr, clip ? part : nullptr, hp->max_grad_norm, hp->lr, b1,
+                 b2, hp->adam_eps, bc1, bc2);
+    e = hipGetLastError();
+    if (e != hipSuccess) { note_hip_error(e); return HTS_EHIP; }
+    opt->step = t;
+    return HTS_OK;
+}
