@@ -56,10 +56,12 @@ typedef struct {
                                      input-gradient products, bias gradients included).  Sums, biases, the FC output,
                                      heads, loss and optimiser stay exact.  Derivatives treat a rounding as the
                                      identity.                                                                        */
-    int32_t gates_exact;          /* diagnostic, with operand_bf16 = 1 only: the ReLU gates of the backward pass are
-                                     those of an unrounded forward pass of the same sample, so that the difference to
-                                     the unrounded gradient is the accumulated operand rounding alone and the
-                                     difference to the operand_bf16 = 1 gradient is the effect of flipped gates.      */
+    int32_t gates_exact;          /* diagnostic, with operand_bf16 = 1 only: every discontinuous decision of the
+                                     derivative -- the ReLU gates, the clipped surrogate's "ratio outside the band"
+                                     decision, the branch of the clipped value loss -- is taken from an unrounded
+                                     forward pass of the same sample, so that the difference to the unrounded gradient
+                                     is the accumulated operand rounding alone and the difference to the
+                                     operand_bf16 = 1 gradient is the effect of flipped decisions.                    */
 } orc_net;
 
 typedef struct {
@@ -392,7 +394,15 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
     for (int b = 0; b < B; ++b) {
         const int64_t row = index ? index[b] : b;
         double v;
-        if (exact_gates) { double v_g; forward_one(&plain, &s, params_in, obs + row * in_sz, x, act_g, h_g, logits_g, &v_g); }
+        double v_g = 0.0, logp_g = 0.0;       /* gates_exact: value and log-probability of the unrounded pass */
+        if (exact_gates) {
+            forward_one(&plain, &s, params_in, obs + row * in_sz, x, act_g, h_g, logits_g, &v_g);
+            double mg = logits_g[0];
+            for (int j = 1; j < A; ++j) if (logits_g[j] > mg) mg = logits_g[j];
+            double zg = 0.0;
+            for (int j = 0; j < A; ++j) zg += exp(logits_g[j] - mg);
+            logp_g = logits_g[actions[row]] - mg - log(zg);
+        }
         forward_one(n, &s, params, obs + row * in_sz, x, act, h, logits, &v);
 
         /* log-softmax, entropy */
@@ -423,7 +433,9 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
             const double rc = rho < lo ? lo : (rho > hi ? hi : rho);
             const double s1 = rho * ad, s2 = rc * ad;
             sum_pi += -(s1 < s2 ? s1 : s2);
-            const int clipped = (ad > 0.0 && rho > hi) || (ad < 0.0 && rho < lo);
+            /* the surrogate's own gate: with gates_exact it is decided by the unrounded pass's ratio */
+            const double rho_d = exact_gates ? exp(logp_g - old_logp[row]) : rho;
+            const int clipped = (ad > 0.0 && rho_d > hi) || (ad < 0.0 && rho_d < lo);
             dlogp = clipped ? 0.0 : -ad * rho * invB;
             sum_clip += (rho > hi || rho < lo) ? 1.0 : 0.0;
             sum_kl += old_logp[row] - logp;
@@ -435,9 +447,17 @@ int32_t orc_loss_grads(const orc_net *n, const double *params_in, const uint8_t 
             const double dc = d < -hp->value_clip ? -hp->value_clip : (d > hp->value_clip ? hp->value_clip : d);
             const double vc = old_values[row] + dc;
             const double c_term = (vc - R) * (vc - R);
-            if (c_term > v_term) {
+            int take_clipped = c_term > v_term, inside = dc == d;
+            if (exact_gates) {                     /* both decisions from the unrounded pass's value */
+                const double dg = v_g - old_values[row];
+                const double dcg = dg < -hp->value_clip ? -hp->value_clip : (dg > hp->value_clip ? hp->value_clip : dg);
+                const double vcg = old_values[row] + dcg;
+                take_clipped = (vcg - R) * (vcg - R) > (R - v_g) * (R - v_g);
+                inside = dcg == dg;
+            }
+            if (take_clipped) {
                 v_term = c_term;
-                dv_row = (dc == d) ? 2.0 * (vc - R) : 0.0;   /* the clipped value does not move with v */
+                dv_row = inside ? 2.0 * (vc - R) : 0.0;      /* the clipped value does not move with v */
             }
         }
         sum_v += v_term;

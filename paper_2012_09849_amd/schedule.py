@@ -141,12 +141,10 @@ class OverlapLoop:
         T, N = cfg["T"], cfg["N"]
         prev, cur, nxt = self.theta
         st = self.store[self.j % 2]
-        self.ctx_act.hts_act_rows(self.rows[self.j % 2], cur, ACT_SEED, self.j * (T + 1), 0)
-        self.ctx_act.hts_returns_gae(b.rew, st["values"], b.dones, cfg["gamma"], cfg["lam"], st["adv"], st["ret"])
-        if cfg["algo"] == 1:
-            self.ctx_act.hts_normalize_advantages(st["adv"])
-        self.ev_roll.record(self.s_roll)
         single = cfg["epochs"] * cfg["minibatches"] == 1
+        # The learner's calls are issued first: they are few and long, the rollout is hundreds of short calls whose
+        # issue alone takes the host milliseconds -- issued after the rollout, the learner would start when the actors
+        # are nearly done.  The order of issue changes nothing in what either stream computes.
         with torch.cuda.stream(self.s_learn):
             nxt.copy_(cur)
             if self.j > 0:
@@ -161,6 +159,11 @@ class OverlapLoop:
                         for k in range(cfg["minibatches"]):
                             self.ctx_learn.hts_learner_step(*data, nxt, self.opt, b.hp,
                                                             index=b.perms[e][k * b.B:(k + 1) * b.B], B=b.B)
+        self.ctx_act.hts_act_rows(self.rows[self.j % 2], cur, ACT_SEED, self.j * (T + 1), 0)
+        self.ctx_act.hts_returns_gae(b.rew, st["values"], b.dones, cfg["gamma"], cfg["lam"], st["adv"], st["ret"])
+        if cfg["algo"] == 1:
+            self.ctx_act.hts_normalize_advantages(st["adv"])
+        self.ev_roll.record(self.s_roll)
         self.ev_learn.record(self.s_learn)
         self.s_roll.wait_event(self.ev_learn)
         self.s_learn.wait_event(self.ev_roll)

@@ -143,7 +143,13 @@ def _act(ctx, obs, params, seed, step, env_offset, A):
 @pytest.mark.parametrize("shape,A,N,prec,tol", [
     (ATARI, 6, 4, 0, 1e-4), (ATARI, 18, 16, 0, 1e-4), (ATARI, 18, 37, 0, 1e-4), (FOOT, 19, 16, 0, 1e-4),
     ((2, 36, 36), 5, 9, 0, 1e-4), ((3, 44, 52), 7, 130, 0, 1e-4),
-    (ATARI, 18, 32, 1, 2e-2), (FOOT, 19, 16, 1, 2e-2), ((3, 44, 52), 7, 130, 1, 2e-2)])
+    (ATARI, 18, 32, 1, 2e-2), (FOOT, 19, 16, 1, 2e-2), ((3, 44, 52), 7, 130, 1, 2e-2),
+    # the multi-agent football workload: 16 environments x 3 controlled players = 48 rows per call
+    (FOOT, 19, 48, 1, 2e-2), (FOOT, 19, 48, 0, 1e-4),
+    # many actions: a second round of policy-head rows (A > 20), one lane per row sum (A > 32), the largest head, and
+    # more than 512 rows (four wavefronts per workgroup, more than 64 KiB of LDS with 64 actions)
+    ((2, 36, 36), 21, 9, 0, 1e-4), ((2, 36, 36), 33, 40, 0, 1e-4), ((2, 36, 36), 64, 17, 0, 1e-4),
+    ((2, 36, 36), 64, 530, 0, 1e-4), ((2, 36, 36), 33, 530, 1, 2e-2)])
 def test_act_parity(hts, oracle, shape, A, N, prec, tol):
     Cc, H, W = shape
     ctx = hts.Context(Cc, H, W, A, precision=prec, max_act_batch=N)
@@ -282,6 +288,12 @@ LEARN_CASES = [
     (FOOT, 19, 6, 5, 1, 0.08, 0.0, 0),
     ((3, 44, 52), 7, 70, 67, 1, 0.1, 0.5, 0),       # several tiles and ragged tails in every contraction
     ((2, 36, 36), 5, 3, None, 0, 0.1, 0.0, 0),
+    # many actions: policy-head weight gradient with more than 32 rows, second round of head rows in the heads kernel
+    ((2, 36, 36), 21, 30, 23, 1, 0.1, 0.0, 0),
+    ((2, 36, 36), 33, 30, None, 0, 0.1, 0.5, 0),
+    ((2, 36, 36), 64, 140, 131, 1, 0.1, 0.0, 0),
+    ((2, 36, 36), 64, 560, 530, 1, 0.1, 0.0, 0),   # more than 512 rows: four wavefronts per heads workgroup
+    (FOOT, 19, 50, 48, 1, 0.08, 0.0, 0),           # the multi-agent workload's rows per call as a minibatch
 ]
 
 
@@ -572,6 +584,32 @@ def test_learner_errors_launch_nothing(hts):
     with pytest.raises(hts.HtsError):
         ctx.hts_loss_and_grads(obs, a, lp, lp, v, p, hts.HParams(algo=0), torch.zeros(ctx.P, device="cuda"))    # B = 8 > max
     torch.cuda.synchronize()
+    ctx.close()
+
+
+def test_nonfinite_flag_on_injected_infinity(hts, oracle):
+    """hts_stats.nonfinite is 0 on a healthy minibatch and 1 when a loss term is not finite (an infinite advantage)."""
+    shape, A, count = (2, 36, 36), 5, 12
+    Cc, H, W = shape
+    net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 77, True)
+    ctx = hts.Context(Cc, H, W, A, max_learn_batch=count)
+    hp = hts.HParams(algo=1, clip_eps=0.1)
+    grads, stats = torch.zeros(ctx.P, device="cuda"), ctx.new_stats()
+    for bad in (False, True):
+        a = adv.copy()
+        if bad:
+            a[5] = np.inf
+        ctx.hts_loss_and_grads(dev(obs), dev(actions), dev(old_logp), dev(a), dev(ret), dev(params), hp, grads, stats=stats)
+        torch.cuda.synchronize()
+        st = ctx.read_stats(stats)
+        assert st["nonfinite"] == (1 if bad else 0), st
+    # the same through hts_learner_step (the flag is raised; what the caller does with the update is its business)
+    P = ctx.P
+    opt = hts.OptState(torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda"), 0)
+    r = ret.copy(); r[3] = np.nan
+    ctx.hts_learner_step(dev(obs), dev(actions), dev(old_logp), dev(adv), dev(r), dev(params), opt, hp, stats=stats)
+    torch.cuda.synchronize()
+    assert ctx.read_stats(stats)["nonfinite"] == 1
     ctx.close()
 
 

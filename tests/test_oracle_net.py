@@ -387,9 +387,10 @@ def test_operand_model_matches_torch_with_rounded_operands(oracle):
 
 
 def test_exact_gate_diagnostic_matches_torch(oracle):
-    """gates_exact: rounded operands, but the derivative's ReLU gates come from the unrounded forward pass."""
+    """gates_exact: rounded operands, but every discontinuous decision of the derivative (ReLU gates, the clipped
+    surrogate's band decision) comes from the unrounded forward pass."""
     kw = _QKW
-    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 62, 6, 1, kw)
+    net, flat, obs, actions, old_logp, adv, ret = _problem(oracle, 62, 8, 1, kw)
     flat = flat.astype(np.float32).astype(np.float64)
     pe = _torch_params(flat, kw, 5)                                   # unrounded forward pass: its gates
     x = torch.from_numpy(obs.astype(np.float64)) / 255.0
@@ -399,21 +400,43 @@ def test_exact_gate_diagnostic_matches_torch(oracle):
             pre = F.conv2d(x, pe[f"conv{i + 1}.w"], pe[f"conv{i + 1}.b"], stride=s)
             masks.append((pre > 0).to(torch.float64))
             x = F.relu(pre)
-        masks.append((F.linear(x.flatten(1), pe["fc.w"], pe["fc.b"]) > 0).to(torch.float64))
+        pre = F.linear(x.flatten(1), pe["fc.w"], pe["fc.b"])
+        masks.append((pre > 0).to(torch.float64))
+        h = F.relu(pre)
+        lsm_e = F.log_softmax(F.linear(h, pe["pi.w"], pe["pi.b"]), dim=1)
+        logp_e = lsm_e.gather(1, torch.from_numpy(actions.astype(np.int64))[:, None])[:, 0].numpy()
+    # put the unrounded ratio of every row a hair inside or outside the band's edge that its advantage makes active, so
+    # that the rounded pass lands on the other side for some of them
+    eps = 0.1
+    edge = np.where(adv > 0, 1.0 + eps, 1.0 - eps)
+    old_logp = logp_e - np.log(edge * (1.0 + 1e-6 * np.where(np.arange(8) % 2 == 0, 1.0, -1.0)))
+    rho_e = np.exp(logp_e - old_logp)
+    cut_e = ((adv > 0) & (rho_e > 1 + eps)) | ((adv < 0) & (rho_e < 1 - eps))
+    assert cut_e.any() and not cut_e.all()
     p = _torch_params(flat, kw, 5)
     logits, v, pres = _rounded_model_torch(kw, p, obs, gate_masks=masks)
     flips = sum(int(((pr.detach() > 0).to(torch.float64) != mk).sum()) for pr, mk in zip(pres, masks))
     assert flips > 0                                                   # otherwise the case tests nothing
-    _ppo_loss_torch(logits, v, actions, old_logp, adv, ret).backward()
+    lsm = F.log_softmax(logits, dim=1)
+    logp = lsm.gather(1, torch.from_numpy(actions.astype(np.int64))[:, None])[:, 0]
+    rho = (logp - torch.from_numpy(old_logp)).exp()
+    rho_q = rho.detach().numpy()
+    cut_q = ((adv > 0) & (rho_q > 1 + eps)) | ((adv < 0) & (rho_q < 1 - eps))
+    assert (cut_q != cut_e).any()                                      # the rounded pass decides differently somewhere
+    ad = torch.from_numpy(adv)
+    keep = torch.from_numpy((~cut_e).astype(np.float64))
+    surrogate = -(rho * ad * keep).mean()                              # derivative: -adv rho / B where not cut (unrounded decision)
+    loss = surrogate + 0.5 * ((torch.from_numpy(ret) - v) ** 2).mean() - 0.01 * (-(lsm.exp() * lsm).sum(1)).mean()
+    loss.backward()
     tg = _qflat_grad(p)
-    hp = oracle.make_hparams(algo=1, clip_eps=0.1)
+    hp = oracle.make_hparams(algo=1, clip_eps=eps)
     gnet = oracle.make_net(3, 44, 52, 5, operand_bf16=True, gates_exact=True)
     g, st = oracle.loss_grads(gnet, flat, obs, actions, old_logp, adv, ret, hp)
     np.testing.assert_allclose(g, tg, rtol=1e-8, atol=1e-13)
     gq, stq = oracle.loss_grads(oracle.make_net(3, 44, 52, 5, operand_bf16=True), flat, obs, actions, old_logp, adv,
                                 ret, hp)
     assert st["total_loss"] == stq["total_loss"]                       # the losses are those of the rounded pass
-    assert np.abs(g - gq).max() > 0                                    # and the flipped gates do change the gradient
+    assert np.abs(g - gq).max() > 0                                    # and the flipped decisions do change the gradient
 
 
 def test_threaded_variants_equal_the_plain_calls(oracle):
