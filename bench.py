@@ -76,9 +76,32 @@ def time_sites(loop, steps=2):
     return per_step
 
 
+ACT_SITES = ("prep", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc_fwd", "heads_act")
+
+
+def bracket_overhead(loop, torch, per_step):
+    """What an event bracket adds to a kernel's time IN SITU, from this workload's own rollout: the actor calls' launches
+    run back to back on one stream, so the rollout's wall time is the sum of its kernels' times, and the sum of the raw
+    brackets of the same launches exceeds it by (launches x overhead).  (An empty bracket -- two events with nothing
+    between them -- reads about 4.5 us on this machine, but a bracket around a kernel costs less than that: the
+    kernel's own completion covers part of it.)  -> (overhead ms, rollout ms per step)."""
+    for _ in range(2):
+        loop.rollout()
+    torch.cuda.synchronize()
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        loop.rollout()
+    torch.cuda.synchronize()
+    roll_ms = (time.perf_counter() - t0) / reps * 1e3
+    raw = sum(per_step[k][0] for k in ACT_SITES if k in per_step)
+    n = sum(per_step[k][1] for k in ACT_SITES if k in per_step)
+    return max((raw - roll_ms) / max(n, 1), 0.0), roll_ms
+
+
 def roofline_entry(cfg, name, kind, per_launch, rows, avg_bracket_s, overhead_s, n_timed, launches_per_step, traffic):
-    """The dominant kernel against its roofline.  `achieved` uses the event bracket less what an empty bracket reads;
-    both raw figures are printed beside it."""
+    """The dominant kernel against its roofline.  `achieved` uses the event bracket less the bracket's own in-situ cost
+    (see bracket_overhead); the raw bracket and that cost are printed beside it."""
     net_s = max(avg_bracket_s - overhead_s, 1e-9)
     if kind == "flop":
         peak = PEAK["mfma_f32"] if cfg["precision"] == 0 else PEAK["mfma_bf16"]
@@ -291,15 +314,12 @@ def main():
     torch.cuda.synchronize()
     work = site_work(cfg, loop.ctx.P)
     names = loop.ctx.profile_sites()
-    overhead_ms = loop.ctx.hts_profile_overhead(256)     # what an empty event bracket reads
+    empty_bracket_ms = loop.ctx.hts_profile_overhead(256)     # what two events with nothing between them read
+    per_step = time_sites(loop)
+    overhead_ms, rollout_ms = bracket_overhead(loop, torch, per_step)
     if args.site:
-        dominant, per_step = args.site, {}
-        loop.ctx.hts_profile_begin(names.index(dominant))
-        loop.step()
-        n1, ms1 = loop.ctx.hts_profile_end()
-        per_step[dominant] = (ms1, n1)
+        dominant = args.site
     else:
-        per_step = time_sites(loop)
         ranked = sorted(((v[0] - v[1] * overhead_ms, k) for k, v in per_step.items() if k in work), reverse=True)
         dominant = ranked[0][1]
     launches_per_step = per_step[dominant][1]
@@ -334,6 +354,8 @@ def main():
         traffic = TRAFFIC[args.workload][0][dominant]
     out["roofline"] = roofline_entry(cfg, dominant, kind, per_launch, rows, ms_timed / max(n_timed, 1) * 1e-3,
                                      overhead_ms * 1e-3, n_timed, launches_per_step, traffic)
+    out["roofline"]["empty_bracket_us"] = empty_bracket_ms * 1e3
+    out["rollout_ms_per_step"] = rollout_ms
     # every launch site of this workload: event-bracket time per launch (raw, and less the empty bracket) and its share
     kernels = {}
     for k, (ms, n) in sorted(per_step.items(), key=lambda kv: -(kv[1][0] - kv[1][1] * overhead_ms)):

@@ -230,6 +230,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     // Small minibatches take the wave-per-segment kernels: many more, much shorter dependency chains.
     const bool small = B <= c.small_b;
     const bool atari_grid = g.H1 == 20 && g.W1 == 20;      // 84x84 frames: conv2 sees 20x20, conv3 9x9
+    const bool foot_grid = g.H1 == 17 && g.W1 == 23;       // 72x96 frames: conv2 sees 17x23, conv3 7x10
     // groups of 64-row segments for the split weight gradients on that path: at most max_groups partial buffers per
     // layer, at least min_segs segments per group (never more groups than the tile path's split_for allows for the
     // same reduction length, which is what the partial buffers are sized for)
@@ -314,6 +315,11 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
                 a.in = (const bf16_t *)c.ws.dy3; a.w = (const bf16_t *)c.ws.wd3; a.mask = (const bf16_t *)c.ws.act2;
                 a.out = (bf16_t *)c.ws.dy2; a.B = B;
                 e = launch_imgconv<ImgDgrad<64, 3, 1, 9, 9, 6>>(a, c.stream);
+            } else if (!small && sizeof(T) == 2 && foot_grid) {
+                ImgConvArgs a = {};
+                a.in = (const bf16_t *)c.ws.dy3; a.w = (const bf16_t *)c.ws.wd3; a.mask = (const bf16_t *)c.ws.act2;
+                a.out = (bf16_t *)c.ws.dy2; a.B = B;
+                e = launch_imgconv<ImgDgrad<64, 3, 1, 7, 10, 7>>(a, c.stream);
             } else
             // binary32: eight segments of 72 for eight wavefronts, both operands through LDS: a lane that fetches its own
             // weight column touches 32 cache lines per load instruction, and with sixteen wavefronts on a compute unit
@@ -348,6 +354,11 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
                 a.in = (const bf16_t *)c.ws.dy2; a.w = (const bf16_t *)c.ws.wd2; a.mask = (const bf16_t *)c.ws.act1;
                 a.out = (bf16_t *)c.ws.dy1; a.B = B;
                 e = launch_imgconv<ImgDgrad<32, 4, 2, 20, 20, 4>>(a, c.stream);
+            } else if (!small && sizeof(T) == 2 && foot_grid) {
+                ImgConvArgs a = {};
+                a.in = (const bf16_t *)c.ws.dy2; a.w = (const bf16_t *)c.ws.wd2; a.mask = (const bf16_t *)c.ws.act1;
+                a.out = (bf16_t *)c.ws.dy1; a.B = B;
+                e = launch_imgconv<ImgDgrad<32, 4, 2, 17, 23, 4>>(a, c.stream);
             } else
             e = small ? launch_wsgemm<ConvDgrad<T, Layer2>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);
         }
