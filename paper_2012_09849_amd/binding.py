@@ -189,13 +189,15 @@ class Context:
                 for s in range(S)]
         return (N, rows, (obs, actions, logp, values, logits))
 
-    def hts_act_rows(self, act_rows, params, seed, step0, env_offset):
-        """One hts_act call per entry of act_rows (see act_rows), steps step0, step0+1, ...; the parameters are passed
-        to the first call only (the actors keep one parameter version for a whole storage)."""
+    def hts_act_rows(self, act_rows, params, seed, step0, env_offset, first=0, last=None):
+        """One hts_act call per entry [first, last) of act_rows (see act_rows); entry s is step step0 + s.  The
+        parameters are passed to entry 0 only (the actors keep one parameter version for a whole storage)."""
         N, rows, _keep = act_rows
         fn, h = self.lib.hts_act, self._h
         pp = _ptr(params, torch.float32, "params")
-        for s, (o, a, l, v, g) in enumerate(rows):
+        last = len(rows) if last is None else last
+        for s in range(first, last):
+            o, a, l, v, g = rows[s]
             rc = fn(h, o, pp if s == 0 else None, seed, step0 + s, N, env_offset, a, l, v, g)
             if rc != 0:
                 _check(rc, "hts_act")

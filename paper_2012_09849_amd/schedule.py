@@ -117,9 +117,10 @@ class OverlapLoop:
     single gradient step only; here the learner runs its ordinary epochs on storage j-1 starting from theta_j, the
     stored behaviour log-probabilities (of theta_{j-1}) entering through PPO's own probability ratio."""
 
-    def __init__(self, base):
+    def __init__(self, base, learner_after=8):
         torch, hts, cfg = base.torch, base.hts, base.cfg
         self.base, self.cfg, self.torch = base, cfg, torch
+        self.learner_after = learner_after          # actor calls issued before the learner's calls (see step)
         N, T = cfg["N"], cfg["T"]
         self.s_roll, self.s_learn = torch.cuda.Stream(), torch.cuda.Stream()
         mk = lambda **kw: hts.Context(cfg["C"], cfg["H"], cfg["W"], cfg["A"], precision=cfg["precision"], **kw)
@@ -142,9 +143,13 @@ class OverlapLoop:
         prev, cur, nxt = self.theta
         st = self.store[self.j % 2]
         single = cfg["epochs"] * cfg["minibatches"] == 1
-        # The learner's calls are issued first: they are few and long, the rollout is hundreds of short calls whose
-        # issue alone takes the host milliseconds -- issued after the rollout, the learner would start when the actors
-        # are nearly done.  The order of issue changes nothing in what either stream computes.
+        # When the learner's calls are issued matters on this hardware (it changes nothing in what either stream
+        # computes): the rollout is hundreds of short calls whose issue alone takes the host milliseconds, so a learner
+        # issued after it starts when the actors are nearly done; a learner issued before it fills the machine with
+        # large kernels first, and the actors' short dependent kernels then wait behind them.  So the first
+        # `learner_after` actor calls go out first, then the learner's calls, then the rest of the rollout.
+        k = min(self.learner_after, T + 1)
+        self.ctx_act.hts_act_rows(self.rows[self.j % 2], cur, ACT_SEED, self.j * (T + 1), 0, 0, k)
         with torch.cuda.stream(self.s_learn):
             nxt.copy_(cur)
             if self.j > 0:
@@ -156,10 +161,10 @@ class OverlapLoop:
                     self.ctx_learn.hts_learner_step_delayed(*data, prev, nxt, self.opt, b.hp)
                 else:
                     for e in range(cfg["epochs"]):
-                        for k in range(cfg["minibatches"]):
+                        for m in range(cfg["minibatches"]):
                             self.ctx_learn.hts_learner_step(*data, nxt, self.opt, b.hp,
-                                                            index=b.perms[e][k * b.B:(k + 1) * b.B], B=b.B)
-        self.ctx_act.hts_act_rows(self.rows[self.j % 2], cur, ACT_SEED, self.j * (T + 1), 0)
+                                                            index=b.perms[e][m * b.B:(m + 1) * b.B], B=b.B)
+        self.ctx_act.hts_act_rows(self.rows[self.j % 2], cur, ACT_SEED, self.j * (T + 1), 0, k, T + 1)
         self.ctx_act.hts_returns_gae(b.rew, st["values"], b.dones, cfg["gamma"], cfg["lam"], st["adv"], st["ret"])
         if cfg["algo"] == 1:
             self.ctx_act.hts_normalize_advantages(st["adv"])
