@@ -75,7 +75,9 @@ int32_t hts_destroy(hts_ctx *ctx);
  *                            hts_loss_and_grads on this context are used again -- the paper's actors keep one
  *                            parameter version for a whole storage (Sec. 4.1 "Concurrent rollout and learning"), so
  *                            only the first step of a rollout needs to pass them.  HTS_EINVAL if nothing is loaded,
- *                            or if hts_learner_step / hts_adam_apply ran on this context since the last load.
+ *                            or if hts_learner_step / hts_adam_apply ran on this context since the last load (with
+ *                            hts_track_params on, an update keeps the loaded copy in step instead, and the call uses
+ *                            the updated parameters).
  *   seed, step, env_offset   observation i belongs to environment env_offset+i; its action is drawn with the
  *                            uniform u = top 24 bits of word 0 of Philox4x32-10(key = seed lo/hi,
  *                            counter = (env, step, 0, 0)) * 2^-24, so the action does not depend on which call
@@ -90,6 +92,15 @@ int32_t hts_act(hts_ctx *ctx, const uint8_t *obs, const float *params, uint64_t 
  * (matrix operands converted to the context's precision and re-ordered for their gathers), refreshed by this call.
  * The copy is what hts_act(params = NULL) uses.  The learner calls always load the vector they are given. */
 int32_t hts_sync_params(hts_ctx *ctx, const float *params);
+
+/* on = 1: the caller promises that every parameter vector it hands to this context is modified only by this context's
+ * learner calls (hts_learner_step, hts_learner_step_delayed, hts_adam_apply on the whole vector) -- or that it calls
+ * hts_sync_params after writing the vector itself.  The optimiser kernel then rewrites the context's copy of the network
+ * (see hts_sync_params) from the values it has just computed, and a following hts_act / learner call that is handed the
+ * same vector skips the load: one pass over all parameters less per update and per rollout.  Results are bit-identical
+ * with and without.  on = 0 (the default): every call that is handed a vector loads it.  Either way the call forgets
+ * what is loaded.  In the paper's terms: the learner owns the parameters, the actors only read them (Sec. 4.1). */
+int32_t hts_track_params(hts_ctx *ctx, int32_t on);
 
 /* The sampling stage of hts_act alone, on caller-supplied logits f32 [N,A] (test hook for bit-exact parity). */
 int32_t hts_sample_from_logits(hts_ctx *ctx, const float *logits, uint64_t seed, uint32_t step, int32_t N,

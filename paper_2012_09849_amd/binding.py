@@ -16,7 +16,7 @@ OPT_ADAM, OPT_RMSPROP = 0, 1
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_learner_step_delayed", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
            "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
-           "hts_profile_end", "hts_profile_overhead", "hts_profile_begin_sampled", "hts_adam_apply_static"]
+           "hts_profile_end", "hts_profile_overhead", "hts_profile_begin_sampled", "hts_adam_apply_static", "hts_track_params"]
 
 
 class HtsError(RuntimeError):
@@ -78,6 +78,7 @@ def load_library():
         lib.hts_act.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.hts_sync_params.argtypes = [C.c_void_p, C.c_void_p]
+        lib.hts_track_params.argtypes = [C.c_void_p, C.c_int32]
         lib.hts_sample_from_logits.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
                                                C.c_void_p, C.c_void_p]
         lib.hts_returns_gae.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
@@ -201,6 +202,9 @@ class Context:
             rc = fn(h, o, pp if s == 0 else None, seed, step0 + s, N, env_offset, a, l, v, g)
             if rc != 0:
                 _check(rc, "hts_act")
+
+    def hts_track_params(self, on: bool):
+        _check(self.lib.hts_track_params(self._h, 1 if on else 0), "hts_track_params")
 
     def hts_sync_params(self, params):
         _check(self.lib.hts_sync_params(self._h, _ptr(params, torch.float32, "params")), "hts_sync_params")

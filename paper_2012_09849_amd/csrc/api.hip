@@ -123,7 +123,7 @@ extern "C" int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, i
     c.max_b = max_act_batch > max_learn_batch ? max_act_batch : max_learn_batch;
     c.small_b = 128;
     c.fc_groups = (g.F + FC_GROUP_K - 1) / FC_GROUP_K;
-    c.synced = false; c.synced_learn = false;
+    c.synced = false; c.synced_learn = false; c.track_params = false; c.shadow_of = nullptr;
     {
         auto pad4 = [](long long x) { return (x + 3) & ~3ll; };
         ShadowOffsets &s = c.sh;
@@ -171,8 +171,10 @@ extern "C" int32_t hts_act(hts_ctx *ctx, const uint8_t *obs, const float *params
     if (N > ctx->c.max_act) return HTS_ESHAPE;
     if (((uintptr_t)obs & 3u) || ((uintptr_t)params & 15u)) return HTS_EINVAL;
     Ctx &c = ctx->c;
-    if (params) HIP_TRY(launch_prep(c, params, false));
-    else if (!c.synced) return HTS_EINVAL;        // no parameters given and none loaded
+    if (params) {
+        // a vector this context updated itself (and that the caller promised not to touch otherwise) is already loaded
+        if (!(c.track_params && c.synced && c.shadow_of == params)) HIP_TRY(launch_prep(c, params, c.track_params && c.max_learn > 0));
+    } else if (!c.synced) return HTS_EINVAL;      // no parameters given and none loaded
     HIP_TRY(run_forward(c, obs, nullptr, N, false));
     HIP_TRY(launch_heads_act(c, nullptr, seed, step, N, env_offset, actions, logp, values, logits_or_null));
     return HTS_OK;
@@ -183,6 +185,14 @@ extern "C" int32_t hts_sync_params(hts_ctx *ctx, const float *params)
     if (!ctx || !params) return HTS_EINVAL;
     if ((uintptr_t)params & 15u) return HTS_EINVAL;
     HIP_TRY(launch_prep(ctx->c, params, ctx->c.max_learn > 0));
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_track_params(hts_ctx *ctx, int32_t on)
+{
+    if (!ctx || (on != 0 && on != 1)) return HTS_EINVAL;
+    ctx->c.track_params = on == 1;
+    ctx->c.synced = false; ctx->c.synced_learn = false; ctx->c.shadow_of = nullptr;     // start from a fresh load either way
     return HTS_OK;
 }
 
@@ -236,7 +246,7 @@ static int32_t loss_and_grads(Ctx &c, const hts_buffer *buf, const float *params
     la.old_values = buf->old_values; la.adv = buf->advantages; la.ret = buf->returns;
     la.algo = hp->algo; la.clip_eps = hp->clip_eps; la.vf_coef = hp->vf_coef; la.ent_coef = hp->ent_coef;
     la.rho_bar = hp->rho_bar; la.value_clip = hp->value_clip;
-    HIP_TRY(launch_prep(c, params, true));
+    if (!(c.track_params && c.synced_learn && c.shadow_of == params)) HIP_TRY(launch_prep(c, params, true));
     HIP_TRY(run_forward(c, buf->obs, buf->index, buf->B, true));
     HIP_TRY(launch_heads_learn(c, la, buf->B));
     HIP_TRY(run_backward(c, buf->obs, buf->index, buf->B, grads));
@@ -273,11 +283,17 @@ static int32_t adam_apply(Ctx &c, float *params, const float *grads, hts_opt_sta
     const bool clip = hp->max_grad_norm > 0.0f;
     // the optimiser kernel forms the clip factor from the per-chunk sums itself unless it already exists
     if (clip && have_norm == 0) { HIP_TRY(launch_grad_norm(c, grads, P, hp->max_grad_norm, false)); have_norm = 1; }
-    HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, clip && have_norm == 2 ? c.ws.clip : nullptr,
-                        clip && have_norm == 1 ? c.ws.norm_part : nullptr, hp->max_grad_norm, hp->lr, b1, b2,
-                        hp->adam_eps, bc1, bc2));
+    const float *scale = clip && have_norm == 2 ? c.ws.clip : nullptr, *parts = clip && have_norm == 1 ? c.ws.norm_part : nullptr;
+    if (c.track_params && P == c.g.P) {
+        // the optimiser kernel rewrites the workspace copy from the new values: it stays in step with the caller's vector
+        HIP_TRY(launch_adam_shadow(c, params, grads, opt->m, opt->v, scale, parts, hp->max_grad_norm, hp->lr, b1, b2,
+                                   hp->adam_eps, bc1, bc2, c.max_learn > 0));
+    } else {
+        HIP_TRY(launch_adam(c, params, grads, opt->m, opt->v, P, scale, parts, hp->max_grad_norm, hp->lr, b1, b2,
+                            hp->adam_eps, bc1, bc2));
+        c.synced = false; c.synced_learn = false;     // the caller's vector has moved on; the workspace copy has not
+    }
     opt->step = t;
-    c.synced = false; c.synced_learn = false;     // the caller's vector has moved on; the workspace copy has not
     return HTS_OK;
 }
 

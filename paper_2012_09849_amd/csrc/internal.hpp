@@ -67,6 +67,8 @@ struct Ctx {
     int fc_slices;            // slices of fc_part the last forward pass wrote (fc_groups, or 1)
     bool synced;              // the workspace's copy of the network matches the last parameter vector handed in
     bool synced_learn;        // ... including the learner-only parts
+    bool track_params;        // the caller modifies its parameter vectors only through this context (hts_track_params)
+    const float *shadow_of;   // the caller's vector that the workspace copy mirrors while `synced`
     ShadowOffsets sh;
     Workspace ws;
 };
@@ -144,5 +146,9 @@ hipError_t launch_grad_norm(Ctx &c, const float *g, long long P, float max_norm,
 hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v, long long P, const float *scale_or_null,
                        const float *norm_part_or_null, float max_norm, float lr, float b1, float b2, float eps, float bc1,
                        float bc2);
+// the same update of the whole network's vector, which also rewrites the workspace copy of the network from the new values
+hipError_t launch_adam_shadow(Ctx &c, float *theta, const float *g, float *m, float *v, const float *scale_or_null,
+                              const float *norm_part_or_null, float max_norm, float lr, float b1, float b2, float eps,
+                              float bc1, float bc2, bool learn);
 
 }  // namespace hts

@@ -114,9 +114,8 @@ template <typename T> __global__ __launch_bounds__(256) void prep_kernel(const P
     }
 }
 
-hipError_t launch_prep(Ctx &c, const float *params, bool learn)
+static PrepArgs prep_args(const Ctx &c, const float *params, bool learn)
 {
-    SiteTimer tm(c, SITE_PREP);
     PrepArgs a;
     a.params = params; a.g = c.g; a.sh = c.sh;
     a.w1s = c.ws.w1s; a.wf2 = c.ws.wf2; a.wf3 = c.ws.wf3; a.wfc = c.ws.wfc;
@@ -126,13 +125,20 @@ hipError_t launch_prep(Ctx &c, const float *params, bool learn)
     a.nb_w1 = (32 * c.g.K1 + 255) / 256;
     a.nb_hb = (int)((c.sh.count + 255) / 256);
     a.learn = learn ? 1 : 0;
+    return a;
+}
+
+hipError_t launch_prep(Ctx &c, const float *params, bool learn)
+{
+    SiteTimer tm(c, SITE_PREP);
+    const PrepArgs a = prep_args(c, params, learn);
     const int nb = a.nb_fc + a.nb_conv + a.nb_w1 + a.nb_hb;
     if (c.desc.precision == HTS_PRECISION_BF16)
         hipLaunchKernelGGL(prep_kernel<bf16_t>, dim3(nb), dim3(256), 0, c.stream, a);
     else
         hipLaunchKernelGGL(prep_kernel<float>, dim3(nb), dim3(256), 0, c.stream, a);
     const hipError_t e = hipGetLastError();
-    if (e == hipSuccess) { c.synced = true; c.synced_learn = learn; }
+    if (e == hipSuccess) { c.synced = true; c.synced_learn = learn; c.shadow_of = params; }
     return e;
 }
 
@@ -885,6 +891,149 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ theta, co
     }
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The same update over the whole network's vector, organised like prep_kernel: a workgroup owns a piece of one
+// parameter tensor, updates theta / m / v there (the element-wise arithmetic of adam_kernel, so the same bits) and
+// writes the new values straight into the workspace copy of the network (converted, re-ordered, fc.w also transposed
+// through the LDS tile) -- the separate pass that would otherwise re-read the whole vector before the next forward
+// pass is not needed.  Every parameter belongs to exactly one job: fc.w tiles, conv2.w / conv3.w, conv1.w, and the
+// fp32 block (biases, heads).
+// ------------------------------------------------------------------------------------------------------------
+struct AdamShadowArgs {
+    PrepArgs pa;                  // destinations, geometry and job sizes (pa.params is not used)
+    float *theta;
+    const float *g;
+    float *m, *v;
+    const float *scale, *norm_part;
+    int nparts;
+    float max_norm, lr, b1, b2, eps, ibc1, ibc2;
+};
+
+template <typename T> __global__ __launch_bounds__(256) void adam_shadow_kernel(const AdamShadowArgs a)
+{
+    __shared__ float tile[64][65];
+    __shared__ float red[256];
+    float gs = 1.0f;
+    if (a.norm_part) gs = clip_scale(norm_from_parts(a.norm_part, a.nparts, red), a.max_norm);
+    else if (a.scale) gs = a.scale[0];
+    float *__restrict__ theta = a.theta;
+    const float *__restrict__ g = a.g;
+    float *__restrict__ m = a.m, *__restrict__ v = a.v;
+    auto update = [&](long long idx) -> float {
+        float th = theta[idx], mm = m[idx], vv = v[idx];
+        adam_one(th, g[idx], mm, vv, gs, a.lr, a.b1, a.b2, a.eps, a.ibc1, a.ibc2);
+        theta[idx] = th; m[idx] = mm; v[idx] = vv;
+        return th;
+    };
+    const PrepArgs &p = a.pa;
+    const int t = threadIdx.x;
+    int blk = blockIdx.x;
+    if (blk < p.nb_fc) {
+        const int F = p.g.F, tf = F / 64;
+        const int j0 = (blk / tf) * 64, f0 = (blk % tf) * 64;
+        T *wfc = (T *)p.wfc;
+        const int col = t & 63, r0 = t >> 6;
+        // 16-byte accesses: a thread takes four neighbouring columns of four rows (16 lanes cover a tile row); all its
+        // loads are independent and the update runs on registers.  (fc.w starts on a 16-byte boundary when the tensors
+        // in front of it hold a multiple of four values; otherwise the element-wise form below is taken.)
+        if (((p.g.fcw | (long long)F) & 3) == 0 && ((((uintptr_t)theta | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15u) == 0)) {
+            const int c4 = (t & 15) * 4, rr = t >> 4;
+            f32x4 th[4], gg[4], mm[4], vv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const long long idx = p.g.fcw + (long long)(j0 + rr + 16 * i) * F + f0 + c4;
+                th[i] = *reinterpret_cast<const f32x4 *>(theta + idx); gg[i] = *reinterpret_cast<const f32x4 *>(g + idx);
+                mm[i] = *reinterpret_cast<const f32x4 *>(m + idx); vv[i] = *reinterpret_cast<const f32x4 *>(v + idx);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = rr + 16 * i;
+                const long long o = (long long)(j0 + r) * F + f0 + c4;
+                Vec<T, 4> w4;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float a0 = th[i][k], a1 = mm[i][k], a2 = vv[i][k];
+                    adam_one(a0, gg[i][k], a1, a2, gs, a.lr, a.b1, a.b2, a.eps, a.ibc1, a.ibc2);
+                    th[i][k] = a0; mm[i][k] = a1; vv[i][k] = a2;
+                    w4[k] = from_f32<T>(a0);
+                    tile[r][c4 + k] = a0;
+                }
+                *reinterpret_cast<f32x4 *>(theta + p.g.fcw + o) = th[i];
+                *reinterpret_cast<f32x4 *>(m + p.g.fcw + o) = mm[i];
+                *reinterpret_cast<f32x4 *>(v + p.g.fcw + o) = vv[i];
+                *reinterpret_cast<Vec<T, 4> *>(wfc + o) = w4;
+            }
+        } else {
+            float th[16], gg[16], mm[16], vv[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const long long idx = p.g.fcw + (long long)(j0 + r0 + 4 * i) * F + f0 + col;
+                th[i] = theta[idx]; gg[i] = g[idx]; mm[i] = m[idx]; vv[i] = v[idx];
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = r0 + 4 * i;
+                const long long o = (long long)(j0 + r) * F + f0 + col;
+                adam_one(th[i], gg[i], mm[i], vv[i], gs, a.lr, a.b1, a.b2, a.eps, a.ibc1, a.ibc2);
+                theta[p.g.fcw + o] = th[i]; m[p.g.fcw + o] = mm[i]; v[p.g.fcw + o] = vv[i];
+                wfc[o] = from_f32<T>(th[i]);
+                tile[r][col] = th[i];
+            }
+        }
+        if (!p.learn) return;
+        __syncthreads();
+        T *wfcd = (T *)p.wfcd;
+        const int P3 = p.g.P3;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int fl = r0 + 4 * i, f = f0 + fl;
+            const int c = f / P3, q = f - c * P3;
+            wfcd[(long long)(q * 64 + c) * 512 + j0 + col] = from_f32<T>(tile[col][fl]);
+        }
+        return;
+    }
+    blk -= p.nb_fc;
+    if (blk < p.nb_conv) {
+        const int i = blk * 256 + t;
+        T *wf2 = (T *)p.wf2, *wf3 = (T *)p.wf3, *wd2 = (T *)p.wd2, *wd3 = (T *)p.wd3;
+        if (i < 64 * 32 * 16) {               // conv2.w[n][c][u][v], 64 x 32 x 4 x 4
+            const int n = i / 512, r = i % 512, c = r / 16, tap = r % 16;
+            const T w = from_f32<T>(update(p.g.w2 + i));
+            wf2[n * 512 + tap * 32 + c] = w;
+            if (p.learn) wd2[c * 1024 + tap * 64 + n] = w;
+        }
+        if (i < 64 * 64 * 9) {                // conv3.w[n][c][u][v], 64 x 64 x 3 x 3
+            const int n = i / 576, r = i % 576, c = r / 9, tap = r % 9;
+            const T w = from_f32<T>(update(p.g.w3 + i));
+            wf3[n * 576 + tap * 64 + c] = w;
+            if (p.learn) wd3[c * 576 + tap * 64 + n] = w;
+        }
+        return;
+    }
+    blk -= p.nb_conv;
+    if (blk < p.nb_w1) {
+        const int i = blk * 256 + t;
+        if (i < 32 * p.g.K1) ((T *)p.w1s)[i] = from_f32<T>(update(p.g.w1 + i));
+        return;
+    }
+    blk -= p.nb_w1;
+    {
+        const int i = blk * 256 + t;
+        const int A = p.g.A;
+        long long src = -1;
+        if (i < 32) src = p.g.b1 + i;
+        else if (i >= p.sh.b2 && i < p.sh.b2 + 64) src = p.g.b2 + (i - p.sh.b2);
+        else if (i >= p.sh.b3 && i < p.sh.b3 + 64) src = p.g.b3 + (i - p.sh.b3);
+        else if (i >= p.sh.fcb && i < p.sh.fcb + 512) src = p.g.fcb + (i - p.sh.fcb);
+        else if (i >= p.sh.piw && i < p.sh.piw + 512 * A) src = p.g.piw + (i - p.sh.piw);
+        else if (i >= p.sh.pib && i < p.sh.pib + A) src = p.g.pib + (i - p.sh.pib);
+        else if (i >= p.sh.vw && i < p.sh.vw + 512) src = p.g.vw + (i - p.sh.vw);
+        else if (i == p.sh.vb) src = p.g.vb;
+        if (src < 0) return;
+        p.hb[i] = update(src);
+    }
+}
+
 static void enqueue_adam(hipStream_t stream, float *theta, const float *g, float *m, float *v, long long P,
                          const float *scale, const float *norm_part, float max_norm, float lr, float b1, float b2,
                          float eps, float bc1, float bc2)
@@ -908,6 +1057,26 @@ hipError_t launch_adam(Ctx &c, float *theta, const float *g, float *m, float *v,
     SiteTimer tm(c, SITE_ADAM);
     enqueue_adam(c.stream, theta, g, m, v, P, scale, norm_part, max_norm, lr, b1, b2, eps, bc1, bc2);
     return hipGetLastError();
+}
+
+hipError_t launch_adam_shadow(Ctx &c, float *theta, const float *g, float *m, float *v, const float *scale,
+                              const float *norm_part, float max_norm, float lr, float b1, float b2, float eps, float bc1,
+                              float bc2, bool learn)
+{
+    SiteTimer tm(c, SITE_ADAM);
+    AdamShadowArgs a;
+    a.pa = prep_args(c, nullptr, learn);
+    a.theta = theta; a.g = g; a.m = m; a.v = v; a.scale = scale; a.norm_part = norm_part;
+    a.nparts = (int)((c.g.P + NORM_CHUNK - 1) / NORM_CHUNK);
+    a.max_norm = max_norm; a.lr = lr; a.b1 = b1; a.b2 = b2; a.eps = eps; a.ibc1 = 1.0f / bc1; a.ibc2 = 1.0f / bc2;
+    const int nb = a.pa.nb_fc + a.pa.nb_conv + a.pa.nb_w1 + a.pa.nb_hb;
+    if (c.desc.precision == HTS_PRECISION_BF16)
+        hipLaunchKernelGGL(adam_shadow_kernel<bf16_t>, dim3(nb), dim3(256), 0, c.stream, a);
+    else
+        hipLaunchKernelGGL(adam_shadow_kernel<float>, dim3(nb), dim3(256), 0, c.stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) { c.synced = true; c.synced_learn = learn; c.shadow_of = theta; }
+    return e;
 }
 
 }  // namespace hts

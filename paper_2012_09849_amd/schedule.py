@@ -62,6 +62,9 @@ class Loop:
         self.B = B
         self.ctx = hts.Context(cfg["C"], cfg["H"], cfg["W"], A, precision=cfg["precision"], max_act_batch=N,
                                max_learn_batch=B)
+        # this loop writes self.params through this context's learner calls only, so the context may keep its copy of
+        # the network in step with it instead of re-loading the vector before every update and every rollout
+        self.ctx.hts_track_params(True)
         P = self.ctx.P
         self.opt = hts.OptState(torch.zeros(P, device=dev), torch.zeros(P, device=dev), 0)
         self.actions = torch.zeros(T + 1, N, dtype=torch.int32, device=dev)

@@ -587,6 +587,48 @@ def test_learner_errors_launch_nothing(hts):
     ctx.close()
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+def test_tracked_parameters_give_the_same_bits(hts, oracle, prec):
+    """hts_track_params: the optimiser kernel rewrites the context's copy of the network and later calls skip the load.
+    Rollout, three updates, rollout -- with and without -- must agree bit for bit; a write by the caller is announced
+    with hts_sync_params."""
+    shape, A, count, B = (3, 44, 52), 7, 40, 24
+    Cc, H, W = shape
+    net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 91, True)
+    hp = hts.HParams(algo=1, clip_eps=0.1, max_grad_norm=0.5, lr=1e-3)
+    outs = []
+    for track in (False, True):
+        ctx = hts.Context(Cc, H, W, A, precision=prec, max_act_batch=count, max_learn_batch=B)
+        ctx.hts_track_params(track)
+        p_d = dev(params)
+        P = ctx.P
+        opt = hts.OptState(torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda"), 0)
+        data = (dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret))
+        res = [_act(ctx, data[0], p_d, 5, 1, 0, A)]
+        for k in range(3):
+            ctx.hts_learner_step(*data, p_d, opt, hp, index=dev(syn.permutation(60 + k, count)[:B]))
+        res.append(_act(ctx, data[0], p_d, 5, 2, 0, A))
+        if track:       # the loaded copy followed the updates: params = NULL acts on the updated network
+            z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device="cuda")
+            a2, lp2, v2, lg2 = z(count, dt=torch.int32), z(count), z(count), z(count, A)
+            ctx.hts_act(data[0], None, 5, 2, 0, a2, lp2, v2, lg2)
+            torch.cuda.synchronize()
+            assert np.array_equal(lg2.cpu().numpy(), res[-1][3]) and np.array_equal(a2.cpu().numpy(), res[-1][0])
+        # a write by the caller, announced
+        p_d.mul_(0.5)
+        ctx.hts_sync_params(p_d)
+        ctx.hts_learner_step(*data, p_d, opt, hp, index=dev(syn.permutation(70, count)[:B]))
+        res.append(_act(ctx, data[0], p_d, 5, 3, 0, A))
+        torch.cuda.synchronize()
+        outs.append((res, p_d.cpu().numpy(), opt.m.cpu().numpy(), opt.v.cpu().numpy()))
+        ctx.close()
+    (r0, p0, m0, v0), (r1, p1, m1, v1) = outs
+    assert np.array_equal(p0, p1) and np.array_equal(m0, m1) and np.array_equal(v0, v1)
+    for x, y in zip(r0, r1):
+        assert all(np.array_equal(u, w) for u, w in zip(x, y))
+    assert not np.array_equal(r0[0][3], r0[1][3])            # the updates did change the network
+
+
 def test_nonfinite_flag_on_injected_infinity(hts, oracle):
     """hts_stats.nonfinite is 0 on a healthy minibatch and 1 when a loss term is not finite (an infinite advantage)."""
     shape, A, count = (2, 36, 36), 5, 12
