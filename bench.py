@@ -275,6 +275,11 @@ def act_sweep(hts, torch, syn):
     return out
 
 
+def progress(msg):
+    """A line on stderr at the end of each phase (stdout carries the one JSON line)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -315,11 +320,21 @@ def main():
     work = site_work(cfg, loop.ctx.P)
     names = loop.ctx.profile_sites()
     empty_bracket_ms = loop.ctx.hts_profile_overhead(256)     # what two events with nothing between them read
-    per_step = time_sites(loop)
-    overhead_ms, rollout_ms = bracket_overhead(loop, torch, per_step)
+    progress(f"{args.workload}: warm-up done")
     if args.site:
+        # light form for runs under a profiler's counter collection (every dispatch is slow there): one bracketed
+        # step of the named site, the empty bracket's reading as the bracket cost
         dominant = args.site
+        loop.ctx.hts_profile_begin(names.index(dominant))
+        loop.step()
+        n1, ms1 = loop.ctx.hts_profile_end()
+        per_step = {dominant: (ms1, float(n1))}
+        overhead_ms, rollout_ms = empty_bracket_ms, None
     else:
+        per_step = time_sites(loop)
+        overhead_ms, rollout_ms = bracket_overhead(loop, torch, per_step)
+    progress("launch sites timed")
+    if not args.site:
         ranked = sorted(((v[0] - v[1] * overhead_ms, k) for k, v in per_step.items() if k in work), reverse=True)
         dominant = ranked[0][1]
     launches_per_step = per_step[dominant][1]
@@ -329,6 +344,7 @@ def main():
 
     # timed region: a sample of the dominant kernel's launches is bracketed by HIP events on the library's stream
     wall, (n_timed, ms_timed) = run_iterations(loop, torch, args.steps, 0, names.index(dominant), every)
+    progress(f"{args.steps} timed steps done")
     t_learn = time_learner(loop, torch, max(1, args.steps // 4))
 
     N, T = cfg["N"], cfg["T"]
@@ -391,6 +407,7 @@ def main():
         del ov
     if not args.no_cpu_baseline:
         import oracle
+        progress("timing the CPU oracle")
         out["cpu_baseline"] = cpu_baseline(cfg, loop)
         out["cpu_baseline_all_cores"] = cpu_baseline(cfg, loop, budget_s=8.0, threads=oracle.host_threads())
     loop.ctx.close()
@@ -400,6 +417,7 @@ def main():
         others = {}
         for name, steps, warmup in (("atari_ppo_n32_t128_bf16", 40, 3), ("atari_a2c_n16_t5_fp32", 1000, 50)):
             if name != args.workload:
+                progress(f"other workload {name}")
                 others[name] = workload_summary(name, steps, warmup, hts, torch, syn)
         others["act_sweep_bf16"] = act_sweep(hts, torch, syn)
         out["other_workloads"] = others

@@ -71,7 +71,6 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) void c
     // 4q..4q+3 (of the group's 16 rows / columns) at reduction index j and receives the four reduction indices of
     // entry (lane % 16); groups 0,1 hold entries 0-15 and 16-31 at reduction 0-7 (two reads), groups 2,3 at 8-15.
     const int col0 = 16 * g1 + 4 * q;                             // first of the four columns this lane points at
-    const int lane_img = ((w >> 1) * a.H + 4 * (w & 1) + (col0 >> 3)) * Wp + (col0 & 7);
     const bf16_t *a_lane = dyl + (8 * kg + jj) * 32 + col0;
     typedef i16x4 __attribute__((address_space(3))) *lds_ptr;
     auto tr4 = [](const bf16_t *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p)); };
@@ -90,12 +89,25 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) void c
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) acc[cg][r] = 0.0f;
     }
-    const int step_wrap = 64 + 4 * Wp - 4 * a.W1;                 // image offset from position m to m+16 across a row end
-    // positions m = 16 ks + 8 kg + jj (first read) and m + 4 (second read), walked incrementally (W1 >= 16); the
-    // padding positions of the last step (their gradient rows are zero) read position 0
-    const int ma0 = 8 * kg + jj, mb0 = ma0 + 4;
-    const int oya0 = a.dW1.div(ma0), oxa0 = ma0 - oya0 * a.W1, oyb0 = a.dW1.div(mb0), oxb0 = mb0 - oyb0 * a.W1;
-    const int offa0 = lane_img + 4 * oya0 * Wp + 4 * oxa0, offb0 = lane_img + 4 * oyb0 * Wp + 4 * oxb0;
+    // Positions m = 16 ks + 8 kg + jj (first read) and m + 4 (second read) of step ks: where a lane's two image reads of a
+    // step start is the same for every sample and channel group, so it is tabulated once (LDS addresses, wave-independent
+    // part; one 8-byte entry per step and lane, one row more than there are steps so that the read-ahead needs no check).
+    // Walking the positions in registers cost about twenty vector instructions per matrix instruction, and these kernels
+    // are bound by exactly that.  The padding positions of the last step (their gradient rows are zero) read position 0.
+    typedef __attribute__((address_space(3))) unsigned char *lds_bytes;
+    uint2 *tab = reinterpret_cast<uint2 *>(dyl + nks * 16 * 32);
+    for (int e = tid; e < (nks + 1) * 64; e += C1WG_THREADS) {
+        const int ks = e >> 6 < nks ? e >> 6 : 0, l = e & 63;
+        const int lkg = l >> 5, lg1 = (l >> 4) & 1, ljj = (l & 15) >> 2, lq = l & 3, lcol0 = 16 * lg1 + 4 * lq;
+        int ma = 16 * ks + 8 * lkg + ljj, mb = ma + 4;
+        ma = (PADDED && ma >= a.P1) ? 0 : ma; mb = (PADDED && mb >= a.P1) ? 0 : mb;
+        const int oya = a.dW1.div(ma), oxa = ma - oya * a.W1, oyb = a.dW1.div(mb), oxb = mb - oyb * a.W1;
+        const int lane_part = (lcol0 >> 3) * Wp + (lcol0 & 7);
+        const uint32_t base = (uint32_t)(uintptr_t)(lds_bytes)(unsigned char *)img;
+        tab[e] = make_uint2(base + 2u * (uint32_t)(lane_part + 4 * oya * Wp + 4 * oxa),
+                            base + 2u * (uint32_t)(lane_part + 4 * oyb * Wp + 4 * oxb));
+    }
+    const uint32_t wave_img = 2u * (uint32_t)(((w >> 1) * a.H + 4 * (w & 1)) * Wp);      // this wavefront's channel and row half, in bytes
     // zero rows behind the sample's gradient (written once: the copies below never touch them)
     for (int v = nvec + tid; v < nks * 64; v += C1WG_THREADS) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = zero_vec<bf16_t, 8>();
 
@@ -125,19 +137,21 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) void c
             if (cg + 1 < NG) fetch_image(b, cg + 1);
             else if (b + (int)gridDim.x < a.B) { fetch_image(b + gridDim.x, 0); fetch_dy(b + gridDim.x); }
 
-            int oxa = oxa0, oxb = oxb0, offa = offa0, offb = offb0;
             const bf16_t *ap = a_lane;
+            const uint2 *tp = tab + lane;
             // Software pipeline: the four reads of step k+1 are issued before the matrix instruction of step k (the
-            // transposing reads are not moved by the compiler).  Two straight-line bodies (with / without the bias
-            // column); whole groups of 5 steps are written out.
+            // transposing reads are not moved by the compiler), and the table entry of step k+2 before them.  Two
+            // straight-line bodies (with / without the bias column); whole groups of 5 steps are written out.
             auto walk = [&](auto with_bias) {
                 i16x4 ra0, ra1, rb0, rb1;
-                auto read = [&](int m0) {                      // m0: first position of the step
-                    const bool pa = !PADDED || m0 + ma0 < a.P1, pb = !PADDED || m0 + mb0 < a.P1;
-                    ra0 = tr4(ap); ra1 = tr4(ap + 4 * 32); rb0 = tr4(img + (pa ? offa : lane_img)); rb1 = tr4(img + (pb ? offb : lane_img));
+                uint2 tn = tp[0];
+                auto read = [&](int ks) {                      // the operands of step ks; tn holds its table entry
+                    const uint2 t = tn;
+                    tn = tp[(ks + 1) * 64];
+                    ra0 = tr4(ap); ra1 = tr4(ap + 4 * 32);
+                    rb0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(uintptr_t)(t.x + wave_img));
+                    rb1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(uintptr_t)(t.y + wave_img));
                     ap += 16 * 32;
-                    oxa += 16; { const bool wr = oxa >= a.W1; oxa -= wr ? a.W1 : 0; offa += wr ? step_wrap : 64; }
-                    oxb += 16; { const bool wr = oxb >= a.W1; oxb -= wr ? a.W1 : 0; offb += wr ? step_wrap : 64; }
                 };
                 auto mult = [&](const bf16x8 av, const bf16x8 bv) {
                     acc[cg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[cg], 0, 0, 0);
@@ -149,14 +163,14 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) void c
 #pragma unroll
                     for (int u = 0; u < 5; ++u) {
                         const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
-                        read(16 * (ks + u + 1));
+                        read(ks + u + 1);
                         __builtin_amdgcn_sched_barrier(0);     // keep the reads of the next step ahead of this step's product
                         mult(av, bv);
                     }
                 }
                 for (; ks < nks; ++ks) {
                     const bf16x8 av = join(ra0, ra1), bv = join(rb0, rb1);
-                    if (ks + 1 < nks) read(16 * (ks + 1));
+                    if (ks + 1 < nks) read(ks + 1);
                     mult(av, bv);
                 }
             };
@@ -180,7 +194,8 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) void c
 
 static size_t conv1_wgrad_image_lds(const Geom &g)
 {
-    return (((size_t)4 * g.H * g.W + 7) & ~(size_t)7) * 2 + (size_t)((g.P1 + 15) / 16) * 16 * 64;
+    const size_t nks = (size_t)((g.P1 + 15) / 16);
+    return (((size_t)4 * g.H * g.W + 7) & ~(size_t)7) * 2 + nks * 16 * 64 + (nks + 1) * 64 * 8;     // image, gradient rows, address table
 }
 
 // true if the frame shape and pointers fit conv1_wgrad_image_kernel
