@@ -177,7 +177,12 @@ def source_digest():
 # FETCH_SIZE / WRITE_SIZE (KiB per dispatch, averaged over the site's launches of the run, each scaled by what the
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
-TRAFFIC = {}
+TRAFFIC = {
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099059, "conv1_fwd_learn": 316484299, "conv1_wgrad": 314847635,
+                                    "conv2_fwd": 2626309, "conv3_fwd": 1214351, "fc_fwd": 3475117}, "7bd7bdb49d32801f"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846551, "conv1_fwd_learn": 56934458, "conv1_wgrad": 63785633,
+                                 "conv2_wgrad": 45561511}, "7bd7bdb49d32801f"),
+}
 
 
 def run_iterations(loop, torch, steps, warmup, sample_site=None, sample_every=1):
