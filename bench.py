@@ -185,6 +185,16 @@ TRAFFIC = {
 }
 
 
+# Average duration (us) of the same launch sites' kernels in the committed rocprofv3 kernel traces
+# (profiles/all_kernels_<workload>.txt), for comparison with the live event figure; same digest rule as TRAFFIC.
+TRACE_AVG_US = {
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.16, "heads_act": 5.43, "conv2_fwd": 3.87, "conv3_fwd": 3.50,
+                                    "fc_fwd": 3.21, "conv1_fwd_learn": 158.12, "conv1_wgrad": 123.66}, "7bd7bdb49d32801f"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.00, "heads_act": 5.42, "conv1_fwd_learn": 22.92, "conv1_wgrad": 20.93,
+                                 "conv2_wgrad": 23.34}, "7bd7bdb49d32801f"),
+}
+
+
 def run_iterations(loop, torch, steps, warmup, sample_site=None, sample_every=1):
     """warmup untimed steps, then `steps` timed ones between two synchronisations.  sample_site: bracket every
     sample_every-th launch of that site with events during the timed steps."""
@@ -376,6 +386,10 @@ def main():
     out["roofline"] = roofline_entry(cfg, dominant, kind, per_launch, rows, ms_timed / max(n_timed, 1) * 1e-3,
                                      overhead_ms * 1e-3, n_timed, launches_per_step, traffic)
     out["roofline"]["empty_bracket_us"] = empty_bracket_ms * 1e3
+    if args.workload in TRACE_AVG_US and dominant in TRACE_AVG_US[args.workload][0] and TRACE_AVG_US[args.workload][1] == source_digest():
+        tr_us = TRACE_AVG_US[args.workload][0][dominant]
+        out["roofline"]["trace_avg_us"] = tr_us        # the kernel's average in profiles/all_kernels_<workload>.txt
+        out["roofline"]["frac_from_trace"] = per_launch / (tr_us * 1e-6) / (out["roofline"]["peak"] * (1e12 if kind == "flop" else 1e9))
     out["rollout_ms_per_step"] = rollout_ms
     # every launch site of this workload: event-bracket time per launch (raw, and less the empty bracket) and its share
     kernels = {}
