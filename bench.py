@@ -391,6 +391,23 @@ def main():
         out["roofline"]["trace_avg_us"] = tr_us        # the kernel's average in profiles/all_kernels_<workload>.txt
         out["roofline"]["frac_from_trace"] = per_launch / (tr_us * 1e-6) / (out["roofline"]["peak"] * (1e12 if kind == "flop" else 1e9))
     out["rollout_ms_per_step"] = rollout_ms
+    # the same accounting for the learner's dominant kernel (minibatch-sized launches: a throughput figure, where the
+    # actor kernels at N rows per call are latency figures); brackets from the per-site pass
+    learn_sites = [(v[0] - v[1] * overhead_ms, k) for k, v in per_step.items()
+                   if k in work and work[k][2] == loop.B and work[k][0] == "flop"]
+    if learn_sites and not args.site:
+        _, lk = max(learn_sites)
+        lkind, lper, lrows = work[lk]
+        lms, ln = per_step[lk]
+        ltraffic = None
+        if args.workload in TRAFFIC and lk in TRAFFIC[args.workload][0] and TRAFFIC[args.workload][1] == source_digest():
+            ltraffic = TRAFFIC[args.workload][0][lk]
+        out["roofline_learner"] = roofline_entry(cfg, lk, lkind, lper, lrows, lms / ln * 1e-3, overhead_ms * 1e-3, int(ln * 2),
+                                                 ln, ltraffic)
+        if args.workload in TRACE_AVG_US and lk in TRACE_AVG_US[args.workload][0] and TRACE_AVG_US[args.workload][1] == source_digest():
+            tr_us = TRACE_AVG_US[args.workload][0][lk]
+            out["roofline_learner"]["trace_avg_us"] = tr_us
+            out["roofline_learner"]["frac_from_trace"] = lper / (tr_us * 1e-6) / (out["roofline_learner"]["peak"] * 1e12)
     # every launch site of this workload: event-bracket time per launch (raw, and less the empty bracket) and its share
     kernels = {}
     for k, (ms, n) in sorted(per_step.items(), key=lambda kv: -(kv[1][0] - kv[1][1] * overhead_ms)):

@@ -135,6 +135,8 @@ extern "C" int32_t hts_create(const hts_net_desc *desc, int32_t max_act_batch, i
     c.tile16_below = 128;
     if (const char *t16 = getenv("HTS_TILE16_BELOW")) c.tile16_below = atoi(t16);   // tuning knob, same bits either way
     if (const char *fr = getenv("HTS_FC_FOLD_ROWS")) c.fc_fold_rows = atoi(fr);   // tuning knob, same bits either way
+    c.conv1_slab_rows = 256;
+    if (const char *sr = getenv("HTS_CONV1_SLAB_ROWS")) c.conv1_slab_rows = atoi(sr);   // tuning knob, same bits either way
     c.ws = Workspace();
     Carver size_pass;
     carve(c, size_pass);

@@ -223,6 +223,32 @@ def test_act_small_and_large_batch_kernels_agree_bitwise(hts, shape, A, prec, mo
         assert all(np.array_equal(x, y) for x, y in zip(o, outs[0]))
 
 
+@pytest.mark.parametrize("N", [256, 301, 700])
+def test_conv1_slab_kernel_agrees_bitwise(hts, N, monkeypatch):
+    """Large bf16 batches of 16x72x96 frames take a conv1 kernel of their own (frame slabs of four channels resident in
+    LDS, producer and consumer wavefronts); it adds the same 64-long segments in the same order as the tile kernel, so
+    an observation's outputs do not depend on which of them served it.  N = 301 and 700 leave workgroups with
+    different numbers of observations (256 workgroups walk the batch)."""
+    Cc, H, W = FOOT
+    A = 19
+    params = dev(syn.init_params(21, Cc, H, W, A, bias_scale=0.05))
+    obs = dev(syn.obs_football(23, 1, N)[0])
+    outs = []
+    for rows in ("256", "100000000"):
+        monkeypatch.setenv("HTS_CONV1_SLAB_ROWS", rows)
+        ctx = hts.Context(Cc, H, W, A, precision=1, max_act_batch=N)
+        outs.append(_act(ctx, obs, params, 5, 1, 0, A))
+        ctx.close()
+    assert all(np.array_equal(x, y) for x, y in zip(*outs))
+    # and against the wave-per-segment kernels, 100 observations at a time
+    monkeypatch.delenv("HTS_CONV1_SLAB_ROWS", raising=False)
+    ctx = hts.Context(Cc, H, W, A, precision=1, max_act_batch=N)
+    for lo in range(0, N, 100):
+        part = _act(ctx, obs[lo:lo + 100], params, 5, 1, lo, A)
+        assert all(np.array_equal(x, y[lo:lo + 100]) for x, y in zip(part, outs[0]))
+    ctx.close()
+
+
 @pytest.mark.parametrize("prec", [0, 1])
 def test_act_with_loaded_parameters(hts, prec):
     """hts_act(params = NULL) reuses the parameters loaded before (bitwise the same outputs); it is refused when
