@@ -238,6 +238,258 @@ static hipError_t launch_conv1_wgrad_image(Ctx &c, const uint8_t *obs, const int
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The same weight gradient for 16-channel frames (16x72x96) with the work split between wavefronts: wavefronts 4-7
+// (producers) fetch the next four-channel slab of the frame into registers, convert it into one of TWO LDS images and
+// bring in the next sample's output gradient, while wavefronts 0-3 (consumers, one per SIMD next to a producer)
+// multiply the current slab -- consumer w owns input channel w of the slab, i.e. two column tiles (rows u = 0..3 and
+// 4..7 of the 8x8 window) that share the gradient operand.  In the kernel above every wavefront does both jobs in
+// turn, so the compute unit alternates between a conversion phase and a multiply phase (2048 frames: 118 us there).
+// One barrier per slab, one more per sample (the gradient rows in LDS are replaced between two samples).
+// The bias column (a constant 255 against the gradient) is formed in the first slab of a sample, every consumer taking
+// each fourth step; the four partial columns are added in wavefront order at the end.
+// ------------------------------------------------------------------------------------------------------------
+constexpr int C1WS_THREADS = 512, C1WS_PRODUCERS = 256;
+constexpr int C1WS_NP = 7;                 // 16-byte vectors of a slab per producer thread (slab of at most 28 KB)
+constexpr int C1WS_DYV = 7;                // 16-byte vectors of a sample's output gradient per producer thread
+constexpr int C1WS_DP = 2;                 // steps of operand reads a consumer keeps in flight
+constexpr int C1WS_MAX_SAMPLES = 64;       // samples per workgroup (their row indices are read once, into LDS)
+
+template <bool PADDED> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgrad_slab_kernel(const Conv1WgImgArgs a)
+{
+    constexpr int NG = 4, C = 16, PT = C1WS_PRODUCERS, DP = C1WS_DP;
+    extern __shared__ __attribute__((aligned(16))) unsigned char c1ws_smem[];
+    const int Wp = a.W, slab = 4 * a.H * a.W;                     // bytes of a slab in memory; its bf16 image takes twice that
+    const int nks = (a.P1 + 15) >> 4;                             // matrix-instruction steps per sample and slab
+    bf16_t *dyl = reinterpret_cast<bf16_t *>(c1ws_smem + 4 * slab);      // [P1 padded to 16][32]
+    uint2 *tab = reinterpret_cast<uint2 *>(dyl + nks * 16 * 32);
+    float *xch = reinterpret_cast<float *>(tab + (nks + C1WS_DP) * 64);        // [4][32] partial bias columns
+    int *rowid = reinterpret_cast<int *>(xch + 4 * 32);                  // [C1WS_MAX_SAMPLES] rows of this workgroup's samples
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = lane >> 5, g1 = (lane >> 4) & 1, jj = (lane & 15) >> 2, q4 = lane & 3;
+    const int nvec = a.P1 * 4;                                    // 16-byte vectors in one sample's [P1][32]
+    const int nsamp = (a.B - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int nphase = nsamp * NG;                                // slab p: sample p / NG of this workgroup, channels 4 (p % NG) .. + 3
+    typedef __attribute__((address_space(3))) unsigned char *lds_bytes;
+    // where a lane's two image reads of a step start (see the kernel above), relative to an image's first byte; DP rows
+    // more than there are steps, so that the read-ahead needs no check
+    for (int e = tid; e < (nks + C1WS_DP) * 64; e += C1WS_THREADS) {
+        const int ks = e >> 6 < nks ? e >> 6 : 0, l = e & 63;
+        const int lkg = l >> 5, lg1 = (l >> 4) & 1, ljj = (l & 15) >> 2, lq = l & 3, lcol0 = 16 * lg1 + 4 * lq;
+        int ma = 16 * ks + 8 * lkg + ljj, mb = ma + 4;
+        ma = (PADDED && ma >= a.P1) ? 0 : ma; mb = (PADDED && mb >= a.P1) ? 0 : mb;
+        const int oya = a.dW1.div(ma), oxa = ma - oya * a.W1, oyb = a.dW1.div(mb), oxb = mb - oyb * a.W1;
+        const int lane_part = (lcol0 >> 3) * Wp + (lcol0 & 7);
+        const uint32_t base = (uint32_t)(uintptr_t)(lds_bytes)c1ws_smem;
+        tab[e] = make_uint2(base + 2u * (uint32_t)(lane_part + 4 * oya * Wp + 4 * oxa),
+                            base + 2u * (uint32_t)(lane_part + 4 * oyb * Wp + 4 * oxb));
+    }
+    if (tid < nsamp) { const int b = blockIdx.x + tid * gridDim.x; rowid[tid] = a.index ? a.index[b] : b; }
+    // zero rows behind the sample's gradient (written once: the copies below never touch them)
+    for (int v = nvec + tid; v < nks * 64; v += C1WS_THREADS) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = zero_vec<bf16_t, 8>();
+
+    f32x16 acc[NG][2], accb;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        accb[r] = 0.0f;
+#pragma unroll
+        for (int cg = 0; cg < NG; ++cg) { acc[cg][0][r] = 0.0f; acc[cg][1][r] = 0.0f; }
+    }
+    if (w >= 4) {
+        // ---- producers ----
+        const int pt = tid - (C1WS_THREADS - PT);
+        const int nv = slab >> 4;
+        uint4 raw[2][C1WS_NP];
+        bf16x8 dyr[C1WS_DYV];
+        auto fetch_image = [&](int p, uint4 (&r)[C1WS_NP]) {
+            const int s = p / NG, cg = p - s * NG;
+            const uint8_t *src = a.obs + ((long long)rowid[s] * C + 4 * cg) * a.H * a.W;
+#pragma unroll
+            for (int i = 0; i < C1WS_NP; ++i) r[i] = *reinterpret_cast<const uint4 *>(src + 16 * min(pt + i * PT, nv - 1));
+        };
+        auto fetch_dy = [&](int s) {
+            const bf16_t *dsrc = a.dy + (long long)(blockIdx.x + s * gridDim.x) * a.P1 * 32;
+#pragma unroll
+            for (int i = 0; i < C1WS_DYV; ++i) dyr[i] = *reinterpret_cast<const bf16x8 *>(dsrc + 8 * min(pt + i * PT, nvec - 1));
+        };
+        auto convert = [&](const uint4 (&r)[C1WS_NP], int buf) {
+            unsigned char *dst = c1ws_smem + buf * 2 * slab + 32 * pt;
+#pragma unroll
+            for (int i = 0; i < C1WS_NP; ++i) {
+                if (pt + i * PT >= nv) continue;
+                const uint32_t x[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+                bf16x8 lo, hi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    lo[e] = from_f32<bf16_t>((float)((x[0] >> (8 * e)) & 0xFFu));
+                    lo[4 + e] = from_f32<bf16_t>((float)((x[1] >> (8 * e)) & 0xFFu));
+                    hi[e] = from_f32<bf16_t>((float)((x[2] >> (8 * e)) & 0xFFu));
+                    hi[4 + e] = from_f32<bf16_t>((float)((x[3] >> (8 * e)) & 0xFFu));
+                }
+                *reinterpret_cast<bf16x8 *>(dst + i * PT * 32) = lo;
+                *reinterpret_cast<bf16x8 *>(dst + i * PT * 32 + 16) = hi;
+            }
+        };
+        auto write_dy = [&]() {
+#pragma unroll
+            for (int i = 0; i < C1WS_DYV; ++i) {
+                const int v = pt + i * PT;
+                if (v < nvec) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
+            }
+        };
+        __syncthreads();                                           // the row indices are in LDS
+        fetch_image(0, raw[0]);
+        fetch_image(1, raw[1]);                                    // (NG > 1: slab 1 always exists)
+        fetch_dy(0);
+        convert(raw[0], 0);
+        write_dy();
+        fetch_image(2, raw[0]);
+        if (nsamp > 1) fetch_dy(1);
+        __syncthreads();
+        for (int s = 0; s < nsamp; ++s) {
+#pragma unroll
+            for (int cg = 0; cg < NG; ++cg) {                     // slab p + 1 sits in register set (cg + 1) % 2
+                const int p = s * NG + cg;
+                if (p + 1 < nphase) convert(raw[(cg + 1) & 1], (cg + 1) & 1);
+                if (p + 3 < nphase) fetch_image(p + 3, raw[(cg + 1) & 1]);
+                __syncthreads();
+            }
+            if (s + 1 < nsamp) {                                  // every consumer has left this sample's gradient rows
+                write_dy();
+                if (s + 2 < nsamp) fetch_dy(s + 2);
+                __syncthreads();
+            }
+        }
+    } else {
+        // ---- consumers ----
+        // Transposing read: lane 4j+q of a 16-lane group points at entries 4q..4q+3 (of the group's 16 rows / columns) at
+        // reduction index j and receives the four reduction indices of entry (lane % 16); groups 0,1 hold entries 0-15
+        // and 16-31 at reduction 0-7 (two reads), groups 2,3 at 8-15.
+        const int col0 = 16 * g1 + 4 * q4;
+        const bf16_t *a_lane = dyl + (8 * kg + jj) * 32 + col0;
+        typedef i16x4 __attribute__((address_space(3))) *lds_ptr;
+        auto tr4 = [](const bf16_t *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p)); };
+        auto trb = [](uint32_t addr) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(uintptr_t)addr); };
+        auto join = [](const i16x4 lo, const i16x4 hi) {
+            typedef short i16x8 __attribute__((ext_vector_type(8)));
+            const i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            return __builtin_bit_cast(bf16x8, v);
+        };
+        bf16x8 ones;                                              // bias column: 255 in column 0 of the tile
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ones[e] = from_f32<bf16_t>((lane & 31) == 0 ? 255.0f : 0.0f);
+        const uint2 *tp = tab + lane;
+        __syncthreads();
+        __syncthreads();
+        for (int s = 0; s < nsamp; ++s) {
+#pragma unroll
+            for (int cg = 0; cg < NG; ++cg) {
+                // this wavefront's channel of the slab in image (cg & 1), rows u = 0..3 / 4..7 of the window, in bytes
+                const uint32_t img0 = (uint32_t)((cg & 1) * 2 * slab + 2 * (w * a.H) * Wp), img1 = img0 + (uint32_t)(2 * 4 * Wp);
+                // Software pipeline: the six operand reads of step k+DP are issued before the matrix instructions of step
+                // k (a wavefront runs alone on its SIMD here, and one step's products are much shorter than an LDS round
+                // trip), and the table entry of step k+2DP with them.  DP operand sets; the loop is written out DP steps at a time.
+                struct Ops { i16x4 a0, a1, b0, b1, c0, c1; uint2 tn; };
+                Ops o[DP];
+                auto read = [&](int ks, Ops &x) {                  // the operands of step ks; x.tn holds its table entry
+                    const uint2 t = x.tn;
+                    x.tn = tp[(ks + DP) * 64];
+                    const bf16_t *ap = a_lane + ks * (16 * 32);
+                    x.a0 = tr4(ap); x.a1 = tr4(ap + 4 * 32);
+                    x.b0 = trb(t.x + img0); x.b1 = trb(t.y + img0);
+                    x.c0 = trb(t.x + img1); x.c1 = trb(t.y + img1);
+                };
+                auto step = [&](int ks, Ops &x) {
+                    const bf16x8 av = join(x.a0, x.a1), bv = join(x.b0, x.b1), cv = join(x.c0, x.c1);
+                    if (ks + DP < nks) read(ks + DP, x);
+                    __builtin_amdgcn_sched_barrier(0);             // keep those reads ahead of this step's products
+                    acc[cg][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[cg][0], 0, 0, 0);
+                    acc[cg][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, cv, acc[cg][1], 0, 0, 0);
+                    if (cg == 0 && (ks & 3) == w) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, ones, accb, 0, 0, 0);
+                };
+#pragma unroll
+                for (int d = 0; d < DP; ++d) { o[d].tn = tp[d * 64]; if (d < nks) read(d, o[d]); }
+                int ks = 0;
+                for (; ks + DP <= nks; ks += DP) {
+#pragma unroll
+                    for (int d = 0; d < DP; ++d) step(ks + d, o[d]);
+                }
+#pragma unroll
+                for (int d = 0; d < DP - 1; ++d) if (ks + d < nks) step(ks + d, o[d]);
+                __syncthreads();
+            }
+            if (s + 1 < nsamp) __syncthreads();
+        }
+        // accumulator register r of lane l is D[n = 8(r/4) + 4(l/32) + r%4][column l%32]
+#pragma unroll
+        for (int cg = 0; cg < NG; ++cg)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float *dst = a.part + (long long)blockIdx.x * 32 * a.N + cg * 256 + (2 * w + h) * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dst[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = acc[cg][h][r];
+            }
+        if ((lane & 31) == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) xch[w * 32 + 8 * (r / 4) + 4 * kg + (r % 4)] = accb[r];
+        }
+    }
+    __syncthreads();
+    if (tid < 32) {
+        float t = xch[tid];
+#pragma unroll
+        for (int ww = 1; ww < 4; ++ww) t += xch[ww * 32 + tid];
+        a.part[(long long)blockIdx.x * 32 * a.N + (long long)tid * a.N + 64 * C] = t;
+    }
+}
+
+static size_t conv1_wgrad_slab_lds(const Geom &g)
+{
+    const size_t nks = (size_t)((g.P1 + 15) / 16);
+    return (size_t)16 * g.H * g.W + nks * 16 * 64 + (nks + C1WS_DP) * 64 * 8 + 4 * 32 * 4 + C1WS_MAX_SAMPLES * 4;      // two images, gradient rows, address table, bias partials, row indices
+}
+
+// true if a batch of B samples cut into at most max_parts workgroups leaves each of them no more samples than its index table holds
+static bool conv1_wgrad_slab_batch_fits(int B, int max_parts)
+{
+    const int grid = B < max_parts ? B : max_parts;
+    return grid > 0 && (B + grid - 1) / grid <= C1WS_MAX_SAMPLES;
+}
+
+// true if the frame shape and pointers fit conv1_wgrad_slab_kernel
+static bool conv1_wgrad_slab_fits(const Geom &g, const uint8_t *obs)
+{
+    return g.C == 16 && !(g.W & 3) && !((g.H * g.W) & 3) && !(((uintptr_t)obs) & 15u) && g.W1 >= 16 && g.P1 >= 16 &&
+           4 * g.H * g.W <= C1WS_NP * C1WS_PRODUCERS * 16 && g.P1 * 4 <= C1WS_DYV * C1WS_PRODUCERS &&
+           conv1_wgrad_slab_lds(g) <= 160 * 1024;
+}
+
+static hipError_t launch_conv1_wgrad_slab(Ctx &c, const uint8_t *obs, const int32_t *index, int B, float *part, int max_parts,
+                                          int *nz)
+{
+    const Geom &g = c.g;
+    Conv1WgImgArgs a;
+    a.obs = obs; a.index = index; a.dy = (const bf16_t *)c.ws.dy1; a.part = part;
+    a.B = B; a.H = g.H; a.W = g.W; a.W1 = g.W1; a.P1 = g.P1; a.N = g.K1 + 1;
+    a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
+    const size_t lds = conv1_wgrad_slab_lds(g);
+    const bool padded = (g.P1 & 15) != 0;
+    void (*kern)(const Conv1WgImgArgs) = padded ? conv1_wgrad_slab_kernel<true> : conv1_wgrad_slab_kernel<false>;
+    static std::atomic<bool> attr_set[2] = {};       // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
+    if (!attr_set[padded ? 1 : 0].load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set[padded ? 1 : 0].store(true, std::memory_order_release);
+    }
+    const int grid = B < max_parts ? B : max_parts;
+    if ((B + grid - 1) / grid > C1WS_MAX_SAMPLES) return hipErrorInvalidValue;      // (the caller checks conv1_wgrad_slab_batch_fits)
+    *nz = grid;
+    SiteTimer tm(c, SITE_CONV1_WGRAD);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C1WS_THREADS), lds, c.stream, a);
+    return hipGetLastError();
+}
+
 template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, const int32_t *index, int B, float *grads)
 {
     const Geom &g = c.g;
@@ -388,7 +640,8 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
             SiteTimer tm(c, SITE_CONV1_WGRAD);
             return small ? launch_wsgemm<decltype(p), 4, 64, false>(p, c.stream, spg1) : launch_gemm(p, c.stream);
         };
-        if (!small && sizeof(T) == 2 && conv1_wgrad_image_fits(g, obs)) e = launch_conv1_wgrad_image(c, obs, index, B, part1, s1.nz, &nz1);
+        if (!small && sizeof(T) == 2 && B >= c.conv1_slab_rows && conv1_wgrad_slab_fits(g, obs) && conv1_wgrad_slab_batch_fits(B, s1.nz)) e = launch_conv1_wgrad_slab(c, obs, index, B, part1, s1.nz, &nz1);
+        else if (!small && sizeof(T) == 2 && conv1_wgrad_image_fits(g, obs)) e = launch_conv1_wgrad_image(c, obs, index, B, part1, s1.nz, &nz1);
         else e = index ? conv1_wgrad(Conv1Wgrad<T, true>{}) : conv1_wgrad(Conv1Wgrad<T, false>{});
         if (e != hipSuccess) return e;
     }

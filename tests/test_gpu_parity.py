@@ -249,6 +249,40 @@ def test_conv1_slab_kernel_agrees_bitwise(hts, N, monkeypatch):
     ctx.close()
 
 
+@pytest.mark.parametrize("count,B", [(330, 301), (600, 600)])
+def test_conv1_slab_gradient_kernels_agree(hts, oracle, count, B, monkeypatch):
+    """The learner's two conv1 kernels for large bf16 batches of 16x72x96 frames (forward and weight gradient, both with
+    producer and consumer wavefronts) against the kernels they replace: the forward bits are identical, and the weight
+    gradient adds the same products in the same order -- only the bias column is formed from four partial columns
+    instead of one -- so every tensor of the gradient but conv1.b is bitwise the same."""
+    shape, A = FOOT, 19
+    Cc, H, W = shape
+    net, params, obs, actions, old_logp, adv, ret = _rollout(oracle, shape, A, count, 1200 + count, True)
+    index = syn.permutation(9, count)[:B]
+    out = []
+    for rows in ("256", "100000000"):
+        monkeypatch.setenv("HTS_CONV1_SLAB_ROWS", rows)
+        ctx = hts.Context(Cc, H, W, A, precision=1, max_learn_batch=B)
+        hp = hts.HParams(algo=1, clip_eps=0.1)
+        grads = torch.full((ctx.P,), float("nan"), device="cuda")
+        stats = ctx.new_stats()
+        ctx.hts_loss_and_grads(dev(obs), dev(actions), dev(old_logp), dev(adv), dev(ret), dev(params), hp, grads,
+                               index=dev(index), stats=stats)
+        torch.cuda.synchronize()
+        out.append((grads.cpu().numpy(), ctx.read_stats(stats)))
+        ctx.close()
+    (g_new, st_new), (g_old, st_old) = out
+    assert np.all(np.isfinite(g_new))
+    for k in ("policy_loss", "value_loss", "entropy"):
+        assert st_new[k] == st_old[k], (k, st_new[k], st_old[k])
+    for name, gn in _split(g_new, shape, A).items():
+        go = _split(g_old, shape, A)[name]
+        if name == "conv1.b":
+            assert rel_err(gn, go) <= 1e-5, (name, rel_err(gn, go))
+        else:
+            assert np.array_equal(gn, go), (name, rel_err(gn, go))
+
+
 @pytest.mark.parametrize("prec", [0, 1])
 def test_act_with_loaded_parameters(hts, prec):
     """hts_act(params = NULL) reuses the parameters loaded before (bitwise the same outputs); it is refused when
