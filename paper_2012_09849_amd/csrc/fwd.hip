@@ -170,18 +170,20 @@ static hipError_t launch_conv1_image(Ctx &c, const uint8_t *obs, const int32_t *
 }
 
 // ------------------------------------------------------------------------------------------------------------
-// conv1 for large bf16 batches of frames with 8, 12 or 16 channels whose four-channel slab (4*H*W bytes, 16x72x96: 27 KB)
-// fits twice into LDS as bf16: one workgroup per compute unit walks a share of the observations.
+// conv1 for large bf16 batches of the two frame shapes of the paper's experiments (16x72x96, and 4x84x84 for the largest
+// batches), whose four-channel slab (4*H*W bytes, about 27 KB) fits twice into LDS as bf16: one workgroup per compute
+// unit walks a share of the observations.
 // A frame passes in slabs of four channels.  Wavefronts 4-7 (producers) fetch slab q+2 into registers, convert slab q+1
 // to bf16 once into one of two LDS images [(c,y)][W] and copy the 32 x 256 slice of conv1.w that belongs to its
 // channels beside it; meanwhile wavefronts 0-3 (consumers, one per SIMD next to a producer) multiply slab q: position
 // tiles w, w+4, ... of 32 positions each, the matrix instruction's weight operand read from the LDS slice (shared by two
-// tiles), its position operand straight from the image (8 consecutive k of conv1.w's (c,u,v) order are 8 neighbouring
+// tiles; a four-channel frame is a single slab and its weights stay in the consumers' registers instead), its position
+// operand straight from the image (8 consecutive k of conv1.w's (c,u,v) order are 8 neighbouring
 // pixels of one row).  A tile's running total stays in the consumer's registers across the frame's slabs, so the
 // channels' 64-long segment sums are added in channel order exactly as in Conv1Fwd: same bits as the other conv1
 // kernels.  One barrier per slab.  (The tile kernel converts every pixel four times and fetches it in 8-byte pieces;
 // with every wavefront doing both jobs in turn the compute unit alternates between a conversion phase and a multiply
-// phase and is no faster than the tile kernel: 155 us for 2048 frames of 16x72x96 against 130 us this way.)
+// phase and is no faster than the tile kernel, 155 us for 2048 frames of 16x72x96; this way: 115 us.)
 // ------------------------------------------------------------------------------------------------------------
 struct Conv1SlabArgs {
     const uint8_t *obs;
@@ -204,7 +206,7 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
     constexpr int C = 4 * NG, K = 64 * C, SLAB = 4 * H * W, NV = SLAB / 16, PT = C1S_PRODUCERS, NP = (NV + PT - 1) / PT;
     constexpr int IMG = 2 * SLAB;          // bytes of one bf16 image
     constexpr int D = 2;                   // slabs in flight in the producers' registers
-    static_assert(SLAB % 16 == 0 && NG % D == 0, "slab shape");
+    static_assert(SLAB % 16 == 0 && (NG == 1 || NG % D == 0), "slab shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char c1s_smem[];
     unsigned char *wl = c1s_smem + 2 * IMG;
     float *lbias = reinterpret_cast<float *>(wl + 2 * C1S_WBUF);
@@ -227,10 +229,12 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
                 const int v = pt + i * PT;                     // a vector behind the slab's end repeats its last one
                 r[i] = *reinterpret_cast<const uint4 *>(src + 16 * (NV % PT == 0 ? v : min(v, NV - 1)));
             }
+            if constexpr (NG > 1) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int v = pt + i * PT;                     // row v / 32, 16-byte column v % 32 of the 32 x 256 slice
-                wr[i] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.w) + (v >> 5) * (2 * K) + cg * 512 + (v & 31) * 16);
+                for (int i = 0; i < 4; ++i) {
+                    const int v = pt + i * PT;                 // row v / 32, 16-byte column v % 32 of the 32 x 256 slice
+                    wr[i] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.w) + (v >> 5) * (2 * K) + cg * 512 + (v & 31) * 16);
+                }
             }
         };
         auto convert = [&](const uint4 (&r)[NP], const uint4 (&wr)[4], int buf) {
@@ -250,10 +254,12 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
                 *reinterpret_cast<bf16x8 *>(dst + i * PT * 32) = lo;
                 *reinterpret_cast<bf16x8 *>(dst + i * PT * 32 + 16) = hi;
             }
+            if constexpr (NG > 1) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int v = pt + i * PT;
-                *reinterpret_cast<uint4 *>(wl + buf * C1S_WBUF + (v >> 5) * C1S_WPITCH + (v & 31) * 16) = wr[i];
+                for (int i = 0; i < 4; ++i) {
+                    const int v = pt + i * PT;
+                    *reinterpret_cast<uint4 *>(wl + buf * C1S_WBUF + (v >> 5) * C1S_WPITCH + (v & 31) * 16) = wr[i];
+                }
             }
         };
 #pragma unroll
@@ -264,7 +270,8 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
         for (int q0 = 0; q0 < nphase; q0 += D) {
 #pragma unroll
             for (int j = 0; j < D; ++j) {                      // slab q+1 sits in register set (j+1) % D
-                const int q = q0 + j;                          // (nphase is a multiple of D: no check)
+                const int q = q0 + j;
+                if (NG % D != 0 && q >= nphase) break;         // (the same for the whole workgroup)
                 if (q + 1 < nphase) convert(raw[(j + 1) % D], wraw[(j + 1) % D], (q & 1) ^ 1);
                 if (q + 1 + D < nphase) fetch(q + 1 + D, raw[(j + 1) % D], wraw[(j + 1) % D]);
                 __syncthreads();
@@ -285,6 +292,12 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
     }
     const int mytiles = w < ntiles ? (ntiles - w + 3) / 4 : 0;       // the same for the whole wavefront
     const uint32_t woff = (uint32_t)(lrow * C1S_WPITCH + 16 * lk);
+    // a four-channel frame is one slab: its weights never change and stay in registers
+    bf16x8 breg[NG == 1 ? 16 : 1];
+    if constexpr (NG == 1) {
+#pragma unroll
+        for (int t = 0; t < 16; ++t) breg[t] = *reinterpret_cast<const bf16x8 *>(a.w + lrow * K + 16 * t + 8 * lk);
+    }
     f32x16 tot[C1S_TILES];
     auto read16 = [&](const unsigned char *p) {                      // 8 pixels of one image row (8-byte aligned)
         const Vec<bf16_t, 4> lo = *reinterpret_cast<const Vec<bf16_t, 4> *>(p), hi = *reinterpret_cast<const Vec<bf16_t, 4> *>(p + 8);
@@ -317,7 +330,9 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
-                    const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(wb + 2 * (64 * (c0 + c) + 16 * t));
+                    bf16x8 wv;
+                    if constexpr (NG == 1) wv = breg[(c0 + c) * 4 + t];
+                    else wv = *reinterpret_cast<const bf16x8 *>(wb + 2 * (64 * (c0 + c) + 16 * t));
 #pragma unroll
                     for (int i = 0; i < NT; ++i) {
                         const bf16x8 av = read16(ib[i] + 2 * (((c0 + c) * H + 2 * t) * W));
@@ -370,7 +385,7 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
         const int b = blockIdx.x + s * gridDim.x;
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
-            const int buf = cg & 1;                            // NG is even: slab s*NG + cg has the parity of cg
+            const int buf = (s * NG + cg) & 1;
             if (cg == 0) slab(buf, std::true_type{}, std::integral_constant<bool, NG == 1>{}, b);
             else if (cg == NG - 1) slab(buf, std::false_type{}, std::true_type{}, b);
             else slab(buf, std::false_type{}, std::false_type{}, b);
@@ -382,7 +397,8 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
 // true if the frame shape and pointers fit conv1_slab_kernel as it is instantiated
 static bool conv1_slab_fits(const Geom &g, const uint8_t *obs)
 {
-    return g.C == 16 && g.H == 72 && g.W == 96 && (g.P1 + 31) / 32 <= 4 * C1S_TILES && !(((uintptr_t)obs) & 15u);
+    const bool football = g.C == 16 && g.H == 72 && g.W == 96, atari = g.C == 4 && g.H == 84 && g.W == 84;
+    return (football || atari) && (g.P1 + 31) / 32 <= 4 * C1S_TILES && !(((uintptr_t)obs) & 15u);
 }
 
 static hipError_t launch_conv1_slab(Ctx &c, const uint8_t *obs, const int32_t *index, int B)
@@ -391,13 +407,14 @@ static hipError_t launch_conv1_slab(Ctx &c, const uint8_t *obs, const int32_t *i
     Conv1SlabArgs a;
     a.obs = obs; a.index = index; a.w = (const bf16_t *)c.ws.w1s; a.bias = c.ws.hb + c.sh.b1; a.out = (bf16_t *)c.ws.act1;
     a.B = B; a.W1 = g.W1; a.P1 = g.P1;
-    auto kern = conv1_slab_kernel<4, 72, 96>;
-    const size_t lds = conv1_slab_lds<72, 96>();
-    static std::atomic<bool> attr_set{false};       // raise the dynamic-LDS limit once (setting it twice is harmless)
-    if (!attr_set.load(std::memory_order_acquire)) {
+    const bool football = g.C == 16;
+    void (*kern)(const Conv1SlabArgs) = football ? conv1_slab_kernel<4, 72, 96> : conv1_slab_kernel<1, 84, 84>;
+    const size_t lds = football ? conv1_slab_lds<72, 96>() : conv1_slab_lds<84, 84>();
+    static std::atomic<bool> attr_set[2] = {};      // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
+    if (!attr_set[football ? 1 : 0].load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set.store(true, std::memory_order_release);
+        attr_set[football ? 1 : 0].store(true, std::memory_order_release);
     }
     int grid = B < 256 ? B : 256;                    // one workgroup per compute unit (its LDS), walking the batch
     const int least = (B + C1S_MAX_SAMPLES - 1) / C1S_MAX_SAMPLES;
@@ -440,7 +457,9 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
             if (done) {}
             else if (small) e = g.K1 >= 1024 ? launch_wsgemm<Conv1Fwd<T>, 16, Conv1Fwd<T>::SEG, false, (sizeof(T) == 4)>(p, c.stream)
                                         : launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream);
-            else if (sizeof(T) == 2 && B >= c.conv1_slab_rows && conv1_slab_fits(g, obs)) e = launch_conv1_slab(c, obs, index, B);
+            // (four-channel frames: the slab kernel gains only where a workgroup walks eight or more observations --
+            // 4096 rows of 4x84x84: an act call 212 -> 206 us; 1024 rows: no difference to the image kernel)
+            else if (sizeof(T) == 2 && B >= (g.C == 4 ? 8 : 1) * c.conv1_slab_rows && conv1_slab_fits(g, obs)) e = launch_conv1_slab(c, obs, index, B);
             else if (sizeof(T) == 2 && conv1_image_fits(g, obs)) e = launch_conv1_image(c, obs, index, B);
             else e = launch_gemm(p, c.stream);
         }

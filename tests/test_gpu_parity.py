@@ -223,16 +223,16 @@ def test_act_small_and_large_batch_kernels_agree_bitwise(hts, shape, A, prec, mo
         assert all(np.array_equal(x, y) for x, y in zip(o, outs[0]))
 
 
-@pytest.mark.parametrize("N", [256, 301, 700])
-def test_conv1_slab_kernel_agrees_bitwise(hts, N, monkeypatch):
+@pytest.mark.parametrize("shape,A,N", [(FOOT, 19, 256), (FOOT, 19, 301), (FOOT, 19, 700), (ATARI, 18, 2100)])
+def test_conv1_slab_kernel_agrees_bitwise(hts, shape, A, N, monkeypatch):
     """Large bf16 batches of 16x72x96 frames take a conv1 kernel of their own (frame slabs of four channels resident in
     LDS, producer and consumer wavefronts); it adds the same 64-long segments in the same order as the tile kernel, so
     an observation's outputs do not depend on which of them served it.  N = 301 and 700 leave workgroups with
-    different numbers of observations (256 workgroups walk the batch)."""
-    Cc, H, W = FOOT
-    A = 19
+    different numbers of observations (256 workgroups walk the batch).  4x84x84 frames take it from 2048 rows on (there
+    against the LDS-image kernel of that shape)."""
+    Cc, H, W = shape
     params = dev(syn.init_params(21, Cc, H, W, A, bias_scale=0.05))
-    obs = dev(syn.obs_football(23, 1, N)[0])
+    obs = dev(syn.obs_football(23, 1, N)[0] if shape == FOOT else syn.obs_atari(23, 1, N)[0])
     outs = []
     for rows in ("256", "100000000"):
         monkeypatch.setenv("HTS_CONV1_SLAB_ROWS", rows)
