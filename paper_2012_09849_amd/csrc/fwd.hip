@@ -183,7 +183,7 @@ static hipError_t launch_conv1_image(Ctx &c, const uint8_t *obs, const int32_t *
 // channels' 64-long segment sums are added in channel order exactly as in Conv1Fwd: same bits as the other conv1
 // kernels.  One barrier per slab.  (The tile kernel converts every pixel four times and fetches it in 8-byte pieces;
 // with every wavefront doing both jobs in turn the compute unit alternates between a conversion phase and a multiply
-// phase and is no faster than the tile kernel, 155 us for 2048 frames of 16x72x96; this way: 115 us.)
+// phase and is no faster than the tile kernel, 155 us for 2048 frames of 16x72x96; this way: 96 us.)
 // ------------------------------------------------------------------------------------------------------------
 struct Conv1SlabArgs {
     const uint8_t *obs;
@@ -201,7 +201,9 @@ constexpr int C1S_TILES = 4;              // position tiles per consumer wavefro
 
 template <int H, int W> constexpr size_t conv1_slab_lds() { return (size_t)2 * (8 * H * W) + 2 * C1S_WBUF + 128 + C1S_MAX_SAMPLES * 4; }
 
-template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void conv1_slab_kernel(const Conv1SlabArgs a)
+// (LDS admits one workgroup per compute unit, two wavefronts per SIMD: the register budget is stated, or the compiler
+// aims at three and keeps fewer loads in flight -- 107 -> 96 us)
+template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv1_slab_kernel(const Conv1SlabArgs a)
 {
     constexpr int C = 4 * NG, K = 64 * C, SLAB = 4 * H * W, NV = SLAB / 16, PT = C1S_PRODUCERS, NP = (NV + PT - 1) / PT;
     constexpr int IMG = 2 * SLAB;          // bytes of one bf16 image
@@ -220,8 +222,9 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
     if (w >= 4) {
         // ---- producers ----
         const int pt = tid - (C1S_THREADS - PT);
-        uint4 raw[D][NP], wraw[D][4];
-        auto fetch = [&](int q, uint4 (&r)[NP], uint4 (&wr)[4]) {
+        constexpr int NWV = NG > 1 ? 4 : 0;                // 16-byte vectors of the weight slice per producer thread
+        uint4 raw[D][NP + NWV];                            // a slab's vectors, then its weight slice's
+        auto fetch = [&](int q, uint4 (&r)[NP + NWV]) {
             const int s = q / NG, cg = q - s * NG;
             const uint8_t *src = a.obs + ((long long)rowid[s] * C + 4 * cg) * (H * W);
 #pragma unroll
@@ -233,11 +236,11 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int v = pt + i * PT;                 // row v / 32, 16-byte column v % 32 of the 32 x 256 slice
-                    wr[i] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.w) + (v >> 5) * (2 * K) + cg * 512 + (v & 31) * 16);
+                    r[NP + i] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.w) + (v >> 5) * (2 * K) + cg * 512 + (v & 31) * 16);
                 }
             }
         };
-        auto convert = [&](const uint4 (&r)[NP], const uint4 (&wr)[4], int buf) {
+        auto convert = [&](const uint4 (&r)[NP + NWV], int buf) {
             unsigned char *dst = c1s_smem + buf * IMG + 32 * pt;
 #pragma unroll
             for (int i = 0; i < NP; ++i) {
@@ -258,22 +261,22 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int v = pt + i * PT;
-                    *reinterpret_cast<uint4 *>(wl + buf * C1S_WBUF + (v >> 5) * C1S_WPITCH + (v & 31) * 16) = wr[i];
+                    *reinterpret_cast<uint4 *>(wl + buf * C1S_WBUF + (v >> 5) * C1S_WPITCH + (v & 31) * 16) = r[NP + i];
                 }
             }
         };
 #pragma unroll
-        for (int d = 0; d < D; ++d) if (d < nphase) fetch(d, raw[d], wraw[d]);
-        convert(raw[0], wraw[0], 0);
-        if (D < nphase) fetch(D, raw[0], wraw[0]);
+        for (int d = 0; d < D; ++d) if (d < nphase) fetch(d, raw[d]);
+        convert(raw[0], 0);
+        if (D < nphase) fetch(D, raw[0]);
         __syncthreads();
         for (int q0 = 0; q0 < nphase; q0 += D) {
 #pragma unroll
             for (int j = 0; j < D; ++j) {                      // slab q+1 sits in register set (j+1) % D
                 const int q = q0 + j;
                 if (NG % D != 0 && q >= nphase) break;         // (the same for the whole workgroup)
-                if (q + 1 < nphase) convert(raw[(j + 1) % D], wraw[(j + 1) % D], (q & 1) ^ 1);
-                if (q + 1 + D < nphase) fetch(q + 1 + D, raw[(j + 1) % D], wraw[(j + 1) % D]);
+                if (q + 1 < nphase) convert(raw[(j + 1) % D], (q & 1) ^ 1);
+                if (q + 1 + D < nphase) fetch(q + 1 + D, raw[(j + 1) % D]);
                 __syncthreads();
             }
         }
@@ -352,21 +355,32 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) void c
         }
     };
     // The weights are the FIRST operand of the matrix instruction, so a lane's accumulator registers are 16 output
-    // channels (8g + 4 lk + j, g and j < 4) of ONE position and leave as four 8-byte stores.
+    // channels (8g + 4 lk + j, g and j < 4) of ONE position.  Lanes l and l + 32 hold the two interleaved halves of a
+    // position's 64-byte row; they exchange two of their four 8-byte groups so that each writes 32 contiguous bytes
+    // (as four 8-byte stores per lane the row left in 16-byte pieces, and the kernel wrote three times its output).
     auto finish = [&](int b, int m, const f32x16 &tt) {
-        if (m < a.P1) {
-            bf16_t *dst = a.out + ((long long)b * a.P1 + m) * 32 + 4 * lk;
+        uint2 p[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 bias = *reinterpret_cast<const f32x4 *>(lbias + 8 * g + 4 * lk);
-                Vec<bf16_t, 4> o;
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 bias = *reinterpret_cast<const f32x4 *>(lbias + 8 * g + 4 * lk);
+            Vec<bf16_t, 4> o;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float y = __builtin_fmaf(tt[4 * g + j], 1.0f / 255.0f, bias[j]);
-                    o[j] = from_f32<bf16_t>(y > 0.0f ? y : 0.0f);
-                }
-                *reinterpret_cast<Vec<bf16_t, 4> *>(dst + 8 * g) = o;
+            for (int j = 0; j < 4; ++j) {
+                const float y = __builtin_fmaf(tt[4 * g + j], 1.0f / 255.0f, bias[j]);
+                o[j] = from_f32<bf16_t>(y > 0.0f ? y : 0.0f);
             }
+            p[g] = __builtin_bit_cast(uint2, o);
+        }
+        // lane lk = 0 keeps groups 0, 1 (channels 0-3, 8-11) and receives its partner's (4-7, 12-15);
+        // lane lk = 1 keeps groups 2, 3 (channels 20-23, 28-31) and receives its partner's (16-19, 24-27)
+        const uint2 s0 = lk ? p[0] : p[2], s1 = lk ? p[1] : p[3];
+        uint2 r0, r1;
+        r0.x = __shfl_xor(s0.x, 32, 64); r0.y = __shfl_xor(s0.y, 32, 64);
+        r1.x = __shfl_xor(s1.x, 32, 64); r1.y = __shfl_xor(s1.y, 32, 64);
+        if (m < a.P1) {
+            uint4 *dst = reinterpret_cast<uint4 *>(a.out + ((long long)b * a.P1 + m) * 32 + 16 * lk);
+            dst[0] = lk ? make_uint4(r0.x, r0.y, p[2].x, p[2].y) : make_uint4(p[0].x, p[0].y, r0.x, r0.y);
+            dst[1] = lk ? make_uint4(r1.x, r1.y, p[3].x, p[3].y) : make_uint4(p[1].x, p[1].y, r1.x, r1.y);
         }
     };
     using I0 = std::integral_constant<int, 0>;
