@@ -353,8 +353,8 @@ def main():
         ranked = sorted(((v[0] - v[1] * overhead_ms, k) for k, v in per_step.items() if k in work), reverse=True)
         dominant = ranked[0][1]
     launches_per_step = per_step[dominant][1]
-    # about 64 brackets per step: a bracket costs the stream about as much as a small kernel
-    every = max(1, int(launches_per_step // 64))
+    # about 16 brackets per step: a bracket costs the stream about as much as a small kernel
+    every = max(1, int(launches_per_step // 16))
     torch.cuda.synchronize()
 
     # timed region: a sample of the dominant kernel's launches is bracketed by HIP events on the library's stream

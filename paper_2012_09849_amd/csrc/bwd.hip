@@ -33,7 +33,7 @@ constexpr int C1WG_PASSES = 20;            // passes of a wavefront over its sha
 constexpr int C1WG_DYV = 4;                // 16-byte vectors of the sample's output gradient per thread
 
 // PADDED: P1 is not a multiple of 16 (the last step has padding positions)
-template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) void conv1_wgrad_image_kernel(const Conv1WgImgArgs a)
+template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv1_wgrad_image_kernel(const Conv1WgImgArgs a)
 {
     constexpr int C = 4 * NG;
     extern __shared__ __attribute__((aligned(16))) unsigned char c1w_smem[];

@@ -84,7 +84,7 @@ template <class S> constexpr size_t imgconv_lds_bytes()
 
 constexpr int IMGCONV_THREADS = 512;
 
-template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) void imgconv_kernel(const ImgConvArgs a)
+template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void imgconv_kernel(const ImgConvArgs a)
 {
     constexpr int CIN = S::CIN, NCOL = S::NCOL, TAPS = S::TAPS, NCLS = S::NCLS, G = S::G, TN = NCOL / 32;
     constexpr int KC = TAPS * CIN, WP = KC + 8, IP = CIN + 8, PIN = S::PIN, ZR = G * PIN;   // pitches; the zero row
