@@ -178,20 +178,20 @@ def source_digest():
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
 TRAFFIC = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099059, "conv1_fwd_learn": 316484299, "conv1_wgrad": 314847635,
-                                    "conv2_fwd": 2626309, "conv3_fwd": 1214351, "fc_fwd": 3475117}, "7bd7bdb49d32801f"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846551, "conv1_fwd_learn": 56934458, "conv1_wgrad": 63785633,
-                                 "conv2_wgrad": 45561511}, "7bd7bdb49d32801f"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5097010, "conv1_fwd_learn": 279635616, "conv1_wgrad": 317483871,
+                                    "conv2_fwd": 2626306, "conv3_fwd": 1214351, "fc_fwd": 3475117}, "72dd184d9e7b140b"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846563, "conv1_fwd_learn": 56934411, "conv1_wgrad": 63789711,
+                                 "conv2_wgrad": 45566210}, "72dd184d9e7b140b"),
 }
 
 
 # Average duration (us) of the same launch sites' kernels in the committed rocprofv3 kernel traces
 # (profiles/all_kernels_<workload>.txt), for comparison with the live event figure; same digest rule as TRAFFIC.
 TRACE_AVG_US = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.16, "heads_act": 5.43, "conv2_fwd": 3.87, "conv3_fwd": 3.50,
-                                    "fc_fwd": 3.21, "conv1_fwd_learn": 158.12, "conv1_wgrad": 123.66}, "7bd7bdb49d32801f"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.00, "heads_act": 5.42, "conv1_fwd_learn": 22.92, "conv1_wgrad": 20.93,
-                                 "conv2_wgrad": 23.34}, "7bd7bdb49d32801f"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.33, "heads_act": 5.50, "conv2_fwd": 3.86, "conv3_fwd": 3.51,
+                                    "fc_fwd": 3.23, "conv1_fwd_learn": 100.97, "conv1_wgrad": 107.66}, "72dd184d9e7b140b"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 4.91, "heads_act": 5.35, "conv1_fwd_learn": 22.98, "conv1_wgrad": 20.71,
+                                 "conv2_wgrad": 23.52}, "72dd184d9e7b140b"),
 }
 
 
