@@ -422,7 +422,7 @@ def main():
         kernels[k] = e
     out["kernels"] = kernels
     if not args.site and not args.no_others:
-        ov = OverlapLoop(loop)
+        ov = OverlapLoop(loop, actor_cus=cfg.get("overlap_actor_cus"))
         ov_steps = max(1, args.steps // 2)
         for _ in range(2):
             ov.step()
@@ -437,9 +437,9 @@ def main():
                              "schedule": "rollout with theta_j on one stream while the learner works on the previous "
                                          "storage on a second stream (one update per storage: the one-step-delayed "
                                          "update; several: ordinary epochs from theta_j); same work per step as "
-                                         "`value`, which runs the three parts in sequence"}
-        ov.ctx_act.close()
-        ov.ctx_learn.close()
+                                         "`value`, which runs the three parts in sequence",
+                             "actor_compute_units": cfg.get("overlap_actor_cus") or "all (shared with the learner)"}
+        ov.close()
         del ov
     if not args.no_cpu_baseline:
         import oracle

@@ -229,6 +229,19 @@ int32_t     hts_profile_end(hts_ctx *ctx, int32_t *launches, double *total_ms);
  * the timer itself contributes.  Ends any open profiling window. */
 int32_t     hts_profile_overhead(hts_ctx *ctx, int32_t reps, double *mean_ms);
 
+/* A stream whose kernels run on the compute units [first_cu, first_cu + n_cus) only (numbered 0 .. the device's count - 1
+ * in the order of the runtime's compute-unit mask), for the concurrent schedule of Sec. 4.1 "Concurrent rollout and
+ * learning": the actors' calls on one such stream and the learner's on another, over disjoint ranges, do not wait for each
+ * other's workgroups to leave a compute unit.  Results never depend on where a kernel runs.  Default priority.  Every such
+ * stream takes one of the process's few hardware queues until hts_stream_destroy.
+ *   hip_stream_out   receives a hipStream_t of the current device
+ * HTS_EINVAL for a null pointer or a range that is empty or leaves the device; HTS_EHIP if the runtime refuses (on a
+ * device of several dies the mask's bits go to the dies in turn and every die must keep a compute unit: ranges whose
+ * bounds are multiples of the number of dies, 8 on MI355X, are always accepted). */
+int32_t     hts_stream_create_cu_range(int32_t first_cu, int32_t n_cus, void **hip_stream_out);
+/* Waits for the stream's work and destroys it (streams made by hts_stream_create_cu_range only). */
+int32_t     hts_stream_destroy(void *hip_stream);
+
 int32_t     hts_last_hip_error(void);
 const char *hts_strerror(int32_t code);
 

@@ -16,7 +16,8 @@ OPT_ADAM, OPT_RMSPROP = 0, 1
 EXPORTS = ["hts_param_count", "hts_create", "hts_destroy", "hts_act", "hts_sync_params", "hts_sample_from_logits", "hts_returns_gae",
            "hts_normalize_advantages", "hts_learner_step", "hts_learner_step_delayed", "hts_loss_and_grads", "hts_adam_apply", "hts_test_gemm",
            "hts_last_hip_error", "hts_strerror", "hts_profile_site_count", "hts_profile_site_name", "hts_profile_begin",
-           "hts_profile_end", "hts_profile_overhead", "hts_profile_begin_sampled", "hts_adam_apply_static", "hts_track_params"]
+           "hts_profile_end", "hts_profile_overhead", "hts_profile_begin_sampled", "hts_adam_apply_static", "hts_track_params",
+           "hts_stream_create_cu_range", "hts_stream_destroy"]
 
 
 class HtsError(RuntimeError):
@@ -100,6 +101,8 @@ def load_library():
         lib.hts_profile_begin_sampled.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         lib.hts_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         lib.hts_profile_overhead.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]
+        lib.hts_stream_create_cu_range.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        lib.hts_stream_destroy.argtypes = [C.c_void_p]
         _lib = lib
     return _lib
 
@@ -135,6 +138,23 @@ def hts_adam_apply_static(params, grads, opt: OptState, hp: HParams, stream=None
                                      C.byref(oc), C.byref(hp), params.numel(), C.c_void_p(stream.cuda_stream)),
            "hts_adam_apply_static")
     opt.step = oc.step
+
+
+class CuRangeStream:
+    """hts_stream_create_cu_range: a stream whose kernels run on compute units [first_cu, first_cu + n_cus) only, wrapped
+    as a torch stream (`.stream`).  close() synchronises and destroys it."""
+
+    def __init__(self, first_cu: int, n_cus: int):
+        lib = load_library()
+        h = C.c_void_p()
+        _check(lib.hts_stream_create_cu_range(first_cu, n_cus, C.byref(h)), "hts_stream_create_cu_range")
+        self._h = h
+        self.stream = torch.cuda.ExternalStream(h.value)
+
+    def close(self):
+        if self._h is not None and self._h.value:
+            _check(load_library().hts_stream_destroy(self._h), "hts_stream_destroy")
+            self._h = None
 
 
 class Context:

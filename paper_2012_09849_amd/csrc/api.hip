@@ -190,6 +190,30 @@ extern "C" int32_t hts_sync_params(hts_ctx *ctx, const float *params)
     return HTS_OK;
 }
 
+extern "C" int32_t hts_stream_create_cu_range(int32_t first_cu, int32_t n_cus, void **hip_stream_out)
+{
+    if (!hip_stream_out || first_cu < 0 || n_cus <= 0) return HTS_EINVAL;
+    int dev = 0, cus = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (first_cu > cus - n_cus) return HTS_EINVAL;
+    uint32_t mask[32] = {};                                    // one bit per compute unit, up to 1024 of them
+    if (cus > 1024) return HTS_ESHAPE;
+    for (int i = first_cu; i < first_cu + n_cus; ++i) mask[i >> 5] |= 1u << (i & 31);
+    hipStream_t s = nullptr;
+    HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)((cus + 31) / 32), mask));
+    *hip_stream_out = (void *)s;
+    return HTS_OK;
+}
+
+extern "C" int32_t hts_stream_destroy(void *hip_stream)
+{
+    if (!hip_stream) return HTS_EINVAL;
+    HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+    HIP_TRY(hipStreamDestroy((hipStream_t)hip_stream));
+    return HTS_OK;
+}
+
 extern "C" int32_t hts_track_params(hts_ctx *ctx, int32_t on)
 {
     if (!ctx || (on != 0 && on != 1)) return HTS_EINVAL;

@@ -19,7 +19,7 @@ CONFIGS = {
     # Football-shaped PPO: 16x72x96 extracted-map stacks, 16 environments, unroll 512, 2 epochs x 4 minibatches of 2048
     "football_ppo_n16_t512_bf16": dict(C=16, H=72, W=96, A=19, N=16, T=512, precision=1, algo=1, gamma=0.993,
                                        lam=0.95, lr=3.4e-4, epochs=2, minibatches=4, clip=0.08, max_norm=0.0,
-                                       ent=0.003, obs="football"),
+                                       ent=0.003, obs="football", overlap_actor_cus=192),
     # the paper's multi-agent football experiment controls three players per environment: every controlled player is
     # one row of every call (16 environments x 3 players = 48 rows per step), unroll 128 as in the paper's runs
     "football_multiagent_ppo_n16x3_t128_bf16": dict(C=16, H=72, W=96, A=19, N=48, T=128, precision=1, algo=1,
@@ -120,12 +120,22 @@ class OverlapLoop:
     single gradient step only; here the learner runs its ordinary epochs on storage j-1 starting from theta_j, the
     stored behaviour log-probabilities (of theta_{j-1}) entering through PPO's own probability ratio."""
 
-    def __init__(self, base, learner_after=8):
+    def __init__(self, base, learner_after=8, actor_cus=None):
         torch, hts, cfg = base.torch, base.hts, base.cfg
         self.base, self.cfg, self.torch = base, cfg, torch
         self.learner_after = learner_after          # actor calls issued before the learner's calls (see step)
         N, T = cfg["N"], cfg["T"]
-        self.s_roll, self.s_learn = torch.cuda.Stream(), torch.cuda.Stream()
+        # actor_cus: the actors' stream is confined to the first `actor_cus` compute units and the learner's to the
+        # rest.  It pays where the two sides' workgroups each want a whole compute unit's LDS (16x72x96 frames: the actor's
+        # conv1 and the learner's conv1 kernels), so that on shared compute units every actor call waits for a learner
+        # workgroup to leave; it costs where they interleave well anyway (4x84x84 frames).  Results do not depend on it.
+        self._masked = []
+        if actor_cus:
+            total = torch.cuda.get_device_properties(torch.cuda.current_device()).multi_processor_count
+            self._masked = [hts.CuRangeStream(0, actor_cus), hts.CuRangeStream(actor_cus, total - actor_cus)]
+            self.s_roll, self.s_learn = self._masked[0].stream, self._masked[1].stream
+        else:
+            self.s_roll, self.s_learn = torch.cuda.Stream(), torch.cuda.Stream()
         mk = lambda **kw: hts.Context(cfg["C"], cfg["H"], cfg["W"], cfg["A"], precision=cfg["precision"], **kw)
         self.ctx_act = mk(max_act_batch=N, stream=self.s_roll)
         self.ctx_learn = mk(max_learn_batch=base.B, stream=self.s_learn)
@@ -177,3 +187,12 @@ class OverlapLoop:
         self.s_learn.wait_event(self.ev_roll)
         self.theta = [cur, nxt, prev]
         self.j += 1
+
+    def close(self):
+        """Ends the two contexts and gives back the hardware queues of compute-unit-confined streams."""
+        self.torch.cuda.synchronize()
+        self.ctx_act.close()
+        self.ctx_learn.close()
+        for m in self._masked:
+            m.close()
+        self._masked = []

@@ -103,3 +103,45 @@ def test_overlapped_ppo_schedule_equals_serial_schedule():
     assert opt.step == (iters - 1) * 4 and ov.opt.step == opt.step
     assert not torch.equal(theta[1], base.params)
     ctx.close()
+
+
+def test_compute_unit_ranges_do_not_change_results():
+    """The concurrent schedule with the actors' and the learner's streams confined to disjoint ranges of compute units
+    (hts_stream_create_cu_range) gives the same bits as with ordinary streams: where a kernel runs never enters what it
+    computes.  Football-shaped frames, a few steps of a short unroll."""
+    import paper_2012_09849_amd as hts
+    from paper_2012_09849_amd import schedule
+    cfg = dict(schedule.CONFIGS["football_ppo_n16_t512_bf16"], N=16, T=6, epochs=1, minibatches=2)
+    outs = []
+    for cus in (None, 192, 64):
+        base = schedule.Loop(cfg, hts, torch, syn)
+        ov = schedule.OverlapLoop(base, actor_cus=cus)
+        for _ in range(3):
+            ov.step()
+        torch.cuda.synchronize()
+        outs.append(([t.clone() for t in ov.theta], [s["actions"].clone() for s in ov.store]))
+        ov.close()
+        base.ctx.close()
+    for theta, actions in outs[1:]:
+        assert all(torch.equal(a, b) for a, b in zip(theta, outs[0][0]))
+        assert all(torch.equal(a, b) for a, b in zip(actions, outs[0][1]))
+    assert not torch.equal(outs[0][0][1], outs[0][0][0])
+
+
+def test_compute_unit_range_stream_errors():
+    import ctypes as C
+    import paper_2012_09849_amd as hts
+    lib = hts.load_library()
+    h = C.c_void_p()
+    total = torch.cuda.get_device_properties(0).multi_processor_count
+    assert lib.hts_stream_create_cu_range(0, 0, C.byref(h)) == -1            # HTS_EINVAL: empty range
+    assert lib.hts_stream_create_cu_range(-1, 4, C.byref(h)) == -1
+    assert lib.hts_stream_create_cu_range(total - 3, 4, C.byref(h)) == -1    # leaves the device
+    assert lib.hts_stream_create_cu_range(0, 4, None) == -1
+    assert lib.hts_stream_destroy(None) == -1
+    s = hts.CuRangeStream(total - 8, 8)                                      # the last eight compute units (one per die): fine
+    x = torch.zeros(1024, device="cuda")
+    with torch.cuda.stream(s.stream):
+        x += 1.0
+    s.close()
+    assert float(x.sum()) == 1024.0
