@@ -424,7 +424,13 @@ def main():
         kernels[k] = e
     out["kernels"] = kernels
     if not args.site and not args.no_others:
-        ov = OverlapLoop(loop, actor_cus=cfg.get("overlap_actor_cus"))
+        actor_cus = cfg.get("overlap_actor_cus")
+        try:
+            ov = OverlapLoop(loop, actor_cus=actor_cus)
+        except hts.HtsError as err:                    # e.g. a device with another number of compute units
+            progress(f"compute-unit ranges refused ({err}); concurrent schedule on ordinary streams")
+            actor_cus = None
+            ov = OverlapLoop(loop)
         ov_steps = max(1, args.steps // 2)
         for _ in range(2):
             ov.step()
@@ -440,7 +446,7 @@ def main():
                                          "storage on a second stream (one update per storage: the one-step-delayed "
                                          "update; several: ordinary epochs from theta_j); same work per step as "
                                          "`value`, which runs the three parts in sequence",
-                             "actor_compute_units": cfg.get("overlap_actor_cus") or "all (shared with the learner)"}
+                             "actor_compute_units": actor_cus or "all (shared with the learner)"}
         ov.close()
         del ov
     if not args.no_cpu_baseline:
