@@ -193,6 +193,25 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
+// max over the 64 lanes, in every lane (exact whatever the order).  Row shifts inside each row of 16 lanes, then the
+// two row broadcasts: six dependent steps instead of one lane read and one comparison per lane.
+__device__ __forceinline__ float wave_max(float x)
+{
+    auto step = [](float v, auto ctrl, auto row_mask) {
+        const int moved = __builtin_amdgcn_update_dpp(__float_as_int(-INFINITY), __float_as_int(v), decltype(ctrl)::value,
+                                                      decltype(row_mask)::value, 0xF, false);
+        return fmaxf(v, __int_as_float(moved));
+    };
+    using std::integral_constant;
+    x = step(x, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});     // row_shr:1
+    x = step(x, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});     // row_shr:2
+    x = step(x, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});     // row_shr:4
+    x = step(x, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});     // row_shr:8: lane 15 of a row holds the row's max
+    x = step(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});     // row_bcast:15 into rows 1 and 3
+    x = step(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});     // row_bcast:31 into rows 2 and 3: lane 63 holds the max
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
 // value of x in lane `src`; src must be the same in every lane (it is read into a scalar register)
 __device__ __forceinline__ float lane_value(float x, int src)
 {
@@ -319,38 +338,27 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
         if (lane < A) mylogit = tot + head_bias;
     }
 
-    // A wavefront runs alone on its SIMD here, so every dependent instruction costs its full latency: the loops over
-    // the actions go eight at a time without branches (lanes >= A hold neutral values: -inf for the maximum, +0 for the
-    // sums), the lane reads of a group are issued together, and the loop that finds the action is folded into the one
-    // that forms the sums (phase stamps: 2.2 of the kernel's 5 us were spent in these loops).
-    const int A8 = (A + 7) & ~7;
+    // A wavefront runs alone on its SIMD here, so every dependent instruction costs its full latency, and the steps over
+    // the actions are kept to one instruction each: the maximum by lane shifts (six steps), the running sums by a shift
+    // and an add per action; lanes >= A hold neutral values (-inf for the maximum, +0 for the sums).  (Phase stamps:
+    // with one lane read and two or three instructions per action 2.3 of the kernel's 9.6 thousand clock ticks were
+    // spent here.)
     const float lg = lane < A ? mylogit : -INFINITY;
-    float m = -INFINITY;
-    for (int j0 = 0; j0 < A8; j0 += 8) {
-        float s8[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) s8[t] = lane_value(lg, j0 + t);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) m = fmaxf(m, s8[t]);
-    }
+    const float m = wave_max(lg);
 
     if constexpr (!LEARN) {
         // binary32 inverse CDF: lane j evaluates e_j once; the running sums c_j are formed sequentially in index order
-        // from those values (read lane by lane), identically in every lane; lane j keeps c_j, and the action is the
+        // along the lanes; lane j keeps c_j, and the action is the
         // first j with c_j > u * c_{A-1} (A-1 if there is none)
+        // (c_j = c_{j-1} + e_j along the lanes: every step each lane takes its left neighbour's value -- lane 0 takes
+        // +0 -- and adds its own e_j.  After k steps lanes 0..k hold their c_j and keep it, so A - 1 steps of one
+        // instruction give every lane its running sum in index order; lane reads into scalar registers cost three
+        // instructions per action.)
         const float ej = lane < A ? sampler_exp(mylogit - m) : 0.0f;
-        float run = 0.0f, mine = 0.0f;
-        for (int j0 = 0; j0 < A8; j0 += 8) {
-            float s8[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) s8[t] = lane_value(ej, j0 + t);
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                run = run + s8[t];
-                mine = lane == j0 + t ? run : mine;
-            }
-        }
-        const float total = run;
+        float mine = ej;
+        for (int k = 1; k < A; ++k)
+            mine = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mine), 0x138 /* wave_shr:1 */, 0xF, 0xF, true)) + ej;
+        const float total = lane_value(mine, A - 1);
         const float thr = u01 * total;
         const unsigned long long above = __ballot(lane < A && mine > thr);
         const int act = above ? __ffsll((long long)above) - 1 : A - 1;
