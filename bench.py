@@ -180,20 +180,20 @@ def source_digest():
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
 TRAFFIC = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5097010, "conv1_fwd_learn": 279635616, "conv1_wgrad": 317483871,
-                                    "conv2_fwd": 2626306, "conv3_fwd": 1214351, "fc_fwd": 3475117}, "f6622cf35cf5b400"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846563, "conv1_fwd_learn": 56934411, "conv1_wgrad": 63789711,
-                                 "conv2_wgrad": 45566210}, "f6622cf35cf5b400"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5097045, "conv1_fwd_learn": 279652720, "conv1_wgrad": 316660884,
+                                    "conv2_fwd": 2626324, "conv3_fwd": 1214359, "fc_fwd": 3475141}, "d14b7b604ac47710"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846578, "conv1_fwd_learn": 56940120, "conv1_wgrad": 63790109,
+                                 "conv2_wgrad": 45564437}, "d14b7b604ac47710"),
 }
 
 
 # Average duration (us) of the same launch sites' kernels in the committed rocprofv3 kernel traces
 # (profiles/all_kernels_<workload>.txt), for comparison with the live event figure; same digest rule as TRAFFIC.
 TRACE_AVG_US = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.33, "heads_act": 5.50, "conv2_fwd": 3.86, "conv3_fwd": 3.51,
-                                    "fc_fwd": 3.23, "conv1_fwd_learn": 100.97, "conv1_wgrad": 107.66}, "f6622cf35cf5b400"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 4.91, "heads_act": 5.35, "conv1_fwd_learn": 22.98, "conv1_wgrad": 20.71,
-                                 "conv2_wgrad": 23.52}, "f6622cf35cf5b400"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.15, "heads_act": 5.00, "conv2_fwd": 4.02, "conv3_fwd": 3.50,
+                                    "fc_fwd": 3.15, "conv1_fwd_learn": 100.91, "conv1_wgrad": 108.00}, "d14b7b604ac47710"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.03, "heads_act": 5.07, "conv1_fwd_learn": 22.82, "conv1_wgrad": 20.44,
+                                 "conv2_wgrad": 23.36}, "d14b7b604ac47710"),
 }
 
 
