@@ -586,7 +586,7 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
                 ImgConvArgs a = {};
                 a.in = (const bf16_t *)c.ws.dy3; a.w = (const bf16_t *)c.ws.wd3; a.mask = (const bf16_t *)c.ws.act2;
                 a.out = (bf16_t *)c.ws.dy2; a.B = B;
-                e = launch_imgconv<ImgDgrad<64, 3, 1, 7, 10, 7>>(a, c.stream);
+                e = launch_imgconv<ImgDgrad<64, 3, 1, 7, 10, 8>>(a, c.stream);
             } else
             // binary32: eight segments of 72 for eight wavefronts, both operands through LDS: a lane that fetches its own
             // weight column touches 32 cache lines per load instruction, and with sixteen wavefronts on a compute unit

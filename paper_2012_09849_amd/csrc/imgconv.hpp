@@ -77,12 +77,15 @@ template <class S> constexpr int imgconv_tiles(int cls)            // 32-row til
     for (int c = 0; c < cls; ++c) t += (S::G * S::cls_h(c) * S::cls_w(c) + 31) / 32;
     return t;
 }
+// elements of the LDS copy of a group's channel-major output (forward pass with FLAT), else 0
+template <class S> constexpr size_t imgconv_stage_elems() { return S::FWD && S::FLAT ? (size_t)S::G * S::NCOL * S::POUT_ALL : 0; }
 template <class S> constexpr size_t imgconv_lds_bytes()
 {
-    return ((size_t)S::NCLS * S::NCOL * (S::TAPS * S::CIN + 8) + (size_t)(S::G * S::PIN + 1) * (S::CIN + 8)) * sizeof(bf16_t);
+    return ((size_t)S::NCLS * S::NCOL * (S::TAPS * S::CIN + 8) + (size_t)(S::G * S::PIN + 1) * (S::CIN + 8) + imgconv_stage_elems<S>()) * sizeof(bf16_t)
+           + (S::FWD ? S::NCOL * sizeof(float) : 0);          // the biases
 }
 
-constexpr int IMGCONV_THREADS = 512;
+constexpr int IMGCONV_THREADS = 512;     // (16 wavefronts on the 32-column input gradient's short tiles: no faster, measured)
 
 template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void imgconv_kernel(const ImgConvArgs a)
 {
@@ -95,20 +98,29 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) __attribute__((
     extern __shared__ __attribute__((aligned(16))) unsigned char ic_smem[];
     bf16_t *wl = reinterpret_cast<bf16_t *>(ic_smem);                // [NCLS][NCOL][WP]
     bf16_t *inl = wl + NCLS * NCOL * WP;                             // [G*PIN + 1][IP]
+    bf16_t *stg = inl + (G * PIN + 1) * IP;                          // FLAT: [G][NCOL][POUT_ALL], the group's output as it lies in memory
+    float *biasl = reinterpret_cast<float *>(stg + imgconv_stage_elems<S>());   // forward: [NCOL]
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lrow = lane & 31, kg = lane >> 5;
 
-    // the weight matrix, class by class (a class keeps the taps that reach it, in tap order)
-    constexpr int WV = NCLS * NCOL * TAPS * (CIN / 8);
-    for (int v = tid; v < WV; v += NT) {
+    // The weight matrix, class by class (a class keeps the taps that reach it, in tap order).  All of it is requested
+    // before anything is waited for, and the first group of samples right behind it: one memory round trip, not two.
+    constexpr int WV = NCLS * NCOL * TAPS * (CIN / 8), NWPF = (WV + NT - 1) / NT;
+    bf16x8 wpf[NWPF];
+    auto wslot = [&](int v, int *lds_off) {                          // source offset in a.w; LDS offset in wl
         const int c8 = v % (CIN / 8);
         int t = v / (CIN / 8);
         const int tap = t % TAPS;
         t /= TAPS;
         const int col = t % NCOL, cls = t / NCOL;
-        *reinterpret_cast<bf16x8 *>(wl + (cls * NCOL + col) * WP + tap * CIN + c8 * 8) =
-            *reinterpret_cast<const bf16x8 *>(a.w + (long long)col * S::KTOT + S::src_tap(cls, tap) * CIN + c8 * 8);
+        *lds_off = (cls * NCOL + col) * WP + tap * CIN + c8 * 8;
+        return col * S::KTOT + S::src_tap(cls, tap) * CIN + c8 * 8;
+    };
+#pragma unroll
+    for (int i = 0; i < NWPF; ++i) {
+        const int v = tid + i * NT;
+        int lo;
+        if (v < WV) wpf[i] = *reinterpret_cast<const bf16x8 *>(a.w + wslot(v, &lo));
     }
-    if (tid < CIN / 8) *reinterpret_cast<bf16x8 *>(inl + ZR * IP + tid * 8) = zero_vec<bf16_t, 8>();
 
     bf16x8 pf[NPF];
     const long long in_elems = (long long)a.B * PIN * CIN;
@@ -122,6 +134,14 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) __attribute__((
     };
     const int ngroups = (a.B + G - 1) / G;
     if ((int)blockIdx.x < ngroups) fetch(blockIdx.x);
+#pragma unroll
+    for (int i = 0; i < NWPF; ++i) {
+        const int v = tid + i * NT;
+        int lo;
+        if (v < WV) { wslot(v, &lo); *reinterpret_cast<bf16x8 *>(wl + lo) = wpf[i]; }
+    }
+    if (tid < CIN / 8) *reinterpret_cast<bf16x8 *>(inl + ZR * IP + tid * 8) = zero_vec<bf16_t, 8>();
+    if constexpr (S::FWD) { if (tid >= NT - NCOL) biasl[tid - (NT - NCOL)] = a.bias[tid - (NT - NCOL)]; }   // (an epilogue that fetched them would wait a memory round trip)
 
     for (int grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
 #pragma unroll
@@ -152,14 +172,15 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) __attribute__((
             // What the epilogue needs from memory (the ReLU masks of the input gradient) is requested now, so that it
             // travels while the products are formed: fetched after them, every tile would end with a bare memory
             // round trip.
-            const long long o = (b * S::POUT_ALL + S::out_pos(CLS, yy, xx)) * NCOL + 4 * kg;
-            Vec<bf16_t, 4> mk[TN][4];
+            // (a lane reads and writes 16 consecutive channels of each 32, see the epilogue)
+            const long long o = (b * S::POUT_ALL + S::out_pos(CLS, yy, xx)) * NCOL + 16 * kg;
+            bf16x8 mk[TN][2];
             if constexpr (!S::FWD) {
                 if (store_row) {
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) mk[j][q] = *reinterpret_cast<const Vec<bf16_t, 4> *>(a.mask + o + j * 32 + 8 * q);
+                        for (int h = 0; h < 2; ++h) mk[j][h] = *reinterpret_cast<const bf16x8 *>(a.mask + o + j * 32 + 8 * h);
                 }
             }
             f32x16 acc[TN];
@@ -239,33 +260,65 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) __attribute__((
             }
             if (!store_row) return;
             // register 4q+e of accumulator j is column j*32 + 8q + 4kg + e
+            // The two lanes of a row hold alternate groups of four columns.  They trade halves so that one has columns
+            // 0-15 and the other 16-31 of each 32: two 16-byte stores (and mask loads) per lane and 32 columns instead
+            // of four 8-byte ones -- half the cache-line visits of these memory-bound passes.
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            auto trade = [&](const u32x2 (&pk)[4], int h) {                    // columns 16 kg + 8 h .. + 7 of the 32
+                const u32x2 mine = kg ? pk[2 + h] : pk[h], send = kg ? pk[h] : pk[2 + h];
+                u32x2 got;
+                got.x = __shfl_xor(send.x, 32, 64);
+                got.y = __shfl_xor(send.y, 32, 64);
+                const u32x4 v = kg ? u32x4{got.x, got.y, mine.x, mine.y} : u32x4{mine.x, mine.y, got.x, got.y};
+                return __builtin_bit_cast(bf16x8, v);
+            };
             if constexpr (S::FWD) {
                 const long long m = b * S::POUT_ALL + p;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j) {
+                    u32x2 pk[4];
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int ch = j * 32 + 8 * q + 4 * kg;
-                        const f32x4 bn = *reinterpret_cast<const f32x4 *>(a.bias + ch);
+                        const f32x4 bn = *reinterpret_cast<const f32x4 *>(biasl + ch);
                         Vec<bf16_t, 4> y;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) { const float tv = acc[j][4 * q + e] + bn[e]; y[e] = from_f32<bf16_t>(tv > 0.0f ? tv : 0.0f); }
                         if constexpr (S::FLAT) {
+                            // channel-major: a lane's 32 values lie POUT_ALL apart, so they go to the LDS copy of the
+                            // group's output and leave from there in whole vectors (two-byte stores to memory, 32
+                            // instructions per tile, were a third of this kernel's time)
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) a.out[(b * NCOL + ch + e) * S::POUT_ALL + p] = y[e];
-                            if (a.out2) *reinterpret_cast<Vec<bf16_t, 4> *>(a.out2 + m * NCOL + ch) = y;
-                        } else *reinterpret_cast<Vec<bf16_t, 4> *>(a.out + m * NCOL + ch) = y;
+                            for (int e = 0; e < 4; ++e) stg[(g * NCOL + ch + e) * S::POUT_ALL + p] = y[e];
+                        }
+                        pk[q] = __builtin_bit_cast(u32x2, y);
                     }
+                    bf16_t *rowmajor = S::FLAT ? a.out2 : a.out;               // [row][NCOL]
+                    if (rowmajor) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) *reinterpret_cast<bf16x8 *>(rowmajor + m * NCOL + j * 32 + 16 * kg + 8 * h) = trade(pk, h);
+                    }
+                }
             } else {
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j) {
+                    u32x2 pk[4];
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         Vec<bf16_t, 4> y;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) y[e] = from_f32<bf16_t>(to_f32(mk[j][q][e]) > 0.0f ? acc[j][4 * q + e] : 0.0f);
-                        *reinterpret_cast<Vec<bf16_t, 4> *>(a.out + o + j * 32 + 8 * q) = y;
+                        for (int e = 0; e < 4; ++e) y[e] = from_f32<bf16_t>(acc[j][4 * q + e]);
+                        pk[q] = __builtin_bit_cast(u32x2, y);
                     }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        bf16x8 y = trade(pk, h);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) y[i] = to_f32(mk[j][h][i]) > 0.0f ? y[i] : from_f32<bf16_t>(0.0f);
+                        *reinterpret_cast<bf16x8 *>(a.out + o + j * 32 + 8 * h) = y;
+                    }
+                }
             }
         };
         for (int tile = w; tile < TILES; tile += NWV) {                       // `tile` is the same in all lanes of a wavefront
@@ -278,6 +331,13 @@ template <class S> __global__ __launch_bounds__(IMGCONV_THREADS) __attribute__((
             }
         }
         __syncthreads();          // the resident rows are overwritten by the next group
+        if constexpr (S::FWD && S::FLAT) {
+            // (the next group's tiles write the copy only after the barrier that follows its rows' arrival)
+            constexpr int PER = NCOL * S::POUT_ALL;
+            static_assert(PER % 8 == 0, "whole vectors per sample");
+            bf16_t *dst = a.out + (long long)grp * G * PER;
+            for (int v = tid; v < ng * (PER / 8); v += NT) *reinterpret_cast<bf16x8 *>(dst + v * 8) = *reinterpret_cast<const bf16x8 *>(stg + v * 8);
+        }
     }
 }
 
