@@ -180,20 +180,20 @@ def source_digest():
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
 TRAFFIC = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5097045, "conv1_fwd_learn": 279652720, "conv1_wgrad": 316660884,
-                                    "conv2_fwd": 2626324, "conv3_fwd": 1214359, "fc_fwd": 3475141}, "d14b7b604ac47710"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846578, "conv1_fwd_learn": 56940120, "conv1_wgrad": 63790109,
-                                 "conv2_wgrad": 45564437}, "d14b7b604ac47710"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099061, "conv1_fwd_learn": 279606599, "conv1_wgrad": 315751971,
+                                    "conv2_fwd": 2626308, "conv3_fwd": 1214352, "fc_fwd": 3475120}, "f9feff286a216c71"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2839394, "conv1_fwd_learn": 56940716, "conv1_wgrad": 63789745,
+                                 "conv2_wgrad": 45557904}, "f9feff286a216c71"),
 }
 
 
 # Average duration (us) of the same launch sites' kernels in the committed rocprofv3 kernel traces
 # (profiles/all_kernels_<workload>.txt), for comparison with the live event figure; same digest rule as TRAFFIC.
 TRACE_AVG_US = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.15, "heads_act": 5.00, "conv2_fwd": 4.02, "conv3_fwd": 3.50,
-                                    "fc_fwd": 3.15, "conv1_fwd_learn": 100.91, "conv1_wgrad": 108.00}, "d14b7b604ac47710"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.03, "heads_act": 5.07, "conv1_fwd_learn": 22.82, "conv1_wgrad": 20.44,
-                                 "conv2_wgrad": 23.36}, "d14b7b604ac47710"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.19, "heads_act": 5.13, "conv2_fwd": 3.78, "conv3_fwd": 3.51,
+                                    "fc_fwd": 3.22, "conv1_fwd_learn": 100.06, "conv1_wgrad": 107.20}, "f9feff286a216c71"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 4.94, "heads_act": 5.19, "conv1_fwd_learn": 22.86, "conv1_wgrad": 20.38,
+                                 "conv2_wgrad": 23.26}, "f9feff286a216c71"),
 }
 
 
