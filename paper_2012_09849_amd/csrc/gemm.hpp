@@ -198,6 +198,10 @@ template <class P> struct HasRunB<P, std::void_t<decltype(&P::load_b_run)>> : st
 // Optional batching: a problem with `int batches() const`, `int max_m() const`, `int batch_m(int z) const` is
 // launched with gridDim.z = batches(); batch z has batch_m(z) rows and its own gathers: ctx_a(row, z),
 // ctx_b(col, z) and store(m, n, acc, split, z) receive the batch index (the problem object stays read-only).
+// Optional tile order (see the kernel): N slowest instead of M slowest.
+template <class P, class = void> struct TilesAlongM : std::false_type {};
+template <class P> struct TilesAlongM<P, std::void_t<decltype(P::TILES_ALONG_M)>> : std::integral_constant<bool, P::TILES_ALONG_M> {};
+
 template <class P, class = void> struct HasBatch : std::false_type {};
 template <class P> struct HasBatch<P, std::void_t<decltype(std::declval<const P &>().batches())>> : std::true_type {};
 template <class P> inline int grid_rows(const P &p)
@@ -330,9 +334,26 @@ __global__ __launch_bounds__(P::WAVES_M * P::WAVES_N * 64) void gemm_kernel(cons
             z = (slot / tiles) * 8 + xcd;
             tile = slot % tiles;
             if ((long long)z * p.klen >= p.K) return;        // padding of the last round of eight chunks
+        } else {
+            // Otherwise gridDim.x is the number of tiles rounded up to a multiple of 8, and XCD x takes the x-th
+            // eighth of the tile order: neighbouring tiles share an operand panel, and a panel that is needed on one
+            // XCD only is fetched into one L2 only.  (Round-robin, every XCD read the whole of the operand that the
+            // tile order walks slowest: the FC forward pass fetched its activations eight times, 107 MB for 34.)
+            // (A single column of tiles shares nothing but the small weight panel and keeps the round-robin order.)
+            const int tiles = ((M + BM - 1) / BM) * tiles_n, per_xcd = gridDim.x >> 3;
+            if (tiles_n > 1) tile = (tile & 7) * per_xcd + (tile >> 3);
+            if (tile >= tiles) return;
         }
     }
-    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+    // the tile order walks N fastest, so an XCD's share is a range of rows and all columns; a problem whose column
+    // operand is the larger one asks for the transposed order (`static constexpr bool TILES_ALONG_M = true`)
+    int m0, n0;
+    if constexpr (TilesAlongM<P>::value) {
+        const int tiles_m = (M + BM - 1) / BM;
+        m0 = (tile % tiles_m) * BM; n0 = (tile / tiles_m) * BN;
+    } else {
+        m0 = (tile / tiles_n) * BM; n0 = (tile % tiles_n) * BN;
+    }
     if (m0 >= M) return;                   // a batch smaller than the largest one: the whole workgroup leaves
     const int kbeg = z * p.klen;
     const int kend = min(p.K, kbeg + p.klen);
@@ -683,6 +704,7 @@ template <class P> inline hipError_t launch_gemm(const P &p, hipStream_t stream)
     dim3 grid(tiles, nz, grid_batches(p));
     if constexpr (!HasBatch<P>::value) {
         if (nz >= 32) grid = dim3(((nz + 7) / 8) * 8 * tiles, 1, 1);      // XCD-aware order, decoded in the kernel
+        else grid.x = ((tiles + 7) / 8) * 8;                              // likewise: an eighth of the tiles per XCD
     }
     hipLaunchKernelGGL(gemm_kernel<P>, grid, dim3(P::WAVES_M * P::WAVES_N * 64, 1, 1), 0, stream, p);
     return hipGetLastError();

@@ -263,6 +263,7 @@ template <typename T_> struct FcWgrad {
     static constexpr int VA = 4, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
     static constexpr bool NATURAL_LDS = true;
+    static constexpr bool TILES_ALONG_M = true;      // the activations (N side, B x F) outweigh dh (M side, B x 512): an XCD takes a range of columns
     struct CtxA { int j; };
     struct CtxB { int f; };
     int M, N, K, klen;     // M = 512, N = F+1, K = B
