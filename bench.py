@@ -180,20 +180,20 @@ def source_digest():
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
 TRAFFIC = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099061, "conv1_fwd_learn": 279606599, "conv1_wgrad": 315751971,
-                                    "conv2_fwd": 2626308, "conv3_fwd": 1214352, "fc_fwd": 3475120}, "f9feff286a216c71"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2839394, "conv1_fwd_learn": 56940716, "conv1_wgrad": 63789745,
-                                 "conv2_wgrad": 45557904}, "f9feff286a216c71"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099092, "conv1_fwd_learn": 279605674, "conv1_wgrad": 315760426,
+                                    "conv2_fwd": 2626323, "conv3_fwd": 1214359, "fc_fwd": 3474117}, "78daff3a998827d0"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2839409, "conv1_fwd_learn": 56939720, "conv1_wgrad": 63790101,
+                                 "conv2_wgrad": 45558770}, "78daff3a998827d0"),
 }
 
 
 # Average duration (us) of the same launch sites' kernels in the committed rocprofv3 kernel traces
 # (profiles/all_kernels_<workload>.txt), for comparison with the live event figure; same digest rule as TRAFFIC.
 TRACE_AVG_US = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.19, "heads_act": 5.13, "conv2_fwd": 3.78, "conv3_fwd": 3.51,
-                                    "fc_fwd": 3.22, "conv1_fwd_learn": 100.06, "conv1_wgrad": 107.20}, "f9feff286a216c71"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 4.94, "heads_act": 5.19, "conv1_fwd_learn": 22.86, "conv1_wgrad": 20.38,
-                                 "conv2_wgrad": 23.26}, "f9feff286a216c71"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.22, "heads_act": 5.18, "conv2_fwd": 3.83, "conv3_fwd": 3.50,
+                                    "fc_fwd": 3.21, "conv1_fwd_learn": 100.39, "conv1_wgrad": 107.63}, "78daff3a998827d0"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 4.93, "heads_act": 5.20, "conv1_fwd_learn": 22.94, "conv1_wgrad": 20.66,
+                                 "conv2_wgrad": 23.27}, "78daff3a998827d0"),
 }
 
 
