@@ -246,8 +246,8 @@ static hipError_t launch_conv1_wgrad_image(Ctx &c, const uint8_t *obs, const int
 // 4..7 of the 8x8 window) that share the gradient operand.  In the kernel above every wavefront does both jobs in
 // turn, so the compute unit alternates between a conversion phase and a multiply phase (2048 frames: 118 us there).
 // One barrier per slab, one more per sample (the gradient rows in LDS are replaced between two samples).
-// The bias column (a constant 255 against the gradient) is formed in the first slab of a sample, every consumer taking
-// each fourth step; the four partial columns are added in wavefront order at the end.
+// The bias column (the column sums of the gradient, against the constant 255) is added up by the producer threads as
+// they copy the gradient rows into LDS, and their sums are added in thread order at the end.
 // ------------------------------------------------------------------------------------------------------------
 constexpr int C1WS_THREADS = 512, C1WS_PRODUCERS = 256;
 constexpr int C1WS_NP = 7;                 // 16-byte vectors of a slab per producer thread (slab of at most 28 KB)
@@ -255,16 +255,19 @@ constexpr int C1WS_DYV = 7;                // 16-byte vectors of a sample's outp
 constexpr int C1WS_DP = 2;                 // steps of operand reads a consumer keeps in flight
 constexpr int C1WS_MAX_SAMPLES = 64;       // samples per workgroup (their row indices are read once, into LDS)
 
-template <bool PADDED> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgrad_slab_kernel(const Conv1WgImgArgs a)
+// NKS: matrix-instruction steps per sample and slab as a compile-time constant (0: taken from the arguments).  With it
+// the consumers' step loop is written out without a branch; in a rolled loop with conditional read-aheads the compiler
+// waits for every outstanding LDS read at the top of each step, and a consumer, alone on its SIMD, then sits out an LDS
+// round trip per step (115 ticks per matrix instruction, measured with phase stamps).
+template <bool PADDED, int NKS> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgrad_slab_kernel(const Conv1WgImgArgs a)
 {
     constexpr int NG = 4, C = 16, PT = C1WS_PRODUCERS, DP = C1WS_DP;
     extern __shared__ __attribute__((aligned(16))) unsigned char c1ws_smem[];
     const int Wp = a.W, slab = 4 * a.H * a.W;                     // bytes of a slab in memory; its bf16 image takes twice that
-    const int nks = (a.P1 + 15) >> 4;                             // matrix-instruction steps per sample and slab
+    const int nks = NKS ? NKS : (a.P1 + 15) >> 4;                 // matrix-instruction steps per sample and slab
     bf16_t *dyl = reinterpret_cast<bf16_t *>(c1ws_smem + 4 * slab);      // [P1 padded to 16][32]
     uint2 *tab = reinterpret_cast<uint2 *>(dyl + nks * 16 * 32);
-    float *xch = reinterpret_cast<float *>(tab + (nks + C1WS_DP) * 64);        // [4][32] partial bias columns
-    int *rowid = reinterpret_cast<int *>(xch + 4 * 32);                  // [C1WS_MAX_SAMPLES] rows of this workgroup's samples
+    int *rowid = reinterpret_cast<int *>(tab + (nks + C1WS_DP) * 64);    // [C1WS_MAX_SAMPLES] rows of this workgroup's samples
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = lane >> 5, g1 = (lane >> 4) & 1, jj = (lane & 15) >> 2, q4 = lane & 3;
     const int nvec = a.P1 * 4;                                    // 16-byte vectors in one sample's [P1][32]
@@ -288,13 +291,15 @@ template <bool PADDED> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgr
     // zero rows behind the sample's gradient (written once: the copies below never touch them)
     for (int v = nvec + tid; v < nks * 64; v += C1WS_THREADS) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = zero_vec<bf16_t, 8>();
 
-    f32x16 acc[NG][2], accb;
+    f32x16 acc[NG][2];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        accb[r] = 0.0f;
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) { acc[cg][0][r] = 0.0f; acc[cg][1][r] = 0.0f; }
     }
+    float bsum[8];          // producers: column sums of the gradient rows this thread copies (columns 8 (pt % 4) .. + 7): the bias column
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bsum[e] = 0.0f;
     if (w >= 4) {
         // ---- producers ----
         const int pt = tid - (C1WS_THREADS - PT);
@@ -334,7 +339,11 @@ template <bool PADDED> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgr
 #pragma unroll
             for (int i = 0; i < C1WS_DYV; ++i) {
                 const int v = pt + i * PT;
-                if (v < nvec) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
+                if (v < nvec) {
+                    *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) bsum[e] += to_f32(dyr[i][e]);
+                }
             }
         };
         __syncthreads();                                           // the row indices are in LDS
@@ -375,9 +384,6 @@ template <bool PADDED> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgr
             const i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             return __builtin_bit_cast(bf16x8, v);
         };
-        bf16x8 ones;                                              // bias column: 255 in column 0 of the tile
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ones[e] = from_f32<bf16_t>((lane & 31) == 0 ? 255.0f : 0.0f);
         const uint2 *tp = tab + lane;
         __syncthreads();
         __syncthreads();
@@ -405,17 +411,21 @@ template <bool PADDED> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgr
                     __builtin_amdgcn_sched_barrier(0);             // keep those reads ahead of this step's products
                     acc[cg][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[cg][0], 0, 0, 0);
                     acc[cg][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, cv, acc[cg][1], 0, 0, 0);
-                    if (cg == 0 && (ks & 3) == w) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, ones, accb, 0, 0, 0);
                 };
 #pragma unroll
                 for (int d = 0; d < DP; ++d) { o[d].tn = tp[d * 64]; if (d < nks) read(d, o[d]); }
-                int ks = 0;
-                for (; ks + DP <= nks; ks += DP) {
+                if constexpr (NKS > 0) {
 #pragma unroll
-                    for (int d = 0; d < DP; ++d) step(ks + d, o[d]);
+                    for (int ks = 0; ks < NKS; ++ks) step(ks, o[ks % DP]);
+                } else {
+                    int ks = 0;
+                    for (; ks + DP <= nks; ks += DP) {
+#pragma unroll
+                        for (int d = 0; d < DP; ++d) step(ks + d, o[d]);
+                    }
+#pragma unroll
+                    for (int d = 0; d < DP - 1; ++d) if (ks + d < nks) step(ks + d, o[d]);
                 }
-#pragma unroll
-                for (int d = 0; d < DP - 1; ++d) if (ks + d < nks) step(ks + d, o[d]);
                 __syncthreads();
             }
             if (s + 1 < nsamp) __syncthreads();
@@ -429,24 +439,26 @@ template <bool PADDED> __global__ __launch_bounds__(C1WS_THREADS) void conv1_wgr
 #pragma unroll
                 for (int r = 0; r < 16; ++r) dst[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = acc[cg][h][r];
             }
-        if ((lane & 31) == 0) {
+    }
+    // bias column: the producers' sums, added in thread order; against the constant 255 (the reduction scales every
+    // conv1 column by 1/255).  (Every wavefront has left the images: the sums take their place.)
+    float *bl = reinterpret_cast<float *>(c1ws_smem);
+    if (w >= 4) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) xch[w * 32 + 8 * (r / 4) + 4 * kg + (r % 4)] = accb[r];
-        }
+        for (int e = 0; e < 8; ++e) bl[(tid - (C1WS_THREADS - PT)) * 8 + e] = bsum[e];
     }
     __syncthreads();
     if (tid < 32) {
-        float t = xch[tid];
-#pragma unroll
-        for (int ww = 1; ww < 4; ++ww) t += xch[ww * 32 + tid];
-        a.part[(long long)blockIdx.x * 32 * a.N + (long long)tid * a.N + 64 * C] = t;
+        float t = 0.0f;
+        for (int th = tid >> 3; th < PT; th += 4) t += bl[th * 8 + (tid & 7)];
+        a.part[(long long)blockIdx.x * 32 * a.N + (long long)tid * a.N + 64 * C] = 255.0f * t;
     }
 }
 
 static size_t conv1_wgrad_slab_lds(const Geom &g)
 {
     const size_t nks = (size_t)((g.P1 + 15) / 16);
-    return (size_t)16 * g.H * g.W + nks * 16 * 64 + (nks + C1WS_DP) * 64 * 8 + 4 * 32 * 4 + C1WS_MAX_SAMPLES * 4;      // two images, gradient rows, address table, bias partials, row indices
+    return (size_t)16 * g.H * g.W + nks * 16 * 64 + (nks + C1WS_DP) * 64 * 8 + C1WS_MAX_SAMPLES * 4;      // two images, gradient rows, address table, row indices
 }
 
 // true if a batch of B samples cut into at most max_parts workgroups leaves each of them no more samples than its index table holds
@@ -474,13 +486,16 @@ static hipError_t launch_conv1_wgrad_slab(Ctx &c, const uint8_t *obs, const int3
     a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
     const size_t lds = conv1_wgrad_slab_lds(g);
     const bool padded = (g.P1 & 15) != 0;
-    void (*kern)(const Conv1WgImgArgs) = padded ? conv1_wgrad_slab_kernel<true> : conv1_wgrad_slab_kernel<false>;
-    static std::atomic<bool> attr_set[2] = {};       // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
-    if (!attr_set[padded ? 1 : 0].load(std::memory_order_acquire)) {
+    const bool football = g.P1 == 391;               // 16x72x96 frames: 17 x 23 positions, 25 steps
+    void (*kern)(const Conv1WgImgArgs) = football ? conv1_wgrad_slab_kernel<true, 25>
+                                         : padded ? conv1_wgrad_slab_kernel<true, 0> : conv1_wgrad_slab_kernel<false, 0>;
+    static std::atomic<bool> attr_set[3] = {};       // raise the dynamic-LDS limit once per instantiation (setting it twice is harmless)
+    const int which = football ? 2 : padded ? 1 : 0;
+    if (!attr_set[which].load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_set[padded ? 1 : 0].store(true, std::memory_order_release);
+        attr_set[which].store(true, std::memory_order_release);
     }
     const int grid = B < max_parts ? B : max_parts;
     if ((B + grid - 1) / grid > C1WS_MAX_SAMPLES) return hipErrorInvalidValue;      // (the caller checks conv1_wgrad_slab_batch_fits)

@@ -209,7 +209,7 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) __attr
 {
     constexpr int C = 4 * NG, K = 64 * C, SLAB = 4 * H * W, NV = SLAB / 16, PT = C1S_PRODUCERS, NP = (NV + PT - 1) / PT;
     constexpr int IMG = 2 * SLAB;          // bytes of one bf16 image
-    constexpr int D = 2;                   // slabs in flight in the producers' registers
+    constexpr int D = 2;                   // slabs in flight in the producers' registers (four: no faster, 99 vs 96 us)
     static_assert(SLAB % 16 == 0 && (NG == 1 || NG % D == 0), "slab shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char c1s_smem[];
     unsigned char *wl = c1s_smem + 2 * IMG;
@@ -304,57 +304,78 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) __attr
         for (int t = 0; t < 16; ++t) breg[t] = *reinterpret_cast<const bf16x8 *>(a.w + lrow * K + 16 * t + 8 * lk);
     }
     f32x16 tot[C1S_TILES];
-    auto read16 = [&](const unsigned char *p) {                      // 8 pixels of one image row (8-byte aligned)
-        const Vec<bf16_t, 4> lo = *reinterpret_cast<const Vec<bf16_t, 4> *>(p), hi = *reinterpret_cast<const Vec<bf16_t, 4> *>(p + 8);
+    // 8 pixels of one image row (8-byte aligned) as two single 8-byte reads.  Left alone, the compiler merges them
+    // (or reads of two steps) into one two-address read, which the LDS serves at half the rate of two single ones --
+    // 8.0 against 2 x 2.4 ticks per wavefront -- and the LDS pipe is what the consumers wait for: hence volatile
+    // reads on explicit LDS addresses (conv1 forward at 2048 frames of 16x72x96: 93 -> 84 us).
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    typedef const volatile u32x2 __attribute__((address_space(3))) *lds_u32x2;
+    typedef __attribute__((address_space(3))) unsigned char *lds_bytes;
+    const uint32_t smem0 = (uint32_t)(uintptr_t)(lds_bytes)c1s_smem;
+    auto read16 = [&](uint32_t p) {
+        const u32x2 lw = *(lds_u32x2)(uintptr_t)p, hw = *(lds_u32x2)(uintptr_t)(p + 8u);
+        const Vec<bf16_t, 4> lo = __builtin_bit_cast(Vec<bf16_t, 4>, lw), hi = __builtin_bit_cast(Vec<bf16_t, 4>, hw);
         bf16x8 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
         return v;
     };
-    // tiles T0 .. T0+NT-1 of this wavefront against the slab in `buf`.  One 64-long segment per input channel; two
-    // channels' chains at a time per tile, so no matrix instruction waits for its predecessor; within a segment k
-    // ascends, and the segment sums are added in channel order (a segment sum is never -0, so the total of a frame
-    // starts as its first).
+    // tiles T0 .. T0+NT-1 of this wavefront against the slab in `buf`.  One 64-long segment per input channel, formed
+    // in a fresh accumulator (k ascending) and added to the running total in channel order (a segment sum is never
+    // -0, so the total of a frame starts as its first).
+    // The 16 steps (channel, k-step) are written out as a software pipeline: a consumer is alone on its SIMD's matrix
+    // pipe, so nothing hides an LDS round trip but its own earlier reads.  The operands of step e + PD are read before
+    // the products of step e are issued; the channels alternate between two accumulators, and the 16 additions per
+    // tile that fold a finished segment into the total are spread over the next channel's four steps, where they run
+    // beside its matrix instructions.  (Left to the compiler, most matrix instructions waited for a read issued just
+    // before them, and the additions of two channels ran in a block behind their products: 5400 ticks per slab for
+    // the wavefront with four tiles, against 2048 of matrix instructions.)
     auto mult = [&](int buf, auto t0c, auto ntc, auto firstc) {
-        constexpr int T0 = decltype(t0c)::value, NT = decltype(ntc)::value;
+        constexpr int T0 = decltype(t0c)::value, NT = decltype(ntc)::value, PD = 3;
         constexpr bool FIRST = decltype(firstc)::value;
         const unsigned char *wb = wl + buf * C1S_WBUF + woff;
-        const unsigned char *ib[NT];
+        uint32_t ib[NT];
 #pragma unroll
-        for (int i = 0; i < NT; ++i) ib[i] = c1s_smem + buf * IMG + toff[T0 + i];
+        for (int i = 0; i < NT; ++i) ib[i] = smem0 + buf * IMG + toff[T0 + i];
+        bf16x8 wq[PD], aq[PD][NT];
+        auto rd = [&](int e, int slot) {                  // both compile-time constants after unrolling
+            const int ch = e >> 2, t = e & 3;
+            if constexpr (NG == 1) wq[slot] = breg[ch * 4 + t];
+            else wq[slot] = *reinterpret_cast<const bf16x8 *>(wb + 2 * (64 * ch + 16 * t));
 #pragma unroll
-        for (int c0 = 0; c0 < 4; c0 += 2) {
-            f32x16 acc[NT][2];
+            for (int i = 0; i < NT; ++i) aq[slot][i] = read16(ib[i] + 2 * ((ch * H + 2 * t) * W));
+        };
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
+        for (int e = 0; e < PD; ++e) rd(e, e);
+        f32x16 acc[NT][2], zero;
 #pragma unroll
-                for (int c = 0; c < 2; ++c)
+        for (int r = 0; r < 16; ++r) zero[r] = 0.0f;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][c][r] = 0.0f;
+        for (int e = 0; e < 16; ++e) {
+            const int ch = e >> 2, t = e & 3, par = ch & 1;
+            const bf16x8 wv = wq[e % PD];
+            bf16x8 av[NT];
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int i = 0; i < NT; ++i) av[i] = aq[e % PD][i];
+            if (e + PD < 16) rd(e + PD, e % PD);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    bf16x8 wv;
-                    if constexpr (NG == 1) wv = breg[(c0 + c) * 4 + t];
-                    else wv = *reinterpret_cast<const bf16x8 *>(wb + 2 * (64 * (c0 + c) + 16 * t));
+            for (int i = 0; i < NT; ++i) acc[i][par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, av[i], t == 0 ? zero : acc[i][par], 0, 0, 0);
+            if (ch > 0) {                                  // a quarter of the previous channel's segment sum joins the total
 #pragma unroll
-                    for (int i = 0; i < NT; ++i) {
-                        const bf16x8 av = read16(ib[i] + 2 * (((c0 + c) * H + 2 * t) * W));
-                        acc[i][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, av, acc[i][c], 0, 0, 0);
+                for (int i = 0; i < NT; ++i)
+#pragma unroll
+                    for (int r = 4 * t; r < 4 * t + 4; ++r) {
+                        if (FIRST && ch == 1) tot[T0 + i][r] = acc[i][par ^ 1][r];
+                        else tot[T0 + i][r] += acc[i][par ^ 1][r];
                     }
-                }
-#pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                if (FIRST && c0 == 0) tot[T0 + i] = acc[i][0];
-                else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) tot[T0 + i][r] += acc[i][0][r];
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) tot[T0 + i][r] += acc[i][1][r];
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tot[T0 + i][r] += acc[i][1][r];
     };
     // The weights are the FIRST operand of the matrix instruction, so a lane's accumulator registers are 16 output
     // channels (8g + 4 lk + j, g and j < 4) of ONE position.  Lanes l and l + 32 hold the two interleaved halves of a
