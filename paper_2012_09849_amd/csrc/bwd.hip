@@ -306,16 +306,25 @@ template <bool PADDED, int NKS> __global__ __launch_bounds__(C1WS_THREADS) void 
         const int nv = slab >> 4;
         uint4 raw[2][C1WS_NP];
         bf16x8 dyr[C1WS_DYV];
+        // A thread's byte offsets inside a slab / a sample's gradient never change; what changes per slab is the same
+        // for the whole workgroup and is kept in scalar registers, so a fetch is loads and nothing else (the address
+        // arithmetic of seven 64-bit pointers per slab was a fifth of a producer's time beside a busy consumer).
+        uint32_t ioff[C1WS_NP], doff[C1WS_DYV];
+#pragma unroll
+        for (int i = 0; i < C1WS_NP; ++i) ioff[i] = 16u * (uint32_t)min(pt + i * PT, nv - 1);
+#pragma unroll
+        for (int i = 0; i < C1WS_DYV; ++i) doff[i] = 16u * (uint32_t)min(pt + i * PT, nvec - 1);
         auto fetch_image = [&](int p, uint4 (&r)[C1WS_NP]) {
             const int s = p / NG, cg = p - s * NG;
-            const uint8_t *src = a.obs + ((long long)rowid[s] * C + 4 * cg) * a.H * a.W;
+            const long long row = __builtin_amdgcn_readfirstlane(rowid[s]);
+            const uint8_t *src = a.obs + (row * C + 4 * cg) * a.H * a.W;
 #pragma unroll
-            for (int i = 0; i < C1WS_NP; ++i) r[i] = *reinterpret_cast<const uint4 *>(src + 16 * min(pt + i * PT, nv - 1));
+            for (int i = 0; i < C1WS_NP; ++i) r[i] = *reinterpret_cast<const uint4 *>(src + ioff[i]);
         };
         auto fetch_dy = [&](int s) {
-            const bf16_t *dsrc = a.dy + (long long)(blockIdx.x + s * gridDim.x) * a.P1 * 32;
+            const unsigned char *dsrc = reinterpret_cast<const unsigned char *>(a.dy + (long long)(blockIdx.x + s * gridDim.x) * a.P1 * 32);
 #pragma unroll
-            for (int i = 0; i < C1WS_DYV; ++i) dyr[i] = *reinterpret_cast<const bf16x8 *>(dsrc + 8 * min(pt + i * PT, nvec - 1));
+            for (int i = 0; i < C1WS_DYV; ++i) dyr[i] = *reinterpret_cast<const bf16x8 *>(dsrc + doff[i]);
         };
         auto convert = [&](const uint4 (&r)[C1WS_NP], int buf) {
             unsigned char *dst = c1ws_smem + buf * 2 * slab + 32 * pt;

@@ -226,20 +226,23 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) __attr
         const int pt = tid - (C1S_THREADS - PT);
         constexpr int NWV = NG > 1 ? 4 : 0;                // 16-byte vectors of the weight slice per producer thread
         uint4 raw[D][NP + NWV];                            // a slab's vectors, then its weight slice's
+        // A thread's byte offsets inside a slab / a weight slice never change; what changes per slab is the same for the
+        // whole workgroup and is kept in scalar registers, so a fetch is loads and nothing else.
+        uint32_t ioff[NP], woffs[NWV ? NWV : 1];
+#pragma unroll
+        for (int i = 0; i < NP; ++i) { const int v = pt + i * PT; ioff[i] = 16u * (uint32_t)(NV % PT == 0 ? v : min(v, NV - 1)); }   // a vector behind the slab's end repeats its last one
+#pragma unroll
+        for (int i = 0; i < NWV; ++i) { const int v = pt + i * PT; woffs[i] = (uint32_t)((v >> 5) * (2 * K) + (v & 31) * 16); }       // row v / 32, 16-byte column v % 32 of the 32 x 256 slice
         auto fetch = [&](int q, uint4 (&r)[NP + NWV]) {
             const int s = q / NG, cg = q - s * NG;
-            const uint8_t *src = a.obs + ((long long)rowid[s] * C + 4 * cg) * (H * W);
+            const long long row = __builtin_amdgcn_readfirstlane(rowid[s]);
+            const uint8_t *src = a.obs + (row * C + 4 * cg) * (H * W);
 #pragma unroll
-            for (int i = 0; i < NP; ++i) {
-                const int v = pt + i * PT;                     // a vector behind the slab's end repeats its last one
-                r[i] = *reinterpret_cast<const uint4 *>(src + 16 * (NV % PT == 0 ? v : min(v, NV - 1)));
-            }
+            for (int i = 0; i < NP; ++i) r[i] = *reinterpret_cast<const uint4 *>(src + ioff[i]);
             if constexpr (NG > 1) {
+                const unsigned char *wsrc = reinterpret_cast<const unsigned char *>(a.w) + cg * 512;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int v = pt + i * PT;                 // row v / 32, 16-byte column v % 32 of the 32 x 256 slice
-                    r[NP + i] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.w) + (v >> 5) * (2 * K) + cg * 512 + (v & 31) * 16);
-                }
+                for (int i = 0; i < NWV; ++i) r[NP + i] = *reinterpret_cast<const uint4 *>(wsrc + woffs[i]);
             }
         };
         auto convert = [&](const uint4 (&r)[NP + NWV], int buf) {
