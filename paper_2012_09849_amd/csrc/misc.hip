@@ -247,6 +247,8 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
     const int A = a.A;
 
     float hv[8];
+    constexpr int HEAD_CHUNK = 20;
+    float wv8[8], wrow[HEAD_CHUNK][8];     // value head and (up to) HEAD_CHUNK rows of pi.w: this lane's 8 columns
     float mylogit = 0.0f, value = 0.0f;
     float u01 = 0.0f;          // the sample's uniform: needs nothing from memory, so it is formed while the loads travel
     if constexpr (!LEARN) u01 = seeded_uniform(a.seed, (uint32_t)(a.env_offset + b), a.step);
@@ -255,8 +257,7 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
     } else {
         // Everything this wavefront needs from the weights is requested before the FC partial sums are waited for
         // (they are independent): value head, FC bias and the first HEAD_CHUNK rows of pi.w.
-        constexpr int HEAD_CHUNK = 20;
-        float wv8[8], bv8[8], wrow[HEAD_CHUNK][8];
+        float bv8[8];
         const float head_bias = lane < A ? a.bpi[lane] : 0.0f, value_bias = a.bv[0];
         load_vec(a.wv + lane * 8, wv8);
         load_vec(a.fc_bias + lane * 8, bv8);
@@ -427,20 +428,30 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
             float *t = a.terms + (long long)b * N_TERMS;
             t[0] = pi_term; t[1] = v_term; t[2] = ent; t[3] = clipped; t[4] = kl;
         }
-        // dL/d(FC pre-activation) for this lane's 8 hidden units
+        // dL/d(FC pre-activation) for this lane's 8 hidden units.  With at most HEAD_CHUNK actions the rows of pi.w are
+        // still in the registers the logits were formed from (fetching them a second time was nearly half of what a
+        // wavefront pulls through its L1, and that is what bounds this kernel); same products in the same order.
         float acc[8];
-        {
-            float wv8[8];
-            load_vec(a.wv + lane * 8, wv8);
+        const bool rows_held = !a.logits_in && A <= HEAD_CHUNK;
+        if (!rows_held || a.logits_in) load_vec(a.wv + lane * 8, wv8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = dv * wv8[i];
-        }
-        for (int j = 0; j < A; ++j) {
-            const float dj = lane_value(dl, j);
-            float w8[8];
-            load_vec(a.wpi + (long long)j * 512 + lane * 8, w8);
+        for (int i = 0; i < 8; ++i) acc[i] = dv * wv8[i];
+        if (rows_held) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(dj, w8[i], acc[i]);
+            for (int q = 0; q < HEAD_CHUNK; ++q)
+                if (q < A) {
+                    const float dj = lane_value(dl, q);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(dj, wrow[q][i], acc[i]);
+                }
+        } else {
+            for (int j = 0; j < A; ++j) {
+                const float dj = lane_value(dl, j);
+                float w8[8];
+                load_vec(a.wpi + (long long)j * 512 + lane * 8, w8);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(dj, w8[i], acc[i]);
+            }
         }
         f32x4 o0, o1;
 #pragma unroll
