@@ -497,9 +497,9 @@ template <typename T> static hipError_t forward_t(Ctx &c, const uint8_t *obs, co
             if (done) {}
             else if (small) e = g.K1 >= 1024 ? launch_wsgemm<Conv1Fwd<T>, 16, Conv1Fwd<T>::SEG, false, (sizeof(T) == 4)>(p, c.stream)
                                         : launch_wsgemm<Conv1Fwd<T>, 4, Conv1Fwd<T>::SEG, false>(p, c.stream);
-            // (four-channel frames: the slab kernel gains only where a workgroup walks eight or more observations --
-            // 4096 rows of 4x84x84: an act call 212 -> 206 us; 1024 rows: no difference to the image kernel)
-            else if (sizeof(T) == 2 && B >= (g.C == 4 ? 8 : 1) * c.conv1_slab_rows && conv1_slab_fits(g, obs)) e = launch_conv1_slab(c, obs, index, B);
+            // (four-channel frames too: against the LDS-image kernel of that shape, conv1 at 1024 rows of 4x84x84
+            // 21.7 -> 19.0 us, an act call at 256 / 4096 rows 38.8 -> 36.7 / 203 -> 188 us)
+            else if (sizeof(T) == 2 && B >= c.conv1_slab_rows && conv1_slab_fits(g, obs)) e = launch_conv1_slab(c, obs, index, B);
             else if (sizeof(T) == 2 && conv1_image_fits(g, obs)) e = launch_conv1_image(c, obs, index, B);
             else e = launch_gemm(p, c.stream);
         }

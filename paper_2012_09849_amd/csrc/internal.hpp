@@ -65,7 +65,7 @@ struct Ctx {
     int tile16_below;         // small-batch forward layers with fewer 32x32-tile workgroups than this use 16x16 tiles
     int fc_fold_rows;         // batches of at least this many rows add the FC groups inside the FC kernel (one slice of fc_part)
     int fc_slices;            // slices of fc_part the last forward pass wrote (fc_groups, or 1)
-    int conv1_slab_rows;      // bf16 batches of at least this many 16x72x96 frames take the slab conv1 kernel
+    int conv1_slab_rows;      // bf16 batches of at least this many 16x72x96 or 4x84x84 frames take the slab conv1 kernels
     bool synced;              // the workspace's copy of the network matches the last parameter vector handed in
     bool synced_learn;        // ... including the learner-only parts
     bool track_params;        // the caller modifies its parameter vectors only through this context (hts_track_params)
