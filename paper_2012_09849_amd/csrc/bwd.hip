@@ -17,19 +17,46 @@ namespace hts {
 // slow index in LDS; the transposing LDS read hands each lane the 8 positions of its row / column -- for the image
 // with a per-lane address, so the im2col matrix is never materialised.  (The tile kernel converts every pixel four
 // times and fetches it in 8-byte pieces: it is bound by that.)  Positions are padded to a multiple of 16 with zero
-// gradient rows.  Wavefront 0 also forms the bias column against a constant 255 (the reduction scales every conv1
-// column by 1/255).  Partials part[workgroup][32][64C+1], combined in workgroup order by the reduction kernel.
+// gradient rows.  The bias column is the column sums of the gradient, taken by the copying threads, against the
+// constant 255 (the reduction scales every conv1 column by 1/255).  Partials part[workgroup][32][64C+1], combined in workgroup order by the reduction kernel.
 // ------------------------------------------------------------------------------------------------------------
+// Column sums of a sample share's gradient rows from the per-thread sums bl[NTH][8] (thread t holds columns
+// 8 (t % 4) .. + 7): column tid (< 32) is returned to thread tid.  Four groups of 32 threads each add a quarter of a
+// column's NTH/4 terms in thread order (their loads batched: one thread walking all of them alone paid an LDS round trip
+// per term, 10 us at the end of a 20 us kernel), and the four sums are added in order.  Fixed shape: deterministic.
+// Every thread of the workgroup (at least 128) must call it; it contains a barrier; bl[NTH*8 .. +127] is used too.
+template <int NTH> __device__ __forceinline__ float bias_column_sum(float *bl, int tid)
+{
+    constexpr int TERMS = NTH / 4, QUARTER = TERMS / 4;
+    static_assert(TERMS % 4 == 0 && QUARTER % 8 == 0, "term counts");
+    float *cs = bl + NTH * 8;
+    if (tid < 128) {
+        const int col = tid & 31, chunk = tid >> 5;
+        const float *src = bl + ((col >> 3) + 4 * chunk * QUARTER) * 8 + (col & 7);
+        float t = 0.0f;
+        for (int k0 = 0; k0 < QUARTER; k0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(k0 + u) * 32];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t += v[u];
+        }
+        cs[chunk * 32 + col] = t;
+    }
+    __syncthreads();
+    return tid < 32 ? ((cs[tid] + cs[32 + tid]) + cs[64 + tid]) + cs[96 + tid] : 0.0f;
+}
+
 struct Conv1WgImgArgs {
     const uint8_t *obs;
     const int32_t *index;
     const bf16_t *dy;       // [B][P1][32]
     float *part;
     int B, H, W, W1, P1, N; // N = 64*C + 1
-    FastDiv dGpr, dW1;
+    FastDiv dW1;
 };
 constexpr int C1WG_THREADS = 512;          // 8 wavefronts = the 8 column tiles of four input channels
-constexpr int C1WG_PASSES = 20;            // passes of a wavefront over its share of a channel group's image rows
+constexpr int C1WG_NV = 4;                 // 16-byte vectors of a four-channel slab per thread (a slab of at most 32 KB)
 constexpr int C1WG_DYV = 4;                // 16-byte vectors of the sample's output gradient per thread
 
 // PADDED: P1 is not a multiple of 16 (the last step has padding positions)
@@ -42,22 +69,17 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attr
     bf16_t *dyl = img + ((rows * Wp + 7) & ~7);                   // [P1 padded to 16][32]
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int kg = lane >> 5, g1 = (lane >> 4) & 1, jj = (lane & 15) >> 2, q = lane & 3;
-    // frame -> image, as in the forward image kernel: a wavefront takes 64/gpr image rows per pass
-    const int gpr = a.W >> 2, rpp = 64 / gpr;
-    const int lr = a.dGpr.div(lane), xg = lane - lr * gpr;
-    const bool lane_on = lr < rpp;
-    constexpr int NW = C1WG_THREADS / 64;
+    // frame -> image: the slab's 4*H*W bytes are contiguous in memory and its image is contiguous in LDS (pitch = W),
+    // so the copy is linear: 16 pixels per 16-byte load, converted once, two 16-byte LDS stores
+    const int nv = (rows * Wp) >> 4;                              // 16-byte vectors of a slab
     const int nvec = a.P1 * 4;                                    // 16-byte vectors in one sample's [P1][32]
     const int nks = (a.P1 + 15) >> 4;                             // matrix-instruction steps per sample and group
-    uint32_t raw[C1WG_PASSES];
+    uint4 raw[C1WG_NV];
     bf16x8 dyr[C1WG_DYV];
     auto fetch_image = [&](int b, int cg) {
-        const uint8_t *src = a.obs + ((long long)(a.index ? a.index[b] : b) * C + 4 * cg) * a.H * a.W + 4 * xg;
+        const uint8_t *src = a.obs + ((long long)(a.index ? a.index[b] : b) * C + 4 * cg) * a.H * a.W;
 #pragma unroll
-        for (int i = 0; i < C1WG_PASSES; ++i) {
-            const int row = (w + i * NW) * rpp + lr;
-            if (lane_on && row < rows) raw[i] = *reinterpret_cast<const uint32_t *>(src + row * a.W);
-        }
+        for (int i = 0; i < C1WG_NV; ++i) raw[i] = *reinterpret_cast<const uint4 *>(src + 16 * min(tid + i * C1WG_THREADS, nv - 1));
     };
     auto fetch_dy = [&](int b) {
         const bf16_t *dsrc = a.dy + (long long)b * a.P1 * 32;
@@ -79,16 +101,18 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attr
         const i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, v);
     };
-    bf16x8 ones;                                                  // bias column: 255 in column 0 of the tile
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ones[e] = from_f32<bf16_t>((lane & 31) == 0 ? 255.0f : 0.0f);
-    f32x16 acc[NG], accb;
+    f32x16 acc[NG];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        accb[r] = 0.0f;
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) acc[cg][r] = 0.0f;
     }
+    // Bias column: the column sums of the gradient rows, taken by the threads that copy them into LDS (columns
+    // 8 (tid % 4) .. + 7 each) and added in thread order at the end.  (As products against a constant in wavefront 0,
+    // that wavefront issued twice the matrix instructions of the others, who waited for it at every barrier.)
+    float bsum[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bsum[e] = 0.0f;
     // Positions m = 16 ks + 8 kg + jj (first read) and m + 4 (second read) of step ks: where a lane's two image reads of a
     // step start is the same for every sample and channel group, so it is tabulated once (LDS addresses, wave-independent
     // part; one 8-byte entry per step and lane, one row more than there are steps so that the read-ahead needs no check).
@@ -117,19 +141,30 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attr
         for (int cg = 0; cg < NG; ++cg) {
             if (cg > 0) __syncthreads();      // the previous group's image has been read
 #pragma unroll
-            for (int i = 0; i < C1WG_PASSES; ++i) {
-                const int row = (w + i * NW) * rpp + lr;
-                if (!lane_on || row >= rows) continue;
-                Vec<bf16_t, 4> px;
+            for (int i = 0; i < C1WG_NV; ++i) {
+                const int v = tid + i * C1WG_THREADS;
+                if (v >= nv) continue;
+                const uint32_t x[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+                bf16x8 lo, hi;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) px[e] = from_f32<bf16_t>((float)((raw[i] >> (8 * e)) & 0xFFu));
-                *reinterpret_cast<Vec<bf16_t, 4> *>(img + row * Wp + 4 * xg) = px;
+                for (int e = 0; e < 4; ++e) {
+                    lo[e] = from_f32<bf16_t>((float)((x[0] >> (8 * e)) & 0xFFu));
+                    lo[4 + e] = from_f32<bf16_t>((float)((x[1] >> (8 * e)) & 0xFFu));
+                    hi[e] = from_f32<bf16_t>((float)((x[2] >> (8 * e)) & 0xFFu));
+                    hi[4 + e] = from_f32<bf16_t>((float)((x[3] >> (8 * e)) & 0xFFu));
+                }
+                *reinterpret_cast<bf16x8 *>(img + v * 16) = lo;
+                *reinterpret_cast<bf16x8 *>(img + v * 16 + 8) = hi;
             }
             if (cg == 0) {
 #pragma unroll
                 for (int i = 0; i < C1WG_DYV; ++i) {
                     const int v = tid + i * C1WG_THREADS;
-                    if (v < nvec) *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
+                    if (v < nvec) {
+                        *reinterpret_cast<bf16x8 *>(dyl + v * 8) = dyr[i];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) bsum[e] += to_f32(dyr[i][e]);
+                    }
                 }
             }
             __syncthreads();
@@ -140,9 +175,9 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attr
             const bf16_t *ap = a_lane;
             const uint2 *tp = tab + lane;
             // Software pipeline: the four reads of step k+1 are issued before the matrix instruction of step k (the
-            // transposing reads are not moved by the compiler), and the table entry of step k+2 before them.  Two
-            // straight-line bodies (with / without the bias column); whole groups of 5 steps are written out.
-            auto walk = [&](auto with_bias) {
+            // transposing reads are not moved by the compiler), and the table entry of step k+2 before them.  Whole
+            // groups of 5 steps are written out.
+            auto walk = [&]() {
                 i16x4 ra0, ra1, rb0, rb1;
                 uint2 tn = tp[0];
                 auto read = [&](int ks) {                      // the operands of step ks; tn holds its table entry
@@ -155,7 +190,6 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attr
                 };
                 auto mult = [&](const bf16x8 av, const bf16x8 bv) {
                     acc[cg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[cg], 0, 0, 0);
-                    if constexpr (decltype(with_bias)::value) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, ones, accb, 0, 0, 0);
                 };
                 read(0);
                 int ks = 0;
@@ -174,7 +208,7 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attr
                     mult(av, bv);
                 }
             };
-            if (w == 0 && cg == 0) walk(std::true_type{}); else walk(std::false_type{});
+            walk();
         }
         __syncthreads();          // image and gradient are overwritten by the next sample
     }
@@ -185,11 +219,13 @@ template <int NG, bool PADDED> __global__ __launch_bounds__(C1WG_THREADS) __attr
 #pragma unroll
         for (int r = 0; r < 16; ++r) dst[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = acc[cg][r];
     }
-    if (w == 0 && (lane & 31) == 0) {
-        float *bd = a.part + (long long)blockIdx.x * 32 * a.N + 64 * C;
+    // (every wavefront has left the image: the threads' column sums take its place)
+    float *bl = reinterpret_cast<float *>(c1w_smem);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) bd[(long long)(8 * (r / 4) + 4 * kg + (r % 4)) * a.N] = accb[r];
-    }
+    for (int e = 0; e < 8; ++e) bl[tid * 8 + e] = bsum[e];
+    __syncthreads();
+    const float bias = bias_column_sum<C1WG_THREADS>(bl, tid);
+    if (tid < 32) a.part[(long long)blockIdx.x * 32 * a.N + (long long)tid * a.N + 64 * C] = 255.0f * bias;
 }
 
 static size_t conv1_wgrad_image_lds(const Geom &g)
@@ -201,10 +237,9 @@ static size_t conv1_wgrad_image_lds(const Geom &g)
 // true if the frame shape and pointers fit conv1_wgrad_image_kernel
 static bool conv1_wgrad_image_fits(const Geom &g, const uint8_t *obs)
 {
-    if ((g.C != 4 && g.C != 8 && g.C != 12 && g.C != 16) || g.W > 256 || (g.W & 3) || (((uintptr_t)obs) & 3u) || g.W1 < 16 || g.P1 < 16)
+    if ((g.C != 4 && g.C != 8 && g.C != 12 && g.C != 16) || ((4 * g.H * g.W) & 15) || (((uintptr_t)obs) & 15u) || g.W1 < 16 || g.P1 < 16)
         return false;
-    const int gpr = g.W / 4, rpp = 64 / gpr, rows = 4 * g.H;
-    return rows <= C1WG_PASSES * rpp * (C1WG_THREADS / 64) && g.P1 * 4 <= C1WG_DYV * C1WG_THREADS &&
+    return 4 * g.H * g.W <= C1WG_NV * C1WG_THREADS * 16 && g.P1 * 4 <= C1WG_DYV * C1WG_THREADS &&
            conv1_wgrad_image_lds(g) <= 160 * 1024;
 }
 
@@ -216,7 +251,7 @@ static hipError_t launch_conv1_wgrad_image(Ctx &c, const uint8_t *obs, const int
     Conv1WgImgArgs a;
     a.obs = obs; a.index = index; a.dy = (const bf16_t *)c.ws.dy1; a.part = part;
     a.B = B; a.H = g.H; a.W = g.W; a.W1 = g.W1; a.P1 = g.P1; a.N = g.K1 + 1;
-    a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
+    a.dW1 = FastDiv::make(g.W1);
     const size_t lds = conv1_wgrad_image_lds(g);
     const bool padded = (g.P1 & 15) != 0;
     void (*kern)(const Conv1WgImgArgs);
@@ -457,11 +492,8 @@ template <bool PADDED, int NKS> __global__ __launch_bounds__(C1WS_THREADS) void 
         for (int e = 0; e < 8; ++e) bl[(tid - (C1WS_THREADS - PT)) * 8 + e] = bsum[e];
     }
     __syncthreads();
-    if (tid < 32) {
-        float t = 0.0f;
-        for (int th = tid >> 3; th < PT; th += 4) t += bl[th * 8 + (tid & 7)];
-        a.part[(long long)blockIdx.x * 32 * a.N + (long long)tid * a.N + 64 * C] = 255.0f * t;
-    }
+    const float bias = bias_column_sum<PT>(bl, tid);
+    if (tid < 32) a.part[(long long)blockIdx.x * 32 * a.N + (long long)tid * a.N + 64 * C] = 255.0f * bias;
 }
 
 static size_t conv1_wgrad_slab_lds(const Geom &g)
@@ -492,7 +524,7 @@ static hipError_t launch_conv1_wgrad_slab(Ctx &c, const uint8_t *obs, const int3
     Conv1WgImgArgs a;
     a.obs = obs; a.index = index; a.dy = (const bf16_t *)c.ws.dy1; a.part = part;
     a.B = B; a.H = g.H; a.W = g.W; a.W1 = g.W1; a.P1 = g.P1; a.N = g.K1 + 1;
-    a.dGpr = FastDiv::make(g.W / 4); a.dW1 = FastDiv::make(g.W1);
+    a.dW1 = FastDiv::make(g.W1);
     const size_t lds = conv1_wgrad_slab_lds(g);
     const bool padded = (g.P1 & 15) != 0;
     const bool football = g.P1 == 391;               // 16x72x96 frames: 17 x 23 positions, 25 steps
