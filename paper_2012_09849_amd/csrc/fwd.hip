@@ -337,16 +337,21 @@ template <int NG, int H, int W> __global__ __launch_bounds__(C1S_THREADS) __attr
         constexpr int T0 = decltype(t0c)::value, NT = decltype(ntc)::value, PD = 3;
         constexpr bool FIRST = decltype(firstc)::value;
         const unsigned char *wb = wl + buf * C1S_WBUF + woff;
-        uint32_t ib[NT];
+        uint32_t ib[NT][4];                               // per tile and channel, so that a step's offset is an immediate
 #pragma unroll
-        for (int i = 0; i < NT; ++i) ib[i] = smem0 + buf * IMG + toff[T0 + i];
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int ch = 0; ch < 4; ++ch) {
+                ib[i][ch] = smem0 + buf * IMG + toff[T0 + i] + 2 * (ch * H * W);
+                asm volatile("" : "+v"(ib[i][ch]));       // (kept in a register: folded back into one base plus a constant, the
+            }                                             //  constant exceeds the instruction's offset field and costs an addition per read)
         bf16x8 wq[PD], aq[PD][NT];
         auto rd = [&](int e, int slot) {                  // both compile-time constants after unrolling
             const int ch = e >> 2, t = e & 3;
             if constexpr (NG == 1) wq[slot] = breg[ch * 4 + t];
             else wq[slot] = *reinterpret_cast<const bf16x8 *>(wb + 2 * (64 * ch + 16 * t));
 #pragma unroll
-            for (int i = 0; i < NT; ++i) aq[slot][i] = read16(ib[i] + 2 * ((ch * H + 2 * t) * W));
+            for (int i = 0; i < NT; ++i) aq[slot][i] = read16(ib[i][ch] + 2 * (2 * t * W));
         };
 #pragma unroll
         for (int e = 0; e < PD; ++e) rd(e, e);
