@@ -589,14 +589,14 @@ template <typename T> static hipError_t backward_t(Ctx &c, const uint8_t *obs, c
     {   // fc.w, fc.b
         FcWgrad<T> p;
         p.M = 512; p.N = g.F + 1; p.K = B; p.klen = B;
-        p.dh = c.ws.dh; p.a3 = (const T *)c.ws.a3; p.g = grads; p.F = g.F; p.fcw = g.fcw; p.fcb = g.fcb;
+        p.dh = (const T *)c.ws.dh; p.a3 = (const T *)c.ws.a3; p.g = grads; p.F = g.F; p.fcw = g.fcw; p.fcb = g.fcb;
         { SiteTimer tm(c, SITE_FC_WGRAD); e = launch_gemm(p, c.stream); }
         if (e != hipSuccess) return e;
     }
     {   // d(conv3 pre-activation)
         FcDgrad<T> p;
         p.M = B; p.N = g.F; p.K = 512; p.klen = 512;
-        p.dh = c.ws.dh; p.wfcd = (const T *)c.ws.wfcd; p.a3n = (const T *)c.ws.a3n; p.dy3 = (T *)c.ws.dy3;
+        p.dh = (const T *)c.ws.dh; p.wfcd = (const T *)c.ws.wfcd; p.a3n = (const T *)c.ws.a3n; p.dy3 = (T *)c.ws.dy3;
         {
             SiteTimer tm(c, SITE_FC_DGRAD);
             e = small ? launch_wsgemm<FcDgrad<T>, 4, 64, false>(p, c.stream) : launch_gemm(p, c.stream);

@@ -235,7 +235,8 @@ struct HeadsArgs {
     // learner inputs / outputs
     LossArgs la;
     float *dz, *dh, *terms;
-};
+    bf16_t *dh16;              // not null: dL/dh is written here in bfloat16 (the operand type of the FC layer's backward
+};                             // kernels, which then fetch half the bytes; they rounded it the same way as they loaded it)
 
 template <bool LEARN>
 __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
@@ -459,8 +460,15 @@ __global__ __launch_bounds__(256) void heads_kernel(const HeadsArgs a)
             o0[i] = hv[i] > 0.0f ? acc[i] : 0.0f;
             o1[i] = hv[4 + i] > 0.0f ? acc[4 + i] : 0.0f;
         }
-        f32x4 *dst = reinterpret_cast<f32x4 *>(a.dh + (long long)b * 512 + lane * 8);
-        dst[0] = o0; dst[1] = o1;
+        if (a.dh16) {
+            bf16x8 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { o[i] = from_f32<bf16_t>(o0[i]); o[4 + i] = from_f32<bf16_t>(o1[i]); }
+            *reinterpret_cast<bf16x8 *>(a.dh16 + (long long)b * 512 + lane * 8) = o;
+        } else {
+            f32x4 *dst = reinterpret_cast<f32x4 *>(a.dh + (long long)b * 512 + lane * 8);
+            dst[0] = o0; dst[1] = o1;
+        }
     }
 }
 
@@ -507,7 +515,8 @@ hipError_t launch_heads_learn(Ctx &c, const LossArgs &la, int B)
     a.h_out = c.ws.h;
     a.B = B; a.A = c.g.A;
     a.la = la;
-    a.dz = c.ws.dz; a.dh = c.ws.dh; a.terms = c.ws.terms;
+    a.dz = c.ws.dz; a.terms = c.ws.terms;
+    if (c.desc.precision == HTS_PRECISION_BF16) a.dh16 = reinterpret_cast<bf16_t *>(c.ws.dh); else a.dh = c.ws.dh;
     const int wv = heads_waves(B);
     const size_t lds = heads_lds_bytes(c.g.A, wv);
     if (lds > 65536) { const hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(heads_kernel<true>), lds); if (e != hipSuccess) return e; }

@@ -260,14 +260,14 @@ struct HeadsWgrad {
 template <typename T_> struct FcWgrad {
     using T = T_;
     static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16_WGRAD : 32), WAVES_M = 2, WAVES_N = 2;   // 8 x 50 workgroups
-    static constexpr int VA = 4, VB = OperandTraits<T>::VEC;
+    static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = false, B_ALONG_K = false;
     static constexpr bool NATURAL_LDS = true;
     static constexpr bool TILES_ALONG_M = true;      // the activations (N side, B x F) outweigh dh (M side, B x 512): an XCD takes a range of columns
     struct CtxA { int j; };
     struct CtxB { int f; };
     int M, N, K, klen;     // M = 512, N = F+1, K = B
-    const float *dh;
+    const T *dh;           // in the operand type (the heads kernel rounds it once as it writes it)
     const T *a3;
     float *g;
     int F;
@@ -300,10 +300,10 @@ template <typename T_> struct FcDgrad {
     static constexpr int BM = 64, BN = 64, BK = (sizeof(T) == 2 ? BK_BF16 : 32), WAVES_M = 2, WAVES_N = 2;
     static constexpr int VA = OperandTraits<T>::VEC, VB = OperandTraits<T>::VEC;
     static constexpr bool A_ALONG_K = true, B_ALONG_K = true;
-    typedef PtrCtx<float> CtxA;
+    typedef PtrCtx<T> CtxA;
     typedef PtrCtx<T> CtxB;
     int M, N, K, klen;     // M = B, N = F, K = 512
-    const float *dh;
+    const T *dh;           // in the operand type
     const T *wfcd, *a3n;
     T *dy3;
     HTS_HD CtxA ctx_a(int b) const { return {dh + (long long)clamp_row(b, M) * 512}; }
