@@ -180,20 +180,20 @@ def source_digest():
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
 TRAFFIC = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099064, "conv1_fwd_learn": 279415505, "conv1_wgrad": 314326162,
-                                    "conv2_fwd": 2626309, "conv3_fwd": 1214352, "fc_fwd": 3475121}, "00d9eaac0c04b9e4"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846563, "conv1_fwd_learn": 55546895, "conv1_wgrad": 63732412,
-                                 "conv2_wgrad": 45566781}, "00d9eaac0c04b9e4"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099062, "conv1_fwd_learn": 279412483, "conv1_wgrad": 314320632,
+                                    "conv2_fwd": 2626307, "conv3_fwd": 1214351, "fc_fwd": 3475119}, "4bddbec41cc16bfb"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846564, "conv1_fwd_learn": 55546876, "conv1_wgrad": 63732383,
+                                 "conv2_wgrad": 45562016}, "4bddbec41cc16bfb"),
 }
 
 
 # Average duration (us) of the same launch sites' kernels in the committed rocprofv3 kernel traces
 # (profiles/all_kernels_<workload>.txt), for comparison with the live event figure; same digest rule as TRAFFIC.
 TRACE_AVG_US = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.17, "heads_act": 5.09, "conv2_fwd": 3.87, "conv3_fwd": 3.51,
-                                    "fc_fwd": 3.21, "conv1_fwd_learn": 87.31, "conv1_wgrad": 78.98}, "00d9eaac0c04b9e4"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.06, "heads_act": 5.10, "conv1_fwd_learn": 20.00, "conv1_wgrad": 19.02,
-                                 "conv2_wgrad": 23.33}, "00d9eaac0c04b9e4"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.16, "heads_act": 5.07, "conv2_fwd": 3.77, "conv3_fwd": 3.47,
+                                    "fc_fwd": 3.19, "conv1_fwd_learn": 87.54, "conv1_wgrad": 79.12}, "4bddbec41cc16bfb"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.00, "heads_act": 5.07, "conv1_fwd_learn": 19.92, "conv1_wgrad": 19.01,
+                                 "conv2_wgrad": 23.34}, "4bddbec41cc16bfb"),
 }
 
 
