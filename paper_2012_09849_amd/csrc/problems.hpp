@@ -276,12 +276,12 @@ template <typename T_> struct FcWgrad {
     HTS_HD CtxB ctx_b(int f) const { return {f}; }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int b, int kend) const
     {
-        return keep_if<T, VA>(b < kend, load_vec<T, VA>(dh + (long long)(b < kend ? b : 0) * 512 + c.j));   // M = 512: no row tail
+        return keep_if<T, VA>(b < kend, load_vec<T, VA>(dh + (uint32_t)((b < kend ? b : 0) * 512 + c.j)));   // M = 512: no row tail; 32-bit element offsets
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int b, int kend) const
     {
         const bool in = b < kend && c.f < F;
-        Vec<T, VB> v = keep_if<T, VB>(in, load_vec<T, VB>(a3 + (in ? (long long)b * F + c.f : 0)));
+        Vec<T, VB> v = keep_if<T, VB>(in, load_vec<T, VB>(a3 + (in ? (uint32_t)(b * F + c.f) : 0u)));      // (fewer than 2^31 elements at the largest minibatch)
         v[0] = (b < kend && c.f == F) ? from_f32<T>(1.0f) : v[0];
         return v;
     }
@@ -473,15 +473,16 @@ template <typename T_, class L> struct ConvWgrad {
     }
     HTS_HD Vec<T, VA> load_a(const CtxA &c, int m, int kend) const
     {
-        return keep_if<T, VA>(m < kend, load_vec<T, VA>(dy + (long long)(m < kend ? m : 0) * L::COUT + c.n));      // M = 64 = BM
+        return keep_if<T, VA>(m < kend, load_vec<T, VA>(dy + (uint32_t)((m < kend ? m : 0) * L::COUT + c.n)));      // M = 64 = BM
     }
     HTS_HD Vec<T, VB> load_b(const CtxB &c, int m, int kend) const
     {
         const bool inside = m < kend && c.goff >= 0;
         const int mm = inside ? m : 0;
         const int b = dPo.div(mm), p = mm - b * Po, oy = dWo.div(p), ox = p - oy * Wo;
-        Vec<T, VB> v = keep_if<T, VB>(inside, load_vec<T, VB>(in + (((long long)b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN +
-                                                              (inside ? c.goff : 0)));
+        // (an element offset of 32 bits: the layer input of the largest minibatch has fewer than 2^31 elements)
+        const uint32_t off = (uint32_t)(((b * Hin + oy * L::STRIDE) * Win + ox * L::STRIDE) * L::CIN) + (uint32_t)(inside ? c.goff : 0);
+        Vec<T, VB> v = keep_if<T, VB>(inside, load_vec<T, VB>(in + off));
         v[0] = (m < kend && c.goff == -1) ? from_f32<T>(1.0f) : v[0];
         return v;
     }
