@@ -180,20 +180,20 @@ def source_digest():
 # counter reads for a plain copy of known size): workload -> ({launch site: bytes per launch}, digest of the kernel
 # sources the counters were taken on).
 TRAFFIC = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099062, "conv1_fwd_learn": 279412483, "conv1_wgrad": 314320632,
-                                    "conv2_fwd": 2626307, "conv3_fwd": 1214351, "fc_fwd": 3475119}, "4bddbec41cc16bfb"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846564, "conv1_fwd_learn": 55546876, "conv1_wgrad": 63732383,
-                                 "conv2_wgrad": 45562016}, "4bddbec41cc16bfb"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 5099060, "conv1_fwd_learn": 279396464, "conv1_wgrad": 314394353,
+                                    "conv2_fwd": 2626307, "conv3_fwd": 1214351, "fc_fwd": 3475119}, "394f517a35e13028"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 2846561, "conv1_fwd_learn": 55546870, "conv1_wgrad": 63732383,
+                                 "conv2_wgrad": 45561325}, "394f517a35e13028"),
 }
 
 
 # Average duration (us) of the same launch sites' kernels in the committed rocprofv3 kernel traces
 # (profiles/all_kernels_<workload>.txt), for comparison with the live event figure; same digest rule as TRAFFIC.
 TRACE_AVG_US = {
-    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.16, "heads_act": 5.07, "conv2_fwd": 3.77, "conv3_fwd": 3.47,
-                                    "fc_fwd": 3.19, "conv1_fwd_learn": 87.54, "conv1_wgrad": 79.12}, "4bddbec41cc16bfb"),
-    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.00, "heads_act": 5.07, "conv1_fwd_learn": 19.92, "conv1_wgrad": 19.01,
-                                 "conv2_wgrad": 23.34}, "4bddbec41cc16bfb"),
+    "football_ppo_n16_t512_bf16": ({"conv1_fwd": 6.30, "heads_act": 5.07, "conv2_fwd": 3.87, "conv3_fwd": 3.52,
+                                    "fc_fwd": 3.20, "conv1_fwd_learn": 86.50, "conv1_wgrad": 78.18}, "394f517a35e13028"),
+    "atari_ppo_n32_t128_bf16": ({"conv1_fwd": 5.03, "heads_act": 5.20, "conv1_fwd_learn": 20.44, "conv1_wgrad": 19.09,
+                                 "conv2_wgrad": 22.54}, "394f517a35e13028"),
 }
 
 
